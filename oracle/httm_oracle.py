@@ -1,0 +1,356 @@
+"""CPU oracle for the HTTM global-attention layer (arXiv 2511.21317).
+
+TEST INFRASTRUCTURE ONLY.  This module is a plain, slow, step-by-step NumPy
+implementation of what the paper's Algorithm 1 computes (without the outlier
+filter).  It exists so that the HIP kernels can be checked against something
+written independently from the paper.  Only the test-suite, the smoke check and
+the benchmark's CPU-baseline leg may import it; the product path never does,
+and this module imports nothing from the product.
+
+Every function takes the steps of the paper in the paper's order:
+
+    Alg. 1 step "TemporalReorder"   -> temporal_reorder
+    Alg. 1 step "Reorder"           -> reorder
+    Sec. 3.2 Eq. 1 + best match,
+    Alg. 1 step "BlockwiseToMe"     -> blockwise_tome  (match_block per block)
+    Sec. 3.2 mean of constituents,
+    Alg. 1 step "BlockAggregate"    -> block_aggregate
+    Sec. 3.2 Eq. 3-4                -> attention
+    Sec. 3.2 Eq. 5                  -> unmerge_by_cluster
+    Alg. 1 step "InverseReorder"    -> inverse_reorder
+    Sec. 3.2 Eq. 6-7 (head concat)  -> layer_forward
+
+Arithmetic runs in `dtype` (float32 by default, the precision the acceptance
+bar is stated in; float64 is accepted for cross-checks).
+
+Readings taken where the paper is silent (all listed in the design notes):
+  * a spatial block is a b x b window of patches, stacked over T consecutive
+    frames (Sec. 3.3 only fixes sizes n_s and n_t); partial windows at the
+    right/bottom edge and a partial last frame group are blocks of their own;
+  * the 5 special tokens of each frame are never merged and sit, in (frame,
+    slot) order, in front of all blocks in the reordered sequence;
+  * inside a block tokens are ordered (frame, row, column);
+  * a block of n tokens keeps k = max(1, n - floor(rho*n + 1e-9)) clusters
+    (Alg. 1 is parameterised by a cluster number per block; Sec. 4.1 fixes
+    "merge ratio rho leaves (1 - rho) of the tokens");
+  * the dst tokens of a block are those at positions floor(m*n/k), m = 0..k-1;
+    every other token is src and merges into its most similar dst (lowest m on
+    exact ties);
+  * means are taken over the raw (un-normalised) tokens; V uses K's matches;
+  * no size-weighted attention bias (Eq. 3 has none).
+
+Parity status: every function below is pinned by tests/test_oracle_*.py
+(brute force, closed forms, invariants).  The conventions above are readings,
+not statements of the paper, and are therefore "parity unpinned" against the
+paper's own (unpublished) code.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+
+import numpy as np
+
+EPS_NORM = 1e-12
+
+
+@dataclass(frozen=True)
+class Geometry:
+    """Token layout of one global-attention layer and the merging block shape."""
+    S: int              # frames
+    Hp: int             # patch rows per frame
+    Wp: int             # patch columns per frame
+    b: int              # spatial block edge (patches)
+    T: int              # temporal block length (frames)
+    n_special: int = 5  # special tokens at the front of each frame
+
+    @property
+    def tokens_per_frame(self) -> int:
+        return self.n_special + self.Hp * self.Wp
+
+    @property
+    def N(self) -> int:
+        return self.S * self.tokens_per_frame
+
+    @property
+    def n_prefix(self) -> int:
+        return self.S * self.n_special
+
+
+# --------------------------------------------------------------------------
+# Alg. 1, "TemporalReorder" / "Reorder" / "InverseReorder"   (Sec. 3.3)
+# --------------------------------------------------------------------------
+
+def token_index(g: Geometry, frame: int, slot: int) -> int:
+    """Position of (frame, slot) in the layer's input sequence."""
+    return frame * g.tokens_per_frame + slot
+
+
+def temporal_reorder(g: Geometry):
+    """Permutation pi and block list of the temporal reordering (Sec. 3.3).
+
+    pi[j] is the input position of the token that sits at reordered position
+    j.  `blocks` lists (start, n) in reordered coordinates: the same spatial
+    window of every frame of a temporal group, stacked.
+    """
+    pi = []
+    for f in range(g.S):
+        for s in range(g.n_special):
+            pi.append(token_index(g, f, s))
+    blocks = []
+    n_groups = -(-g.S // g.T)
+    n_by = -(-g.Hp // g.b)
+    n_bx = -(-g.Wp // g.b)
+    for grp in range(n_groups):
+        frames = range(grp * g.T, min(g.S, (grp + 1) * g.T))
+        for by in range(n_by):
+            rows = range(by * g.b, min(g.Hp, (by + 1) * g.b))
+            for bx in range(n_bx):
+                cols = range(bx * g.b, min(g.Wp, (bx + 1) * g.b))
+                start = len(pi)
+                for f in frames:
+                    for y in rows:
+                        for x in cols:
+                            pi.append(token_index(g, f, g.n_special + y * g.Wp + x))
+                blocks.append((start, len(pi) - start))
+    return np.asarray(pi, dtype=np.int64), blocks
+
+
+def reorder(x: np.ndarray, pi: np.ndarray) -> np.ndarray:
+    """x[..., L, E] -> rows gathered into block order: out[j] = x[pi[j]]."""
+    return np.take(x, pi, axis=-2)
+
+
+def inverse_reorder(xr: np.ndarray, pi: np.ndarray) -> np.ndarray:
+    """Undo `reorder`: out[pi[j]] = xr[j]."""
+    out = np.empty_like(xr)
+    out[..., pi, :] = xr
+    return out
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.2 "Merging" restricted to blocks (Sec. 3.3); Alg. 1 "BlockwiseToMe"
+# --------------------------------------------------------------------------
+
+def cluster_count(n: int, rho: float) -> int:
+    """Tokens a block of n keeps when a fraction rho is merged away (M = N - r)."""
+    r = int(math.floor(rho * n + 1e-9))
+    return max(1, n - r)
+
+
+def dst_positions(n: int, k: int) -> list:
+    """Block-local positions of the k dst tokens (evenly strided, first token included)."""
+    return [(m * n) // k for m in range(k)]
+
+
+def row_norm(x: np.ndarray) -> np.ndarray:
+    """RowNorm of Eq. 1: every row scaled to unit L2 norm (norm clamped at 1e-12)."""
+    nrm = np.sqrt(np.sum(x * x, axis=1, dtype=x.dtype))
+    return x / np.maximum(nrm, x.dtype.type(EPS_NORM))[:, None]
+
+
+def match_block(xb: np.ndarray, k: int):
+    """Bipartite matching inside one block (Eq. 1 and the best-match rule).
+
+    xb: [n, E] tokens of the block.  Returns
+      cluster[n]  cluster id m in 0..k-1 of every token (a dst is its own cluster),
+      score[n]    cosine similarity of a src to its best dst (1.0 for dst tokens),
+      gap[n]      best minus second-best similarity (inf for dst tokens / k = 1).
+    """
+    n = xb.shape[0]
+    dpos = dst_positions(n, k)
+    is_dst = np.zeros(n, dtype=bool)
+    is_dst[dpos] = True
+    spos = np.flatnonzero(~is_dst)
+    cluster = np.empty(n, dtype=np.int64)
+    score = np.ones(n, dtype=xb.dtype)
+    gap = np.full(n, np.inf, dtype=xb.dtype)
+    cluster[dpos] = np.arange(k)
+    if spos.size:
+        sim = row_norm(xb[spos]) @ row_norm(xb[dpos]).T           # Eq. 1, [n_src, n_dst]
+        best = np.argmax(sim, axis=1)                            # first maximum = lowest m
+        cluster[spos] = best
+        score[spos] = sim[np.arange(spos.size), best]
+        if k > 1:
+            rest = sim.copy()
+            rest[np.arange(spos.size), best] = -np.inf
+            gap[spos] = score[spos] - rest.max(axis=1)
+    return cluster, score, gap
+
+
+def merged_layout(g: Geometry, blocks, rho: float):
+    """Per block: number of clusters k_b and the first merged slot of the block.
+
+    The merged sequence is [all specials] ++ [clusters of block 0] ++ ...
+    Returns (k_list, offset_list, M).
+    """
+    ks, offs = [], []
+    pos = g.n_prefix
+    for (_, n) in blocks:
+        k = cluster_count(n, rho)
+        ks.append(k)
+        offs.append(pos)
+        pos += k
+    return ks, offs, pos
+
+
+def blockwise_tome(xr: np.ndarray, g: Geometry, blocks, rho: float):
+    """Cluster assignment of one head's reordered tokens (Alg. 1, "BlockwiseToMe").
+
+    xr: [L, E] reordered tokens of one head.  Returns
+      assign[L]  slot of every reordered token in this head's merged sequence,
+      score[L], gap[L]  as in match_block (specials: 1.0 / inf).
+    """
+    L = xr.shape[0]
+    ks, offs, _ = merged_layout(g, blocks, rho)
+    assign = np.empty(L, dtype=np.int64)
+    score = np.ones(L, dtype=xr.dtype)
+    gap = np.full(L, np.inf, dtype=xr.dtype)
+    assign[:g.n_prefix] = np.arange(g.n_prefix)        # specials pass through
+    for (start, n), k, off in zip(blocks, ks, offs):
+        c, s, gp = match_block(xr[start:start + n], k)
+        assign[start:start + n] = off + c
+        score[start:start + n] = s
+        gap[start:start + n] = gp
+    return assign, score, gap
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.2: merged token = mean of its constituents; Alg. 1 "BlockAggregate"
+# --------------------------------------------------------------------------
+
+def block_aggregate(xr: np.ndarray, assign: np.ndarray, g: Geometry, blocks, rho: float) -> np.ndarray:
+    """Merged tokens [M, E] of one head: mean of the dst and of every src assigned to it.
+
+    Summation order is fixed: the dst token first, then its src tokens in
+    ascending reordered position.
+    """
+    ks, offs, M = merged_layout(g, blocks, rho)
+    out = np.zeros((M, xr.shape[1]), dtype=xr.dtype)
+    count = np.zeros(M, dtype=np.int64)
+    out[:g.n_prefix] = xr[:g.n_prefix]
+    count[:g.n_prefix] = 1
+    for (start, n), k, off in zip(blocks, ks, offs):
+        dpos = dst_positions(n, k)
+        dset = set(dpos)
+        for m, j in enumerate(dpos):
+            out[off + m] = xr[start + j]
+            count[off + m] = 1
+        for j in range(n):
+            if j in dset:
+                continue
+            slot = assign[start + j]
+            out[slot] += xr[start + j]
+            count[slot] += 1
+    return out / count[:, None].astype(xr.dtype)
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.2 Eq. 3-4: attention over the reduced sequences
+# --------------------------------------------------------------------------
+
+def attention(qm: np.ndarray, km: np.ndarray, vm: np.ndarray, rows=None, chunk: int = 2048) -> np.ndarray:
+    """softmax(qm km^T / sqrt(E)) vm for one head.
+
+    `rows` selects query rows (rows are independent, so a subset is exact);
+    queries are processed `chunk` rows at a time only to bound memory.
+    """
+    dt = qm.dtype
+    if rows is not None:
+        qm = qm[rows]
+    scale = dt.type(1.0 / math.sqrt(qm.shape[1]))
+    out = np.empty((qm.shape[0], vm.shape[1]), dtype=dt)
+    for r0 in range(0, qm.shape[0], chunk):
+        logits = (qm[r0:r0 + chunk] @ km.T) * scale
+        logits = logits - logits.max(axis=1, keepdims=True)
+        p = np.exp(logits)
+        p = p / p.sum(axis=1, keepdims=True)
+        out[r0:r0 + chunk] = p @ vm
+    return out
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.2 Eq. 5: unmerge
+# --------------------------------------------------------------------------
+
+def unmerge_by_cluster(om: np.ndarray, assign_q: np.ndarray) -> np.ndarray:
+    """Every reordered token copies the output row of the merged query it belongs to."""
+    return om[assign_q]
+
+
+# --------------------------------------------------------------------------
+# Head-uniform comparison variant (Sec. 2.3 / Sec. 3.2: one topology for all heads)
+# --------------------------------------------------------------------------
+
+def head_mean(x: np.ndarray) -> np.ndarray:
+    """Metric token of the head-uniform variant: mean over heads, summed in head order."""
+    acc = x[0].copy()
+    for h in range(1, x.shape[0]):
+        acc = acc + x[h]
+    return acc / x.dtype.type(x.shape[0])
+
+
+# --------------------------------------------------------------------------
+# Alg. 1 end to end (outlier filter and the two projections left out)
+# --------------------------------------------------------------------------
+
+def layer_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray, g: Geometry,
+                  rho_q: float, rho_kv: float, variant: str = "headwise",
+                  heads=None, dtype=np.float32):
+    """Q, K, V [H, N, E] -> dict with O [N, len(heads)*E] and every intermediate.
+
+    variant: "headwise" (the paper's method), "uniform" (one matching for all
+    heads, from head-averaged tokens), or "none" (no merging).
+    `heads` restricts the computation to a subset of heads (heads are
+    independent except for the uniform variant's averaged metric, which always
+    uses all heads).
+    """
+    H, N, E = q.shape
+    assert N == g.N
+    heads = list(range(H)) if heads is None else list(heads)
+    q = q.astype(dtype, copy=False)
+    k = k.astype(dtype, copy=False)
+    v = v.astype(dtype, copy=False)
+    pi, blocks = temporal_reorder(g)
+    if variant == "none":
+        rho_q = rho_kv = 0.0
+    if variant == "uniform":
+        uq = blockwise_tome(reorder(head_mean(q), pi), g, blocks, rho_q)
+        uk = blockwise_tome(reorder(head_mean(k), pi), g, blocks, rho_kv)
+    res = {"pi": pi, "blocks": blocks, "assign_q": [], "assign_k": [], "gap_q": [], "gap_k": [],
+           "score_q": [], "score_k": [], "q_m": [], "k_m": [], "v_m": [], "o_m": []}
+    cols = []
+    for h in heads:
+        qr, kr, vr = reorder(q[h], pi), reorder(k[h], pi), reorder(v[h], pi)
+        if variant == "uniform":
+            (aq, sq, gq), (ak, sk, gk) = uq, uk
+        else:
+            aq, sq, gq = blockwise_tome(qr, g, blocks, rho_q)
+            ak, sk, gk = blockwise_tome(kr, g, blocks, rho_kv)
+        qm = block_aggregate(qr, aq, g, blocks, rho_q)
+        km = block_aggregate(kr, ak, g, blocks, rho_kv)
+        vm = block_aggregate(vr, ak, g, blocks, rho_kv)
+        om = attention(qm, km, vm)
+        o = inverse_reorder(unmerge_by_cluster(om, aq), pi)
+        cols.append(o)
+        for key, val in (("assign_q", aq), ("assign_k", ak), ("gap_q", gq), ("gap_k", gk),
+                         ("score_q", sq), ("score_k", sk), ("q_m", qm), ("k_m", km),
+                         ("v_m", vm), ("o_m", om)):
+            res[key].append(val)
+    res["O"] = np.concatenate(cols, axis=1)           # Eq. 7: heads side by side on channels
+    res["heads"] = heads
+    return res
+
+
+def rep_map(assign: np.ndarray, pi: np.ndarray, g: Geometry, blocks, rho: float) -> np.ndarray:
+    """Layout-independent form of an assignment: for every INPUT position i, the input
+    position of the dst token (or itself, for specials) that token i was merged into."""
+    ks, offs, M = merged_layout(g, blocks, rho)
+    slot_owner = np.empty(M, dtype=np.int64)
+    slot_owner[:g.n_prefix] = pi[:g.n_prefix]
+    for (start, n), k, off in zip(blocks, ks, offs):
+        for m, j in enumerate(dst_positions(n, k)):
+            slot_owner[off + m] = pi[start + j]
+    rep = np.empty(g.N, dtype=np.int64)
+    rep[pi] = slot_owner[assign]
+    return rep

@@ -1,0 +1,145 @@
+"""Brute force on tiny inputs: a literal pure-Python float64 re-statement of the layer,
+built from the paper's definitions with none of the oracle's code, must agree with the oracle.
+
+The brute force works in INPUT coordinates throughout (it never reorders anything): blocks are
+sets of tokens, a src token merges into the most similar dst token of its block (Eq. 1), merged
+tokens are means (Sec. 3.2), attention is Eq. 3-4 over the set of merged tokens, and each input
+token reads the output of the merged token that contains it (Eq. 5)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import httm_oracle as orc
+
+
+def _dot(a, b):
+    return math.fsum(x * y for x, y in zip(a, b))
+
+
+def _cos(a, b):
+    return _dot(a, b) / (max(math.sqrt(_dot(a, a)), 1e-12) * max(math.sqrt(_dot(b, b)), 1e-12))
+
+
+def _blocks_bruteforce(S, Hp, Wp, b, T, n_special):
+    """Token sets per block, each listed in (frame, row, col) order, blocks in (group,by,bx) order."""
+    tpf = n_special + Hp * Wp
+    groups = {}
+    for f in range(S):
+        for y in range(Hp):
+            for x in range(Wp):
+                groups.setdefault((f // T, y // b, x // b), []).append(f * tpf + n_special + y * Wp + x)
+    specials = [f * tpf + s for f in range(S) for s in range(n_special)]
+    return specials, [groups[key] for key in sorted(groups)]
+
+
+def _merge_head(x, specials, blocks, rho):
+    """x: list of N vectors.  Returns (clusters, owner): clusters = list of member lists (input
+    indices, dst first), in merged order; owner[i] = index into clusters for input token i."""
+    clusters = [[i] for i in specials]
+    owner = {i: c for c, i in enumerate(specials)}
+    for toks in blocks:
+        n = len(toks)
+        k = max(1, n - int(math.floor(rho * n + 1e-9)))
+        dpos = [(m * n) // k for m in range(k)]
+        base = len(clusters)
+        for m, p in enumerate(dpos):
+            clusters.append([toks[p]])
+            owner[toks[p]] = base + m
+        for p, i in enumerate(toks):
+            if p in dpos:
+                continue
+            best_m, best_s = 0, -float("inf")
+            for m, dp in enumerate(dpos):
+                s = _cos(x[i], x[toks[dp]])
+                if s > best_s:                       # strict: lowest m wins exact ties
+                    best_m, best_s = m, s
+            clusters[base + best_m].append(i)
+            owner[i] = base + best_m
+    return clusters, owner
+
+
+def _mean(vectors):
+    E = len(vectors[0])
+    return [math.fsum(v[c] for v in vectors) / len(vectors) for c in range(E)]
+
+
+def _layer_bruteforce(q, k, v, S, Hp, Wp, b, T, n_special, rho_q, rho_kv):
+    H, N, E = q.shape
+    specials, blocks = _blocks_bruteforce(S, Hp, Wp, b, T, n_special)
+    out = np.zeros((N, H * E))
+    owners_q, owners_k = [], []
+    for h in range(H):
+        qh, kh, vh = q[h].tolist(), k[h].tolist(), v[h].tolist()
+        cq, own_q = _merge_head(qh, specials, blocks, rho_q)
+        ck, own_k = _merge_head(kh, specials, blocks, rho_kv)
+        qm = [_mean([qh[i] for i in mem]) for mem in cq]
+        km = [_mean([kh[i] for i in mem]) for mem in ck]
+        vm = [_mean([vh[i] for i in mem]) for mem in ck]      # V follows K's matches
+        om = []
+        for qrow in qm:
+            logit = [_dot(qrow, krow) / math.sqrt(E) for krow in km]
+            mx = max(logit)
+            w = [math.exp(l - mx) for l in logit]
+            z = math.fsum(w)
+            om.append([math.fsum(wj * vrow[c] for wj, vrow in zip(w, vm)) / z for c in range(E)])
+        for i in range(N):
+            out[i, h * E:(h + 1) * E] = om[own_q[i]]
+        owners_q.append([cq[own_q[i]][0] for i in range(N)])   # representative = the dst token
+        owners_k.append([ck[own_k[i]][0] for i in range(N)])
+    return out, np.array(owners_q), np.array(owners_k)
+
+
+CASES = [
+    # S, Hp, Wp, b, T, n_special, rho_q, rho_kv
+    (3, 3, 4, 2, 2, 5, 0.5, 0.5),
+    (2, 4, 4, 2, 2, 5, 0.75, 0.5),
+    (4, 3, 3, 2, 3, 1, 0.6, 0.8),
+    (2, 5, 2, 4, 1, 0, 0.5, 0.0),
+    (3, 2, 6, 3, 4, 2, 0.9, 0.34),
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_oracle_equals_bruteforce(case, dtype):
+    S, Hp, Wp, b, T, nsp, rho_q, rho_kv = case
+    g = orc.Geometry(S, Hp, Wp, b, T, n_special=nsp)
+    H, E = 2, 8
+    rng = np.random.default_rng(1234 + S * 100 + Hp * 10 + Wp)
+    q, k, v = (rng.standard_normal((H, g.N, E)) for _ in range(3))
+    ref_out, ref_rep_q, ref_rep_k = _layer_bruteforce(q, k, v, S, Hp, Wp, b, T, nsp, rho_q, rho_kv)
+
+    res = orc.layer_forward(q, k, v, g, rho_q, rho_kv, dtype=dtype)
+    pi, blocks = res["pi"], res["blocks"]
+    for h in range(H):
+        assert np.array_equal(orc.rep_map(res["assign_q"][h], pi, g, blocks, rho_q), ref_rep_q[h])
+        assert np.array_equal(orc.rep_map(res["assign_k"][h], pi, g, blocks, rho_kv), ref_rep_k[h])
+    tol = 1e-5 if dtype == np.float32 else 1e-12
+    assert np.abs(res["O"] - ref_out).max() < tol
+
+
+def test_bruteforce_catches_a_transposed_or_dropped_term():
+    """The pin is sensitive: planting typical mistakes in a copy of the oracle's steps changes O."""
+    g = orc.Geometry(2, 4, 4, 2, 2)
+    rng = np.random.default_rng(7)
+    q, k, v = (rng.standard_normal((2, g.N, 8)) for _ in range(3))
+    ref_out, _, _ = _layer_bruteforce(q, k, v, 2, 4, 4, 2, 2, 5, 0.5, 0.5)
+    good = orc.layer_forward(q, k, v, g, 0.5, 0.5, dtype=np.float64)["O"]
+    assert np.abs(good - ref_out).max() < 1e-12
+    # V merged with its own matches instead of K's -> must differ
+    pi, blocks = orc.temporal_reorder(g)
+    h = 0
+    qr, kr, vr = (orc.reorder(t[h], pi) for t in (q, k, v))
+    aq, _, _ = orc.blockwise_tome(qr, g, blocks, 0.5)
+    ak, _, _ = orc.blockwise_tome(kr, g, blocks, 0.5)
+    av, _, _ = orc.blockwise_tome(vr, g, blocks, 0.5)
+    qm = orc.block_aggregate(qr, aq, g, blocks, 0.5)
+    km = orc.block_aggregate(kr, ak, g, blocks, 0.5)
+    vm_wrong = orc.block_aggregate(vr, av, g, blocks, 0.5)
+    o_wrong = orc.inverse_reorder(orc.unmerge_by_cluster(orc.attention(qm, km, vm_wrong), aq), pi)
+    assert np.abs(o_wrong - ref_out[:, :8]).max() > 1e-3
+    # unmerging with K's assignment instead of Q's -> must differ
+    vm = orc.block_aggregate(vr, ak, g, blocks, 0.5)
+    o_wrong2 = orc.inverse_reorder(orc.unmerge_by_cluster(orc.attention(qm, km, vm), ak), pi)
+    assert np.abs(o_wrong2 - ref_out[:, :8]).max() > 1e-3
