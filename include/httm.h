@@ -1,0 +1,215 @@
+/*
+ * libhttm - HTTM (Head-wise Temporal Token Merging, arXiv 2511.21317) global-attention
+ * layer for AMD MI355X (gfx950).  C ABI.
+ *
+ * The library computes the hot path of the paper's Algorithm 1 (App. D.1) between the QKV
+ * projection and the output projection, without the outlier filter:
+ *
+ *   temporal reorder -> block-wise matching -> aggregation -> attention -> unmerge -> inverse reorder
+ *
+ * Conventions common to every call
+ *   - All tensor pointers are DEVICE pointers unless a parameter says "host".  Tensors are
+ *     dense, row-major, 16-byte aligned, bf16 (bfloat16) unless stated otherwise.
+ *   - The caller owns every tensor and the workspace.  The library owns only the plan and the
+ *     small device index tables inside it (allocated in httm_plan_create, freed in
+ *     httm_plan_destroy).  No other call allocates, frees or synchronises.
+ *   - Every compute call is asynchronous on the HIP stream passed as `stream`
+ *     (a hipStream_t cast to void*; NULL is the default stream).
+ *   - Inputs are never modified.  In-place operation is not supported.
+ *   - Return value: 0 (HTTM_OK) on success, a negative HTTM_E_* code otherwise.  Nothing
+ *     aborts or throws across this boundary.  Argument checks happen on the host before
+ *     any kernel is launched; a call that returns an error has launched nothing.
+ *
+ * Token layout (Sec. 3.2-3.3 of the paper; the frame layout follows VGGT):
+ *   N = S * (n_special + Hp*Wp) tokens.  Token i = frame * (n_special + Hp*Wp) + slot;
+ *   slots 0..n_special-1 are special tokens, slot n_special + y*Wp + x is patch (row y, col x).
+ *   Per-head tensors are [H, N, d_head]; the layer output is [N, H*d_head].
+ *
+ * Reordered layout (Sec. 3.3, "Temporal Reordering"):
+ *   [ all S*n_special specials in (frame, slot) order ] ++ [ merging blocks ].
+ *   A merging block is a b x b window of patches stacked over T consecutive frames, blocks are
+ *   ordered (frame group, window row, window col), tokens inside a block (frame, row, col).
+ *   Windows at the right/bottom edge and the last frame group may be partial.
+ *
+ * Merged layout (Sec. 3.2, "Merging", restricted to blocks as in Sec. 3.3 / Alg. 1):
+ *   a block of n tokens keeps k = max(1, n - floor(rho*n + 1e-9)) clusters; its dst tokens are
+ *   the block positions floor(m*n/k), m = 0..k-1; every other token (src) joins the dst with
+ *   the highest cosine similarity (Eq. 1; lowest m on ties).  A merged token is the mean of
+ *   its constituents.  The merged sequence of a head is
+ *   [ specials, unmerged ] ++ [ the k clusters of block 0 ] ++ [ block 1 ] ...
+ *   with length M = S*n_special + sum of k.  Q and K are matched independently per head
+ *   (Eq. 2); V follows K's matches.
+ */
+#ifndef HTTM_H
+#define HTTM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HTTM_VERSION 100
+
+#if defined(__GNUC__)
+#define HTTM_API __attribute__((visibility("default")))
+#else
+#define HTTM_API
+#endif
+
+enum {
+  HTTM_OK = 0,
+  HTTM_E_INVALID_ARG = -1,        /* null pointer, misaligned pointer, non-positive size, bad enum */
+  HTTM_E_UNSUPPORTED = -2,        /* d_head != 64, block of more than HTTM_MAX_BLOCK tokens, H > HTTM_MAX_HEADS */
+  HTTM_E_WORKSPACE_TOO_SMALL = -3,
+  HTTM_E_HIP = -4,                /* a HIP runtime call failed; see httm_last_hip_error() */
+  HTTM_E_NO_DEVICE = -5           /* no usable GPU */
+};
+
+enum {
+  HTTM_VARIANT_HEADWISE = 0,      /* the paper's method: every head matches on its own tokens (Sec. 3.2) */
+  HTTM_VARIANT_UNIFORM = 1,       /* comparison: one matching for all heads, computed on the head-averaged
+                                     tokens (the "shared merge topology" the paper argues against, Sec. 3.2) */
+  HTTM_VARIANT_NONE = 2           /* no merging (rho ignored): plain multi-head attention, Eq. 3-4 with M = N */
+};
+
+#define HTTM_MAX_BLOCK 512        /* largest merging block (b*b*T tokens) the kernels accept */
+#define HTTM_MAX_HEADS 64
+
+/* Problem description.  Plain data, filled by the caller. */
+typedef struct httm_geom {
+  int32_t S;          /* frames */
+  int32_t Hp;         /* patch rows per frame */
+  int32_t Wp;         /* patch columns per frame */
+  int32_t n_special;  /* special tokens at the front of every frame (5 for VGGT); never merged */
+  int32_t H;          /* attention heads */
+  int32_t d_head;     /* channels per head; must be 64 */
+  int32_t b;          /* spatial block edge in patches (n_s = b*b) */
+  int32_t T;          /* temporal block length in frames (n_t) */
+  double rho_q;       /* fraction of each block's query tokens merged away, 0 <= rho < 1 or 1 */
+  double rho_kv;      /* the same for key/value tokens */
+  int32_t variant;    /* HTTM_VARIANT_* */
+  int32_t reserved;   /* must be 0 */
+} httm_geom_t;
+
+/* Sizes derived from a geometry. */
+typedef struct httm_sizes {
+  int64_t N;                /* tokens per head */
+  int64_t n_prefix;         /* S * n_special */
+  int64_t n_blocks;         /* merging blocks per head */
+  int64_t max_block;        /* tokens in the largest block */
+  int64_t M_q;              /* merged query length per head */
+  int64_t M_k;              /* merged key/value length per head */
+  int64_t workspace_bytes;  /* what httm_layer_forward needs */
+} httm_sizes_t;
+
+typedef struct httm_plan httm_plan_t;
+
+/* ---- host-only helpers (no GPU needed) --------------------------------------------- */
+
+HTTM_API int httm_version(void);
+HTTM_API const char* httm_strerror(int code);
+/* hipError_t of the most recent failing HIP call on this thread (0 if none). */
+HTTM_API int httm_last_hip_error(void);
+
+/* Fill *out from *g.  Host only. */
+HTTM_API int httm_geom_sizes(const httm_geom_t* g, httm_sizes_t* out);
+
+/* Write the index tables of a geometry into caller-provided HOST arrays (any may be NULL):
+ *   pi[N]            input position of the token at reordered position j   (Alg. 1, TemporalReorder)
+ *   block_start[n_blocks], block_n[n_blocks]   block extents in reordered coordinates
+ *   block_kq[n_blocks], block_kk[n_blocks]     clusters kept per block for Q and for K/V
+ *   block_offq[n_blocks], block_offk[n_blocks] first merged slot of the block, for Q and for K/V
+ */
+HTTM_API int httm_geom_tables(const httm_geom_t* g, int32_t* pi, int32_t* block_start, int32_t* block_n,
+                     int32_t* block_kq, int32_t* block_kk, int32_t* block_offq, int32_t* block_offk);
+
+/* ---- plan ---------------------------------------------------------------------------- */
+
+/* Build the index tables of *g on the current HIP device.  Allocates a few int32 per token of
+ * device memory (and, for HTTM_VARIANT_UNIFORM, 2*N*d_head floats for the head-averaged tokens).
+ * Synchronous.  The plan may be used by any number of later calls but not by two calls
+ * running concurrently when variant == HTTM_VARIANT_UNIFORM (they share the averaged-token
+ * buffer). */
+HTTM_API int httm_plan_create(const httm_geom_t* g, httm_plan_t** out);
+HTTM_API int httm_plan_destroy(httm_plan_t* plan);
+HTTM_API int httm_plan_query(const httm_plan_t* plan, httm_sizes_t* out);
+
+/* ---- stage 1: temporal reordering (Sec. 3.3; Alg. 1 "Reorder" / "InverseReorder") ----- */
+
+/* direction 0: dst[h][j] = src[h][pi[j]]      (gather into block order)
+ * direction 1: dst[h][pi[j]] = src[h][j]      (back to input order)
+ * src, dst: [H, N, d_head] bf16, distinct buffers. */
+HTTM_API int httm_reorder(const httm_plan_t* plan, const void* src, void* dst, int direction, void* stream);
+
+/* ---- stage 2: block-wise matching and aggregation (Sec. 3.2 Eq. 1-2; Alg. 1
+ *      "BlockwiseToMe" + "BlockAggregate") ------------------------------------------------- */
+
+/* q_r, k_r, v_r : [H, N, d_head] bf16, REORDERED layout (output of httm_reorder).
+ * q_m           : [H, M_q, d_head] bf16 out, merged queries.
+ * k_m, v_m      : [H, M_k, d_head] bf16 out, merged keys / values (V merged with K's matches).
+ * assign_q      : [H, N] int32 out; assign_q[h][j] = slot in 0..M_q-1 of reordered token j.
+ * assign_k      : [H, N] int32 out; the same for keys.
+ * score_q/k     : [H, N] float out or NULL; cosine similarity of token j to the dst it joined
+ *                 (1.0 for dst and special tokens).
+ * Similarities are fp32 sums of exact bf16 products; means are fp32 sums taken in a fixed
+ * order (dst first, then src in ascending position) and rounded once to bf16, so results are
+ * run-to-run identical. */
+HTTM_API int httm_match_merge(const httm_plan_t* plan, const void* q_r, const void* k_r, const void* v_r,
+                     void* q_m, void* k_m, void* v_m, int32_t* assign_q, int32_t* assign_k,
+                     float* score_q, float* score_k, void* stream);
+
+/* Stages 1 + 2 in one pass: the same computation on tensors in INPUT token order; the kernel
+ * gathers each block's rows through pi, so no reordered copy of Q/K/V is ever written.
+ * q, k, v : [H, N, d_head] bf16, input order.  Outputs exactly as httm_match_merge (assign_*
+ * and score_* are indexed by REORDERED position j), bit-identical to
+ * httm_reorder x3 followed by httm_match_merge. */
+HTTM_API int httm_reorder_match_merge(const httm_plan_t* plan, const void* q, const void* k, const void* v,
+                             void* q_m, void* k_m, void* v_m, int32_t* assign_q, int32_t* assign_k,
+                             float* score_q, float* score_k, void* stream);
+
+/* ---- stage 3: attention over the reduced sequences (Sec. 3.2 Eq. 3-4) ------------------- */
+
+/* o = softmax(q k^T * scale) v, per head, non-causal, no mask.
+ * Packed ragged layout: head h owns rows [q_offsets[h], q_offsets[h+1]) of q_m / o_m and rows
+ * [k_offsets[h], k_offsets[h+1]) of k_m / v_m.  q_offsets, k_offsets are HOST arrays of H+1
+ * non-decreasing int64 row indices (they are copied into the kernel arguments).
+ * A head with no keys writes zeros; a head with no queries writes nothing.
+ * d_head must be 64; H <= HTTM_MAX_HEADS.  bf16 in/out, fp32 softmax state and accumulation. */
+HTTM_API int httm_attention(const void* q_m, const void* k_m, const void* v_m, void* o_m,
+                   const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
+                   float scale, void* stream);
+
+/* ---- stage 4: unmerge (Sec. 3.2 Eq. 5-7) and inverse reorder (Sec. 3.3) ------------------ */
+
+/* o_m      : [H, M_q, d_head] bf16, attention output per merged query.
+ * assign_q : [H, N] int32 from httm_match_merge.
+ * fuse_inverse_reorder != 0:  out is [N, H*d_head] in INPUT token order, heads concatenated on
+ *     channels:  out[pi[j]][h*d_head + c] = o_m[h][assign_q[h][j]][c].
+ * fuse_inverse_reorder == 0:  out is [H, N, d_head] in REORDERED order:
+ *     out[h][j] = o_m[h][assign_q[h][j]]   (follow with httm_reorder(..., 1, ...)). */
+HTTM_API int httm_unmerge(const httm_plan_t* plan, const void* o_m, const int32_t* assign_q, void* out,
+                 int fuse_inverse_reorder, void* stream);
+
+/* ---- the whole layer (Alg. 1 without projections and outlier filter) --------------------- */
+
+/* q, k, v : [H, N, d_head] bf16 in INPUT token order.  out : [N, H*d_head] bf16.
+ * workspace: at least httm_sizes_t.workspace_bytes bytes, 256-byte aligned.  After the call it
+ * holds, in this order (each 256-byte aligned): q_m, k_m, v_m, o_m ([H, M, d_head] bf16),
+ * assign_q, assign_k ([H, N] int32) - see httm_workspace_layout.
+ * The reorder is fused into the matching kernel's loads and the inverse reorder into the
+ * unmerge kernel's stores; results are identical to calling the four stages one by one. */
+HTTM_API int httm_layer_forward(const httm_plan_t* plan, const void* q, const void* k, const void* v,
+                       void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Byte offsets of the six regions inside the workspace (host only). */
+typedef struct httm_workspace_layout {
+  int64_t q_m, k_m, v_m, o_m, assign_q, assign_k, total;
+} httm_workspace_layout_t;
+HTTM_API int httm_workspace_layout(const httm_geom_t* g, httm_workspace_layout_t* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HTTM_H */

@@ -1,0 +1,243 @@
+"""ctypes binding of libhttm.so.  Argument marshalling only: every step of the path runs in
+the HIP kernels behind the C ABI declared in include/httm.h.  torch is used for device memory
+and the current stream, nothing else.  There is no CPU fallback: if the library is missing or
+a call fails, an exception is raised."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG_DIR, "libhttm.so")
+
+VARIANT_HEADWISE, VARIANT_UNIFORM, VARIANT_NONE = 0, 1, 2
+VARIANTS = {"headwise": VARIANT_HEADWISE, "uniform": VARIANT_UNIFORM, "none": VARIANT_NONE}
+MAX_BLOCK = 512
+MAX_HEADS = 64
+
+
+class HttmError(RuntimeError):
+    pass
+
+
+class Geom(C.Structure):
+    _fields_ = [("S", C.c_int32), ("Hp", C.c_int32), ("Wp", C.c_int32), ("n_special", C.c_int32),
+                ("H", C.c_int32), ("d_head", C.c_int32), ("b", C.c_int32), ("T", C.c_int32),
+                ("rho_q", C.c_double), ("rho_kv", C.c_double), ("variant", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+class Sizes(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in
+                ("N", "n_prefix", "n_blocks", "max_block", "M_q", "M_k", "workspace_bytes")]
+
+
+class WorkspaceLayout(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("q_m", "k_m", "v_m", "o_m", "assign_q", "assign_k", "total")]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libhttm.so (built in-tree by paper_2511_21317_amd.build) or raise."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise HttmError(f"{LIB_PATH} is missing: run `python -m paper_2511_21317_amd.build` "
+                        "(or __graft_entry__.build()) first; there is no fallback path")
+    L = C.CDLL(LIB_PATH)
+    vp, i32p, i64p, f32p = C.c_void_p, C.c_void_p, C.POINTER(C.c_int64), C.c_void_p
+    L.httm_version.restype = C.c_int
+    L.httm_strerror.restype = C.c_char_p
+    L.httm_strerror.argtypes = [C.c_int]
+    L.httm_last_hip_error.restype = C.c_int
+    L.httm_geom_sizes.argtypes = [C.POINTER(Geom), C.POINTER(Sizes)]
+    L.httm_workspace_layout.argtypes = [C.POINTER(Geom), C.POINTER(WorkspaceLayout)]
+    L.httm_geom_tables.argtypes = [C.POINTER(Geom)] + [vp] * 7
+    L.httm_plan_create.argtypes = [C.POINTER(Geom), C.POINTER(vp)]
+    L.httm_plan_destroy.argtypes = [vp]
+    L.httm_plan_query.argtypes = [vp, C.POINTER(Sizes)]
+    L.httm_reorder.argtypes = [vp, vp, vp, C.c_int, vp]
+    L.httm_match_merge.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, i32p, f32p, f32p, vp]
+    L.httm_reorder_match_merge.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, i32p, f32p, f32p, vp]
+    L.httm_attention.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, C.c_float, vp]
+    L.httm_unmerge.argtypes = [vp, vp, i32p, vp, C.c_int, vp]
+    L.httm_layer_forward.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    for name in ("httm_geom_sizes", "httm_workspace_layout", "httm_geom_tables", "httm_plan_create",
+                 "httm_plan_destroy", "httm_plan_query", "httm_reorder", "httm_match_merge",
+                 "httm_reorder_match_merge",
+                 "httm_attention", "httm_unmerge", "httm_layer_forward"):
+        getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        L = lib()
+        msg = L.httm_strerror(rc).decode()
+        extra = f" (hipError_t {L.httm_last_hip_error()})" if rc == -4 else ""
+        raise HttmError(f"{what} failed: {msg}{extra} [code {rc}]")
+
+
+def make_geom(S, Hp, Wp, b, T, rho_q, rho_kv=None, *, H=16, d_head=64, n_special=5,
+              variant="headwise") -> Geom:
+    if rho_kv is None:
+        rho_kv = rho_q
+    v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
+    return Geom(S, Hp, Wp, n_special, H, d_head, b, T, float(rho_q), float(rho_kv), v, 0)
+
+
+def geom_sizes(g: Geom) -> Sizes:
+    s = Sizes()
+    _check(lib().httm_geom_sizes(C.byref(g), C.byref(s)), "httm_geom_sizes")
+    return s
+
+
+def workspace_layout(g: Geom) -> WorkspaceLayout:
+    w = WorkspaceLayout()
+    _check(lib().httm_workspace_layout(C.byref(g), C.byref(w)), "httm_workspace_layout")
+    return w
+
+
+def geom_tables(g: Geom) -> dict:
+    """Host index tables of a geometry as int32 NumPy arrays (no GPU needed)."""
+    s = geom_sizes(g)
+    out = {"pi": np.empty(s.N, np.int32)}
+    for name in ("block_start", "block_n", "block_kq", "block_kk", "block_offq", "block_offk"):
+        out[name] = np.empty(s.n_blocks, np.int32)
+    ptr = lambda a: a.ctypes.data_as(C.c_void_p)  # noqa: E731
+    _check(lib().httm_geom_tables(C.byref(g), ptr(out["pi"]), ptr(out["block_start"]),
+                                  ptr(out["block_n"]), ptr(out["block_kq"]), ptr(out["block_kk"]),
+                                  ptr(out["block_offq"]), ptr(out["block_offk"])), "httm_geom_tables")
+    return out
+
+
+def _stream() -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, shape=None) -> C.c_void_p:
+    if not t.is_cuda:
+        raise HttmError("tensor must live on the GPU")
+    if t.dtype != dtype:
+        raise HttmError(f"expected dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise HttmError("tensor must be contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise HttmError(f"expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    return C.c_void_p(t.data_ptr())
+
+
+class Plan:
+    """Owns an httm_plan_t (device index tables of one geometry)."""
+
+    def __init__(self, g: Geom):
+        self.geom = g
+        self._h = C.c_void_p()
+        _check(lib().httm_plan_create(C.byref(g), C.byref(self._h)), "httm_plan_create")
+        self.sizes = Sizes()
+        _check(lib().httm_plan_query(self._h, C.byref(self.sizes)), "httm_plan_query")
+        self.layout = workspace_layout(g)
+
+    def close(self):
+        if self._h:
+            lib().httm_plan_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # convenience
+    @property
+    def N(self): return int(self.sizes.N)
+    @property
+    def M_q(self): return int(self.sizes.M_q)
+    @property
+    def M_k(self): return int(self.sizes.M_k)
+    @property
+    def H(self): return int(self.geom.H)
+
+
+def reorder(plan: Plan, src: torch.Tensor, dst: torch.Tensor, direction: int = 0):
+    shape = (plan.H, plan.N, 64)
+    _check(lib().httm_reorder(plan._h, _dev(src, torch.bfloat16, shape), _dev(dst, torch.bfloat16, shape),
+                              int(direction), _stream()), "httm_reorder")
+    return dst
+
+
+def match_merge(plan: Plan, q_r, k_r, v_r, q_m, k_m, v_m, assign_q, assign_k, score_q=None, score_k=None):
+    H, N = plan.H, plan.N
+    bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+    _check(lib().httm_match_merge(
+        plan._h, _dev(q_r, bf, (H, N, 64)), _dev(k_r, bf, (H, N, 64)), _dev(v_r, bf, (H, N, 64)),
+        _dev(q_m, bf, (H, plan.M_q, 64)), _dev(k_m, bf, (H, plan.M_k, 64)), _dev(v_m, bf, (H, plan.M_k, 64)),
+        _dev(assign_q, i32, (H, N)), _dev(assign_k, i32, (H, N)),
+        _dev(score_q, f32, (H, N)) if score_q is not None else None,
+        _dev(score_k, f32, (H, N)) if score_k is not None else None, _stream()), "httm_match_merge")
+
+
+def reorder_match_merge(plan: Plan, q, k, v, q_m, k_m, v_m, assign_q, assign_k, score_q=None, score_k=None):
+    H, N = plan.H, plan.N
+    bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+    _check(lib().httm_reorder_match_merge(
+        plan._h, _dev(q, bf, (H, N, 64)), _dev(k, bf, (H, N, 64)), _dev(v, bf, (H, N, 64)),
+        _dev(q_m, bf, (H, plan.M_q, 64)), _dev(k_m, bf, (H, plan.M_k, 64)), _dev(v_m, bf, (H, plan.M_k, 64)),
+        _dev(assign_q, i32, (H, N)), _dev(assign_k, i32, (H, N)),
+        _dev(score_q, f32, (H, N)) if score_q is not None else None,
+        _dev(score_k, f32, (H, N)) if score_k is not None else None, _stream()), "httm_reorder_match_merge")
+
+
+def attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, scale: float = 0.125):
+    """q_m/o_m: [sum M_q, 64] (or [H, M, 64]) bf16; offsets: sequences of H+1 row indices (host)."""
+    H = len(q_offsets) - 1
+    qo = (C.c_int64 * (H + 1))(*[int(x) for x in q_offsets])
+    ko = (C.c_int64 * (H + 1))(*[int(x) for x in k_offsets])
+    bf = torch.bfloat16
+    _check(lib().httm_attention(_dev(q_m, bf), _dev(k_m, bf), _dev(v_m, bf), _dev(o_m, bf), qo, ko,
+                                H, 64, float(scale), _stream()), "httm_attention")
+    return o_m
+
+
+def unmerge(plan: Plan, o_m, assign_q, out, fuse_inverse_reorder: bool = True):
+    H, N = plan.H, plan.N
+    shape = (N, H * 64) if fuse_inverse_reorder else (H, N, 64)
+    _check(lib().httm_unmerge(plan._h, _dev(o_m, torch.bfloat16, (H, plan.M_q, 64)),
+                              _dev(assign_q, torch.int32, (H, N)), _dev(out, torch.bfloat16, shape),
+                              1 if fuse_inverse_reorder else 0, _stream()), "httm_unmerge")
+    return out
+
+
+def layer_forward(plan: Plan, q, k, v, out, workspace):
+    H, N = plan.H, plan.N
+    bf = torch.bfloat16
+    if workspace.dtype != torch.uint8:
+        raise HttmError("workspace must be a uint8 tensor")
+    _check(lib().httm_layer_forward(plan._h, _dev(q, bf, (H, N, 64)), _dev(k, bf, (H, N, 64)),
+                                    _dev(v, bf, (H, N, 64)), _dev(out, bf, (N, H * 64)),
+                                    _dev(workspace, torch.uint8), workspace.numel(), _stream()),
+           "httm_layer_forward")
+    return out
+
+
+def workspace_views(plan: Plan, workspace: torch.Tensor) -> dict:
+    """Typed views of the six regions httm_layer_forward leaves in the workspace."""
+    L, H, N = plan.layout, plan.H, plan.N
+    def bf(off, rows):
+        return workspace[off:off + H * rows * 128].view(torch.bfloat16).view(H, rows, 64)
+    def i32(off):
+        return workspace[off:off + H * N * 4].view(torch.int32).view(H, N)
+    return {"q_m": bf(L.q_m, plan.M_q), "k_m": bf(L.k_m, plan.M_k), "v_m": bf(L.v_m, plan.M_k),
+            "o_m": bf(L.o_m, plan.M_q), "assign_q": i32(L.assign_q), "assign_k": i32(L.assign_k)}
+
+
+def alloc_workspace(plan: Plan) -> torch.Tensor:
+    return torch.empty(int(plan.sizes.workspace_bytes), dtype=torch.uint8, device="cuda")

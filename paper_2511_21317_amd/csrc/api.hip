@@ -1,0 +1,296 @@
+// C-ABI layer of libhttm: argument checks, the plan object, and the stage sequencing of
+// httm_layer_forward.  See include/httm.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+
+#include "../../include/httm.h"
+#include "geometry.hpp"
+#include "kernels.hpp"
+
+using namespace httm;
+
+struct httm_plan {
+  httm_geom_t geom;
+  httm_sizes_t sizes;
+  httm_workspace_layout_t ws;
+  int device = -1;
+  int32_t* d_pi = nullptr;
+  WorkItem* d_items_q = nullptr;
+  WorkItem* d_items_k = nullptr;
+  int32_t n_items = 0;
+  // head-uniform variant only
+  float* d_mean = nullptr;    // [2][N][64] fp32: head-averaged Q then K
+  int32_t* d_slot = nullptr;  // [2][N] shared cluster slot of every reordered token
+  float* d_uscore = nullptr;  // [2][N]
+};
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+  g_last_hip_error = (int)e;
+  return HTTM_E_HIP;
+}
+
+#define HTTM_HIP(call)                         \
+  do {                                         \
+    hipError_t e_ = (call);                    \
+    if (e_ != hipSuccess) return hip_fail(e_); \
+  } while (0)
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+void fill_sizes(const httm_geom_t& g, const HostTables& t, httm_sizes_t* s,
+                httm_workspace_layout_t* ws) {
+  s->N = t.N;
+  s->n_prefix = t.n_prefix;
+  s->n_blocks = t.n_blocks;
+  s->max_block = t.max_block;
+  s->M_q = t.M_q;
+  s->M_k = t.M_k;
+  httm_workspace_layout_t l;
+  workspace_layout(g, t, &l);
+  s->workspace_bytes = l.total;
+  if (ws) *ws = l;
+}
+
+template <typename T>
+int upload(const std::vector<T>& host, T** dev) {
+  *dev = nullptr;
+  if (host.empty()) return HTTM_OK;
+  HTTM_HIP(hipMalloc((void**)dev, host.size() * sizeof(T)));
+  HTTM_HIP(hipMemcpy(*dev, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice));
+  return HTTM_OK;
+}
+
+// Matching + aggregation on `q,k,v`, which are in input order when `pi` is given and in
+// reordered order when it is nullptr.
+int run_match_merge(const httm_plan_t* p, const int32_t* pi, const void* q, const void* k,
+                    const void* v, void* q_m, void* k_m, void* v_m, int32_t* assign_q,
+                    int32_t* assign_k, float* score_q, float* score_k, hipStream_t st) {
+  const httm_geom_t& g = p->geom;
+  MatchMergeArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.n_streams = 2;
+  a.pi = pi;
+  a.N = p->sizes.N;
+  a.H = g.H;
+  a.max_block = (int32_t)(p->sizes.max_block < kPrefixChunk ? kPrefixChunk : p->sizes.max_block);
+  a.s[0] = {q, nullptr, q_m, nullptr, assign_q, score_q, p->d_items_q, p->n_items, p->sizes.M_q,
+            nullptr, nullptr};
+  a.s[1] = {k, v, k_m, v_m, assign_k, score_k, p->d_items_k, p->n_items, p->sizes.M_k, nullptr,
+            nullptr};
+  if (g.variant == HTTM_VARIANT_UNIFORM) {
+    const int64_t N = p->sizes.N;
+    const void* src[2] = {q, k};
+    const WorkItem* items[2] = {p->d_items_q, p->d_items_k};
+    for (int t = 0; t < 2; ++t) {
+      float* mean = p->d_mean + (int64_t)t * N * 64;
+      HTTM_HIP(launch_head_mean(src[t], mean, g.H, N, st));
+      HTTM_HIP(launch_match_f32(mean, pi, items[t], p->n_items, a.max_block, p->d_slot + t * N,
+                                p->d_uscore + t * N, st));
+      a.s[t].preset = p->d_slot + t * N;
+      a.s[t].preset_score = p->d_uscore + t * N;
+    }
+  }
+  HTTM_HIP(launch_match_merge(a, st));
+  return HTTM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int httm_version(void) { return HTTM_VERSION; }
+
+const char* httm_strerror(int code) {
+  switch (code) {
+    case HTTM_OK: return "success";
+    case HTTM_E_INVALID_ARG: return "invalid argument (null or misaligned pointer, bad size or enum)";
+    case HTTM_E_UNSUPPORTED: return "unsupported configuration (d_head != 64, block too large, too many heads)";
+    case HTTM_E_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case HTTM_E_HIP: return "HIP runtime error (see httm_last_hip_error)";
+    case HTTM_E_NO_DEVICE: return "no usable GPU";
+    default: return "unknown error code";
+  }
+}
+
+int httm_last_hip_error(void) { return g_last_hip_error; }
+
+int httm_geom_sizes(const httm_geom_t* g, httm_sizes_t* out) {
+  if (!g || !out) return HTTM_E_INVALID_ARG;
+  HostTables t;
+  const int rc = build_tables(*g, false, &t);
+  if (rc != HTTM_OK) return rc;
+  fill_sizes(*g, t, out, nullptr);
+  return HTTM_OK;
+}
+
+int httm_workspace_layout(const httm_geom_t* g, httm_workspace_layout_t* out) {
+  if (!g || !out) return HTTM_E_INVALID_ARG;
+  HostTables t;
+  const int rc = build_tables(*g, false, &t);
+  if (rc != HTTM_OK) return rc;
+  return workspace_layout(*g, t, out);
+}
+
+int httm_geom_tables(const httm_geom_t* g, int32_t* pi, int32_t* block_start, int32_t* block_n,
+                     int32_t* block_kq, int32_t* block_kk, int32_t* block_offq, int32_t* block_offk) {
+  if (!g) return HTTM_E_INVALID_ARG;
+  HostTables t;
+  const int rc = build_tables(*g, pi != nullptr, &t);
+  if (rc != HTTM_OK) return rc;
+  const size_t nb = (size_t)t.n_blocks * sizeof(int32_t);
+  if (pi) std::memcpy(pi, t.pi.data(), (size_t)t.N * sizeof(int32_t));
+  if (block_start) std::memcpy(block_start, t.block_start.data(), nb);
+  if (block_n) std::memcpy(block_n, t.block_n.data(), nb);
+  if (block_kq) std::memcpy(block_kq, t.block_kq.data(), nb);
+  if (block_kk) std::memcpy(block_kk, t.block_kk.data(), nb);
+  if (block_offq) std::memcpy(block_offq, t.block_offq.data(), nb);
+  if (block_offk) std::memcpy(block_offk, t.block_offk.data(), nb);
+  return HTTM_OK;
+}
+
+int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
+  if (!g || !out) return HTTM_E_INVALID_ARG;
+  *out = nullptr;
+  HostTables t;
+  int rc = build_tables(*g, true, &t);
+  if (rc != HTTM_OK) return rc;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev == 0) return HTTM_E_NO_DEVICE;
+  httm_plan_t* p = new (std::nothrow) httm_plan_t();
+  if (!p) return HTTM_E_INVALID_ARG;
+  p->geom = *g;
+  fill_sizes(*g, t, &p->sizes, &p->ws);
+  p->n_items = (int32_t)t.items_q.size();
+  hipError_t e = hipGetDevice(&p->device);
+  if (e != hipSuccess) {
+    delete p;
+    return hip_fail(e);
+  }
+  rc = upload(t.pi, &p->d_pi);
+  if (rc == HTTM_OK) rc = upload(t.items_q, &p->d_items_q);
+  if (rc == HTTM_OK) rc = upload(t.items_k, &p->d_items_k);
+  if (rc == HTTM_OK && g->variant == HTTM_VARIANT_UNIFORM) {
+    e = hipMalloc((void**)&p->d_mean, (size_t)2 * t.N * 64 * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void**)&p->d_slot, (size_t)2 * t.N * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void**)&p->d_uscore, (size_t)2 * t.N * sizeof(float));
+    if (e != hipSuccess) rc = hip_fail(e);
+  }
+  if (rc != HTTM_OK) {
+    httm_plan_destroy(p);
+    return rc;
+  }
+  *out = p;
+  return HTTM_OK;
+}
+
+int httm_plan_destroy(httm_plan_t* p) {
+  if (!p) return HTTM_OK;
+  void* ptrs[] = {p->d_pi, p->d_items_q, p->d_items_k, p->d_mean, p->d_slot, p->d_uscore};
+  for (void* q : ptrs)
+    if (q) (void)hipFree(q);
+  delete p;
+  return HTTM_OK;
+}
+
+int httm_plan_query(const httm_plan_t* p, httm_sizes_t* out) {
+  if (!p || !out) return HTTM_E_INVALID_ARG;
+  *out = p->sizes;
+  return HTTM_OK;
+}
+
+int httm_reorder(const httm_plan_t* p, const void* src, void* dst, int direction, void* stream) {
+  if (!p || !src || !dst || src == dst || (direction != 0 && direction != 1)) return HTTM_E_INVALID_ARG;
+  if (!aligned16(src) || !aligned16(dst)) return HTTM_E_INVALID_ARG;
+  HTTM_HIP(launch_reorder(src, dst, p->d_pi, p->geom.H, p->sizes.N, direction, (hipStream_t)stream));
+  return HTTM_OK;
+}
+
+int httm_match_merge(const httm_plan_t* p, const void* q_r, const void* k_r, const void* v_r,
+                     void* q_m, void* k_m, void* v_m, int32_t* assign_q, int32_t* assign_k,
+                     float* score_q, float* score_k, void* stream) {
+  if (!p || !q_r || !k_r || !v_r || !q_m || !k_m || !v_m || !assign_q || !assign_k)
+    return HTTM_E_INVALID_ARG;
+  const void* ptrs[] = {q_r, k_r, v_r, q_m, k_m, v_m, assign_q, assign_k};
+  for (const void* q : ptrs)
+    if (!aligned16(q)) return HTTM_E_INVALID_ARG;
+  return run_match_merge(p, nullptr, q_r, k_r, v_r, q_m, k_m, v_m, assign_q, assign_k, score_q,
+                         score_k, (hipStream_t)stream);
+}
+
+int httm_reorder_match_merge(const httm_plan_t* p, const void* q, const void* k, const void* v,
+                             void* q_m, void* k_m, void* v_m, int32_t* assign_q, int32_t* assign_k,
+                             float* score_q, float* score_k, void* stream) {
+  if (!p || !q || !k || !v || !q_m || !k_m || !v_m || !assign_q || !assign_k)
+    return HTTM_E_INVALID_ARG;
+  const void* ptrs[] = {q, k, v, q_m, k_m, v_m, assign_q, assign_k};
+  for (const void* x : ptrs)
+    if (!aligned16(x)) return HTTM_E_INVALID_ARG;
+  return run_match_merge(p, p->d_pi, q, k, v, q_m, k_m, v_m, assign_q, assign_k, score_q, score_k,
+                         (hipStream_t)stream);
+}
+
+int httm_attention(const void* q_m, const void* k_m, const void* v_m, void* o_m,
+                   const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
+                   float scale, void* stream) {
+  if (!q_offsets || !k_offsets || H <= 0 || !(scale > 0.0f)) return HTTM_E_INVALID_ARG;
+  if (d_head != 64 || H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
+  for (int h = 0; h < H; ++h)
+    if (q_offsets[h + 1] < q_offsets[h] || k_offsets[h + 1] < k_offsets[h] ||
+        q_offsets[h + 1] - q_offsets[h] >= ((int64_t)1 << 30) ||
+        k_offsets[h + 1] - k_offsets[h] >= ((int64_t)1 << 30))
+      return HTTM_E_INVALID_ARG;
+  if (q_offsets[0] < 0 || k_offsets[0] < 0) return HTTM_E_INVALID_ARG;
+  const bool any_q = q_offsets[H] > q_offsets[0], any_k = k_offsets[H] > k_offsets[0];
+  if (any_q && (!q_m || !o_m)) return HTTM_E_INVALID_ARG;
+  if (any_q && any_k && (!k_m || !v_m)) return HTTM_E_INVALID_ARG;
+  if (!aligned16(q_m) || !aligned16(k_m) || !aligned16(v_m) || !aligned16(o_m)) return HTTM_E_INVALID_ARG;
+  HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, H, scale, (hipStream_t)stream));
+  return HTTM_OK;
+}
+
+int httm_unmerge(const httm_plan_t* p, const void* o_m, const int32_t* assign_q, void* out,
+                 int fuse_inverse_reorder, void* stream) {
+  if (!p || !o_m || !assign_q || !out || o_m == out) return HTTM_E_INVALID_ARG;
+  if (!aligned16(o_m) || !aligned16(out) || !aligned16(assign_q)) return HTTM_E_INVALID_ARG;
+  HTTM_HIP(launch_unmerge(o_m, assign_q, p->d_pi, out, p->geom.H, p->sizes.N, p->sizes.M_q,
+                          fuse_inverse_reorder ? 1 : 0, (hipStream_t)stream));
+  return HTTM_OK;
+}
+
+int httm_layer_forward(const httm_plan_t* p, const void* q, const void* k, const void* v, void* out,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (!p || !q || !k || !v || !out || !workspace) return HTTM_E_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return HTTM_E_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return HTTM_E_INVALID_ARG;
+  if ((int64_t)workspace_bytes < p->ws.total) return HTTM_E_WORKSPACE_TOO_SMALL;
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  void* q_m = ws + p->ws.q_m;
+  void* k_m = ws + p->ws.k_m;
+  void* v_m = ws + p->ws.v_m;
+  void* o_m = ws + p->ws.o_m;
+  int32_t* assign_q = (int32_t*)(ws + p->ws.assign_q);
+  int32_t* assign_k = (int32_t*)(ws + p->ws.assign_k);
+  // Stages 1+2 fused: the matching kernel gathers its rows through pi.
+  int rc = run_match_merge(p, p->d_pi, q, k, v, q_m, k_m, v_m, assign_q, assign_k, nullptr, nullptr, st);
+  if (rc != HTTM_OK) return rc;
+  // Stage 3.
+  const int H = p->geom.H;
+  int64_t q_off[HTTM_MAX_HEADS + 1], k_off[HTTM_MAX_HEADS + 1];
+  for (int h = 0; h <= H; ++h) {
+    q_off[h] = (int64_t)h * p->sizes.M_q;
+    k_off[h] = (int64_t)h * p->sizes.M_k;
+  }
+  HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_off, k_off, H, 0.125f, st));
+  // Stage 4 with the inverse reorder fused.
+  HTTM_HIP(launch_unmerge(o_m, assign_q, p->d_pi, out, H, p->sizes.N, p->sizes.M_q, 1, st));
+  return HTTM_OK;
+}
+
+}  // extern "C"

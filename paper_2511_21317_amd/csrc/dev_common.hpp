@@ -1,0 +1,45 @@
+// Device-side helpers shared by the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace httm {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kDHead = 64;            // channels per head
+constexpr int kRowBytes = kDHead * 2; // one bf16 token row
+constexpr int kRowChunks = 8;         // 16-byte chunks per row
+
+// A token row in LDS is padded from 128 to 144 bytes: consecutive rows then start 9 sixteen-byte
+// granules apart, so the 16-byte MFMA operand reads of 8 (or 16) consecutive rows fall into
+// distinct bank groups.
+constexpr int kLdsRowBytes = 144;
+constexpr int kLdsRowElems = kLdsRowBytes / 2;
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
+  return __uint_as_float(bits16 << 16);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32 on gfx950).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return __builtin_bit_cast(uint32_t, r);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
+  bf16_t r = (bf16_t)x;
+  return __builtin_bit_cast(uint16_t, r);
+}
+
+}  // namespace httm

@@ -1,0 +1,122 @@
+// Host-side index tables (see geometry.hpp).
+#include "geometry.hpp"
+
+#include <cmath>
+
+namespace httm {
+
+int check_geom(const httm_geom_t& g) {
+  if (g.S <= 0 || g.Hp <= 0 || g.Wp <= 0 || g.n_special < 0 || g.H <= 0 || g.b <= 0 || g.T <= 0)
+    return HTTM_E_INVALID_ARG;
+  if (!(g.rho_q >= 0.0 && g.rho_q <= 1.0) || !(g.rho_kv >= 0.0 && g.rho_kv <= 1.0))
+    return HTTM_E_INVALID_ARG;
+  if (g.variant != HTTM_VARIANT_HEADWISE && g.variant != HTTM_VARIANT_UNIFORM &&
+      g.variant != HTTM_VARIANT_NONE)
+    return HTTM_E_INVALID_ARG;
+  if (g.reserved != 0) return HTTM_E_INVALID_ARG;
+  if (g.d_head != 64 || g.H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
+  const int64_t tpf = (int64_t)g.n_special + (int64_t)g.Hp * g.Wp;
+  const int64_t N = tpf * g.S;
+  if (N >= (int64_t)1 << 30) return HTTM_E_UNSUPPORTED;  // positions are int32; rows*128 B stay < 2^37
+  const int64_t bh = g.b < g.Hp ? g.b : g.Hp, bw = g.b < g.Wp ? g.b : g.Wp, bt = g.T < g.S ? g.T : g.S;
+  if (bh * bw * bt > HTTM_MAX_BLOCK) return HTTM_E_UNSUPPORTED;
+  return HTTM_OK;
+}
+
+int32_t clusters_kept(int32_t n, double rho) {
+  // Sec. 3.2: r tokens are merged away, M = N - r remain; Sec. 4.1 fixes "ratio rho leaves
+  // (1 - rho)".  Applied per block with the count rounded down; at least one cluster survives.
+  const int32_t r = (int32_t)std::floor(rho * (double)n + 1e-9);
+  const int32_t k = n - r;
+  return k < 1 ? 1 : k;
+}
+
+int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
+  const int rc = check_geom(g);
+  if (rc != HTTM_OK) return rc;
+  HostTables& t = *out;
+  const double rho_q = g.variant == HTTM_VARIANT_NONE ? 0.0 : g.rho_q;
+  const double rho_k = g.variant == HTTM_VARIANT_NONE ? 0.0 : g.rho_kv;
+  const int32_t tpf = g.n_special + g.Hp * g.Wp;
+  t.N = (int64_t)tpf * g.S;
+  t.n_prefix = (int64_t)g.S * g.n_special;
+  const int32_t groups = (g.S + g.T - 1) / g.T;
+  const int32_t wy = (g.Hp + g.b - 1) / g.b, wx = (g.Wp + g.b - 1) / g.b;
+  t.n_blocks = (int64_t)groups * wy * wx;
+  t.block_start.resize(t.n_blocks);
+  t.block_n.resize(t.n_blocks);
+  t.block_kq.resize(t.n_blocks);
+  t.block_kk.resize(t.n_blocks);
+  t.block_offq.resize(t.n_blocks);
+  t.block_offk.resize(t.n_blocks);
+  if (with_pi) t.pi.resize(t.N);
+
+  // Special tokens first, frame-major.
+  int64_t pos = 0;
+  if (with_pi)
+    for (int32_t f = 0; f < g.S; ++f)
+      for (int32_t s = 0; s < g.n_special; ++s) t.pi[pos++] = f * tpf + s;
+  pos = t.n_prefix;
+
+  // Pseudo-blocks over the prefix: identity clusters.
+  t.items_q.clear();
+  t.items_k.clear();
+  for (int64_t p = 0; p < t.n_prefix; p += kPrefixChunk) {
+    const int32_t n = (int32_t)((t.n_prefix - p) < kPrefixChunk ? (t.n_prefix - p) : kPrefixChunk);
+    t.items_q.push_back({(int32_t)p, n, n, (int32_t)p});
+    t.items_k.push_back({(int32_t)p, n, n, (int32_t)p});
+  }
+
+  int64_t mq = t.n_prefix, mk = t.n_prefix;
+  t.max_block = 0;
+  int64_t bi = 0;
+  for (int32_t grp = 0; grp < groups; ++grp) {
+    const int32_t f0 = grp * g.T, f1 = (f0 + g.T < g.S) ? f0 + g.T : g.S;
+    for (int32_t by = 0; by < wy; ++by) {
+      const int32_t y0 = by * g.b, y1 = (y0 + g.b < g.Hp) ? y0 + g.b : g.Hp;
+      for (int32_t bx = 0; bx < wx; ++bx, ++bi) {
+        const int32_t x0 = bx * g.b, x1 = (x0 + g.b < g.Wp) ? x0 + g.b : g.Wp;
+        const int32_t n = (f1 - f0) * (y1 - y0) * (x1 - x0);
+        t.block_start[bi] = (int32_t)pos;
+        t.block_n[bi] = n;
+        if (n > t.max_block) t.max_block = n;
+        if (with_pi) {
+          int64_t w = pos;
+          for (int32_t f = f0; f < f1; ++f)
+            for (int32_t y = y0; y < y1; ++y) {
+              const int32_t row = f * tpf + g.n_special + y * g.Wp;
+              for (int32_t x = x0; x < x1; ++x) t.pi[w++] = row + x;
+            }
+        }
+        const int32_t kq = clusters_kept(n, rho_q), kk = clusters_kept(n, rho_k);
+        t.block_kq[bi] = kq;
+        t.block_kk[bi] = kk;
+        t.block_offq[bi] = (int32_t)mq;
+        t.block_offk[bi] = (int32_t)mk;
+        t.items_q.push_back({(int32_t)pos, n, kq, (int32_t)mq});
+        t.items_k.push_back({(int32_t)pos, n, kk, (int32_t)mk});
+        mq += kq;
+        mk += kk;
+        pos += n;
+      }
+    }
+  }
+  t.M_q = mq;
+  t.M_k = mk;
+  return HTTM_OK;
+}
+
+int workspace_layout(const httm_geom_t& g, const HostTables& t, httm_workspace_layout_t* out) {
+  const int64_t row = (int64_t)g.d_head * 2;
+  int64_t off = 0;
+  out->q_m = off;      off = align_up(off + (int64_t)g.H * t.M_q * row, 256);
+  out->k_m = off;      off = align_up(off + (int64_t)g.H * t.M_k * row, 256);
+  out->v_m = off;      off = align_up(off + (int64_t)g.H * t.M_k * row, 256);
+  out->o_m = off;      off = align_up(off + (int64_t)g.H * t.M_q * row, 256);
+  out->assign_q = off; off = align_up(off + (int64_t)g.H * t.N * 4, 256);
+  out->assign_k = off; off = align_up(off + (int64_t)g.H * t.N * 4, 256);
+  out->total = off;
+  return HTTM_OK;
+}
+
+}  // namespace httm

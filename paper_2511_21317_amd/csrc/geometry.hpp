@@ -1,0 +1,47 @@
+// Host-side index tables of an HTTM geometry: the temporal reordering permutation
+// (paper Sec. 3.3), the merging-block list and the merged-sequence layout (Sec. 3.2, Alg. 1).
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "../../include/httm.h"
+
+namespace httm {
+
+// One unit of matching/aggregation work, identical for every head: a run of `n` consecutive
+// reordered tokens that keeps `k` clusters whose merged slots start at `moff`.
+// Real merging blocks have k <= n; the special-token prefix is cut into pseudo-blocks with
+// k == n (every token its own cluster), which the same kernels handle as plain copies.
+struct WorkItem {
+  int32_t start;  // first reordered position
+  int32_t n;      // tokens
+  int32_t k;      // clusters kept
+  int32_t moff;   // first merged slot
+};
+
+struct HostTables {
+  int64_t N = 0, n_prefix = 0, n_blocks = 0, max_block = 0;
+  int64_t M_q = 0, M_k = 0;
+  std::vector<int32_t> pi;           // reordered position -> input position
+  std::vector<int32_t> block_start;  // per real block
+  std::vector<int32_t> block_n;
+  std::vector<int32_t> block_kq, block_kk, block_offq, block_offk;
+  std::vector<WorkItem> items_q, items_k;  // prefix pseudo-blocks followed by the real blocks
+};
+
+constexpr int kPrefixChunk = 64;  // tokens per pseudo-block of the special prefix
+
+// Validate a geometry (returns an HTTM_E_* code).
+int check_geom(const httm_geom_t& g);
+
+// Clusters kept by a block of n tokens at merge ratio rho.
+int32_t clusters_kept(int32_t n, double rho);
+
+// Build every table.  `with_pi` = false skips the O(N) permutation (sizes only).
+int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out);
+
+inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+int workspace_layout(const httm_geom_t& g, const HostTables& t, httm_workspace_layout_t* out);
+
+}  // namespace httm

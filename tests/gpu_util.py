@@ -1,0 +1,97 @@
+"""Helpers shared by the GPU parity tests (not collected by pytest)."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2511_21317_amd as httm
+import synth
+from oracle import httm_oracle as orc
+from synth.vggt_tokens import bf16_to_f32_numpy
+
+# acceptance bar (bf16 GPU vs fp32 oracle)
+MAX_ABS = 2e-2
+REL_L2 = 1e-2
+TIE_GAP = 1e-3
+TIE_FRACTION = 1e-3
+
+
+def require_gpu():
+    assert torch.cuda.is_available(), "these tests need a GPU (run with -m gpu on an MI355X box)"
+    httm.lib()
+
+
+def f32(t: torch.Tensor) -> np.ndarray:
+    return bf16_to_f32_numpy(t)
+
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 (round to nearest even) -> fp32, on the host, via torch's CPU conversion."""
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16).float().numpy()
+
+
+def oracle_geom(w) -> orc.Geometry:
+    return orc.Geometry(w.S, w.Hp, w.Wp, w.b, w.T, n_special=w.n_special)
+
+
+def plan_for(w, variant="headwise", rho_q=None, rho_kv=None, H=None) -> httm.Plan:
+    rq = w.rho if rho_q is None else rho_q
+    rk = rq if rho_kv is None else rho_kv
+    return httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, rq, rk, H=w.H if H is None else H,
+                                    n_special=w.n_special, variant=variant))
+
+
+def check_assign(gpu_assign: np.ndarray, ref_assign: np.ndarray, ref_gap: np.ndarray, what=""):
+    """Bit-exact indices, except where the oracle's best-vs-second gap is below TIE_GAP, on at
+    most TIE_FRACTION of the tokens."""
+    bad = np.flatnonzero(gpu_assign != ref_assign)
+    assert bad.size <= TIE_FRACTION * ref_assign.size, f"{what}: {bad.size} of {ref_assign.size} indices differ"
+    if bad.size:
+        assert (ref_gap[bad] < TIE_GAP).all(), f"{what}: index differs where the gap is {ref_gap[bad].max()}"
+    return bad.size
+
+
+def check_output(got: np.ndarray, ref: np.ndarray, what=""):
+    err = float(np.abs(got - ref).max())
+    rel = float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30))
+    assert err < MAX_ABS and rel < REL_L2, f"{what}: max_abs={err:.4g} rel_l2={rel:.4g}"
+    return err, rel
+
+
+def run_layer(plan: httm.Plan, q, k, v):
+    out = torch.empty((plan.N, plan.H * 64), dtype=torch.bfloat16, device="cuda")
+    ws = httm.alloc_workspace(plan)
+    httm.layer_forward(plan, q, k, v, out, ws)
+    torch.cuda.synchronize()
+    return out, httm.workspace_views(plan, ws)
+
+
+def run_stages(plan: httm.Plan, q, k, v, with_scores=True):
+    """The four stages one by one through the C ABI; returns every intermediate."""
+    H, N = plan.H, plan.N
+    dev = "cuda"
+    bf, i32 = torch.bfloat16, torch.int32
+    qr, kr, vr = (torch.empty_like(q) for _ in range(3))
+    httm.reorder(plan, q, qr, 0)
+    httm.reorder(plan, k, kr, 0)
+    httm.reorder(plan, v, vr, 0)
+    q_m = torch.empty((H, plan.M_q, 64), dtype=bf, device=dev)
+    k_m = torch.empty((H, plan.M_k, 64), dtype=bf, device=dev)
+    v_m = torch.empty((H, plan.M_k, 64), dtype=bf, device=dev)
+    aq = torch.empty((H, N), dtype=i32, device=dev)
+    ak = torch.empty((H, N), dtype=i32, device=dev)
+    sq = torch.empty((H, N), dtype=torch.float32, device=dev) if with_scores else None
+    sk = torch.empty((H, N), dtype=torch.float32, device=dev) if with_scores else None
+    httm.match_merge(plan, qr, kr, vr, q_m, k_m, v_m, aq, ak, sq, sk)
+    o_m = torch.empty_like(q_m)
+    httm.attention(q_m, k_m, v_m, o_m, [h * plan.M_q for h in range(H + 1)],
+                   [h * plan.M_k for h in range(H + 1)], 0.125)
+    o_r = torch.empty((H, N, 64), dtype=bf, device=dev)
+    httm.unmerge(plan, o_m, aq, o_r, fuse_inverse_reorder=False)
+    o_hn = torch.empty_like(o_r)
+    httm.reorder(plan, o_r, o_hn, 1)
+    out_fused = torch.empty((N, H * 64), dtype=bf, device=dev)
+    httm.unmerge(plan, o_m, aq, out_fused, fuse_inverse_reorder=True)
+    torch.cuda.synchronize()
+    return dict(qr=qr, kr=kr, vr=vr, q_m=q_m, k_m=k_m, v_m=v_m, assign_q=aq, assign_k=ak,
+                score_q=sq, score_k=sk, o_m=o_m, o_r=o_r, o_hn=o_hn, out=out_fused)

@@ -1,0 +1,214 @@
+"""GPU parity, stage by stage, through the C ABI: HIP kernels vs the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_21317_amd as httm
+import synth
+from oracle import httm_oracle as orc
+from synth.vggt_tokens import Workload
+
+from gpu_util import (check_assign, check_output, f32, oracle_geom, plan_for, require_gpu, round_bf16,
+                      run_stages)
+
+pytestmark = pytest.mark.gpu
+
+# Small shapes that span several tiles and have ragged tails; name, S, Hp, Wp, b, T, rho, shift
+ODD = [
+    Workload("odd_partial_everywhere", 11, 5, 7, 9, 4, 3, 0.6, 1, H=3),
+    Workload("odd_single_token_blocks", 12, 3, 5, 5, 4, 2, 0.5, 1, H=2),     # 1x1xT corner blocks
+    Workload("odd_block512_b8T8", 13, 9, 10, 12, 8, 8, 0.9, 1, H=2),          # 512-token blocks + partials
+    Workload("odd_block512_b16T2", 14, 3, 17, 16, 16, 2, 0.75, 1, H=2),
+    Workload("odd_keep_one", 15, 4, 8, 8, 4, 2, 1.0, 1, H=2),                 # rho = 1: one cluster per block
+    Workload("odd_no_special", 16, 4, 6, 6, 3, 2, 0.5, 1, H=2, n_special=0),
+    Workload("odd_k_gt_32", 17, 4, 16, 16, 8, 4, 0.25, 1, H=2),               # 256-token blocks, k = 192
+]
+
+
+def _inputs(w):
+    print(f"[case] {w.name} N={w.N} H={w.H}", flush=True)
+    return synth.make_qkv(w, device="cuda")
+
+
+def _oracle_stages(w, q, k, v, rho_q=None, rho_kv=None):
+    rq = w.rho if rho_q is None else rho_q
+    rk = rq if rho_kv is None else rho_kv
+    return orc.layer_forward(f32(q), f32(k), f32(v), oracle_geom(w), rq, rk)
+
+
+@pytest.mark.parametrize("w", [synth.workload(1), synth.workload(2), synth.workload(3)] + ODD,
+                         ids=lambda w: w.name)
+def test_reorder_is_a_bit_exact_gather_and_inverts(w):
+    require_gpu()
+    q, _, _ = _inputs(w)
+    plan = plan_for(w)
+    qr = torch.empty_like(q)
+    back = torch.empty_like(q)
+    httm.reorder(plan, q, qr, 0)
+    httm.reorder(plan, qr, back, 1)
+    torch.cuda.synchronize()
+    pi, _ = orc.temporal_reorder(oracle_geom(w))
+    want = orc.reorder(q.cpu().view(torch.int16).numpy(), pi)        # raw bf16 bit patterns
+    assert np.array_equal(qr.cpu().view(torch.int16).numpy(), want)
+    assert torch.equal(back, q)
+    plan.close()
+
+
+@pytest.mark.parametrize("w", [synth.workload(1), synth.workload(2), synth.workload(3)] + ODD,
+                         ids=lambda w: w.name)
+def test_every_stage_matches_the_oracle(w):
+    require_gpu()
+    q, k, v = _inputs(w)
+    plan = plan_for(w)
+    got = run_stages(plan, q, k, v)
+    ref = _oracle_stages(w, q, k, v)
+    H = w.H
+    n_bad = 0
+    for name, gap in (("assign_q", "gap_q"), ("assign_k", "gap_k")):
+        g_all = got[name].cpu().numpy()
+        for h in range(H):
+            n_bad += check_assign(g_all[h], ref[name][h], ref[gap][h], f"{w.name} {name} head {h}")
+    # scores
+    for name in ("score_q", "score_k"):
+        g_all = got[name].cpu().numpy()
+        for h in range(H):
+            same = got["assign" + name[5:]].cpu().numpy()[h] == ref["assign" + name[5:]][h]
+            assert np.abs(g_all[h] - ref[name][h])[same].max() < 1e-5
+    # merged tokens: fp32 sums in the oracle's order, rounded once to bf16
+    for name in ("q_m", "k_m", "v_m"):
+        g_all = f32(got[name])
+        for h in range(H):
+            want = round_bf16(ref[name][h])
+            exact = (g_all[h] == want).all(axis=1)
+            if n_bad == 0:
+                assert exact.mean() > 0.999, f"{name} head {h}: {1 - exact.mean():.3g} rows differ"
+            assert np.abs(g_all[h] - ref[name][h]).max() < 2e-2
+    # attention on the GPU's own merged tokens vs the oracle's attention on the same tokens
+    for h in range(H):
+        want = orc.attention(f32(got["q_m"][h]), f32(got["k_m"][h]), f32(got["v_m"][h]))
+        check_output(f32(got["o_m"][h]), want, f"{w.name} attention head {h}")
+    # unmerge: bit-exact copies of the GPU's o_m rows
+    om_bits = got["o_m"].cpu().view(torch.int16).numpy()
+    aq = got["assign_q"].cpu().numpy().astype(np.int64)
+    pi = ref["pi"]
+    o_r_bits = got["o_r"].cpu().view(torch.int16).numpy()
+    o_hn_bits = got["o_hn"].cpu().view(torch.int16).numpy()
+    out_bits = got["out"].cpu().view(torch.int16).numpy()
+    for h in range(H):
+        want_r = orc.unmerge_by_cluster(om_bits[h], aq[h])
+        assert np.array_equal(o_r_bits[h], want_r)
+        want_in = orc.inverse_reorder(want_r, pi)
+        assert np.array_equal(o_hn_bits[h], want_in)
+        assert np.array_equal(out_bits[:, h * 64:(h + 1) * 64], want_in)
+    # and the end-to-end output against the all-fp32 oracle
+    check_output(f32(got["out"]), ref["O"], f"{w.name} layer output (stage by stage)")
+    plan.close()
+
+
+def test_separate_query_and_key_ratios():
+    require_gpu()
+    w = synth.workload(2)
+    q, k, v = _inputs(w)
+    plan = plan_for(w, rho_q=0.75, rho_kv=0.25)
+    got = run_stages(plan, q, k, v, with_scores=False)
+    ref = _oracle_stages(w, q, k, v, 0.75, 0.25)
+    assert plan.M_q == ref["q_m"][0].shape[0] and plan.M_k == ref["k_m"][0].shape[0] and plan.M_q != plan.M_k
+    for h in range(w.H):
+        check_assign(got["assign_q"][h].cpu().numpy(), ref["assign_q"][h], ref["gap_q"][h], f"q head {h}")
+        check_assign(got["assign_k"][h].cpu().numpy(), ref["assign_k"][h], ref["gap_k"][h], f"k head {h}")
+    check_output(f32(got["out"]), ref["O"], "rho_q=0.75 rho_kv=0.25")
+    plan.close()
+
+
+def test_exact_ties_and_zero_vectors_follow_the_lowest_cluster_rule():
+    """Duplicated dst tokens (exact similarity ties) and all-zero tokens, on the GPU and in the oracle."""
+    require_gpu()
+    w = Workload("ties", 21, 4, 8, 8, 4, 2, 0.75, 1, H=2)
+    q, k, v = _inputs(w)
+    g = oracle_geom(w)
+    pi, blocks = orc.temporal_reorder(g)
+    qn = f32(q).copy()
+    # in every block: make dst 1 an exact copy of dst 0, and zero one src token
+    for (start, n) in blocks:
+        kk = orc.cluster_count(n, w.rho)
+        d = orc.dst_positions(n, kk)
+        qn[:, pi[start + d[1]]] = qn[:, pi[start + d[0]]]
+        qn[:, pi[start + d[0] + 1]] = 0.0
+    q = torch.from_numpy(qn).to(torch.bfloat16).cuda()
+    plan = plan_for(w)
+    got = run_stages(plan, q, k, v)
+    ref = _oracle_stages(w, q, k, v)
+    for h in range(w.H):
+        ga = got["assign_q"][h].cpu().numpy()
+        assert np.array_equal(ga, ref["assign_q"][h])          # ties resolved identically: exact
+        ks, offs, _ = orc.merged_layout(g, blocks, w.rho)
+        for (start, n), off in zip(blocks, offs):
+            # cluster 1 duplicates cluster 0, so it never wins: its only member is its own dst token
+            assert int((ga[start:start + n] == off + 1).sum()) == 1
+    check_output(f32(got["out"]), ref["O"], "ties")
+    plan.close()
+
+
+RAGGED = [
+    ([1, 63, 64, 65, 129, 300], [7, 64, 1, 200, 513, 65]),
+    ([128, 0, 5, 257], [64, 33, 0, 1000]),            # a head without queries, a head without keys
+    ([2000], [3001]),
+]
+
+
+@pytest.mark.parametrize("mq,mk", RAGGED)
+def test_attention_on_ragged_heads(mq, mk):
+    require_gpu()
+    print(f"[case] ragged attention mq={mq} mk={mk}", flush=True)
+    gen = torch.Generator().manual_seed(1000 + sum(mq))
+    qo = np.concatenate([[0], np.cumsum(mq)])
+    ko = np.concatenate([[0], np.cumsum(mk)])
+    qm = torch.randn((int(qo[-1]), 64), generator=gen).to(torch.bfloat16).cuda()
+    km = torch.randn((int(ko[-1]), 64), generator=gen).to(torch.bfloat16).cuda()
+    vm = torch.randn((int(ko[-1]), 64), generator=gen).to(torch.bfloat16).cuda()
+    om = torch.full_like(qm, float("nan"))
+    httm.attention(qm, km, vm, om, qo, ko, 0.125)
+    torch.cuda.synchronize()
+    for h in range(len(mq)):
+        got = f32(om[qo[h]:qo[h + 1]])
+        if mq[h] == 0:
+            continue
+        if mk[h] == 0:
+            assert (got == 0).all()
+            continue
+        want = orc.attention(f32(qm[qo[h]:qo[h + 1]]), f32(km[ko[h]:ko[h + 1]]), f32(vm[ko[h]:ko[h + 1]]))
+        check_output(got, want, f"ragged head {h} ({mq[h]}x{mk[h]})")
+
+
+def test_attention_with_large_logits_stays_finite():
+    """Online softmax: rows whose maximum moves a lot between key tiles."""
+    require_gpu()
+    gen = torch.Generator().manual_seed(77)
+    qm = (torch.randn((200, 64), generator=gen) * 6).to(torch.bfloat16).cuda()
+    km = (torch.randn((700, 64), generator=gen) * 6).to(torch.bfloat16).cuda()
+    vm = torch.randn((700, 64), generator=gen).to(torch.bfloat16).cuda()
+    om = torch.empty_like(qm)
+    httm.attention(qm, km, vm, om, [0, 200], [0, 700], 0.125)
+    torch.cuda.synchronize()
+    want = orc.attention(f32(qm), f32(km), f32(vm))
+    got = f32(om)
+    assert np.isfinite(got).all()
+    check_output(got, want, "large logits")
+
+
+def test_bad_arguments_launch_nothing():
+    require_gpu()
+    w = synth.workload(1)
+    q, k, v = _inputs(w)
+    plan = plan_for(w)
+    with pytest.raises(httm.HttmError):
+        httm.reorder(plan, q, q, 0)                                   # in-place
+    with pytest.raises(httm.HttmError):
+        httm.reorder(plan, q[:, :100].contiguous(), torch.empty_like(q), 0)   # wrong shape
+    out = torch.empty((w.N, w.H * 64), dtype=torch.bfloat16, device="cuda")
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(httm.HttmError, match="workspace"):
+        httm.layer_forward(plan, q, k, v, out, small)
+    with pytest.raises(httm.HttmError):
+        httm.attention(q[0], k[0], v[0], torch.empty_like(q[0]), [0, w.N], [0, w.N], scale=-1.0)
+    plan.close()

@@ -1,0 +1,97 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and its host-side index tables agree with the oracle's (written independently, in Python)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2511_21317_amd as httm
+from oracle import httm_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "httm.h")).read()
+    return sorted(set(re.findall(r"HTTM_API\s+[\w\s\*]+?\b(httm_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert len(names) >= 14 and "httm_layer_forward" in names and "httm_attention" in names
+    L = httm.lib()
+    for n in names:
+        assert hasattr(L, n), f"libhttm.so does not export {n}"
+    assert L.httm_version() == 100
+    assert b"workspace" in L.httm_strerror(-3)
+
+
+GEOMS = [
+    (2, 16, 16, 4, 2, 0.5, 0.5),
+    (8, 37, 37, 4, 2, 0.5, 0.5),
+    (32, 21, 37, 4, 4, 0.75, 0.75),
+    (100, 37, 37, 4, 4, 0.8, 0.8),
+    (200, 37, 37, 8, 4, 0.9, 0.9),
+    (3, 5, 7, 4, 2, 0.6, 0.3),
+    (5, 3, 3, 8, 7, 0.9, 0.0),
+]
+
+
+@pytest.mark.parametrize("case", GEOMS)
+def test_host_tables_match_oracle(case):
+    S, Hp, Wp, b, T, rq, rk = case
+    g = httm.make_geom(S, Hp, Wp, b, T, rq, rk)
+    og = orc.Geometry(S, Hp, Wp, b, T)
+    t = httm.geom_tables(g)
+    s = httm.geom_sizes(g)
+    pi, blocks = orc.temporal_reorder(og)
+    assert s.N == og.N and s.n_prefix == og.n_prefix and s.n_blocks == len(blocks)
+    assert np.array_equal(t["pi"], pi)
+    assert t["block_start"].tolist() == [b_[0] for b_ in blocks]
+    assert t["block_n"].tolist() == [b_[1] for b_ in blocks]
+    kq, oq, Mq = orc.merged_layout(og, blocks, rq)
+    kk, ok, Mk = orc.merged_layout(og, blocks, rk)
+    assert t["block_kq"].tolist() == kq and t["block_offq"].tolist() == oq and s.M_q == Mq
+    assert t["block_kk"].tolist() == kk and t["block_offk"].tolist() == ok and s.M_k == Mk
+    assert s.max_block == max(n for _, n in blocks)
+    w = httm.workspace_layout(g)
+    assert w.total == s.workspace_bytes
+    assert w.k_m - w.q_m >= 16 * Mq * 128 and w.assign_k - w.assign_q >= 16 * og.N * 4
+    assert all(getattr(w, f) % 256 == 0 for f in ("q_m", "k_m", "v_m", "o_m", "assign_q", "assign_k"))
+
+
+def test_merged_lengths_of_the_five_workloads():
+    want = {1: 266, 2: 5516, 3: 6376, 4: 28650, 5: 28700}   # tests/golden/merged_counts.txt
+    import synth
+    for i, M in want.items():
+        w = synth.workload(i)
+        s = httm.geom_sizes(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho))
+        assert (s.M_q, s.M_k, s.N) == (M, M, w.N)
+    none = httm.geom_sizes(httm.make_geom(8, 37, 37, 4, 2, 0.5, variant="none"))
+    assert none.M_q == none.N == 10992
+
+
+def test_argument_errors_are_reported_not_crashed():
+    L = httm.lib()
+    s = httm.Sizes()
+    bad = httm.make_geom(2, 16, 16, 4, 2, 0.5, d_head=128)
+    assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -2
+    bad = httm.make_geom(2, 16, 16, 16, 4, 0.5)            # 16*16*2 = 512 ok; 4 frames clipped to S=2
+    assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == 0
+    bad = httm.make_geom(8, 32, 32, 16, 4, 0.5)            # 1024-token block
+    assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -2
+    bad = httm.make_geom(2, 16, 16, 4, 2, 1.5)
+    assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -1
+    bad = httm.make_geom(0, 16, 16, 4, 2, 0.5)
+    assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -1
+    assert L.httm_geom_sizes(None, C.byref(s)) == -1
+    # compute entry points reject null pointers before touching the GPU
+    assert L.httm_reorder(None, None, None, 0, None) == -1
+    assert L.httm_layer_forward(None, None, None, None, None, None, 0, None) == -1
+    off = (C.c_int64 * 2)(0, 4)
+    assert L.httm_attention(None, None, None, None, off, off, 1, 32, 0.125, None) == -2
+    assert L.httm_attention(None, None, None, None, off, off, 1, 64, 0.125, None) == -1
+    with pytest.raises(httm.HttmError):
+        httm.geom_sizes(httm.make_geom(2, 16, 16, 4, 2, -0.1))
