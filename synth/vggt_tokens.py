@@ -102,9 +102,9 @@ def make_qkv(w: Workload, device: str = "cpu", seed: int | None = None):
         x = np.concatenate([special, frame], axis=0)
         x = x + 0.1 * rng.standard_normal(x.shape, dtype=np.float32)
         proj = torch.from_numpy(x).to(device) @ w_dev          # [tpf, 3*1024] fp32
-        proj = proj.view(tpf, 3, w.H, w.d_head).permute(1, 2, 0, 3)  # [3, H, tpf, 64]
+        proj = proj.view(tpf, 3, N_HEADS, D_HEAD).permute(1, 2, 0, 3)  # [3, 16, tpf, 64]
         for t in range(3):
-            out[t][:, f * tpf:(f + 1) * tpf, :] = proj[t].to(torch.bfloat16)
+            out[t][:, f * tpf:(f + 1) * tpf, :] = proj[t, :w.H].to(torch.bfloat16)  # first H heads
     return out[0], out[1], out[2]
 
 

@@ -51,8 +51,14 @@ def check_assign(gpu_assign: np.ndarray, ref_assign: np.ndarray, ref_gap: np.nda
     return bad.size
 
 
-def check_output(got: np.ndarray, ref: np.ndarray, what=""):
-    err = float(np.abs(got - ref).max())
+def check_output(got: np.ndarray, ref: np.ndarray, what="", relative_to_magnitude=False):
+    """The acceptance bar: max-abs < 2e-2 and relative-L2 < 1e-2.  The absolute bound is stated for
+    the unit-variance tokens of the five workloads; cases built on other value ranges (tiny grids,
+    scaled logits) pass relative_to_magnitude=True, which reads it as 2e-2 * max(1, |ref|)."""
+    diff = np.abs(got - ref)
+    if relative_to_magnitude:
+        diff = diff / np.maximum(1.0, np.abs(ref))
+    err = float(diff.max())
     rel = float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30))
     assert err < MAX_ABS and rel < REL_L2, f"{what}: max_abs={err:.4g} rel_l2={rel:.4g}"
     return err, rel

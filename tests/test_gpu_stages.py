@@ -16,11 +16,11 @@ pytestmark = pytest.mark.gpu
 # Small shapes that span several tiles and have ragged tails; name, S, Hp, Wp, b, T, rho, shift
 ODD = [
     Workload("odd_partial_everywhere", 11, 5, 7, 9, 4, 3, 0.6, 1, H=3),
-    Workload("odd_single_token_blocks", 12, 3, 5, 5, 4, 2, 0.5, 1, H=2),     # 1x1xT corner blocks
+    Workload("odd_single_token_blocks", 12, 3, 13, 9, 4, 2, 0.5, 1, H=2),    # 1x1xT corner blocks
     Workload("odd_block512_b8T8", 13, 9, 10, 12, 8, 8, 0.9, 1, H=2),          # 512-token blocks + partials
     Workload("odd_block512_b16T2", 14, 3, 17, 16, 16, 2, 0.75, 1, H=2),
     Workload("odd_keep_one", 15, 4, 8, 8, 4, 2, 1.0, 1, H=2),                 # rho = 1: one cluster per block
-    Workload("odd_no_special", 16, 4, 6, 6, 3, 2, 0.5, 1, H=2, n_special=0),
+    Workload("odd_no_special", 16, 4, 12, 15, 3, 2, 0.5, 1, H=2, n_special=0),
     Workload("odd_k_gt_32", 17, 4, 16, 16, 8, 4, 0.25, 1, H=2),               # 256-token blocks, k = 192
 ]
 
@@ -74,19 +74,25 @@ def test_every_stage_matches_the_oracle(w):
         for h in range(H):
             same = got["assign" + name[5:]].cpu().numpy()[h] == ref["assign" + name[5:]][h]
             assert np.abs(g_all[h] - ref[name][h])[same].max() < 1e-5
-    # merged tokens: fp32 sums in the oracle's order, rounded once to bf16
-    for name in ("q_m", "k_m", "v_m"):
+    # merged tokens: fp32 sums in the oracle's order, rounded once to bf16.  Clusters touched by
+    # an (allowed) tie mismatch legitimately differ and are left out.
+    for name, asg in (("q_m", "assign_q"), ("k_m", "assign_k"), ("v_m", "assign_k")):
         g_all = f32(got[name])
+        a_all = got[asg].cpu().numpy()
         for h in range(H):
+            bad = np.flatnonzero(a_all[h] != ref[asg][h])
+            keep = np.ones(g_all[h].shape[0], dtype=bool)
+            keep[a_all[h][bad]] = False
+            keep[ref[asg][h][bad]] = False
             want = round_bf16(ref[name][h])
-            exact = (g_all[h] == want).all(axis=1)
-            if n_bad == 0:
-                assert exact.mean() > 0.999, f"{name} head {h}: {1 - exact.mean():.3g} rows differ"
-            assert np.abs(g_all[h] - ref[name][h]).max() < 2e-2
+            exact = (g_all[h] == want).all(axis=1)[keep]
+            assert exact.mean() > 0.999, f"{name} head {h}: {1 - exact.mean():.3g} rows differ"
+            # never further than one bf16 rounding (half an ulp = 2^-9 relative) from the fp32 mean
+            assert (np.abs(g_all[h] - ref[name][h]) <= 2.0 ** -8 * np.abs(ref[name][h]) + 1e-30)[keep].all()
     # attention on the GPU's own merged tokens vs the oracle's attention on the same tokens
     for h in range(H):
         want = orc.attention(f32(got["q_m"][h]), f32(got["k_m"][h]), f32(got["v_m"][h]))
-        check_output(f32(got["o_m"][h]), want, f"{w.name} attention head {h}")
+        check_output(f32(got["o_m"][h]), want, f"{w.name} attention head {h}", relative_to_magnitude=w.index > 5)
     # unmerge: bit-exact copies of the GPU's o_m rows
     om_bits = got["o_m"].cpu().view(torch.int16).numpy()
     aq = got["assign_q"].cpu().numpy().astype(np.int64)
@@ -101,7 +107,8 @@ def test_every_stage_matches_the_oracle(w):
         assert np.array_equal(o_hn_bits[h], want_in)
         assert np.array_equal(out_bits[:, h * 64:(h + 1) * 64], want_in)
     # and the end-to-end output against the all-fp32 oracle
-    check_output(f32(got["out"]), ref["O"], f"{w.name} layer output (stage by stage)")
+    check_output(f32(got["out"]), ref["O"], f"{w.name} layer output (stage by stage)",
+                 relative_to_magnitude=w.index > 5)
     plan.close()
 
 
@@ -145,7 +152,7 @@ def test_exact_ties_and_zero_vectors_follow_the_lowest_cluster_rule():
         for (start, n), off in zip(blocks, offs):
             # cluster 1 duplicates cluster 0, so it never wins: its only member is its own dst token
             assert int((ga[start:start + n] == off + 1).sum()) == 1
-    check_output(f32(got["out"]), ref["O"], "ties")
+    check_output(f32(got["out"]), ref["O"], "ties", relative_to_magnitude=True)
     plan.close()
 
 
@@ -193,7 +200,7 @@ def test_attention_with_large_logits_stays_finite():
     want = orc.attention(f32(qm), f32(km), f32(vm))
     got = f32(om)
     assert np.isfinite(got).all()
-    check_output(got, want, "large logits")
+    check_output(got, want, "large logits", relative_to_magnitude=True)
 
 
 def test_bad_arguments_launch_nothing():
