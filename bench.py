@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the HTTM global-attention layer on one MI355X.
+
+A "step" is one httm_layer_forward call (reorder + match/merge + attention + unmerge + inverse
+reorder) on one batch of seeded synthetic VGGT-shaped Q/K/V that already sits in HBM.
+Prints ONE JSON line on stdout; progress goes to stderr.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-extras] [--no-cpu]
+
+metric  : global-attention-layer tokens/s = N / t_layer
+roofline: for the dominant kernel (the MFMA attention kernel): algorithmic flop 4*H*M_q*M_k*64 per
+          launch over its average launch time, measured with events on the launch stream.
+stages  : per-stage time and achieved GB/s (algorithmic bytes) for the HBM-bound kernels.
+extras  : the same inputs without merging (r = 0) and with the head-uniform variant.
+cpu_baseline: the CPU oracle timed on a bounded sample (a few heads) of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def gpu_time_ms(fn, iters, warmup=1):
+    """Average milliseconds per call of fn(), timed with events on the current stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    start = torch.cuda.Event(enable_timing=True)
+    end = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(iters):
+        fn()
+    end.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(end) / iters
+
+
+def cpu_oracle_baseline(w, q, k, v, budget_s=20.0):
+    """Time the oracle (as it stands) on the first heads of the workload until ~budget_s is used."""
+    import numpy as np
+    from oracle import httm_oracle as orc
+    from synth.vggt_tokens import bf16_to_f32_numpy
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    g = orc.Geometry(w.S, w.Hp, w.Wp, w.b, w.T, n_special=w.n_special)
+    done, t0 = 0, time.perf_counter()
+    while done < w.H:
+        qh, kh, vh = (bf16_to_f32_numpy(t[done:done + 1]) for t in (q, k, v))
+        orc.layer_forward(qh, kh, vh, g, w.rho, w.rho)
+        done += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or el / done * (done + 1) > 1.5 * budget_s:
+            break
+    el = time.perf_counter() - t0
+    tokens_per_s = w.N / (el / done * w.H)
+    return {"value": tokens_per_s, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{done} of {w.H} heads of {w.name}, full merged path per head "
+                      f"({el:.1f} s measured, scaled to {w.H} heads)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-extras", action="store_true", help="skip the r=0 and head-uniform runs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--stage-iters", type=int, default=10)
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build targets ONE GPU (no sharding, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2511_21317_amd as httm
+    import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    httm.lib()   # fails loudly if libhttm.so is missing
+    w = synth.workload(args.config)
+    log(f"[bench] workload {w.name}: N={w.N} H={w.H} block {w.b}x{w.b}x{w.T} rho={w.rho}")
+    q, k, v = synth.make_qkv(w, device="cuda")
+    torch.cuda.synchronize()
+
+    plan = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H, n_special=w.n_special))
+    H, N, Mq, Mk = plan.H, plan.N, plan.M_q, plan.M_k
+    out = torch.empty((N, H * 64), dtype=torch.bfloat16, device="cuda")
+    ws = httm.alloc_workspace(plan)
+    views = httm.workspace_views(plan, ws)
+
+    # ---- the timed region: K steps of the whole layer -------------------------------------------
+    step = lambda: httm.layer_forward(plan, q, k, v, out, ws)   # noqa: E731
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    tokens_per_s = N / (ms_per_step * 1e-3)
+    log(f"[bench] layer: {ms_per_step:.3f} ms/step -> {tokens_per_s:.4g} tokens/s")
+
+    # ---- per-stage timings (same kernels, called one by one through the C ABI) ---------------------
+    it = args.stage_iters
+    row = 128
+    q_off = [h * Mq for h in range(H + 1)]
+    k_off = [h * Mk for h in range(H + 1)]
+    qr = torch.empty_like(q)
+    t_reorder = gpu_time_ms(lambda: httm.reorder(plan, q, qr, 0), it)
+    t_fused_merge = gpu_time_ms(lambda: httm.reorder_match_merge(
+        plan, q, k, v, views["q_m"], views["k_m"], views["v_m"], views["assign_q"], views["assign_k"]), it)
+    kr, vr = torch.empty_like(k), torch.empty_like(v)
+    httm.reorder(plan, k, kr, 0)
+    httm.reorder(plan, v, vr, 0)
+    t_merge = gpu_time_ms(lambda: httm.match_merge(
+        plan, qr, kr, vr, views["q_m"], views["k_m"], views["v_m"], views["assign_q"], views["assign_k"]), it)
+    del kr, vr
+    t_attn = gpu_time_ms(lambda: httm.attention(views["q_m"], views["k_m"], views["v_m"], views["o_m"],
+                                                q_off, k_off, 0.125), it)
+    t_unmerge = gpu_time_ms(lambda: httm.unmerge(plan, views["o_m"], views["assign_q"], out, True), it)
+    del qr
+
+    b_reorder = 2 * H * N * row                                   # one tensor, read + write
+    b_merge = 3 * H * N * row + H * (Mq + 2 * Mk) * row + 2 * H * N * 4
+    b_unmerge = N * H * row + H * Mq * row + H * N * 4
+    f_attn = 4.0 * H * Mq * Mk * 64
+
+    def gbs(nbytes, ms):
+        return nbytes / (ms * 1e-3) / 1e9
+
+    stages = {
+        "reorder_one_tensor": {"ms": t_reorder, "GB/s": gbs(b_reorder, t_reorder),
+                               "frac_hbm": gbs(b_reorder, t_reorder) / PEAK_HBM_GBS},
+        "match_merge_on_reordered": {"ms": t_merge, "GB/s": gbs(b_merge, t_merge),
+                                     "frac_hbm": gbs(b_merge, t_merge) / PEAK_HBM_GBS},
+        "reorder_match_merge_fused": {"ms": t_fused_merge, "GB/s": gbs(b_merge, t_fused_merge),
+                                      "frac_hbm": gbs(b_merge, t_fused_merge) / PEAK_HBM_GBS},
+        "attention": {"ms": t_attn, "TFLOP/s": f_attn / (t_attn * 1e-3) / 1e12,
+                      "frac_mfma": f_attn / (t_attn * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+        "unmerge_inverse_reorder_fused": {"ms": t_unmerge, "GB/s": gbs(b_unmerge, t_unmerge),
+                                          "frac_hbm": gbs(b_unmerge, t_unmerge) / PEAK_HBM_GBS},
+    }
+    for name, s in stages.items():
+        log(f"[bench] {name}: " + ", ".join(f"{k_}={v_:.4g}" for k_, v_ in s.items()))
+
+    achieved = f_attn / (t_attn * 1e-3) / 1e12
+    roofline = {"kernel": "attention_kernel", "bound": "mfma", "achieved": achieved,
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                "traffic": None, "flop_per_launch": f_attn, "ms_per_launch": t_attn}
+
+    # ---- extras: unmerged attention and the head-uniform variant on the same inputs -------------
+    extras = {}
+    if not args.no_extras:
+        del ws, views, out
+        torch.cuda.empty_cache()
+        plan_u = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H,
+                                          n_special=w.n_special, variant="uniform"))
+        out_u = torch.empty((N, H * 64), dtype=torch.bfloat16, device="cuda")
+        ws_u = httm.alloc_workspace(plan_u)
+        t_uni = gpu_time_ms(lambda: httm.layer_forward(plan_u, q, k, v, out_u, ws_u), max(2, it // 2))
+        extras["head_uniform_layer"] = {"ms": t_uni, "tokens/s": N / (t_uni * 1e-3)}
+        log(f"[bench] head-uniform layer: {t_uni:.3f} ms")
+        plan_u.close()
+        del ws_u
+        torch.cuda.empty_cache()
+        plan_0 = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, 0.0, H=w.H,
+                                          n_special=w.n_special, variant="none"))
+        ws_0 = httm.alloc_workspace(plan_0)
+        big = N > 100000
+        t_un = gpu_time_ms(lambda: httm.layer_forward(plan_0, q, k, v, out_u, ws_0),
+                           1 if big else it, warmup=0 if big else 1)
+        f_un = 4.0 * H * N * N * 64
+        extras["unmerged_layer_r0"] = {"ms": t_un, "tokens/s": N / (t_un * 1e-3),
+                                       "attention_TFLOP/s_lower_bound": f_un / (t_un * 1e-3) / 1e12,
+                                       "speedup_of_merging": t_un / ms_per_step}
+        log(f"[bench] unmerged (r=0) layer: {t_un:.2f} ms  ({t_un / ms_per_step:.1f}x the merged layer)")
+        plan_0.close()
+        del ws_0, out_u
+        torch.cuda.empty_cache()
+
+    cpu = None
+    if not args.no_cpu:
+        log("[bench] timing the CPU oracle on a bounded sample ...")
+        cpu = cpu_oracle_baseline(w, q.cpu(), k.cpu(), v.cpu())
+        log(f"[bench] cpu oracle: {cpu['value']:.4g} tokens/s on {cpu['cores']} threads ({cpu['sample']})")
+
+    result = {
+        "metric": "global-attn layer tokens/s (merge+attn+unmerge)",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "S": w.S, "grid": [w.Hp, w.Wp], "N": N, "H": H, "d_head": 64,
+                   "block": [w.b, w.b, w.T], "rho": w.rho, "M_q": Mq, "M_k": Mk},
+        "roofline": roofline,
+        "stages": stages,
+        "extras": extras,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result), flush=True)
+    plan.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -61,7 +61,8 @@ extern "C" {
 enum {
   HTTM_OK = 0,
   HTTM_E_INVALID_ARG = -1,        /* null pointer, misaligned pointer, non-positive size, bad enum */
-  HTTM_E_UNSUPPORTED = -2,        /* d_head != 64, block of more than HTTM_MAX_BLOCK tokens, H > HTTM_MAX_HEADS */
+  HTTM_E_UNSUPPORTED = -2,        /* d_head != 64, block of more than HTTM_MAX_BLOCK tokens, H > HTTM_MAX_HEADS,
+                                     N >= 2^25 tokens per head */
   HTTM_E_WORKSPACE_TOO_SMALL = -3,
   HTTM_E_HIP = -4,                /* a HIP runtime call failed; see httm_last_hip_error() */
   HTTM_E_NO_DEVICE = -5           /* no usable GPU */
@@ -176,7 +177,8 @@ HTTM_API int httm_reorder_match_merge(const httm_plan_t* plan, const void* q, co
  * [k_offsets[h], k_offsets[h+1]) of k_m / v_m.  q_offsets, k_offsets are HOST arrays of H+1
  * non-decreasing int64 row indices (they are copied into the kernel arguments).
  * A head with no keys writes zeros; a head with no queries writes nothing.
- * d_head must be 64; H <= HTTM_MAX_HEADS.  bf16 in/out, fp32 softmax state and accumulation. */
+ * d_head must be 64; H <= HTTM_MAX_HEADS; every head shorter than 2^24 rows.  bf16 in/out, fp32
+ * softmax state and accumulation. */
 HTTM_API int httm_attention(const void* q_m, const void* k_m, const void* v_m, void* o_m,
                    const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
                    float scale, void* stream);

@@ -242,8 +242,8 @@ int httm_attention(const void* q_m, const void* k_m, const void* v_m, void* o_m,
   if (d_head != 64 || H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
   for (int h = 0; h < H; ++h)
     if (q_offsets[h + 1] < q_offsets[h] || k_offsets[h + 1] < k_offsets[h] ||
-        q_offsets[h + 1] - q_offsets[h] >= ((int64_t)1 << 30) ||
-        k_offsets[h + 1] - k_offsets[h] >= ((int64_t)1 << 30))
+        q_offsets[h + 1] - q_offsets[h] >= ((int64_t)1 << 24) ||
+        k_offsets[h + 1] - k_offsets[h] >= ((int64_t)1 << 24))
       return HTTM_E_INVALID_ARG;
   if (q_offsets[0] < 0 || k_offsets[0] < 0) return HTTM_E_INVALID_ARG;
   const bool any_q = q_offsets[H] > q_offsets[0], any_k = k_offsets[H] > k_offsets[0];

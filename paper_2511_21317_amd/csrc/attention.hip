@@ -1,28 +1,48 @@
 // Stage 3: attention over the reduced per-head sequences (paper Sec. 3.2 Eq. 3-4):
 //   O = softmax(Q K^T * scale) V, per head, no mask, ragged (M_q[h], M_k[h]).
 //
-// Flash-style single pass with bf16 MFMA (v_mfma_f32_32x32x16_bf16) and fp32 online softmax.
+// Flash-style single pass with bf16 MFMA (v_mfma_f32_32x32x16_bf16) and fp32 softmax state.
 // The kernel is bound by the matrix cores (4*M_q*M_k*64 flop per head against a few MB of
-// K/V that stay in L2 / Infinity Cache).
+// K/V that stay in L2 / Infinity Cache); with d_head = 64 the softmax needs about as many
+// vector-ALU cycles as the two matrix products need MFMA cycles, so the design is about
+// (a) taking vector instructions out of the inner loop and (b) giving every wave independent
+// MFMA and vector work in the same stretch of code so that both pipes run at once.
 //
 // Work decomposition
-//   * workgroup = 4 waves = one tile of BQ = 128*QT query rows of one head; wave w owns 32*QT rows;
-//   * K/V are streamed in tiles of 64 rows through LDS, double buffered: the global loads of
-//     tile i+1 are issued before the MFMAs of tile i and written to the other buffer after them,
-//     one barrier per tile;
+//   * workgroup = NW waves = one tile of 32*QT*NW query rows of one head; a wave owns 32*QT rows;
+//   * K/V are streamed in tiles of 64 rows through LDS, double buffered, one barrier per tile;
 //   * blockIdx -> tile mapping is XCD-aware: workgroups are dispatched round-robin over the 8
 //     XCDs, so tile = (bid % 8) * (grid/8) + bid / 8 gives every XCD a contiguous range of
 //     tiles, i.e. about two heads, whose K/V then stay in that XCD's L2.
 //
 // Transposed formulation.  Each wave computes S^T = K Q^T (A = K tile from LDS, B = Q^T from
 // registers) so that in the 32x32 accumulator layout a lane owns ONE query column and 16 of the
-// 32 key rows: the row-max / row-sum of the softmax are reductions inside a lane plus one
-// exchange with lane^32, and the rescaling factor of the online softmax is a per-lane scalar
-// for the O^T = V^T P^T accumulators as well.  P^T goes from the accumulator registers straight
-// into the B operand of the second MFMA (fp32 -> bf16 in registers, no LDS round trip).  That
-// fixes which 8 keys a lane supplies per MFMA step: {16j + 4*half + 0..3, 16j + 8 + 4*half + 0..3};
-// V is therefore stored transposed in LDS with key positions 2 and 3 bit-swapped, so that the
-// matching A operand (V^T rows = channels) is one aligned 16-byte read.
+// 32 key rows: the softmax reductions are sums inside a lane plus one exchange with lane^32 at
+// the very end, and every per-row quantity is a per-lane scalar for the O^T = V^T P^T
+// accumulators as well.  P^T goes from the accumulator registers straight into the B operand of
+// the second MFMA (fp32 -> bf16 in registers, no LDS round trip).  That fixes which 8 keys a lane
+// supplies per MFMA step: {16j + 4*half + 0..3, 16j + 8 + 4*half + 0..3}; V is therefore stored
+// transposed in LDS with key positions 2 and 3 bit-swapped, so that the matching A operand
+// (V^T rows = channels) is one aligned 16-byte read.
+//
+// Software pipeline.  Work is cut into steps of 32 keys.  In step t a wave issues, in one
+// basic block, the QK^T MFMAs of step t+1, the PV MFMAs of step t-1 and the softmax of step t:
+// the 16 MFMAs do not depend on the ~100 vector instructions next to them, so the matrix core
+// and the vector ALU overlap inside a single wave (two waves per SIMD then fill what is left).
+// V lags K by one tile in LDS because of the t-1.
+//
+// Softmax without a running maximum.  softmax is invariant to the per-row shift m, and fp32 /
+// bf16 keep their relative precision over the whole exponent range, so m only has to keep
+// exp2(s - m) inside that range - it does not have to be the maximum.  Per row, m is the exact
+// maximum of the first 32 keys and is then left alone; the vector ALU does one fma (scale and
+// shift), exp2, the bf16 conversion and the row sum (a bf16 dot2 against ones) per score, and no
+// max, no rescaling of O.  Because the first block's maximum contributes exp2(0) = 1, the row
+// sum can never underflow.  Overflow is caught: if a lane's partial row sum of a step is not
+// below 2^60 (this also catches inf / NaN), the wave redoes that step's softmax with m raised to
+// the step's true maximum and rescales its O and l accumulators - the classic online-softmax
+// update, taken only when needed.
+#include <cstdlib>
+
 #include "dev_common.hpp"
 #include "kernels.hpp"
 
@@ -31,7 +51,9 @@ namespace httm {
 namespace {
 
 constexpr int kKvTile = 64;
-constexpr int kAttnThreads = 256;
+constexpr int kStep = 32;                               // keys per pipeline step
+constexpr float kSumLimit = 1.152921504606846976e18f;  // 2^60
+constexpr float kShiftLimit = 60.0f;
 
 struct AttnArgs {
   const bf16_t* q;
@@ -40,8 +62,12 @@ struct AttnArgs {
   bf16_t* o;
   float scale_log2;  // scale * log2(e)
   int32_t H;
-  int32_t total_tiles;
-  int32_t tile_start[kAttnMaxHeads + 1];
+  int32_t n_full;                             // tiles with all BQ query rows
+  int32_t n_ragged;                           // heads whose last tile is partial
+  int32_t full_per_xcd;                       // ceil(n_full / 8)
+  int32_t ragged_per_xcd;                     // ceil(n_ragged / 8)
+  int32_t tile_start[kAttnMaxHeads + 1];      // first full tile of every head
+  int32_t ragged_head[kAttnMaxHeads];         // head of every partial tile
   int64_t q_off[kAttnMaxHeads + 1];
   int64_t k_off[kAttnMaxHeads + 1];
 };
@@ -50,197 +76,359 @@ struct AttnArgs {
 __device__ __forceinline__ int vt_pos(int kv) {
   return (kv & ~0xC) | ((kv & 4) << 1) | ((kv & 8) >> 1);
 }
+// element offset of channel row d of the transposed V tile: 144-byte rows, and every group of 16
+// rows is skewed by another 32 bytes so that the 4-byte transposing stores of a wave (8 channel
+// groups x 8 key pairs) fall into 64 distinct banks; the 16-byte operand reads stay aligned and
+// conflict-free.
+__device__ __forceinline__ int vt_row(int d) { return d * kLdsRowElems + (d >> 4) * 16; }
+constexpr int kVtTileElems = kDHead * kLdsRowElems + (kDHead / 16) * 16;
 
+__device__ __forceinline__ f32x16 splat16(float x) {
+  f32x16 r;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) r[i] = x;
+  return r;
+}
+
+// Per-wave softmax state and accumulators.
 template <int QT>
-__global__ __launch_bounds__(kAttnThreads) void attention_kernel(const AttnArgs a) {
-  constexpr int BQ = 128 * QT;
-  __shared__ __align__(16) bf16_t s_k[2][kKvTile * kLdsRowElems];   // [kv][d], 144-byte rows
-  __shared__ __align__(16) bf16_t s_vt[2][kDHead * kLdsRowElems];   // [d][kv position]
+struct WaveState {
+  bf16x8 qf[QT][4];      // Q^T fragments
+  f32x16 o_acc[2][QT];   // O^T accumulators, [channel tile][query tile]
+  f32x16 s_cur[QT];      // raw scores of the current step
+  u32x4 p_old[QT][2];    // bf16 P^T of the previous step, packed as MFMA B operands
+  float mc[QT];          // shift m in log2 units
+  float l_run[QT];       // per-lane partial row sums
+};
 
-  const int per_xcd = gridDim.x >> 3;
-  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (tile >= a.total_tiles) return;
-  int h = 0;
-  while (tile >= a.tile_start[h + 1]) ++h;
+// exp2(s*c - m), bf16 pack and row sum of one query tile.
+__device__ __forceinline__ float exp_pack(const f32x16& s, float c, float m, u32x4 (&p)[2]) {
+  const bf16x2 ones2 = {(bf16_t)1.0f, (bf16_t)1.0f};
+  float ps = 0.f;
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float p0 = __builtin_amdgcn_exp2f(fmaf(s[8 * j + 2 * e], c, -m));
+      const float p1 = __builtin_amdgcn_exp2f(fmaf(s[8 * j + 2 * e + 1], c, -m));
+      const uint32_t w = pack_bf16x2(p0, p1);
+      p[j][e] = w;
+      ps = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones2, ps, false);
+    }
+  return ps;
+}
+
+// MFMA A operands of one step: 4 K fragments (32 key rows x 64 channels) and 4 V^T fragments
+// (64 channels x 32 key positions), 16 bytes per lane each.
+struct StepOperands {
+  bf16x8 ak[4];
+  bf16x8 av[4];
+};
+
+__device__ __forceinline__ void load_k_operands(StepOperands& op, const bf16_t* sk, int l32, int half) {
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+    op.ak[ks] = *(const bf16x8*)(sk + l32 * kLdsRowElems + ks * 16 + half * 8);
+}
+__device__ __forceinline__ void load_v_operands(StepOperands& op, const bf16_t* svt, int l32, int half) {
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      op.av[dt * 2 + j] = *(const bf16x8*)(svt + vt_row(dt * 32 + l32) + j * 16 + half * 8);
+}
+
+// One pipeline step of a wave.
+//   DO_QK : scores of the NEXT step from the 32 K rows at `sk`           -> becomes s_cur
+//   DO_PV : O^T += V^T P^T of the PREVIOUS step, V^T columns at `svt`
+//   DO_SM : softmax of the CURRENT step (s_cur -> p_old); its first key is `kv_first`
+//   MASK  : keys >= Mk get weight 0;  FIRST : this is step 0 and fixes m
+//   PRELOADED : `op` already holds this step's operands (otherwise they are read here)
+//   PREFETCH  : after the MFMAs are issued, `op` is refilled from sk_next / svt_next, so that the
+//               LDS latency of the following step hides behind this step's softmax
+template <int QT, bool DO_QK, bool DO_PV, bool DO_SM, bool MASK, bool FIRST, bool PRELOADED = false,
+          bool PREFETCH = false>
+__device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk, const bf16_t* svt,
+                                              float c, int kv_first, int Mk, int l32, int half,
+                                              StepOperands* opp = nullptr, const bf16_t* sk_next = nullptr,
+                                              const bf16_t* svt_next = nullptr) {
+  StepOperands local;
+  StepOperands& op = PRELOADED || PREFETCH ? *opp : local;
+  f32x16 s_next[QT];
+  if (DO_QK) {
+    if (!PRELOADED) load_k_operands(op, sk, l32, half);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt)
+        s_next[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            op.ak[ks], w.qf[qt][ks], ks == 0 ? splat16(0.f) : s_next[qt], 0, 0, 0);
+  }
+  if (DO_PV) {
+    if (!PRELOADED) load_v_operands(op, svt, l32, half);
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt)
+          w.o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              op.av[dt * 2 + j], __builtin_bit_cast(bf16x8, w.p_old[qt][j]), w.o_acc[dt][qt], 0, 0, 0);
+  }
+  if (PREFETCH) {
+    load_k_operands(op, sk_next, l32, half);
+    load_v_operands(op, svt_next, l32, half);
+  }
+  if (DO_SM) {
+    // s_cur[qt][r]: key kv_first + 8*(r/4) + 4*half + r%4, query column l32 of tile qt
+    if (MASK) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int kv = kv_first + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (kv >= Mk) {
+#pragma unroll
+          for (int qt = 0; qt < QT; ++qt) w.s_cur[qt][r] = -INFINITY;
+        }
+      }
+    }
+    u32x4 p_new[QT][2];
+    float psum[QT];
+    if (FIRST) {
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) {
+        float tmax = w.s_cur[qt][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, w.s_cur[qt][r]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        w.mc[qt] = tmax * c;
+        psum[qt] = exp_pack(w.s_cur[qt], c, w.mc[qt], p_new[qt]);
+      }
+    } else {
+      bool redo = false;
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) {
+        psum[qt] = exp_pack(w.s_cur[qt], c, w.mc[qt], p_new[qt]);
+        redo = redo || !(psum[qt] < kSumLimit);
+      }
+      // rare: raise m to this step's maximum where needed and redo the step's softmax
+      if (__any(redo)) {
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+          float tmax = w.s_cur[qt][0];
+#pragma unroll
+          for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, w.s_cur[qt][r]);
+          tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+          const float rel = fmaf(tmax, c, -w.mc[qt]);  // log2 units above the current m
+          const float delta = rel > kShiftLimit ? rel : 0.f;
+          const float sc = __builtin_amdgcn_exp2f(-delta);
+          w.l_run[qt] *= sc;
+#pragma unroll
+          for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) w.o_acc[dt][qt][r] *= sc;
+          w.mc[qt] += delta;
+          psum[qt] = exp_pack(w.s_cur[qt], c, w.mc[qt], p_new[qt]);
+        }
+      }
+    }
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+      w.l_run[qt] += psum[qt];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) w.p_old[qt][j] = p_new[qt][j];
+    }
+  }
+  if (DO_QK) {
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) w.s_cur[qt] = s_next[qt];
+  }
+}
+
+template <int QT, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attention_kernel(const AttnArgs a) {
+  constexpr int NT = 64 * NW;
+  constexpr int BQ = 32 * QT * NW;
+  constexpr int LD_ITER = kKvTile * kRowChunks / NT;       // 16-byte K chunks per thread per tile
+  constexpr int LDV_ITER = LD_ITER / 2;                    // V row pairs per thread per tile
+  constexpr int ROWS_PER_PASS = NT / 8;
+  static_assert(LD_ITER >= 2 && LD_ITER % 2 == 0, "tile staging needs an even chunk count");
+  constexpr int kTileElems = kKvTile * kLdsRowElems;
+  __shared__ __align__(16) bf16_t s_k[2][kTileElems];    // [kv][d], 144-byte rows
+  __shared__ __align__(16) bf16_t s_vt[2][kVtTileElems]; // [d][kv position], skewed 144-byte rows
+
+  // blockIdx -> (head, first query row).  Workgroups go round-robin to the 8 XCDs, and in
+  // blockIdx order to free slots; the partial last tiles of the heads come first (they are
+  // short, so they should not be what the grid ends on), then every XCD walks a contiguous
+  // range of full tiles.
+  const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+  int h = 0, q0;
+  if (idx < a.ragged_per_xcd) {
+    const int i = idx * 8 + xcd;
+    if (i >= a.n_ragged) return;
+    h = a.ragged_head[i];
+    q0 = (a.tile_start[h + 1] - a.tile_start[h]) * BQ;
+  } else {
+    const int tile = xcd * a.full_per_xcd + (idx - a.ragged_per_xcd);
+    if (idx - a.ragged_per_xcd >= a.full_per_xcd || tile >= a.n_full) return;
+    while (tile >= a.tile_start[h + 1]) ++h;
+    q0 = (tile - a.tile_start[h]) * BQ;
+  }
   const int64_t q_base = a.q_off[h], k_base = a.k_off[h];
   const int Mq = (int)(a.q_off[h + 1] - q_base);
   const int Mk = (int)(a.k_off[h + 1] - k_base);
-  const int q0 = (tile - a.tile_start[h]) * BQ;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
   const int wq0 = q0 + wave * 32 * QT;  // first query row of this wave
+  // A wave of a partial tile that owns no valid row only helps to stage K/V and to keep the
+  // barriers; it issues no MFMA and no softmax.
+  const bool active = wq0 < Mq;
 
   if (Mk == 0) {
     // softmax over an empty key set: defined as zero output
-    for (int e = tid; e < BQ * kRowChunks; e += kAttnThreads) {
+    for (int e = tid; e < BQ * kRowChunks; e += NT) {
       const int row = q0 + (e >> 3);
       if (row < Mq) ((u32x4*)a.o)[(q_base + row) * kRowChunks + (e & 7)] = u32x4{0, 0, 0, 0};
     }
     return;
   }
 
+  WaveState<QT> w;
   // ---- Q^T fragments (B operand): lane -> query column, 8 consecutive channels ---------------
-  bf16x8 qf[QT][4];
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
     int row = wq0 + qt * 32 + l32;
     row = row < Mq ? row : Mq - 1;
     const bf16_t* p = a.q + (q_base + row) * kDHead + half * 8;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) qf[qt][ks] = *(const bf16x8*)(p + ks * 16);
+    for (int ks = 0; ks < 4; ++ks) w.qf[qt][ks] = *(const bf16x8*)(p + ks * 16);
+    w.mc[qt] = 0.f;
+    w.l_run[qt] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt) w.o_acc[dt][qt] = splat16(0.f);
   }
 
-  // ---- accumulators ---------------------------------------------------------------------------
-  f32x16 o_acc[2][QT];
-  float m_run[QT], l_run[QT];
+  // ---- K/V tile staging: global -> registers -> LDS ---------------------------------------------
+  const char* kg = (const char*)(a.k + k_base * kDHead);   // wave-uniform bases; per-lane offsets
+  const char* vg = (const char*)(a.v + k_base * kDHead);   // below fit 32 bits (rows < 2^24 here)
+  const int ld_c = tid & 7, ld_r = tid >> 3;  // chunk, row-in-pass
+  u32x4 kreg[LD_ITER], vreg[LD_ITER];
+  auto load_k = [&](int kv0) {
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    m_run[qt] = -INFINITY;
-    l_run[qt] = 0.f;
-#pragma unroll
-    for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o_acc[dt][qt][r] = 0.f;
-  }
-
-  // ---- K/V tile staging -----------------------------------------------------------------------
-  const u32x4* kg = (const u32x4*)(a.k + k_base * kDHead);
-  const u32x4* vg = (const u32x4*)(a.v + k_base * kDHead);
-  const int ld_c = tid & 7, ld_r = tid >> 3;  // chunk, row-in-pass (0..31)
-  u32x4 kreg[2], vreg[2];
-  auto load_tile = [&](int kv0) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      int row = kv0 + ld_r + 32 * i;
+    for (int i = 0; i < LD_ITER; ++i) {
+      int row = kv0 + ld_r + ROWS_PER_PASS * i;
       row = row < Mk ? row : Mk - 1;
-      kreg[i] = kg[(int64_t)row * kRowChunks + ld_c];
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      int row = kv0 + 2 * ld_r + i;
-      row = row < Mk ? row : Mk - 1;
-      vreg[i] = vg[(int64_t)row * kRowChunks + ld_c];
+      kreg[i] = *(const u32x4*)(kg + (uint32_t)(row * kRowBytes + ld_c * 16));
     }
   };
-  auto store_tile = [&](int buf) {
+  auto load_v = [&](int kv0) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-      *(u32x4*)(&s_k[buf][(ld_r + 32 * i) * kLdsRowElems + ld_c * 8]) = kreg[i];
-    // V rows 2*ld_r and 2*ld_r+1, channels ld_c*8 .. +7  ->  V^T[channel][pos], two keys per word
-    const int pos = vt_pos(2 * ld_r);
+    for (int i = 0; i < LDV_ITER; ++i)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const uint32_t w0 = vreg[0][e], w1 = vreg[1][e];
-      const uint32_t lo = (w0 & 0xffffu) | (w1 << 16);          // channel 2e   of both keys
-      const uint32_t hi = (w0 >> 16) | (w1 & 0xffff0000u);      // channel 2e+1 of both keys
-      *(uint32_t*)(&s_vt[buf][(ld_c * 8 + 2 * e) * kLdsRowElems + pos]) = lo;
-      *(uint32_t*)(&s_vt[buf][(ld_c * 8 + 2 * e + 1) * kLdsRowElems + pos]) = hi;
+      for (int u = 0; u < 2; ++u) {
+        int row = kv0 + 2 * (ld_r + ROWS_PER_PASS * i) + u;
+        row = row < Mk ? row : Mk - 1;
+        vreg[2 * i + u] = *(const u32x4*)(vg + (uint32_t)(row * kRowBytes + ld_c * 16));
+      }
+  };
+  auto store_k = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < LD_ITER; ++i)
+      *(u32x4*)(&s_k[buf][(ld_r + ROWS_PER_PASS * i) * kLdsRowElems + ld_c * 8]) = kreg[i];
+  };
+  auto store_v = [&](int buf) {
+    // V rows 2r and 2r+1, channels ld_c*8 .. +7  ->  V^T[channel][pos], two keys per 32-bit word
+#pragma unroll
+    for (int i = 0; i < LDV_ITER; ++i) {
+      const int pos = vt_pos(2 * (ld_r + ROWS_PER_PASS * i));
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t w0 = vreg[2 * i][e], w1 = vreg[2 * i + 1][e];
+        const uint32_t lo = __builtin_amdgcn_perm(w1, w0, 0x05040100u);  // channel 2e   of both keys
+        const uint32_t hi = __builtin_amdgcn_perm(w1, w0, 0x07060302u);  // channel 2e+1 of both keys
+        *(uint32_t*)(&s_vt[buf][vt_row(ld_c * 8 + 2 * e) + pos]) = lo;
+        *(uint32_t*)(&s_vt[buf][vt_row(ld_c * 8 + 2 * e + 1) + pos]) = hi;
+      }
     }
   };
 
+  const float c = a.scale_log2;
   const int n_tiles = (Mk + kKvTile - 1) / kKvTile;
-  load_tile(0);
-  store_tile(0);
+
+  // Steps are numbered t = 0 .. 2*n_tiles-1 (32 keys each).  Outer iteration j runs the pipeline
+  // slots t = 2j-1 and t = 2j, which read K tile j (scores of steps 2j, 2j+1) and V tile j-1
+  // (products of steps 2j-2, 2j-1), while K tile j+1 and V tile j are on their way into the
+  // other LDS buffers.
+
+  // ---- j = 0 ---------------------------------------------------------------------------------------
+  load_k(0);
+  store_k(0);
+  load_v(0);
+  if (n_tiles > 1) load_k(kKvTile);
+  __syncthreads();
+  if (active) {
+    pipeline_step<QT, true, false, false, false, false>(w, &s_k[0][0], nullptr, c, 0, Mk, l32, half);
+    if (n_tiles > 1)
+      pipeline_step<QT, true, false, true, false, true>(w, &s_k[0][kStep * kLdsRowElems], nullptr, c, 0,
+                                                        Mk, l32, half);
+    else
+      pipeline_step<QT, true, false, true, true, true>(w, &s_k[0][kStep * kLdsRowElems], nullptr, c, 0,
+                                                       Mk, l32, half);
+  }
+  store_v(0);
+  if (n_tiles > 1) store_k(1);
   __syncthreads();
 
-  for (int it = 0; it < n_tiles; ++it) {
-    const int buf = it & 1;
-    const int kv0 = it * kKvTile;
-    if (it + 1 < n_tiles) load_tile(kv0 + kKvTile);
-
-    // ---- S^T = K Q^T --------------------------------------------------------------------------
-    f32x16 s_acc[2][QT];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s_acc[kt][qt][r] = 0.f;
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const bf16x8 ak =
-            *(const bf16x8*)(&s_k[buf][(kt * 32 + l32) * kLdsRowElems + ks * 16 + half * 8]);
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt)
-          s_acc[kt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qf[qt][ks], s_acc[kt][qt], 0, 0, 0);
-      }
-
-    // ---- mask the ragged tail of the last tile ----------------------------------------------
-    if (kv0 + kKvTile > Mk) {
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int kv = kv0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-          if (kv >= Mk) {
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt) s_acc[kt][qt][r] = -INFINITY;
-          }
-        }
+  // ---- j = 1 .. n_tiles-2: steady state, no masking ------------------------------------------------
+  int j = 1;
+  StepOperands op;
+  for (; j < n_tiles - 1; ++j) {
+    const bf16_t* kb = &s_k[j & 1][0];
+    const bf16_t* vb = &s_vt[(j - 1) & 1][0];
+    if (active) {
+      load_k_operands(op, kb, l32, half);
+      load_v_operands(op, vb, l32, half);
     }
-
-    // ---- online softmax (per lane = per query column) ------------------------------------------
-    bf16x8 pf[2][2][QT];
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-      float mx = s_acc[0][qt][0];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kt][qt][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[qt], mx * a.scale_log2);
-      const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
-      m_run[qt] = m_new;
-      float psum = 0.f;
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-        float p[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          p[r] = __builtin_amdgcn_exp2f(fmaf(s_acc[kt][qt][r], a.scale_log2, -m_new));
-          psum += p[r];
-        }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          u32x4 w;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(p[8 * j + 2 * e], p[8 * j + 2 * e + 1]);
-          pf[kt][j][qt] = __builtin_bit_cast(bf16x8, w);
-        }
-      }
-      l_run[qt] = l_run[qt] * alpha + psum;
-#pragma unroll
-      for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o_acc[dt][qt][r] *= alpha;
+    load_k((j + 1) * kKvTile);
+    load_v(j * kKvTile);
+    if (active) {
+      pipeline_step<QT, true, true, true, false, false, true, true>(
+          w, nullptr, nullptr, c, 0, Mk, l32, half, &op, kb + kStep * kLdsRowElems, vb + kStep);
+      pipeline_step<QT, true, true, true, false, false, true, false>(w, nullptr, nullptr, c, 0, Mk,
+                                                                     l32, half, &op);
     }
-
-    // ---- O^T += V^T P^T -------------------------------------------------------------------------
-#pragma unroll
-    for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const bf16x8 av = *(const bf16x8*)(
-              &s_vt[buf][(dt * 32 + l32) * kLdsRowElems + kt * 32 + j * 16 + half * 8]);
-#pragma unroll
-          for (int qt = 0; qt < QT; ++qt)
-            o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[kt][j][qt], o_acc[dt][qt], 0, 0, 0);
-        }
-
-    if (it + 1 < n_tiles) store_tile(buf ^ 1);
+    store_k((j + 1) & 1);
+    store_v(j & 1);
     __syncthreads();
+  }
+
+  // ---- j = n_tiles-1 (if it is not j = 0): the last K tile, its first step may be ragged ---------
+  if (j == n_tiles - 1) {
+    load_v(j * kKvTile);
+    const bf16_t* kb = &s_k[j & 1][0];
+    const bf16_t* vb = &s_vt[(j - 1) & 1][0];
+    if (active) {
+      pipeline_step<QT, true, true, true, false, false>(w, kb, vb, c, 0, Mk, l32, half);
+      pipeline_step<QT, true, true, true, true, false>(w, kb + kStep * kLdsRowElems, vb + kStep, c,
+                                                       2 * j * kStep, Mk, l32, half);
+    }
+    store_v(j & 1);
+    __syncthreads();
+  }
+
+  // ---- j = n_tiles: drain ---------------------------------------------------------------------------
+  if (active) {
+    const bf16_t* vb = &s_vt[(n_tiles - 1) & 1][0];
+    pipeline_step<QT, false, true, true, true, false>(w, nullptr, vb, c, (2 * n_tiles - 1) * kStep, Mk,
+                                                      l32, half);
+    pipeline_step<QT, false, true, false, false, false>(w, nullptr, vb + kStep, c, 0, Mk, l32, half);
   }
 
   // ---- normalise and store ---------------------------------------------------------------------
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
-    const float l_tot = l_run[qt] + __shfl_xor(l_run[qt], 32);
+    const float l_tot = w.l_run[qt] + __shfl_xor(w.l_run[qt], 32);
     const float inv = 1.0f / l_tot;
     const int row = wq0 + qt * 32 + l32;
     if (row < Mq) {
@@ -249,13 +437,52 @@ __global__ __launch_bounds__(kAttnThreads) void attention_kernel(const AttnArgs 
       for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          u32x2 w;
-          w[0] = pack_bf16x2(o_acc[dt][qt][4 * g] * inv, o_acc[dt][qt][4 * g + 1] * inv);
-          w[1] = pack_bf16x2(o_acc[dt][qt][4 * g + 2] * inv, o_acc[dt][qt][4 * g + 3] * inv);
-          *(u32x2*)(orow + dt * 32 + 8 * g + 4 * half) = w;
+          u32x2 ow;
+          ow[0] = pack_bf16x2(w.o_acc[dt][qt][4 * g] * inv, w.o_acc[dt][qt][4 * g + 1] * inv);
+          ow[1] = pack_bf16x2(w.o_acc[dt][qt][4 * g + 2] * inv, w.o_acc[dt][qt][4 * g + 3] * inv);
+          *(u32x2*)(orow + dt * 32 + 8 * g + 4 * half) = ow;
         }
     }
   }
+}
+
+template <int QT, int NW>
+hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_off_host, int H,
+                      hipStream_t stream) {
+  constexpr int BQ = 32 * QT * NW;
+  int64_t full = 0;
+  int ragged = 0;
+  for (int h = 0; h < H; ++h) {
+    const int64_t mq = q_off_host[h + 1] - q_off_host[h];
+    a.tile_start[h] = (int32_t)full;
+    a.q_off[h] = q_off_host[h];
+    a.k_off[h] = k_off_host[h];
+    full += mq / BQ;
+    if (mq % BQ) a.ragged_head[ragged++] = h;
+  }
+  for (int h = H; h <= kAttnMaxHeads; ++h) {
+    a.tile_start[h] = (int32_t)full;
+    a.q_off[h] = q_off_host[H];
+    a.k_off[h] = k_off_host[H];
+  }
+  for (int i = ragged; i < kAttnMaxHeads; ++i) a.ragged_head[i] = 0;
+  a.n_full = (int32_t)full;
+  a.n_ragged = ragged;
+  a.full_per_xcd = (int32_t)((full + 7) / 8);
+  a.ragged_per_xcd = (ragged + 7) / 8;
+  if (full + ragged == 0) return hipSuccess;
+  const unsigned grid = 8u * (unsigned)(a.full_per_xcd + a.ragged_per_xcd);
+  hipLaunchKernelGGL((attention_kernel<QT, NW>), dim3(grid), dim3(64 * NW), 0, stream, a);
+  return hipGetLastError();
+}
+
+// Tuning knob for experiments (not part of the ABI): HTTM_ATTN_CFG=<QT><NW>, e.g. 24.
+int attn_cfg() {
+  static int cfg = [] {
+    const char* e = std::getenv("HTTM_ATTN_CFG");
+    return e ? std::atoi(e) : 24;
+  }();
+  return cfg;
 }
 
 }  // namespace
@@ -263,8 +490,6 @@ __global__ __launch_bounds__(kAttnThreads) void attention_kernel(const AttnArgs 
 hipError_t launch_attention(const void* q, const void* k, const void* v, void* o,
                             const int64_t* q_off_host, const int64_t* k_off_host, int H,
                             float scale, hipStream_t stream) {
-  constexpr int QT = 1;
-  constexpr int BQ = 128 * QT;
   AttnArgs a;
   a.q = (const bf16_t*)q;
   a.k = (const bf16_t*)k;
@@ -272,23 +497,10 @@ hipError_t launch_attention(const void* q, const void* k, const void* v, void* o
   a.o = (bf16_t*)o;
   a.scale_log2 = scale * 1.4426950408889634f;
   a.H = H;
-  int64_t tiles = 0;
-  for (int h = 0; h < H; ++h) {
-    a.tile_start[h] = (int32_t)tiles;
-    a.q_off[h] = q_off_host[h];
-    a.k_off[h] = k_off_host[h];
-    tiles += (q_off_host[h + 1] - q_off_host[h] + BQ - 1) / BQ;
+  switch (attn_cfg()) {
+    case 14: return launch_cfg<1, 4>(a, q_off_host, k_off_host, H, stream);
+    default: return launch_cfg<2, 4>(a, q_off_host, k_off_host, H, stream);
   }
-  for (int h = H; h <= kAttnMaxHeads; ++h) {
-    a.tile_start[h] = (int32_t)tiles;
-    a.q_off[h] = q_off_host[H];
-    a.k_off[h] = k_off_host[H];
-  }
-  a.total_tiles = (int32_t)tiles;
-  if (tiles == 0) return hipSuccess;
-  const unsigned grid = (unsigned)((tiles + 7) / 8 * 8);
-  hipLaunchKernelGGL((attention_kernel<QT>), dim3(grid), dim3(kAttnThreads), 0, stream, a);
-  return hipGetLastError();
 }
 
 }  // namespace httm

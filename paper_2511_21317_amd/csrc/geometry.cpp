@@ -17,7 +17,7 @@ int check_geom(const httm_geom_t& g) {
   if (g.d_head != 64 || g.H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
   const int64_t tpf = (int64_t)g.n_special + (int64_t)g.Hp * g.Wp;
   const int64_t N = tpf * g.S;
-  if (N >= (int64_t)1 << 30) return HTTM_E_UNSUPPORTED;  // positions are int32; rows*128 B stay < 2^37
+  if (N >= (int64_t)1 << 25) return HTTM_E_UNSUPPORTED;  // per-head byte offsets (N*128) stay below 2^32
   const int64_t bh = g.b < g.Hp ? g.b : g.Hp, bw = g.b < g.Wp ? g.b : g.Wp, bt = g.T < g.S ? g.T : g.S;
   if (bh * bw * bt > HTTM_MAX_BLOCK) return HTTM_E_UNSUPPORTED;
   return HTTM_OK;

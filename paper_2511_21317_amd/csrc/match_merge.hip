@@ -16,9 +16,10 @@
 //      one token's scores against 16 of 32 dst tokens; scaling by 1/||d|| and the arg-max run in
 //      registers, the two half-waves are combined with one cross-lane exchange.  Lowest cluster
 //      id wins exact ties;
-//   4. every cluster is summed by one wave, lane = channel, dst first and then its src tokens in
-//      ascending position (the member set comes from a wave ballot, so the order is fixed and
-//      results are run-to-run identical), divided by the member count and rounded once to bf16;
+//   4. the tokens are ordered by (cluster, position) with a stable counting sort built from wave
+//      ballots (no atomics, so the order is fixed and results are run-to-run identical); one
+//      thread per (cluster, 16-byte chunk) then adds the dst and its src tokens in ascending
+//      position in fp32, divides by the member count and rounds once to bf16;
 //   5. for the K stream the V rows, held in registers since the start, replace the K rows in LDS
 //      and step 4 runs again with the same clusters.
 // Work items with k == n (special-token prefix, or merge ratio 0) skip 1-5 and copy rows.
@@ -29,18 +30,72 @@ namespace httm {
 
 namespace {
 
+// exclusive prefix sum over 64 lanes of a wave (lane i gets the sum of lanes < i)
+__device__ __forceinline__ int wave_exclusive_scan(int v, int lane) {
+  int incl = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int up = __shfl_up(incl, d);
+    if (lane >= d) incl += up;
+  }
+  return incl - v;
+}
+
+// Selectors (1, 0) and (0, 1) as bf16 pairs, pinned in vector registers: as an instruction
+// literal the pair (1, 0) is not taken as two bf16 halves by v_dot2c_f32_bf16 (measured: wrong
+// sums), from a register it is.
+struct PairSelectors {
+  bf16x2 lo, hi;
+};
+__device__ __forceinline__ PairSelectors make_pair_selectors() {
+  uint32_t slo = 0x00003f80u, shi = 0x3f800000u;
+  asm volatile("" : "+v"(slo), "+v"(shi));
+  return {__builtin_bit_cast(bf16x2, slo), __builtin_bit_cast(bf16x2, shi)};
+}
+
+// acc[0..7] += the 8 bf16 channels of one 16-byte row chunk.  One v_dot2 per channel: the pair
+// (x_lo, x_hi) against (1, 0) or (0, 1) adds exactly one bf16 value to the fp32 accumulator.
+__device__ __forceinline__ void add_row_chunk(float (&acc)[8], const unsigned char* row_chunk,
+                                              const PairSelectors& sel) {
+  const bf16x8 w = *(const bf16x8*)row_chunk;
+  const bf16x2 sel_lo = sel.lo, sel_hi = sel.hi;
+  const bf16x2 pr[4] = {__builtin_shufflevector(w, w, 0, 1), __builtin_shufflevector(w, w, 2, 3),
+                        __builtin_shufflevector(w, w, 4, 5), __builtin_shufflevector(w, w, 6, 7)};
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    acc[2 * q] = __builtin_amdgcn_fdot2_f32_bf16(pr[q], sel_lo, acc[2 * q], false);
+    acc[2 * q + 1] = __builtin_amdgcn_fdot2_f32_bf16(pr[q], sel_hi, acc[2 * q + 1], false);
+  }
+}
+
+// a / b for a small positive integer-valued b, correctly rounded: one Newton step on the product
+// with the hardware reciprocal (the residual is exact thanks to the fma).
+__device__ __forceinline__ float div_by_count(float a, float b, float rb) {
+  const float q = a * rb;
+  const float r = fmaf(-q, b, a);
+  return fmaf(r, rb, q);
+}
+
 template <int NW, int MAXN>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(4, 8))) void match_merge_kernel(const MatchMergeArgs a) {
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(4, 8)))
+void match_merge_kernel(const MatchMergeArgs a) {
   constexpr int NT = 64 * NW;
   constexpr int ITER = MAXN * kRowChunks / NT;
-  constexpr int NC = MAXN / 64;
   static_assert(MAXN * kRowChunks % NT == 0, "tile must divide among the threads");
+  static_assert(NT == MAXN, "one thread per token");
 
   __shared__ __align__(16) unsigned char tile[MAXN * kLdsRowBytes];
-  __shared__ float s_invn[MAXN];
-  __shared__ float s_dinv[MAXN];
-  __shared__ int32_t s_dpos[MAXN];
-  __shared__ int32_t s_cl[MAXN];
+  // phase A (matching): inverse norms of all tokens / of the dst tokens
+  // phase B (aggregation): member lists - the same storage, the phases are separated by barriers
+  constexpr int kUnionA = MAXN * 8, kUnionB = MAXN * 4 + 8 + NW * MAXN;
+  __shared__ __align__(16) unsigned char s_union[kUnionA > kUnionB ? kUnionA : kUnionB];
+  __shared__ uint16_t s_dpos[MAXN];
+  __shared__ int16_t s_cl[MAXN];
+  float* s_invn = (float*)s_union;                    // [MAXN]
+  float* s_dinv = s_invn + MAXN;                      // [MAXN]
+  uint16_t* s_list = (uint16_t*)s_union;              // [MAXN]    tokens ordered by (cluster, position)
+  uint16_t* s_off = s_list + MAXN;                    // [MAXN+1]  first list entry of every cluster
+  uint8_t* s_wcnt = (uint8_t*)(s_off + MAXN + 4);     // [NW][MAXN] members of cluster m inside wave w (<= 64)
 
   const MatchMergeStream& s = a.s[blockIdx.z];
   if ((int)blockIdx.x >= s.n_items) return;
@@ -49,8 +104,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(4, 8)))
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = it.n, k = it.k;
   const int64_t N = a.N, M = s.M;
-  const u32x4* __restrict__ x = (const u32x4*)s.x + h * N * kRowChunks;
-  const u32x4* __restrict__ v = s.v ? (const u32x4*)s.v + h * N * kRowChunks : nullptr;
+  // wave-uniform bases; the per-lane byte offsets below fit 32 bits (N < 2^25 is checked on the host)
+  const char* __restrict__ x = (const char*)s.x + h * N * kRowBytes;
+  const char* __restrict__ v = s.v ? (const char*)s.v + h * N * kRowBytes : nullptr;
   u32x4* __restrict__ xm = (u32x4*)s.xm + (h * M + it.moff) * kRowChunks;
   u32x4* __restrict__ vm = s.v ? (u32x4*)s.vm + (h * M + it.moff) * kRowChunks : nullptr;
   int32_t* __restrict__ assign = s.assign + h * N + it.start;
@@ -63,9 +119,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(4, 8)))
     const int e = tid + i * NT;
     const int row = e >> 3, c = e & 7;
     if (row < n) {
-      const int64_t src = a.pi ? (int64_t)a.pi[it.start + row] : (int64_t)(it.start + row);
-      xr[i] = __builtin_nontemporal_load(&x[src * kRowChunks + c]);
-      if (v) vr[i] = __builtin_nontemporal_load(&v[src * kRowChunks + c]);
+      const uint32_t src = a.pi ? (uint32_t)a.pi[it.start + row] : (uint32_t)(it.start + row);
+      const uint32_t off = src * kRowBytes + c * 16;
+      xr[i] = __builtin_nontemporal_load((const u32x4*)(x + off));
+      if (v) vr[i] = __builtin_nontemporal_load((const u32x4*)(v + off));
     }
   }
 
@@ -79,9 +136,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(4, 8)))
         if (v) vm[e] = vr[i];
       }
     }
-    for (int t = tid; t < n; t += NT) {
-      assign[t] = it.moff + t;
-      if (score) score[t] = 1.0f;
+    if (tid < n) {
+      assign[tid] = it.moff + tid;
+      if (score) score[tid] = 1.0f;
     }
     return;
   }
@@ -93,129 +150,170 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(4, 8)))
     const int row = e >> 3, c = e & 7;
     if (row < n) *(u32x4*)(tile + row * kLdsRowBytes + c * 16) = xr[i];
   }
-  for (int t = tid; t < n; t += NT) s_cl[t] = -1;
+  s_cl[tid] = -1;
   __syncthreads();
 
   const int l32 = lane & 31, half = lane >> 5;
+  int my_cl = -1;  // cluster of token `tid`
 
   if (s.preset) {
     // Head-uniform variant: the clusters were computed once on the head-averaged tokens.
-    for (int m = tid; m < k; m += NT) s_dpos[m] = (m * n) / k;
-    for (int t = tid; t < n; t += NT) {
-      const int32_t slot = s.preset[it.start + t];
-      s_cl[t] = slot - it.moff;
-      assign[t] = slot;
-      if (score) score[t] = s.preset_score ? s.preset_score[it.start + t] : 1.0f;
+    for (int m = tid; m < k; m += NT) s_dpos[m] = (uint16_t)((m * n) / k);
+    if (tid < n) {
+      const int32_t slot = s.preset[it.start + tid];
+      my_cl = slot - it.moff;
+      assign[tid] = slot;
+      if (score) score[tid] = s.preset_score ? s.preset_score[it.start + tid] : 1.0f;
     }
     __syncthreads();
   } else {
     // ---- 2. inverse norms --------------------------------------------------------------------
-    for (int t = tid; t < n; t += NT) {
+    if (tid < n) {
       float ss = 0.f;
 #pragma unroll
       for (int c = 0; c < kRowChunks; ++c) {
-        const u32x4 w = *(const u32x4*)(tile + t * kLdsRowBytes + c * 16);
+        const bf16x8 w = *(const bf16x8*)(tile + tid * kLdsRowBytes + c * 16);
+        const bf16x2 pr[4] = {__builtin_shufflevector(w, w, 0, 1), __builtin_shufflevector(w, w, 2, 3),
+                              __builtin_shufflevector(w, w, 4, 5), __builtin_shufflevector(w, w, 6, 7)};
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float lo = bf16_lo(w[q]), hi = bf16_hi(w[q]);
-          ss = fmaf(lo, lo, ss);
-          ss = fmaf(hi, hi, ss);
-        }
+        for (int q = 0; q < 4; ++q) ss = __builtin_amdgcn_fdot2_f32_bf16(pr[q], pr[q], ss, false);
       }
-      s_invn[t] = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
+      s_invn[tid] = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
     }
     __syncthreads();
     for (int m = tid; m < k; m += NT) {
       const int p = (m * n) / k;  // dst position of cluster m
-      s_dpos[m] = p;
+      s_dpos[m] = (uint16_t)p;
       s_dinv[m] = s_invn[p];
-      s_cl[p] = m;
+      s_cl[p] = (int16_t)m;
     }
     __syncthreads();
 
     // ---- 3. similarities and arg-max -----------------------------------------------------------
-    const int ntt = (n + 31) >> 5, ndt = (k + 31) >> 5;
-    for (int tt = wave; tt < ntt; tt += NW) {
-      const int tok = tt * 32 + l32;
-      const int tokc = tok < n ? tok : n - 1;
-      bf16x8 bx[4];
+    // Wave w owns the tokens 64w .. 64w+63, i.e. the two 32-token tiles 2w and 2w+1.
+    const int ndt = (k + 31) >> 5;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-        bx[ks] = *(const bf16x8*)(tile + tokc * kLdsRowBytes + ks * 32 + half * 16);
-      float best = -INFINITY;
-      int bm = 0;
-      for (int dt = 0; dt < ndt; ++dt) {
-        const int m = dt * 32 + l32;
-        const int drow = s_dpos[m < k ? m : k - 1];
-        f32x16 acc;
+    for (int sub = 0; sub < 2; ++sub) {
+      const int tt = wave * 2 + sub;
+      if (tt * 32 < n) {
+        const int tok = tt * 32 + l32;
+        const int tokc = tok < n ? tok : n - 1;
+        bf16x8 bx[4];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        for (int ks = 0; ks < 4; ++ks)
+          bx[ks] = *(const bf16x8*)(tile + tokc * kLdsRowBytes + ks * 32 + half * 16);
+        float best = -INFINITY;
+        int bm = 0;
+        for (int dt = 0; dt < ndt; ++dt) {
+          const int m = dt * 32 + l32;
+          const int drow = s_dpos[m < k ? m : k - 1];
+          f32x16 acc;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          const bf16x8 ad = *(const bf16x8*)(tile + drow * kLdsRowBytes + ks * 32 + half * 16);
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad, bx[ks], acc, 0, 0, 0);
-        }
-        // acc[r] = <dst row, token>, dst row = dt*32 + 8*(r/4) + 4*half + r%4, token = l32.
+          for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int mm = dt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-          if (mm < k) {
-            const float sc = acc[r] * s_dinv[mm];
-            if (sc > best) {
-              best = sc;
-              bm = mm;
+          for (int ks = 0; ks < 4; ++ks) {
+            const bf16x8 ad = *(const bf16x8*)(tile + drow * kLdsRowBytes + ks * 32 + half * 16);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad, bx[ks], acc, 0, 0, 0);
+          }
+          // acc[r] = <dst row, token>, dst row = dt*32 + 8*(r/4) + 4*half + r%4, token = l32.
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int mb = dt * 32 + 8 * g + 4 * half;
+            const f32x4 dv = *(const f32x4*)(s_dinv + mb);   // mb is a multiple of 4: aligned
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float sc = acc[4 * g + q] * dv[q];
+              if (mb + q < k && sc > best) {
+                best = sc;
+                bm = mb + q;
+              }
             }
           }
         }
-      }
-      const float ob = __shfl_xor(best, 32);
-      const int om = __shfl_xor(bm, 32);
-      if (ob > best || (ob == best && om < bm)) {
-        best = ob;
-        bm = om;
-      }
-      if (half == 0 && tok < n) {
-        int c = s_cl[tok];
-        float sc = 1.0f;
-        if (c < 0) {
-          c = bm;
-          sc = best * s_invn[tok];
-          s_cl[tok] = c;
+        const float ob = __shfl_xor(best, 32);
+        const int om = __shfl_xor(bm, 32);
+        if (ob > best || (ob == best && om < bm)) {
+          best = ob;
+          bm = om;
         }
-        assign[tok] = it.moff + c;
-        if (score) score[tok] = sc;
+        // lanes 0..31 of sub-tile 0 and lanes 32..63 of sub-tile 1 publish, so that afterwards
+        // thread `tid` holds the result of token `tid`
+        if (half == sub && tok < n) {
+          int c = s_cl[tok];
+          float sc = 1.0f;
+          if (c < 0) {
+            c = bm;
+            sc = best * s_invn[tok];
+          }
+          my_cl = c;
+          assign[tok] = it.moff + c;
+          if (score) score[tok] = sc;
+        }
       }
     }
-    __syncthreads();
+    __syncthreads();   // everybody is done with s_invn / s_dinv
   }
 
-  // ---- 4./5. aggregation ---------------------------------------------------------------------
-  int clr[NC];
-#pragma unroll
-  for (int c = 0; c < NC; ++c) {
-    const int t = lane + 64 * c;
-    clr[c] = t < n ? s_cl[t] : -1;
+  // ---- 4. stable counting sort of the tokens by cluster -----------------------------------------
+  // rank of a token among the tokens of its cluster inside its wave, and per-wave cluster sizes
+  int my_rank = 0;
+  {
+    const unsigned long long lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    for (int m = 0; m < k; ++m) {
+      const unsigned long long b = __ballot(my_cl == m);
+      if (my_cl == m) my_rank = __popcll(b & lt_mask);
+      if (lane == 0) s_wcnt[wave * MAXN + m] = (uint8_t)__popcll(b);
+    }
   }
-  const int64_t head_rows = (h * M + it.moff) * kDHead;
-  for (int pass = 0; pass < 2; ++pass) {
-    uint16_t* __restrict__ out = (uint16_t*)(pass == 0 ? s.xm : s.vm) + head_rows;
-    for (int m = wave; m < k; m += NW) {
-      const int dp = s_dpos[m];
-      float acc = bf16_bits_to_f32(*(const uint16_t*)(tile + dp * kLdsRowBytes + lane * 2));
-      int cnt = 1;
+  __syncthreads();
+  if (wave == 0) {
+    int carry = 0;
+    for (int m0 = 0; m0 < k; m0 += 64) {
+      const int m = m0 + lane;
+      int tot = 0;
+      if (m < k) {
 #pragma unroll
-      for (int c = 0; c < NC; ++c) {
-        if (c * 64 < n) {
-          unsigned long long mask = __ballot(clr[c] == m && (lane + 64 * c) != dp);
-          while (mask) {
-            const int j = __ffsll((long long)mask) - 1 + 64 * c;
-            acc += bf16_bits_to_f32(*(const uint16_t*)(tile + j * kLdsRowBytes + lane * 2));
-            ++cnt;
-            mask &= mask - 1;
-          }
-        }
+        for (int w = 0; w < NW; ++w) tot += s_wcnt[w * MAXN + m];
       }
-      out[m * kDHead + lane] = f32_to_bf16_bits(acc / (float)cnt);
+      const int excl = wave_exclusive_scan(tot, lane);
+      if (m < k) s_off[m] = (uint16_t)(carry + excl);
+      carry += __shfl(excl + tot, 63);
+    }
+    if (lane == 0) s_off[k] = (uint16_t)carry;
+  }
+  __syncthreads();
+  if (my_cl >= 0) {
+    int pos = s_off[my_cl] + my_rank;
+    for (int w = 0; w < wave; ++w) pos += s_wcnt[w * MAXN + my_cl];
+    s_list[pos] = (uint16_t)tid;
+  }
+  __syncthreads();
+
+  // ---- 5. aggregation: thread (cluster m, 16-byte chunk c) -----------------------------------------
+  const PairSelectors sel = make_pair_selectors();
+  for (int pass = 0; pass < 2; ++pass) {
+    u32x4* __restrict__ out = pass == 0 ? xm : vm;
+    for (int mc = tid; mc < k * kRowChunks; mc += NT) {
+      const int m = mc >> 3, c = mc & 7;
+      const int dp = s_dpos[m];
+      const int beg = s_off[m], end = s_off[m + 1];
+      float acc[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+      add_row_chunk(acc, tile + dp * kLdsRowBytes + c * 16, sel);         // the dst token first
+      int j = s_list[beg];
+      for (int idx = beg; idx < end; ++idx) {                           // then src, ascending
+        const int jn = idx + 1 < end ? s_list[idx + 1] : dp;
+        if (j != dp) add_row_chunk(acc, tile + j * kLdsRowBytes + c * 16, sel);
+        j = jn;
+      }
+      const float cnt = (float)(end - beg);
+      const float rcnt = 1.0f / cnt;
+      u32x4 o;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        o[q] = pack_bf16x2(div_by_count(acc[2 * q], cnt, rcnt), div_by_count(acc[2 * q + 1], cnt, rcnt));
+      out[mc] = o;
     }
     if (pass == 1 || v == nullptr) break;
     __syncthreads();
