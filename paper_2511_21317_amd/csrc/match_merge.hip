@@ -187,6 +187,9 @@ void match_merge_kernel(const MatchMergeArgs a) {
       s_dinv[m] = s_invn[p];
       s_cl[p] = (int16_t)m;
     }
+    // pad the last 32-wide dst tile with NaN: a NaN score never compares greater, so the
+    // arg-max below needs no bounds test
+    for (int m = k + tid; m < ((k + 31) & ~31); m += NT) s_dinv[m] = __builtin_nanf("");
     __syncthreads();
 
     // ---- 3. similarities and arg-max -----------------------------------------------------------
@@ -223,7 +226,7 @@ void match_merge_kernel(const MatchMergeArgs a) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
               const float sc = acc[4 * g + q] * dv[q];
-              if (mb + q < k && sc > best) {
+              if (sc > best) {
                 best = sc;
                 bm = mb + q;
               }
@@ -255,15 +258,23 @@ void match_merge_kernel(const MatchMergeArgs a) {
   }
 
   // ---- 4. stable counting sort of the tokens by cluster -----------------------------------------
-  // rank of a token among the tokens of its cluster inside its wave, and per-wave cluster sizes
+  // Rank of a token among the tokens of its cluster inside its wave, and per-wave cluster sizes.
+  // The set of lanes that hold the same cluster id is built bit by bit from wave ballots
+  // (log2(k) rounds instead of one round per cluster).
   int my_rank = 0;
+  for (int m = lane; m < k; m += 64) s_wcnt[wave * MAXN + m] = 0;   // each wave clears its own row
   {
-    const unsigned long long lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    for (int m = 0; m < k; ++m) {
-      const unsigned long long b = __ballot(my_cl == m);
-      if (my_cl == m) my_rank = __popcll(b & lt_mask);
-      if (lane == 0) s_wcnt[wave * MAXN + m] = (uint8_t)__popcll(b);
+    unsigned long long same = __ballot(my_cl >= 0);
+    for (int bit = 0; (1 << bit) < k; ++bit) {
+      const bool set = (my_cl >> bit) & 1;
+      const unsigned long long b = __ballot(set);
+      same &= set ? b : ~b;
     }
+    if (my_cl >= 0) {
+      my_rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(same >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)same, 0u));
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // same wave wrote the zeros above
+    if (my_cl >= 0 && my_rank == 0) s_wcnt[wave * MAXN + my_cl] = (uint8_t)__popcll(same);
   }
   __syncthreads();
   if (wave == 0) {
@@ -283,9 +294,13 @@ void match_merge_kernel(const MatchMergeArgs a) {
   }
   __syncthreads();
   if (my_cl >= 0) {
-    int pos = s_off[my_cl] + my_rank;
-    for (int w = 0; w < wave; ++w) pos += s_wcnt[w * MAXN + my_cl];
-    s_list[pos] = (uint16_t)tid;
+    // position among the members of the cluster in ascending token order ...
+    int rank = my_rank;
+    for (int w = 0; w < wave; ++w) rank += s_wcnt[w * MAXN + my_cl];
+    // ... re-ordered so that the dst token comes first and the src tokens keep their order
+    const int dp = s_dpos[my_cl];
+    const int pos = tid == dp ? 0 : rank + (dp < tid ? 0 : 1);
+    s_list[s_off[my_cl] + pos] = (uint16_t)tid;
   }
   __syncthreads();
 
@@ -295,18 +310,21 @@ void match_merge_kernel(const MatchMergeArgs a) {
     u32x4* __restrict__ out = pass == 0 ? xm : vm;
     for (int mc = tid; mc < k * kRowChunks; mc += NT) {
       const int m = mc >> 3, c = mc & 7;
-      const int dp = s_dpos[m];
       const int beg = s_off[m], end = s_off[m + 1];
       float acc[8];
 #pragma unroll
       for (int q = 0; q < 8; ++q) acc[q] = 0.f;
-      add_row_chunk(acc, tile + dp * kLdsRowBytes + c * 16, sel);         // the dst token first
-      int j = s_list[beg];
-      for (int idx = beg; idx < end; ++idx) {                           // then src, ascending
-        const int jn = idx + 1 < end ? s_list[idx + 1] : dp;
-        if (j != dp) add_row_chunk(acc, tile + j * kLdsRowBytes + c * 16, sel);
-        j = jn;
+      // members in list order: the dst token, then its src tokens in ascending position
+      const unsigned char* col = tile + c * 16;
+      int idx = beg;
+      for (; idx + 2 <= end; idx += 2) {
+        const int j0 = s_list[idx], j1 = s_list[idx + 1];
+        const unsigned char* r0 = col + j0 * kLdsRowBytes;
+        const unsigned char* r1 = col + j1 * kLdsRowBytes;
+        add_row_chunk(acc, r0, sel);
+        add_row_chunk(acc, r1, sel);
       }
+      if (idx < end) add_row_chunk(acc, col + s_list[idx] * kLdsRowBytes, sel);
       const float cnt = (float)(end - beg);
       const float rcnt = 1.0f / cnt;
       u32x4 o;
