@@ -93,7 +93,12 @@ __global__ __launch_bounds__(kThreads) void unmerge_fused_kernel(const u32x4* __
   extern __shared__ int32_t lds[];
   int32_t* s_assign = lds;             // [H][kTok]
   int32_t* s_pi = lds + H * kTok;      // [kTok]
-  const int64_t j0 = (int64_t)blockIdx.x * kTok;
+  // Workgroups go round-robin to the 8 XCDs; give every XCD a contiguous range of token tiles so
+  // that the tiles of one merging block, which read the same few rows of o_m, share one L2.
+  const int per_xcd = gridDim.x >> 3;
+  const int64_t tile = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  const int64_t j0 = tile * kTok;
+  if (j0 >= N) return;
   for (int e = threadIdx.x; e < H * kTok; e += kThreads) {
     const int h = e / kTok, t = e % kTok;
     const int64_t j = j0 + t;
@@ -149,7 +154,7 @@ hipError_t launch_unmerge(const void* o_m, const int32_t* assign, const int32_t*
                           int H, int64_t N, int64_t M_q, int fused, hipStream_t stream) {
   if (N == 0 || H == 0) return hipSuccess;
   if (fused) {
-    dim3 grid((unsigned)((N + kTok - 1) / kTok));
+    dim3 grid((unsigned)(((N + kTok - 1) / kTok + 7) / 8 * 8));
     const size_t lds = (size_t)(H * kTok + kTok) * sizeof(int32_t);
     hipLaunchKernelGGL(unmerge_fused_kernel, grid, dim3(kThreads), lds, stream, (const u32x4*)o_m,
                        assign, pi_dev, (u32x4*)out, H, N, M_q);
