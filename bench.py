@@ -50,6 +50,19 @@ def gpu_time_ms(fn, iters, warmup=1):
     return start.elapsed_time(end) / iters
 
 
+def pmc_traffic_bytes(kernel: str, workload_index: int):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload
+    (FETCH_SIZE + WRITE_SIZE, already scaled by the copy-kernel calibration), or None."""
+    import glob
+    for path in glob.glob(os.path.join(ROOT, "profiles", f"hbm_traffic_pmc_cfg{workload_index}_*.txt")):
+        for line in open(path):
+            t = line.split()
+            if t and t[0] == kernel and "|" in t:
+                cols = [c.split() for c in line.split("|")]
+                return (float(cols[1][0]) + float(cols[1][1])) * 1e6
+    return None
+
+
 def cpu_oracle_baseline(w, q, k, v, budget_s=20.0):
     """Time the oracle (as it stands) on the first heads of the workload until ~budget_s is used."""
     import numpy as np
@@ -169,7 +182,9 @@ def main():
     achieved = f_attn / (t_attn * 1e-3) / 1e12
     roofline = {"kernel": "attention_kernel", "bound": "mfma", "achieved": achieved,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                "traffic": None, "flop_per_launch": f_attn, "ms_per_launch": t_attn}
+                "traffic": pmc_traffic_bytes("attention_kernel", w.index),
+                "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, see profiles/)",
+                "flop_per_launch": f_attn, "ms_per_launch": t_attn}
 
     # ---- extras: unmerged attention and the head-uniform variant on the same inputs -------------
     extras = {}

@@ -203,6 +203,35 @@ def test_attention_with_large_logits_stays_finite():
     check_output(got, want, "large logits", relative_to_magnitude=True)
 
 
+@pytest.mark.parametrize("where", ["second_step", "late", "everywhere_growing"])
+def test_attention_shift_is_raised_when_later_keys_dominate(where):
+    """The softmax shift is fixed from the first 32 keys; keys whose logits exceed it by more than
+    2^60 must take the overflow path (raise the shift, rescale the accumulators) and still match."""
+    require_gpu()
+    gen = torch.Generator().manual_seed(99)
+    mq, mk = 150, 1000
+    qm = torch.randn((mq, 64), generator=gen) * 3
+    km = torch.randn((mk, 64), generator=gen) * 0.01          # first keys: logits ~ 0
+    vm = torch.randn((mk, 64), generator=gen)
+    if where == "second_step":
+        km[32:64] = torch.randn((32, 64), generator=gen) * 40     # jump right after the first step
+    elif where == "late":
+        km[700:] = torch.randn((300, 64), generator=gen) * 40
+    else:
+        km = torch.randn((mk, 64), generator=gen) * torch.linspace(0.01, 60, mk)[:, None]
+    qm, km, vm = (t.to(torch.bfloat16).cuda() for t in (qm, km, vm))
+    om = torch.empty_like(qm)
+    httm.attention(qm, km, vm, om, [0, mq], [0, mk], 0.125)
+    torch.cuda.synchronize()
+    want = orc.attention(f32(qm), f32(km), f32(vm))
+    logits = f32(qm) @ f32(km).T * 0.125
+    jump = (logits.max(axis=1) - logits[:, :32].max(axis=1)) * 1.4427
+    assert (jump > 60).mean() > 0.5, "the case must actually exercise the overflow path"
+    got = f32(om)
+    assert np.isfinite(got).all()
+    check_output(got, want, f"shift raise ({where})", relative_to_magnitude=True)
+
+
 def test_bad_arguments_launch_nothing():
     require_gpu()
     w = synth.workload(1)
