@@ -125,10 +125,17 @@ struct StepOperands {
   bf16x8 av[4];
 };
 
+// K tile in LDS: 64 rows of 128 bytes, unpadded (it is written by global->LDS loads, 1 KB per
+// wave instruction); the 16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7), which
+// makes the operand reads of 16 consecutive rows hit 16 distinct bank groups.
+__device__ __forceinline__ int k_swizzle(int row) { return (row >> 1) & 7; }
+
+// `sk` points at the first of the 32 rows of this step (row 0 or 32 of the tile).
 __device__ __forceinline__ void load_k_operands(StepOperands& op, const bf16_t* sk, int l32, int half) {
+  const int sw = k_swizzle(l32);
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks)
-    op.ak[ks] = *(const bf16x8*)(sk + l32 * kLdsRowElems + ks * 16 + half * 8);
+    op.ak[ks] = *(const bf16x8*)(sk + l32 * kDHead + ((ks * 2 + half) ^ sw) * 8);
 }
 __device__ __forceinline__ void load_v_operands(StepOperands& op, const bf16_t* svt, int l32, int half) {
 #pragma unroll
@@ -253,8 +260,9 @@ void attention_kernel(const AttnArgs a) {
   constexpr int LDV_ITER = LD_ITER / 2;                    // V row pairs per thread per tile
   constexpr int ROWS_PER_PASS = NT / 8;
   static_assert(LD_ITER >= 2 && LD_ITER % 2 == 0, "tile staging needs an even chunk count");
-  constexpr int kTileElems = kKvTile * kLdsRowElems;
-  __shared__ __align__(16) bf16_t s_k[2][kTileElems];    // [kv][d], 144-byte rows
+  constexpr int kTileElems = kKvTile * kDHead;
+  constexpr int LDK = 8 / NW;                              // 1 KB global->LDS loads per wave per tile
+  __shared__ __align__(16) bf16_t s_k[2][kTileElems];    // [kv][d], 128-byte rows, chunk-swizzled
   __shared__ __align__(16) bf16_t s_vt[2][kVtTileElems]; // [d][kv position], skewed 144-byte rows
 
   // blockIdx -> (head, first query row).  Workgroups go round-robin to the 8 XCDs, and in
@@ -313,13 +321,22 @@ void attention_kernel(const AttnArgs a) {
   const char* kg = (const char*)(a.k + k_base * kDHead);   // wave-uniform bases; per-lane offsets
   const char* vg = (const char*)(a.v + k_base * kDHead);   // below fit 32 bits (rows < 2^24 here)
   const int ld_c = tid & 7, ld_r = tid >> 3;  // chunk, row-in-pass
-  u32x4 kreg[LD_ITER], vreg[LD_ITER];
-  auto load_k = [&](int kv0) {
+  u32x4 vreg[LD_ITER];
+  // K: straight from global memory into LDS, no registers.  Lane l of a wave instruction fills
+  // bytes [16 l, 16 l + 16) of a 1 KB block = rows 8*blk .. 8*blk+7; it fetches the chunk that
+  // belongs at its position under the swizzle.
+  auto load_k = [&](int kv0, int buf) {
 #pragma unroll
-    for (int i = 0; i < LD_ITER; ++i) {
-      int row = kv0 + ld_r + ROWS_PER_PASS * i;
+    for (int i = 0; i < LDK; ++i) {
+      const int blk = wave * LDK + i;
+      const int r = blk * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ k_swizzle(r);
+      int row = kv0 + r;
       row = row < Mk ? row : Mk - 1;
-      kreg[i] = *(const u32x4*)(kg + (uint32_t)(row * kRowBytes + ld_c * 16));
+      const char* src = kg + (uint32_t)(row * kRowBytes + c * 16);
+      bf16_t* dst = &s_k[buf][blk * 512];
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
     }
   };
   auto load_v = [&](int kv0) {
@@ -331,11 +348,6 @@ void attention_kernel(const AttnArgs a) {
         row = row < Mk ? row : Mk - 1;
         vreg[2 * i + u] = *(const u32x4*)(vg + (uint32_t)(row * kRowBytes + ld_c * 16));
       }
-  };
-  auto store_k = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < LD_ITER; ++i)
-      *(u32x4*)(&s_k[buf][(ld_r + ROWS_PER_PASS * i) * kLdsRowElems + ld_c * 8]) = kreg[i];
   };
   auto store_v = [&](int buf) {
     // V rows 2r and 2r+1, channels ld_c*8 .. +7  ->  V^T[channel][pos], two keys per 32-bit word
@@ -362,22 +374,21 @@ void attention_kernel(const AttnArgs a) {
   // other LDS buffers.
 
   // ---- j = 0 ---------------------------------------------------------------------------------------
-  load_k(0);
-  store_k(0);
+  load_k(0, 0);
   load_v(0);
-  if (n_tiles > 1) load_k(kKvTile);
+  if (n_tiles > 1) load_k(kKvTile, 1);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the global->LDS loads have landed
   __syncthreads();
   if (active) {
     pipeline_step<QT, true, false, false, false, false>(w, &s_k[0][0], nullptr, c, 0, Mk, l32, half);
     if (n_tiles > 1)
-      pipeline_step<QT, true, false, true, false, true>(w, &s_k[0][kStep * kLdsRowElems], nullptr, c, 0,
+      pipeline_step<QT, true, false, true, false, true>(w, &s_k[0][kStep * kDHead], nullptr, c, 0,
                                                         Mk, l32, half);
     else
-      pipeline_step<QT, true, false, true, true, true>(w, &s_k[0][kStep * kLdsRowElems], nullptr, c, 0,
+      pipeline_step<QT, true, false, true, true, true>(w, &s_k[0][kStep * kDHead], nullptr, c, 0,
                                                        Mk, l32, half);
   }
   store_v(0);
-  if (n_tiles > 1) store_k(1);
   __syncthreads();
 
   // ---- j = 1 .. n_tiles-2: steady state, no masking ------------------------------------------------
@@ -390,16 +401,16 @@ void attention_kernel(const AttnArgs a) {
       load_k_operands(op, kb, l32, half);
       load_v_operands(op, vb, l32, half);
     }
-    load_k((j + 1) * kKvTile);
+    load_k((j + 1) * kKvTile, (j + 1) & 1);
     load_v(j * kKvTile);
     if (active) {
       pipeline_step<QT, true, true, true, false, false, true, true>(
-          w, nullptr, nullptr, c, 0, Mk, l32, half, &op, kb + kStep * kLdsRowElems, vb + kStep);
+          w, nullptr, nullptr, c, 0, Mk, l32, half, &op, kb + kStep * kDHead, vb + kStep);
       pipeline_step<QT, true, true, true, false, false, true, false>(w, nullptr, nullptr, c, 0, Mk,
                                                                      l32, half, &op);
     }
-    store_k((j + 1) & 1);
     store_v(j & 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): K tile j+1 is in LDS
     __syncthreads();
   }
 
@@ -410,7 +421,7 @@ void attention_kernel(const AttnArgs a) {
     const bf16_t* vb = &s_vt[(j - 1) & 1][0];
     if (active) {
       pipeline_step<QT, true, true, true, false, false>(w, kb, vb, c, 0, Mk, l32, half);
-      pipeline_step<QT, true, true, true, true, false>(w, kb + kStep * kLdsRowElems, vb + kStep, c,
+      pipeline_step<QT, true, true, true, true, false>(w, kb + kStep * kDHead, vb + kStep, c,
                                                        2 * j * kStep, Mk, l32, half);
     }
     store_v(j & 1);
