@@ -187,6 +187,33 @@ def test_attention_on_ragged_heads(mq, mk):
         check_output(got, want, f"ragged head {h} ({mq[h]}x{mk[h]})")
 
 
+def test_attention_partial_tiles_in_a_large_grid():
+    """In a grid of many workgroups a short partial tile is computed by the workgroup of the head's
+    last full tile (second pass); longer partial tiles and heads that are a whole number of tiles
+    sit beside it.  Checks the rows around every head's end and start."""
+    require_gpu()
+    mq = [65536 + 20, 65536 + 100, 65536 + 200, 65536, 40]
+    mk = [70, 130, 64, 200, 90]
+    print(f"[case] large-grid ragged attention mq={mq} mk={mk}", flush=True)
+    gen = torch.Generator().manual_seed(4242)
+    qo = np.concatenate([[0], np.cumsum(mq)])
+    ko = np.concatenate([[0], np.cumsum(mk)])
+    qm = torch.randn((int(qo[-1]), 64), generator=gen).to(torch.bfloat16).cuda()
+    km = torch.randn((int(ko[-1]), 64), generator=gen).to(torch.bfloat16).cuda()
+    vm = torch.randn((int(ko[-1]), 64), generator=gen).to(torch.bfloat16).cuda()
+    om = torch.full_like(qm, float("nan"))
+    httm.attention(qm, km, vm, om, qo, ko, 0.125)
+    torch.cuda.synchronize()
+    assert not torch.isnan(om.float()).any()
+    for h in range(len(mq)):
+        rows = np.unique(np.concatenate([np.arange(min(300, mq[h])),
+                                         np.arange(max(0, mq[h] - 800), mq[h])]))
+        got = f32(om[qo[h]:qo[h + 1]])[rows]
+        want = orc.attention(f32(qm[qo[h]:qo[h + 1]])[rows], f32(km[ko[h]:ko[h + 1]]),
+                             f32(vm[ko[h]:ko[h + 1]]))
+        check_output(got, want, f"large-grid ragged head {h} ({mq[h]}x{mk[h]})")
+
+
 def test_attention_with_large_logits_stays_finite():
     """Online softmax: rows whose maximum moves a lot between key tiles."""
     require_gpu()
