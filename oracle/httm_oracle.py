@@ -63,6 +63,7 @@ class Geometry:
     b: int              # spatial block edge (patches)
     T: int              # temporal block length (frames)
     n_special: int = 5  # special tokens at the front of each frame
+    anchor: bool = False  # first-frame anchoring (App. C.2): every frame-0 token is a dst
 
     @property
     def tokens_per_frame(self) -> int:
@@ -116,6 +117,27 @@ def temporal_reorder(g: Geometry):
     return np.asarray(pi, dtype=np.int64), blocks
 
 
+def anchor_sizes(g: Geometry) -> list:
+    """Per block (same order as `temporal_reorder`): number of leading tokens forced to be dst.
+
+    First-frame anchoring (App. C.2, "Error Mitigation"): all tokens of frame 0 are dst tokens, so
+    that similar tokens of later frames merge into them.  Blocks are frame-major, hence in the
+    blocks of the first temporal group the frame-0 tokens are the first (rows x cols) positions;
+    every other block has none.
+    """
+    n_groups = -(-g.S // g.T)
+    n_by = -(-g.Hp // g.b)
+    n_bx = -(-g.Wp // g.b)
+    out = []
+    for grp in range(n_groups):
+        for by in range(n_by):
+            rows = min(g.Hp, (by + 1) * g.b) - by * g.b
+            for bx in range(n_bx):
+                cols = min(g.Wp, (bx + 1) * g.b) - bx * g.b
+                out.append(rows * cols if (g.anchor and grp == 0) else 0)
+    return out
+
+
 def reorder(x: np.ndarray, pi: np.ndarray) -> np.ndarray:
     """x[..., L, E] -> rows gathered into block order: out[j] = x[pi[j]]."""
     return np.take(x, pi, axis=-2)
@@ -132,15 +154,24 @@ def inverse_reorder(xr: np.ndarray, pi: np.ndarray) -> np.ndarray:
 # Sec. 3.2 "Merging" restricted to blocks (Sec. 3.3); Alg. 1 "BlockwiseToMe"
 # --------------------------------------------------------------------------
 
-def cluster_count(n: int, rho: float) -> int:
-    """Tokens a block of n keeps when a fraction rho is merged away (M = N - r)."""
+def cluster_count(n: int, rho: float, n0: int = 0) -> int:
+    """Tokens a block of n keeps when a fraction rho is merged away (M = N - r).
+
+    With n0 anchored tokens (all of them dst) the block keeps at least those.
+    """
     r = int(math.floor(rho * n + 1e-9))
-    return max(1, n - r)
+    return max(1, n - r, n0)
 
 
-def dst_positions(n: int, k: int) -> list:
-    """Block-local positions of the k dst tokens (evenly strided, first token included)."""
-    return [(m * n) // k for m in range(k)]
+def dst_positions(n: int, k: int, n0: int = 0) -> list:
+    """Block-local positions of the k dst tokens.
+
+    The n0 anchored tokens at the front of the block are dst; the other k - n0 dst are evenly
+    strided over the remaining n - n0 tokens, the first of them included (n0 = 0: evenly strided
+    over the whole block).
+    """
+    assert n0 <= k <= n
+    return list(range(n0)) + [n0 + (m * (n - n0)) // (k - n0) for m in range(k - n0)]
 
 
 def row_norm(x: np.ndarray) -> np.ndarray:
@@ -149,7 +180,7 @@ def row_norm(x: np.ndarray) -> np.ndarray:
     return x / np.maximum(nrm, x.dtype.type(EPS_NORM))[:, None]
 
 
-def match_block(xb: np.ndarray, k: int):
+def match_block(xb: np.ndarray, k: int, n0: int = 0):
     """Bipartite matching inside one block (Eq. 1 and the best-match rule).
 
     xb: [n, E] tokens of the block.  Returns
@@ -158,7 +189,7 @@ def match_block(xb: np.ndarray, k: int):
       gap[n]      best minus second-best similarity (inf for dst tokens / k = 1).
     """
     n = xb.shape[0]
-    dpos = dst_positions(n, k)
+    dpos = dst_positions(n, k, n0)
     is_dst = np.zeros(n, dtype=bool)
     is_dst[dpos] = True
     spos = np.flatnonzero(~is_dst)
@@ -186,8 +217,8 @@ def merged_layout(g: Geometry, blocks, rho: float):
     """
     ks, offs = [], []
     pos = g.n_prefix
-    for (_, n) in blocks:
-        k = cluster_count(n, rho)
+    for (_, n), n0 in zip(blocks, anchor_sizes(g)):
+        k = cluster_count(n, rho, n0)
         ks.append(k)
         offs.append(pos)
         pos += k
@@ -207,8 +238,8 @@ def blockwise_tome(xr: np.ndarray, g: Geometry, blocks, rho: float):
     score = np.ones(L, dtype=xr.dtype)
     gap = np.full(L, np.inf, dtype=xr.dtype)
     assign[:g.n_prefix] = np.arange(g.n_prefix)        # specials pass through
-    for (start, n), k, off in zip(blocks, ks, offs):
-        c, s, gp = match_block(xr[start:start + n], k)
+    for (start, n), k, off, n0 in zip(blocks, ks, offs, anchor_sizes(g)):
+        c, s, gp = match_block(xr[start:start + n], k, n0)
         assign[start:start + n] = off + c
         score[start:start + n] = s
         gap[start:start + n] = gp
@@ -230,8 +261,8 @@ def block_aggregate(xr: np.ndarray, assign: np.ndarray, g: Geometry, blocks, rho
     count = np.zeros(M, dtype=np.int64)
     out[:g.n_prefix] = xr[:g.n_prefix]
     count[:g.n_prefix] = 1
-    for (start, n), k, off in zip(blocks, ks, offs):
-        dpos = dst_positions(n, k)
+    for (start, n), k, off, n0 in zip(blocks, ks, offs, anchor_sizes(g)):
+        dpos = dst_positions(n, k, n0)
         dset = set(dpos)
         for m, j in enumerate(dpos):
             out[off + m] = xr[start + j]
@@ -348,8 +379,8 @@ def rep_map(assign: np.ndarray, pi: np.ndarray, g: Geometry, blocks, rho: float)
     ks, offs, M = merged_layout(g, blocks, rho)
     slot_owner = np.empty(M, dtype=np.int64)
     slot_owner[:g.n_prefix] = pi[:g.n_prefix]
-    for (start, n), k, off in zip(blocks, ks, offs):
-        for m, j in enumerate(dst_positions(n, k)):
+    for (start, n), k, off, n0 in zip(blocks, ks, offs, anchor_sizes(g)):
+        for m, j in enumerate(dst_positions(n, k, n0)):
             slot_owner[off + m] = pi[start + j]
     rep = np.empty(g.N, dtype=np.int64)
     rep[pi] = slot_owner[assign]

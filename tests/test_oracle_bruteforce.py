@@ -33,15 +33,20 @@ def _blocks_bruteforce(S, Hp, Wp, b, T, n_special):
     return specials, [groups[key] for key in sorted(groups)]
 
 
-def _merge_head(x, specials, blocks, rho):
+def _merge_head(x, specials, blocks, rho, anchor_below=0):
     """x: list of N vectors.  Returns (clusters, owner): clusters = list of member lists (input
-    indices, dst first), in merged order; owner[i] = index into clusters for input token i."""
+    indices, dst first), in merged order; owner[i] = index into clusters for input token i.
+    Tokens with input index < anchor_below (= the tokens of frame 0 under first-frame anchoring,
+    App. C.2) are always dst; the other dst are strided over the rest of the block."""
     clusters = [[i] for i in specials]
     owner = {i: c for c, i in enumerate(specials)}
     for toks in blocks:
         n = len(toks)
-        k = max(1, n - int(math.floor(rho * n + 1e-9)))
-        dpos = [(m * n) // k for m in range(k)]
+        anchored = [p for p, i in enumerate(toks) if i < anchor_below]
+        others = [p for p, i in enumerate(toks) if i >= anchor_below]
+        k = max(1, n - int(math.floor(rho * n + 1e-9)), len(anchored))
+        free = k - len(anchored)
+        dpos = anchored + [others[(m * len(others)) // free] for m in range(free)]
         base = len(clusters)
         for m, p in enumerate(dpos):
             clusters.append([toks[p]])
@@ -64,15 +69,16 @@ def _mean(vectors):
     return [math.fsum(v[c] for v in vectors) / len(vectors) for c in range(E)]
 
 
-def _layer_bruteforce(q, k, v, S, Hp, Wp, b, T, n_special, rho_q, rho_kv):
+def _layer_bruteforce(q, k, v, S, Hp, Wp, b, T, n_special, rho_q, rho_kv, anchor=False):
     H, N, E = q.shape
     specials, blocks = _blocks_bruteforce(S, Hp, Wp, b, T, n_special)
+    anchor_below = (n_special + Hp * Wp) if anchor else 0      # input indices of frame 0
     out = np.zeros((N, H * E))
     owners_q, owners_k = [], []
     for h in range(H):
         qh, kh, vh = q[h].tolist(), k[h].tolist(), v[h].tolist()
-        cq, own_q = _merge_head(qh, specials, blocks, rho_q)
-        ck, own_k = _merge_head(kh, specials, blocks, rho_kv)
+        cq, own_q = _merge_head(qh, specials, blocks, rho_q, anchor_below)
+        ck, own_k = _merge_head(kh, specials, blocks, rho_kv, anchor_below)
         qm = [_mean([qh[i] for i in mem]) for mem in cq]
         km = [_mean([kh[i] for i in mem]) for mem in ck]
         vm = [_mean([vh[i] for i in mem]) for mem in ck]      # V follows K's matches
@@ -117,6 +123,42 @@ def test_oracle_equals_bruteforce(case, dtype):
         assert np.array_equal(orc.rep_map(res["assign_k"][h], pi, g, blocks, rho_kv), ref_rep_k[h])
     tol = 1e-5 if dtype == np.float32 else 1e-12
     assert np.abs(res["O"] - ref_out).max() < tol
+
+
+ANCHORED = [
+    (3, 3, 4, 2, 2, 5, 0.5, 0.5),
+    (4, 3, 3, 2, 3, 1, 0.6, 0.8),
+    (2, 4, 4, 2, 2, 5, 0.9, 0.9),    # the ratio asks for fewer clusters than frame 0 has tokens
+    (5, 2, 5, 3, 4, 0, 0.75, 0.3),
+    (1, 3, 3, 2, 2, 2, 0.5, 0.5),    # a single frame: every token is anchored, nothing merges
+]
+
+
+@pytest.mark.parametrize("case", ANCHORED)
+def test_oracle_equals_bruteforce_with_first_frame_anchoring(case):
+    """App. C.2: all frame-0 tokens are dst.  The brute force decides "frame 0" from the input
+    index; the oracle from the position inside the reordered block."""
+    S, Hp, Wp, b, T, nsp, rho_q, rho_kv = case
+    g = orc.Geometry(S, Hp, Wp, b, T, n_special=nsp, anchor=True)
+    H, E = 2, 8
+    rng = np.random.default_rng(4321 + S * 100 + Hp * 10 + Wp)
+    q, k, v = (rng.standard_normal((H, g.N, E)) for _ in range(3))
+    ref_out, ref_rep_q, ref_rep_k = _layer_bruteforce(q, k, v, S, Hp, Wp, b, T, nsp, rho_q, rho_kv,
+                                                      anchor=True)
+    res = orc.layer_forward(q, k, v, g, rho_q, rho_kv, dtype=np.float64)
+    pi, blocks = res["pi"], res["blocks"]
+    tpf = nsp + Hp * Wp
+    for h in range(H):
+        rq = orc.rep_map(res["assign_q"][h], pi, g, blocks, rho_q)
+        assert np.array_equal(rq, ref_rep_q[h])
+        assert np.array_equal(orc.rep_map(res["assign_k"][h], pi, g, blocks, rho_kv), ref_rep_k[h])
+        assert np.array_equal(rq[:tpf], np.arange(tpf))       # frame 0 is never merged away
+    assert np.abs(res["O"] - ref_out).max() < 1e-12
+    # anchoring is not a no-op on these cases (except the single-frame one)
+    plain = orc.layer_forward(q, k, v, orc.Geometry(S, Hp, Wp, b, T, n_special=nsp), rho_q, rho_kv,
+                              dtype=np.float64)
+    if S > 1:
+        assert np.abs(plain["O"] - res["O"]).max() > 1e-6
 
 
 def test_bruteforce_catches_a_transposed_or_dropped_term():

@@ -111,3 +111,32 @@ def test_dst_positions_are_strided_distinct_and_start_at_zero(n, k):
     assert d[0] == 0 and len(set(d)) == k and d == sorted(d) and d[-1] < n
     gaps = np.diff(d + [n])
     assert gaps.max() - gaps.min() <= 1
+
+
+@pytest.mark.parametrize("S,Hp,Wp,b,T", [(4, 5, 7, 2, 2), (3, 37, 37, 4, 4), (1, 4, 4, 4, 2), (8, 16, 16, 8, 3)])
+def test_anchor_sizes_cover_frame_zero_exactly(S, Hp, Wp, b, T):
+    """App. C.2: the anchored tokens are exactly the patch tokens of frame 0 (closed form: Hp*Wp of
+    them, all in the first temporal group, at the front of their blocks)."""
+    g = orc.Geometry(S, Hp, Wp, b, T, anchor=True)
+    pi, blocks = orc.temporal_reorder(g)
+    n0s = orc.anchor_sizes(g)
+    assert len(n0s) == len(blocks)
+    assert sum(n0s) == Hp * Wp
+    tpf = g.tokens_per_frame
+    for (start, n), n0 in zip(blocks, n0s):
+        frames = pi[start:start + n] // tpf
+        assert (frames[:n0] == 0).all() and (frames[n0:] != 0).all()
+    assert orc.anchor_sizes(orc.Geometry(S, Hp, Wp, b, T)) == [0] * len(blocks)
+
+
+@pytest.mark.parametrize("n,k,n0", [(64, 16, 16), (64, 20, 16), (64, 64, 16), (48, 12, 12), (7, 5, 3), (5, 5, 5)])
+def test_anchored_dst_positions(n, k, n0):
+    d = orc.dst_positions(n, k, n0)
+    assert len(d) == k and len(set(d)) == k and d == sorted(d)
+    assert d[:n0] == list(range(n0))
+    if k > n0:
+        assert d[n0] == n0                      # the first free token is a dst, as without anchoring
+        rest = [p - n0 for p in d[n0:]]
+        assert rest == orc.dst_positions(n - n0, k - n0)
+    assert orc.cluster_count(n, 0.99, n0) == max(1, n0)
+    assert orc.cluster_count(n, 0.0, n0) == n
