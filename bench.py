@@ -201,6 +201,16 @@ def main():
         plan_u.close()
         del ws_u
         torch.cuda.empty_cache()
+        plan_a = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H, n_special=w.n_special,
+                                          anchor_first_frame=True))
+        ws_a = httm.alloc_workspace(plan_a)
+        t_anc = gpu_time_ms(lambda: httm.layer_forward(plan_a, q, k, v, out_u, ws_a), max(2, it // 2))
+        extras["first_frame_anchored_layer"] = {"ms": t_anc, "tokens/s": N / (t_anc * 1e-3),
+                                                "M_q": plan_a.M_q}
+        log(f"[bench] first-frame-anchored layer: {t_anc:.3f} ms (M = {plan_a.M_q})")
+        plan_a.close()
+        del ws_a
+        torch.cuda.empty_cache()
         plan_0 = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, 0.0, H=w.H,
                                           n_special=w.n_special, variant="none"))
         ws_0 = httm.alloc_workspace(plan_0)

@@ -75,6 +75,12 @@ enum {
   HTTM_VARIANT_NONE = 2           /* no merging (rho ignored): plain multi-head attention, Eq. 3-4 with M = N */
 };
 
+/* First-frame anchoring (App. C.2, "Error Mitigation"): every patch token of frame 0 is a dst token,
+ * so that similar tokens of the later frames of the first temporal group merge into them and
+ * frame 0 itself is never merged away.  A block of the first group keeps max(k, n0) clusters, n0 its
+ * frame-0 tokens; its other dst tokens are strided over the rest of the block.  Applies to Q and K. */
+#define HTTM_FLAG_ANCHOR_FIRST_FRAME 1
+
 #define HTTM_MAX_BLOCK 512        /* largest merging block (b*b*T tokens) the kernels accept */
 #define HTTM_MAX_HEADS 64
 
@@ -91,7 +97,7 @@ typedef struct httm_geom {
   double rho_q;       /* fraction of each block's query tokens merged away, 0 <= rho < 1 or 1 */
   double rho_kv;      /* the same for key/value tokens */
   int32_t variant;    /* HTTM_VARIANT_* */
-  int32_t reserved;   /* must be 0 */
+  int32_t flags;      /* HTTM_FLAG_* bits; unknown bits are rejected */
 } httm_geom_t;
 
 /* Sizes derived from a geometry. */

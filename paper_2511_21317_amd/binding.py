@@ -27,7 +27,7 @@ class Geom(C.Structure):
     _fields_ = [("S", C.c_int32), ("Hp", C.c_int32), ("Wp", C.c_int32), ("n_special", C.c_int32),
                 ("H", C.c_int32), ("d_head", C.c_int32), ("b", C.c_int32), ("T", C.c_int32),
                 ("rho_q", C.c_double), ("rho_kv", C.c_double), ("variant", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("flags", C.c_int32)]
 
 
 class Sizes(C.Structure):
@@ -85,12 +85,16 @@ def _check(rc: int, what: str):
         raise HttmError(f"{what} failed: {msg}{extra} [code {rc}]")
 
 
+FLAG_ANCHOR_FIRST_FRAME = 1
+
+
 def make_geom(S, Hp, Wp, b, T, rho_q, rho_kv=None, *, H=16, d_head=64, n_special=5,
-              variant="headwise") -> Geom:
+              variant="headwise", anchor_first_frame=False) -> Geom:
     if rho_kv is None:
         rho_kv = rho_q
     v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
-    return Geom(S, Hp, Wp, n_special, H, d_head, b, T, float(rho_q), float(rho_kv), v, 0)
+    flags = FLAG_ANCHOR_FIRST_FRAME if anchor_first_frame else 0
+    return Geom(S, Hp, Wp, n_special, H, d_head, b, T, float(rho_q), float(rho_kv), v, flags)
 
 
 def geom_sizes(g: Geom) -> Sizes:

@@ -42,4 +42,12 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
   return __builtin_bit_cast(uint16_t, r);
 }
 
+// Block-local position of the dst token of cluster m (Sec. 3.2 dst/src partition inside a block of
+// n tokens that keeps k clusters): the n0 anchored tokens at the front of the block first (App. C.2),
+// the other k - n0 evenly strided over the remaining n - n0 tokens, the first of them included.
+// n0 = 0 gives floor(m * n / k).
+__device__ __forceinline__ int dst_position(int m, int n, int k, int n0) {
+  return m < n0 ? m : n0 + ((m - n0) * (n - n0)) / (k - n0);
+}
+
 }  // namespace httm

@@ -13,7 +13,7 @@ int check_geom(const httm_geom_t& g) {
   if (g.variant != HTTM_VARIANT_HEADWISE && g.variant != HTTM_VARIANT_UNIFORM &&
       g.variant != HTTM_VARIANT_NONE)
     return HTTM_E_INVALID_ARG;
-  if (g.reserved != 0) return HTTM_E_INVALID_ARG;
+  if (g.flags & ~HTTM_FLAG_ANCHOR_FIRST_FRAME) return HTTM_E_INVALID_ARG;
   if (g.d_head != 64 || g.H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
   const int64_t tpf = (int64_t)g.n_special + (int64_t)g.Hp * g.Wp;
   const int64_t N = tpf * g.S;
@@ -23,12 +23,14 @@ int check_geom(const httm_geom_t& g) {
   return HTTM_OK;
 }
 
-int32_t clusters_kept(int32_t n, double rho) {
+int32_t clusters_kept(int32_t n, double rho, int32_t n0) {
   // Sec. 3.2: r tokens are merged away, M = N - r remain; Sec. 4.1 fixes "ratio rho leaves
-  // (1 - rho)".  Applied per block with the count rounded down; at least one cluster survives.
+  // (1 - rho)".  Applied per block with the count rounded down; at least one cluster survives,
+  // and every anchored token (App. C.2) is one.
   const int32_t r = (int32_t)std::floor(rho * (double)n + 1e-9);
-  const int32_t k = n - r;
-  return k < 1 ? 1 : k;
+  int32_t k = n - r;
+  if (k < 1) k = 1;
+  return k < n0 ? n0 : k;
 }
 
 int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
@@ -63,8 +65,8 @@ int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
   t.items_k.clear();
   for (int64_t p = 0; p < t.n_prefix; p += kPrefixChunk) {
     const int32_t n = (int32_t)((t.n_prefix - p) < kPrefixChunk ? (t.n_prefix - p) : kPrefixChunk);
-    t.items_q.push_back({(int32_t)p, n, n, (int32_t)p});
-    t.items_k.push_back({(int32_t)p, n, n, (int32_t)p});
+    t.items_q.push_back({(int32_t)p, n, n, (int32_t)p, 0, {0, 0, 0}});
+    t.items_k.push_back({(int32_t)p, n, n, (int32_t)p, 0, {0, 0, 0}});
   }
 
   int64_t mq = t.n_prefix, mk = t.n_prefix;
@@ -88,13 +90,17 @@ int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
               for (int32_t x = x0; x < x1; ++x) t.pi[w++] = row + x;
             }
         }
-        const int32_t kq = clusters_kept(n, rho_q), kk = clusters_kept(n, rho_k);
+        // first-frame anchoring: blocks are frame-major, so the frame-0 tokens of a block of the
+        // first temporal group are its first (rows x cols) positions
+        const bool anchor = (g.flags & HTTM_FLAG_ANCHOR_FIRST_FRAME) && grp == 0;
+        const int32_t n0 = anchor ? (y1 - y0) * (x1 - x0) : 0;
+        const int32_t kq = clusters_kept(n, rho_q, n0), kk = clusters_kept(n, rho_k, n0);
         t.block_kq[bi] = kq;
         t.block_kk[bi] = kk;
         t.block_offq[bi] = (int32_t)mq;
         t.block_offk[bi] = (int32_t)mk;
-        t.items_q.push_back({(int32_t)pos, n, kq, (int32_t)mq});
-        t.items_k.push_back({(int32_t)pos, n, kk, (int32_t)mk});
+        t.items_q.push_back({(int32_t)pos, n, kq, (int32_t)mq, n0, {0, 0, 0}});
+        t.items_k.push_back({(int32_t)pos, n, kk, (int32_t)mk, n0, {0, 0, 0}});
         mq += kq;
         mk += kk;
         pos += n;

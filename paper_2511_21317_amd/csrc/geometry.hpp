@@ -12,11 +12,15 @@ namespace httm {
 // reordered tokens that keeps `k` clusters whose merged slots start at `moff`.
 // Real merging blocks have k <= n; the special-token prefix is cut into pseudo-blocks with
 // k == n (every token its own cluster), which the same kernels handle as plain copies.
+// The first `n0` tokens of the run are dst tokens whatever the ratio (first-frame anchoring,
+// paper App. C.2); the remaining k - n0 dst tokens are strided over the other n - n0.
 struct WorkItem {
   int32_t start;  // first reordered position
   int32_t n;      // tokens
   int32_t k;      // clusters kept
   int32_t moff;   // first merged slot
+  int32_t n0;     // leading tokens that are always dst
+  int32_t pad[3];
 };
 
 struct HostTables {
@@ -34,8 +38,8 @@ constexpr int kPrefixChunk = 64;  // tokens per pseudo-block of the special pref
 // Validate a geometry (returns an HTTM_E_* code).
 int check_geom(const httm_geom_t& g);
 
-// Clusters kept by a block of n tokens at merge ratio rho.
-int32_t clusters_kept(int32_t n, double rho);
+// Clusters kept by a block of n tokens at merge ratio rho, at least its n0 anchored tokens.
+int32_t clusters_kept(int32_t n, double rho, int32_t n0 = 0);
 
 // Build every table.  `with_pi` = false skips the O(N) permutation (sizes only).
 int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out);

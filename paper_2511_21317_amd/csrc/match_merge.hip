@@ -158,7 +158,7 @@ void match_merge_kernel(const MatchMergeArgs a) {
 
   if (s.preset) {
     // Head-uniform variant: the clusters were computed once on the head-averaged tokens.
-    for (int m = tid; m < k; m += NT) s_dpos[m] = (uint16_t)((m * n) / k);
+    for (int m = tid; m < k; m += NT) s_dpos[m] = (uint16_t)dst_position(m, n, k, it.n0);
     if (tid < n) {
       const int32_t slot = s.preset[it.start + tid];
       my_cl = slot - it.moff;
@@ -182,7 +182,7 @@ void match_merge_kernel(const MatchMergeArgs a) {
     }
     __syncthreads();
     for (int m = tid; m < k; m += NT) {
-      const int p = (m * n) / k;  // dst position of cluster m
+      const int p = dst_position(m, n, k, it.n0);
       s_dpos[m] = (uint16_t)p;
       s_dinv[m] = s_invn[p];
       s_cl[p] = (int16_t)m;
@@ -414,7 +414,7 @@ __global__ __launch_bounds__(256) void match_f32_kernel(const float* __restrict_
   }
   __syncthreads();
   for (int m = tid; m < k; m += 256) {
-    const int p = (m * n) / k;
+    const int p = dst_position(m, n, k, it.n0);
     s_dpos[m] = p;
     s_cl[p] = m;
   }

@@ -47,6 +47,7 @@ class Workload:
     H: int = N_HEADS
     d_head: int = D_HEAD
     n_special: int = N_SPECIAL
+    anchor: bool = False   # first-frame anchoring switched on for this workload
 
     @property
     def tokens_per_frame(self) -> int:

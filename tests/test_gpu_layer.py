@@ -4,6 +4,8 @@ Workloads 1-3 are compared head by head in full.  Workloads 4-5 run on the GPU a
 benchmark's launch configuration; the oracle is evaluated for a few heads only (heads are independent
 in the head-wise method), and its attention for a seeded sample of merged query rows against all
 keys (rows are independent), so every compared number is still an exact oracle value."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -23,10 +25,13 @@ def _inputs(w):
     return synth.make_qkv(w, device="cuda")
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3])
-def test_layer_forward_matches_oracle_in_full(idx):
+@pytest.mark.parametrize("idx,anchor", [(1, False), (2, False), (3, False), (2, True), (3, True)],
+                         ids=["cfg1", "cfg2", "cfg3", "cfg2_anchored", "cfg3_anchored"])
+def test_layer_forward_matches_oracle_in_full(idx, anchor):
     require_gpu()
     w = synth.workload(idx)
+    if anchor:   # first-frame anchoring (App. C.2) on the same tokens
+        w = dataclasses.replace(w, name=w.name + "_anchored", anchor=True)
     q, k, v = _inputs(w)
     plan = plan_for(w)
     out, views = run_layer(plan, q, k, v)

@@ -22,6 +22,10 @@ ODD = [
     Workload("odd_keep_one", 15, 4, 8, 8, 4, 2, 1.0, 1, H=2),                 # rho = 1: one cluster per block
     Workload("odd_no_special", 16, 4, 12, 15, 3, 2, 0.5, 1, H=2, n_special=0),
     Workload("odd_k_gt_32", 17, 4, 16, 16, 8, 4, 0.25, 1, H=2),               # 256-token blocks, k = 192
+    # first-frame anchoring (App. C.2): frame-0 tokens are dst whatever the ratio
+    Workload("anchored_ratio_below_frame0", 18, 6, 13, 9, 4, 4, 0.9, 1, H=2, anchor=True),   # k = n0
+    Workload("anchored_mixed_dst", 19, 5, 12, 15, 4, 3, 0.5, 1, H=3, anchor=True),            # k > n0
+    Workload("anchored_block512", 20, 9, 10, 12, 8, 8, 0.75, 1, H=2, anchor=True),
 ]
 
 

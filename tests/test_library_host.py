@@ -39,11 +39,12 @@ GEOMS = [
 ]
 
 
+@pytest.mark.parametrize("anchor", [False, True], ids=["plain", "anchored"])
 @pytest.mark.parametrize("case", GEOMS)
-def test_host_tables_match_oracle(case):
+def test_host_tables_match_oracle(case, anchor):
     S, Hp, Wp, b, T, rq, rk = case
-    g = httm.make_geom(S, Hp, Wp, b, T, rq, rk)
-    og = orc.Geometry(S, Hp, Wp, b, T)
+    g = httm.make_geom(S, Hp, Wp, b, T, rq, rk, anchor_first_frame=anchor)
+    og = orc.Geometry(S, Hp, Wp, b, T, anchor=anchor)
     t = httm.geom_tables(g)
     s = httm.geom_sizes(g)
     pi, blocks = orc.temporal_reorder(og)
@@ -85,6 +86,9 @@ def test_argument_errors_are_reported_not_crashed():
     bad = httm.make_geom(2, 16, 16, 4, 2, 1.5)
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -1
     bad = httm.make_geom(0, 16, 16, 4, 2, 0.5)
+    assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -1
+    bad = httm.make_geom(2, 16, 16, 4, 2, 0.5)
+    bad.flags = 2                                            # a flag bit this library does not know
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -1
     assert L.httm_geom_sizes(None, C.byref(s)) == -1
     # compute entry points reject null pointers before touching the GPU
