@@ -1,8 +1,8 @@
 """CPU oracle for the HTTM global-attention layer (arXiv 2511.21317).
 
 TEST INFRASTRUCTURE ONLY.  This module is a plain, slow, step-by-step NumPy
-implementation of what the paper's Algorithm 1 computes (without the outlier
-filter).  It exists so that the HIP kernels can be checked against something
+implementation of what the paper's Algorithm 1 computes, including the
+adaptive outlier filter of the queries (Algorithm 2).  It exists so that the HIP kernels can be checked against something
 written independently from the paper.  Only the test-suite, the smoke check and
 the benchmark's CPU-baseline leg may import it; the product path never does,
 and this module imports nothing from the product.
@@ -16,6 +16,8 @@ Every function takes the steps of the paper in the paper's order:
     Sec. 3.2 mean of constituents,
     Alg. 1 step "BlockAggregate"    -> block_aggregate
     Sec. 3.2 Eq. 3-4                -> attention
+    Sec. 3.4 steps 2-4, Alg. 2      -> deviations, outlier_threshold,
+                                       remove_outliers, block_aggregate_quantile
     Sec. 3.2 Eq. 5                  -> unmerge_by_cluster
     Alg. 1 step "InverseReorder"    -> inverse_reorder
     Sec. 3.2 Eq. 6-7 (head concat)  -> layer_forward
@@ -37,7 +39,13 @@ Readings taken where the paper is silent (all listed in the design notes):
     every other token is src and merges into its most similar dst (lowest m on
     exact ties);
   * means are taken over the raw (un-normalised) tokens; V uses K's matches;
-  * no size-weighted attention bias (Eq. 3 has none).
+  * no size-weighted attention bias (Eq. 3 has none);
+  * outlier filtering: the deviation is taken to the fp32 mean; "top d %" is a
+    budget of floor(d * H * N) tokens and the threshold is the largest deviation
+    outside that budget (strictly greater = outlier); Alg. 2's "append retained
+    outliers" and Alg. 1's second attention are the same computation and the
+    second form is the one written out; key outlier quantile: unused (Sec. 3.4
+    filters queries only).
 
 Parity status: every function below is pinned by tests/test_oracle_*.py
 (brute force, closed forms, invariants).  The conventions above are readings,
@@ -277,6 +285,86 @@ def block_aggregate(xr: np.ndarray, assign: np.ndarray, g: Geometry, blocks, rho
 
 
 # --------------------------------------------------------------------------
+# Sec. 3.4 "Adaptive Outlier Filtering"; Alg. 2 "BlockAggregateQuantile" (queries only)
+# --------------------------------------------------------------------------
+
+def deviations(xr: np.ndarray, assign: np.ndarray, xm: np.ndarray) -> np.ndarray:
+    """Sec. 3.4 step 2: L2 distance of every token to the merged token it belongs to; zero for
+    a token that is not merged with any other token (its cluster has one member)."""
+    size = np.bincount(assign, minlength=xm.shape[0])
+    diff = xr - xm[assign]
+    eps = np.sqrt(np.sum(diff * diff, axis=1, dtype=xr.dtype))
+    return np.where(size[assign] >= 2, eps, xr.dtype.type(0))
+
+
+def outlier_budget(total: int, frac: float) -> int:
+    """Number of tokens the top-`frac` share of `total` tokens stands for (rounded down)."""
+    return int(math.floor(frac * total + 1e-9))
+
+
+def outlier_threshold(eps_all: np.ndarray, frac: float) -> float:
+    """Sec. 3.4 step 3 / Alg. 2 "tau <- Quantile(eps, gamma)": the threshold above which a token
+    is an outlier.  Read as an order statistic: tau is the largest deviation that is NOT among the
+    top floor(frac * count) values, so that at most that many tokens lie strictly above it (fewer
+    when values tie with tau)."""
+    flat = np.sort(np.asarray(eps_all).ravel())
+    d = outlier_budget(flat.size, frac)
+    if d >= flat.size:
+        return -math.inf
+    return float(flat[flat.size - d - 1])
+
+
+def remove_outliers(xr: np.ndarray, assign: np.ndarray, xm: np.ndarray, mask: np.ndarray,
+                    g: Geometry, blocks, rho: float) -> np.ndarray:
+    """Sec. 3.4 step 4: the merged tokens that lose a constituent are recomputed from the
+    constituents that remain (same order: the dst token first if it remains, then ascending
+    position).  A merged token that loses all its constituents becomes a zero row nobody reads."""
+    ks, offs, M = merged_layout(g, blocks, rho)
+    out = xm.copy()
+    affected = np.unique(assign[mask])
+    if affected.size == 0:
+        return out
+    aff = np.zeros(M, dtype=bool)
+    aff[affected] = True
+    acc = np.zeros((M, xr.shape[1]), dtype=xr.dtype)
+    cnt = np.zeros(M, dtype=np.int64)
+    for (start, n), k, off, n0 in zip(blocks, ks, offs, anchor_sizes(g)):
+        if not aff[off:off + k].any():
+            continue
+        dpos = dst_positions(n, k, n0)
+        dset = set(dpos)
+        for m, j in enumerate(dpos):
+            if aff[off + m] and not mask[start + j]:
+                acc[off + m] = xr[start + j]
+                cnt[off + m] = 1
+        for j in range(n):
+            slot = assign[start + j]
+            if j in dset or not aff[slot] or mask[start + j]:
+                continue
+            acc[slot] += xr[start + j]
+            cnt[slot] += 1
+    for slot in affected:
+        out[slot] = acc[slot] / xr.dtype.type(cnt[slot]) if cnt[slot] else 0
+    return out
+
+
+def block_aggregate_quantile(qr_heads, assign_heads, g: Geometry, blocks, rho: float, frac: float):
+    """Alg. 2 over all heads: merged queries with the outliers taken out, and the outlier mask.
+
+    qr_heads / assign_heads: per head, reordered queries [L, E] and their cluster slots [L].
+    Returns (qm_heads, mask_heads, eps_heads, tau).  The budget floor(frac * H * L) is shared by
+    all heads (Sec. 3.4 step 3).
+    """
+    qm0 = [block_aggregate(qr, a, g, blocks, rho) for qr, a in zip(qr_heads, assign_heads)]
+    eps = [deviations(qr, a, qm) for qr, a, qm in zip(qr_heads, assign_heads, qm0)]
+    tau = outlier_threshold(np.concatenate(eps), frac)
+    masks = [e > tau for e in eps]
+    qm = [remove_outliers(qr, a, m0, mk, g, blocks, rho)
+          for qr, a, m0, mk in zip(qr_heads, assign_heads, qm0, masks)]
+    return qm, masks, eps, tau
+
+
+# --------------------------------------------------------------------------
 # Sec. 3.2 Eq. 3-4: attention over the reduced sequences
 # --------------------------------------------------------------------------
 
@@ -327,14 +415,17 @@ def head_mean(x: np.ndarray) -> np.ndarray:
 
 def layer_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray, g: Geometry,
                   rho_q: float, rho_kv: float, variant: str = "headwise",
-                  heads=None, dtype=np.float32):
+                  heads=None, dtype=np.float32, outlier_frac: float = 0.0):
     """Q, K, V [H, N, E] -> dict with O [N, len(heads)*E] and every intermediate.
 
     variant: "headwise" (the paper's method), "uniform" (one matching for all
     heads, from head-averaged tokens), or "none" (no merging).
     `heads` restricts the computation to a subset of heads (heads are
-    independent except for the uniform variant's averaged metric, which always
-    uses all heads).
+    independent except for the uniform variant's averaged metric and the
+    outlier budget, which always use all heads).
+    outlier_frac > 0 switches the adaptive outlier filtering of the queries on
+    (Sec. 3.4, Alg. 2; Alg. 1 "BlockAggregateQuantile" and the second attention
+    for the outlier queries): results gain "eps", "outlier_mask" (per head) and "tau".
     """
     H, N, E = q.shape
     assert N == g.N
@@ -350,19 +441,39 @@ def layer_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray, g: Geometry,
         uk = blockwise_tome(reorder(head_mean(k), pi), g, blocks, rho_kv)
     res = {"pi": pi, "blocks": blocks, "assign_q": [], "assign_k": [], "gap_q": [], "gap_k": [],
            "score_q": [], "score_k": [], "q_m": [], "k_m": [], "v_m": [], "o_m": []}
+    filt = None
+    if outlier_frac > 0.0 and variant != "none":
+        # the outlier budget is shared by all heads, so the queries of every head are matched first
+        qr_all = [reorder(q[h], pi) for h in range(H)]
+        aq_all = [uq if variant == "uniform" else blockwise_tome(qr_all[h], g, blocks, rho_q)
+                  for h in range(H)]
+        qm_all, mask_all, eps_all, tau = block_aggregate_quantile(
+            qr_all, [a[0] for a in aq_all], g, blocks, rho_q, outlier_frac)
+        filt = (aq_all, qm_all, mask_all)
+        res.update({"eps": [eps_all[h] for h in heads], "outlier_mask": [mask_all[h] for h in heads],
+                    "tau": tau})
     cols = []
     for h in heads:
         qr, kr, vr = reorder(q[h], pi), reorder(k[h], pi), reorder(v[h], pi)
-        if variant == "uniform":
-            (aq, sq, gq), (ak, sk, gk) = uq, uk
+        if filt is not None:
+            aq, sq, gq = filt[0][h]
+        elif variant == "uniform":
+            aq, sq, gq = uq
         else:
             aq, sq, gq = blockwise_tome(qr, g, blocks, rho_q)
+        if variant == "uniform":
+            ak, sk, gk = uk
+        else:
             ak, sk, gk = blockwise_tome(kr, g, blocks, rho_kv)
-        qm = block_aggregate(qr, aq, g, blocks, rho_q)
+        qm = filt[1][h] if filt is not None else block_aggregate(qr, aq, g, blocks, rho_q)
         km = block_aggregate(kr, ak, g, blocks, rho_kv)
         vm = block_aggregate(vr, ak, g, blocks, rho_kv)
         om = attention(qm, km, vm)
-        o = inverse_reorder(unmerge_by_cluster(om, aq), pi)
+        o_r = unmerge_by_cluster(om, aq)
+        if filt is not None and filt[2][h].any():
+            # Alg. 1: the outlier queries attend on their own, un-merged
+            o_r[filt[2][h]] = attention(qr[filt[2][h]], km, vm)
+        o = inverse_reorder(o_r, pi)
         cols.append(o)
         for key, val in (("assign_q", aq), ("assign_k", ak), ("gap_q", gq), ("gap_k", gk),
                          ("score_q", sq), ("score_k", sk), ("q_m", qm), ("k_m", km),
