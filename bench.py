@@ -211,6 +211,30 @@ def main():
         plan_a.close()
         del ws_a
         torch.cuda.empty_cache()
+        # adaptive outlier filtering of the queries at the paper's setting (Sec. 4.1: 10 % of all
+        # query tokens are taken out of the merging again and attend on their own)
+        plan_f = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H, n_special=w.n_special,
+                                          outlier_frac=0.1))
+        ws_f = httm.alloc_workspace(plan_f)
+        t_fil = gpu_time_ms(lambda: httm.layer_forward(plan_f, q, k, v, out_u, ws_f), max(2, it // 2))
+        vf = httm.workspace_views(plan_f, ws_f)
+        t_s2 = gpu_time_ms(lambda: httm.reorder_match_merge_filtered(
+            plan_f, q, k, v, vf["q_m"], vf["k_m"], vf["v_m"], vf["assign_q"], vf["assign_k"], vf["eps_q"],
+            vf["q_out"]), max(2, it // 2))
+        t_a2 = gpu_time_ms(lambda: httm.attention_outliers(plan_f, vf["q_out"], vf["k_m"], vf["v_m"],
+                                                           vf["o_out"]), max(2, it // 2))
+        tau, counts = httm.outlier_stats(plan_f)
+        f_a2 = 4.0 * sum(counts) * Mk * 64
+        extras["outlier_filtered_layer_d0.1"] = {
+            "ms": t_fil, "tokens/s": N / (t_fil * 1e-3), "outliers": sum(counts),
+            "outliers_per_head_min_max": [min(counts), max(counts)], "tau": tau,
+            "stage2_with_filter_ms": t_s2, "outlier_attention_ms": t_a2,
+            "outlier_attention_TFLOP/s": f_a2 / (t_a2 * 1e-3) / 1e12}
+        log(f"[bench] outlier-filtered layer (d = 0.1): {t_fil:.3f} ms; stage 2 {t_s2:.3f} ms, "
+            f"second attention {t_a2:.3f} ms ({sum(counts)} outlier queries)")
+        plan_f.close()
+        del ws_f, vf
+        torch.cuda.empty_cache()
         plan_0 = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, 0.0, H=w.H,
                                           n_special=w.n_special, variant="none"))
         ws_0 = httm.alloc_workspace(plan_0)

@@ -81,6 +81,7 @@ enum {
  * frame-0 tokens; its other dst tokens are strided over the rest of the block.  Applies to Q and K. */
 #define HTTM_FLAG_ANCHOR_FIRST_FRAME 1
 
+#define HTTM_MAX_OUTLIER_FRAC 0.5
 #define HTTM_MAX_BLOCK 512        /* largest merging block (b*b*T tokens) the kernels accept */
 #define HTTM_MAX_HEADS 64
 
@@ -98,6 +99,10 @@ typedef struct httm_geom {
   double rho_kv;      /* the same for key/value tokens */
   int32_t variant;    /* HTTM_VARIANT_* */
   int32_t flags;      /* HTTM_FLAG_* bits; unknown bits are rejected */
+  double outlier_frac; /* adaptive outlier filtering of the queries (Sec. 3.4): the share d of all H*N
+                          query tokens - those that lie farthest from their merged token, over all
+                          heads together - that is taken out of the merging again; 0 = off,
+                          at most HTTM_MAX_OUTLIER_FRAC.  Ignored for HTTM_VARIANT_NONE. */
 } httm_geom_t;
 
 /* Sizes derived from a geometry. */
@@ -109,6 +114,7 @@ typedef struct httm_sizes {
   int64_t M_q;              /* merged query length per head */
   int64_t M_k;              /* merged key/value length per head */
   int64_t workspace_bytes;  /* what httm_layer_forward needs */
+  int64_t outlier_cap;      /* floor(outlier_frac * H * N): the most outlier queries there can be (0 = off) */
 } httm_sizes_t;
 
 typedef struct httm_plan httm_plan_t;
@@ -205,17 +211,60 @@ HTTM_API int httm_unmerge(const httm_plan_t* plan, const void* o_m, const int32_
 /* q, k, v : [H, N, d_head] bf16 in INPUT token order.  out : [N, H*d_head] bf16.
  * workspace: at least httm_sizes_t.workspace_bytes bytes, 256-byte aligned.  After the call it
  * holds, in this order (each 256-byte aligned): q_m, k_m, v_m, o_m ([H, M, d_head] bf16),
- * assign_q, assign_k ([H, N] int32) - see httm_workspace_layout.
+ * assign_q, assign_k ([H, N] int32) and, with outlier filtering, eps_q, q_out, o_out - see
+ * httm_workspace_layout.
  * The reorder is fused into the matching kernel's loads and the inverse reorder into the
  * unmerge kernel's stores; results are identical to calling the four stages one by one. */
 HTTM_API int httm_layer_forward(const httm_plan_t* plan, const void* q, const void* k, const void* v,
                        void* out, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Byte offsets of the six regions inside the workspace (host only). */
+/* Byte offsets of the regions inside the workspace (host only).  eps_q, q_out and o_out have size
+ * zero unless outlier filtering is on. */
 typedef struct httm_workspace_layout {
-  int64_t q_m, k_m, v_m, o_m, assign_q, assign_k, total;
+  int64_t q_m, k_m, v_m, o_m, assign_q, assign_k, eps_q, q_out, o_out, total;
 } httm_workspace_layout_t;
 HTTM_API int httm_workspace_layout(const httm_geom_t* g, httm_workspace_layout_t* out);
+
+/* ---- adaptive outlier filtering of the merged queries (Sec. 3.4; Alg. 2
+ *      "BlockAggregateQuantile"; Alg. 1, the second attention for the outlier queries) ------------
+ * Only for plans with outlier_frac > 0 (else HTTM_E_INVALID_ARG).  The three calls replace stage 2,
+ * add one attention pass and replace stage 4; httm_layer_forward runs them by itself.
+ *
+ * Sec. 3.4 step 2: the deviation of a query token is its L2 distance to its merged token (the
+ * fp32 mean, before it is rounded to bf16), zero for a token that was not merged with another.
+ * Step 3: with budget = outlier_cap, tau is the largest of the H*N deviations that is not among
+ * the budget largest; a token whose deviation lies strictly above tau is an outlier (values that
+ * tie with tau stay merged, so there can be fewer than budget).  Step 4: a merged query that loses
+ * constituents is recomputed from those that remain (a zero row if none remains); an outlier
+ * attends by itself with its original query row.
+ *
+ * The plan holds the threshold, the per-head counts and the row offsets on the device, so calls
+ * that use one plan must not overlap in time. */
+
+/* Stage 2 with the filter.  q, k, v, q_m, k_m, v_m, assign_k as for httm_reorder_match_merge.
+ * assign_q : [H, N] int32 out; slot in 0..M_q-1, or -1 - r for an outlier whose query sits in row r
+ *            of q_out.
+ * eps_q    : [H, N] float out, the deviations.
+ * q_out    : [outlier_cap, d_head] bf16 out; the outlier queries, grouped by head (the order inside
+ *            a head is not fixed from run to run; results do not depend on it). */
+HTTM_API int httm_reorder_match_merge_filtered(const httm_plan_t* plan, const void* q, const void* k,
+                                               const void* v, void* q_m, void* k_m, void* v_m,
+                                               int32_t* assign_q, int32_t* assign_k, float* eps_q,
+                                               void* q_out, void* stream);
+
+/* o_out[r] = softmax(q_out[r] k_m[h]^T / 8) v_m[h] for every outlier row r, h the head it belongs to.
+ * k_m, v_m: [H, M_k, d_head] bf16; o_out: [outlier_cap, d_head] bf16 out. */
+HTTM_API int httm_attention_outliers(const httm_plan_t* plan, const void* q_out, const void* k_m,
+                                     const void* v_m, void* o_out, void* stream);
+
+/* Stage 4 (inverse reorder fused) with assign_q as written by the filtered stage 2:
+ * out[pi[j]][h*d_head ..] = assign_q[h][j] >= 0 ? o_m[h][assign_q[h][j]] : o_out[-1 - assign_q[h][j]]. */
+HTTM_API int httm_unmerge_filtered(const httm_plan_t* plan, const void* o_m, const void* o_out,
+                                   const int32_t* assign_q, void* out, void* stream);
+
+/* Reads back what the last filtered stage 2 on this plan decided: *tau and counts[H] (outliers per
+ * head).  Waits for the stream; for tests and diagnostics. */
+HTTM_API int httm_outlier_stats(const httm_plan_t* plan, float* tau, int32_t* counts, void* stream);
 
 #ifdef __cplusplus
 }

@@ -27,16 +27,17 @@ class Geom(C.Structure):
     _fields_ = [("S", C.c_int32), ("Hp", C.c_int32), ("Wp", C.c_int32), ("n_special", C.c_int32),
                 ("H", C.c_int32), ("d_head", C.c_int32), ("b", C.c_int32), ("T", C.c_int32),
                 ("rho_q", C.c_double), ("rho_kv", C.c_double), ("variant", C.c_int32),
-                ("flags", C.c_int32)]
+                ("flags", C.c_int32), ("outlier_frac", C.c_double)]
 
 
 class Sizes(C.Structure):
     _fields_ = [(n, C.c_int64) for n in
-                ("N", "n_prefix", "n_blocks", "max_block", "M_q", "M_k", "workspace_bytes")]
+                ("N", "n_prefix", "n_blocks", "max_block", "M_q", "M_k", "workspace_bytes", "outlier_cap")]
 
 
 class WorkspaceLayout(C.Structure):
-    _fields_ = [(n, C.c_int64) for n in ("q_m", "k_m", "v_m", "o_m", "assign_q", "assign_k", "total")]
+    _fields_ = [(n, C.c_int64) for n in ("q_m", "k_m", "v_m", "o_m", "assign_q", "assign_k", "eps_q",
+                                         "q_out", "o_out", "total")]
 
 
 _lib = None
@@ -68,10 +69,16 @@ def lib() -> C.CDLL:
     L.httm_attention.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, C.c_float, vp]
     L.httm_unmerge.argtypes = [vp, vp, i32p, vp, C.c_int, vp]
     L.httm_layer_forward.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.httm_reorder_match_merge_filtered.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, i32p, f32p, vp, vp]
+    L.httm_attention_outliers.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.httm_unmerge_filtered.argtypes = [vp, vp, vp, i32p, vp, vp]
+    L.httm_outlier_stats.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32), vp]
     for name in ("httm_geom_sizes", "httm_workspace_layout", "httm_geom_tables", "httm_plan_create",
                  "httm_plan_destroy", "httm_plan_query", "httm_reorder", "httm_match_merge",
                  "httm_reorder_match_merge",
-                 "httm_attention", "httm_unmerge", "httm_layer_forward"):
+                 "httm_attention", "httm_unmerge", "httm_layer_forward",
+                 "httm_reorder_match_merge_filtered", "httm_attention_outliers", "httm_unmerge_filtered",
+                 "httm_outlier_stats"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -89,12 +96,13 @@ FLAG_ANCHOR_FIRST_FRAME = 1
 
 
 def make_geom(S, Hp, Wp, b, T, rho_q, rho_kv=None, *, H=16, d_head=64, n_special=5,
-              variant="headwise", anchor_first_frame=False) -> Geom:
+              variant="headwise", anchor_first_frame=False, outlier_frac=0.0) -> Geom:
     if rho_kv is None:
         rho_kv = rho_q
     v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
     flags = FLAG_ANCHOR_FIRST_FRAME if anchor_first_frame else 0
-    return Geom(S, Hp, Wp, n_special, H, d_head, b, T, float(rho_q), float(rho_kv), v, flags)
+    return Geom(S, Hp, Wp, n_special, H, d_head, b, T, float(rho_q), float(rho_kv), v, flags,
+                float(outlier_frac))
 
 
 def geom_sizes(g: Geom) -> Sizes:
@@ -169,6 +177,8 @@ class Plan:
     def M_k(self): return int(self.sizes.M_k)
     @property
     def H(self): return int(self.geom.H)
+    @property
+    def outlier_cap(self): return int(self.sizes.outlier_cap)
 
 
 def reorder(plan: Plan, src: torch.Tensor, dst: torch.Tensor, direction: int = 0):
@@ -239,8 +249,53 @@ def workspace_views(plan: Plan, workspace: torch.Tensor) -> dict:
         return workspace[off:off + H * rows * 128].view(torch.bfloat16).view(H, rows, 64)
     def i32(off):
         return workspace[off:off + H * N * 4].view(torch.int32).view(H, N)
-    return {"q_m": bf(L.q_m, plan.M_q), "k_m": bf(L.k_m, plan.M_k), "v_m": bf(L.v_m, plan.M_k),
-            "o_m": bf(L.o_m, plan.M_q), "assign_q": i32(L.assign_q), "assign_k": i32(L.assign_k)}
+    views = {"q_m": bf(L.q_m, plan.M_q), "k_m": bf(L.k_m, plan.M_k), "v_m": bf(L.v_m, plan.M_k),
+             "o_m": bf(L.o_m, plan.M_q), "assign_q": i32(L.assign_q), "assign_k": i32(L.assign_k)}
+    cap = plan.outlier_cap
+    if cap:
+        views["eps_q"] = workspace[L.eps_q:L.eps_q + H * N * 4].view(torch.float32).view(H, N)
+        views["q_out"] = workspace[L.q_out:L.q_out + cap * 128].view(torch.bfloat16).view(cap, 64)
+        views["o_out"] = workspace[L.o_out:L.o_out + cap * 128].view(torch.bfloat16).view(cap, 64)
+    return views
+
+
+def reorder_match_merge_filtered(plan: Plan, q, k, v, q_m, k_m, v_m, assign_q, assign_k, eps_q, q_out):
+    """Stage 2 with the adaptive outlier filter (plans with outlier_frac > 0)."""
+    H, N = plan.H, plan.N
+    bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+    _check(lib().httm_reorder_match_merge_filtered(
+        plan._h, _dev(q, bf, (H, N, 64)), _dev(k, bf, (H, N, 64)), _dev(v, bf, (H, N, 64)),
+        _dev(q_m, bf, (H, plan.M_q, 64)), _dev(k_m, bf, (H, plan.M_k, 64)), _dev(v_m, bf, (H, plan.M_k, 64)),
+        _dev(assign_q, i32, (H, N)), _dev(assign_k, i32, (H, N)), _dev(eps_q, f32, (H, N)),
+        _dev(q_out, bf, (plan.outlier_cap, 64)), _stream()), "httm_reorder_match_merge_filtered")
+
+
+def attention_outliers(plan: Plan, q_out, k_m, v_m, o_out):
+    bf = torch.bfloat16
+    cap = plan.outlier_cap
+    _check(lib().httm_attention_outliers(plan._h, _dev(q_out, bf, (cap, 64)),
+                                         _dev(k_m, bf, (plan.H, plan.M_k, 64)),
+                                         _dev(v_m, bf, (plan.H, plan.M_k, 64)),
+                                         _dev(o_out, bf, (cap, 64)), _stream()), "httm_attention_outliers")
+    return o_out
+
+
+def unmerge_filtered(plan: Plan, o_m, o_out, assign_q, out):
+    H, N = plan.H, plan.N
+    bf = torch.bfloat16
+    _check(lib().httm_unmerge_filtered(plan._h, _dev(o_m, bf, (H, plan.M_q, 64)),
+                                       _dev(o_out, bf, (plan.outlier_cap, 64)),
+                                       _dev(assign_q, torch.int32, (H, N)), _dev(out, bf, (N, H * 64)),
+                                       _stream()), "httm_unmerge_filtered")
+    return out
+
+
+def outlier_stats(plan: Plan):
+    """(tau, outliers per head) of the last filtered stage 2 on this plan; waits for the stream."""
+    tau = C.c_float()
+    counts = (C.c_int32 * plan.H)()
+    _check(lib().httm_outlier_stats(plan._h, C.byref(tau), counts, _stream()), "httm_outlier_stats")
+    return float(tau.value), [int(c) for c in counts]
 
 
 def alloc_workspace(plan: Plan) -> torch.Tensor:

@@ -9,7 +9,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libhttm.so")
 
-SOURCES = ["api.hip", "geometry.cpp", "reorder_unmerge.hip", "match_merge.hip", "attention.hip"]
+SOURCES = ["api.hip", "geometry.cpp", "reorder_unmerge.hip", "match_merge.hip", "outlier_filter.hip",
+           "attention.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -24,6 +24,9 @@ struct httm_plan {
   float* d_mean = nullptr;    // [2][N][64] fp32: head-averaged Q then K
   int32_t* d_slot = nullptr;  // [2][N] shared cluster slot of every reordered token
   float* d_uscore = nullptr;  // [2][N]
+  // outlier filtering only
+  int64_t outlier_cap = 0;
+  OutlierBuffers ob = {};
 };
 
 namespace {
@@ -54,6 +57,7 @@ void fill_sizes(const httm_geom_t& g, const HostTables& t, httm_sizes_t* s,
   httm_workspace_layout_t l;
   workspace_layout(g, t, &l);
   s->workspace_bytes = l.total;
+  s->outlier_cap = outlier_budget(g, t.N);
   if (ws) *ws = l;
 }
 
@@ -70,7 +74,8 @@ int upload(const std::vector<T>& host, T** dev) {
 // reordered order when it is nullptr.
 int run_match_merge(const httm_plan_t* p, const int32_t* pi, const void* q, const void* k,
                     const void* v, void* q_m, void* k_m, void* v_m, int32_t* assign_q,
-                    int32_t* assign_k, float* score_q, float* score_k, hipStream_t st) {
+                    int32_t* assign_k, float* score_q, float* score_k, hipStream_t st,
+                    float* eps_q = nullptr) {
   const httm_geom_t& g = p->geom;
   MatchMergeArgs a;
   std::memset(&a, 0, sizeof(a));
@@ -80,9 +85,9 @@ int run_match_merge(const httm_plan_t* p, const int32_t* pi, const void* q, cons
   a.H = g.H;
   a.max_block = (int32_t)(p->sizes.max_block < kPrefixChunk ? kPrefixChunk : p->sizes.max_block);
   a.s[0] = {q, nullptr, q_m, nullptr, assign_q, score_q, p->d_items_q, p->n_items, p->sizes.M_q,
-            nullptr, nullptr};
+            nullptr, nullptr, eps_q};
   a.s[1] = {k, v, k_m, v_m, assign_k, score_k, p->d_items_k, p->n_items, p->sizes.M_k, nullptr,
-            nullptr};
+            nullptr, nullptr};
   if (g.variant == HTTM_VARIANT_UNIFORM) {
     const int64_t N = p->sizes.N;
     const void* src[2] = {q, k};
@@ -97,6 +102,44 @@ int run_match_merge(const httm_plan_t* p, const int32_t* pi, const void* q, cons
     }
   }
   HTTM_HIP(launch_match_merge(a, st));
+  return HTTM_OK;
+}
+
+// Stage 2 with the outlier filter (Sec. 3.4): matching + aggregation with the deviations written
+// out, the device-wide threshold, then the un-merging of the outliers.
+int run_match_merge_filtered(const httm_plan_t* p, const void* q, const void* k, const void* v,
+                             void* q_m, void* k_m, void* v_m, int32_t* assign_q, int32_t* assign_k,
+                             float* eps_q, void* q_out, hipStream_t st) {
+  int rc = run_match_merge(p, p->d_pi, q, k, v, q_m, k_m, v_m, assign_q, assign_k, nullptr, nullptr,
+                           st, eps_q);
+  if (rc != HTTM_OK) return rc;
+  HTTM_HIP(launch_outlier_select(eps_q, p->geom.H, p->sizes.N, p->outlier_cap, p->ob,
+                                 kAttnDevTileRows, st));
+  RefineArgs r;
+  std::memset(&r, 0, sizeof(r));
+  r.x = q;
+  r.xm = q_m;
+  r.assign = assign_q;
+  r.eps = eps_q;
+  r.q_out = q_out;
+  r.items = p->d_items_q;
+  r.n_items = p->n_items;
+  r.M = p->sizes.M_q;
+  r.pi = p->d_pi;
+  r.N = p->sizes.N;
+  r.H = p->geom.H;
+  r.max_block = (int32_t)(p->sizes.max_block < kPrefixChunk ? kPrefixChunk : p->sizes.max_block);
+  r.b = p->ob;
+  HTTM_HIP(launch_outlier_refine(r, st));
+  return HTTM_OK;
+}
+
+int run_attention_outliers(const httm_plan_t* p, const void* q_out, const void* k_m, const void* v_m,
+                           void* o_out, hipStream_t st) {
+  int64_t k_off[HTTM_MAX_HEADS + 1];
+  for (int h = 0; h <= p->geom.H; ++h) k_off[h] = (int64_t)h * p->sizes.M_k;
+  HTTM_HIP(launch_attention_dev_tiles(q_out, k_m, v_m, o_out, p->ob.offsets, p->ob.tiles,
+                                      p->ob.max_tiles, k_off, p->geom.H, 0.125f, st));
   return HTTM_OK;
 }
 
@@ -181,6 +224,25 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_uscore, (size_t)2 * t.N * sizeof(float));
     if (e != hipSuccess) rc = hip_fail(e);
   }
+  p->outlier_cap = p->sizes.outlier_cap;
+  if (rc == HTTM_OK && p->outlier_cap > 0) {
+    OutlierBuffers& b = p->ob;
+    b.max_tiles = (int32_t)(p->outlier_cap / kAttnDevTileRows + g->H);
+    const size_t words = sizeof(SelectState) / 4 + 2048 + (size_t)g->H * 3 + 1 + 1 + 2 * (size_t)b.max_tiles;
+    uint32_t* base = nullptr;
+    e = hipMalloc((void**)&base, words * 4);
+    if (e == hipSuccess) e = hipMemset(base, 0, words * 4);
+    if (e != hipSuccess) {
+      rc = hip_fail(e);
+    } else {
+      b.state = (SelectState*)base;
+      b.hist = base + sizeof(SelectState) / 4;
+      b.counts = (int32_t*)(b.hist + 2048);
+      b.offsets = b.counts + g->H;
+      b.cursors = b.offsets + g->H + 1;
+      b.tiles = b.cursors + g->H;
+    }
+  }
   if (rc != HTTM_OK) {
     httm_plan_destroy(p);
     return rc;
@@ -191,7 +253,7 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
 
 int httm_plan_destroy(httm_plan_t* p) {
   if (!p) return HTTM_OK;
-  void* ptrs[] = {p->d_pi, p->d_items_q, p->d_items_k, p->d_mean, p->d_slot, p->d_uscore};
+  void* ptrs[] = {p->d_pi, p->d_items_q, p->d_items_k, p->d_mean, p->d_slot, p->d_uscore, p->ob.state};
   for (void* q : ptrs)
     if (q) (void)hipFree(q);
   delete p;
@@ -277,8 +339,15 @@ int httm_layer_forward(const httm_plan_t* p, const void* q, const void* k, const
   void* o_m = ws + p->ws.o_m;
   int32_t* assign_q = (int32_t*)(ws + p->ws.assign_q);
   int32_t* assign_k = (int32_t*)(ws + p->ws.assign_k);
+  const bool filtered = p->outlier_cap > 0;
+  float* eps_q = (float*)(ws + p->ws.eps_q);
+  void* q_out = ws + p->ws.q_out;
+  void* o_out = ws + p->ws.o_out;
   // Stages 1+2 fused: the matching kernel gathers its rows through pi.
-  int rc = run_match_merge(p, p->d_pi, q, k, v, q_m, k_m, v_m, assign_q, assign_k, nullptr, nullptr, st);
+  int rc = filtered ? run_match_merge_filtered(p, q, k, v, q_m, k_m, v_m, assign_q, assign_k, eps_q,
+                                               q_out, st)
+                    : run_match_merge(p, p->d_pi, q, k, v, q_m, k_m, v_m, assign_q, assign_k, nullptr,
+                                      nullptr, st);
   if (rc != HTTM_OK) return rc;
   // Stage 3.
   const int H = p->geom.H;
@@ -288,8 +357,58 @@ int httm_layer_forward(const httm_plan_t* p, const void* q, const void* k, const
     k_off[h] = (int64_t)h * p->sizes.M_k;
   }
   HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_off, k_off, H, 0.125f, st));
+  if (filtered) {
+    // Alg. 1: the outlier queries attend on their own
+    rc = run_attention_outliers(p, q_out, k_m, v_m, o_out, st);
+    if (rc != HTTM_OK) return rc;
+  }
   // Stage 4 with the inverse reorder fused.
-  HTTM_HIP(launch_unmerge(o_m, assign_q, p->d_pi, out, H, p->sizes.N, p->sizes.M_q, 1, st));
+  HTTM_HIP(launch_unmerge(o_m, assign_q, p->d_pi, out, H, p->sizes.N, p->sizes.M_q, 1, st,
+                          filtered ? o_out : nullptr));
+  return HTTM_OK;
+}
+
+int httm_reorder_match_merge_filtered(const httm_plan_t* p, const void* q, const void* k, const void* v,
+                                      void* q_m, void* k_m, void* v_m, int32_t* assign_q,
+                                      int32_t* assign_k, float* eps_q, void* q_out, void* stream) {
+  if (!p || !q || !k || !v || !q_m || !k_m || !v_m || !assign_q || !assign_k || !eps_q || !q_out)
+    return HTTM_E_INVALID_ARG;
+  if (p->outlier_cap <= 0) return HTTM_E_INVALID_ARG;
+  const void* ptrs[] = {q, k, v, q_m, k_m, v_m, assign_q, assign_k, eps_q, q_out};
+  for (const void* x : ptrs)
+    if (!aligned16(x)) return HTTM_E_INVALID_ARG;
+  return run_match_merge_filtered(p, q, k, v, q_m, k_m, v_m, assign_q, assign_k, eps_q, q_out,
+                                  (hipStream_t)stream);
+}
+
+int httm_attention_outliers(const httm_plan_t* p, const void* q_out, const void* k_m, const void* v_m,
+                            void* o_out, void* stream) {
+  if (!p || !q_out || !k_m || !v_m || !o_out) return HTTM_E_INVALID_ARG;
+  if (p->outlier_cap <= 0) return HTTM_E_INVALID_ARG;
+  if (!aligned16(q_out) || !aligned16(k_m) || !aligned16(v_m) || !aligned16(o_out)) return HTTM_E_INVALID_ARG;
+  return run_attention_outliers(p, q_out, k_m, v_m, o_out, (hipStream_t)stream);
+}
+
+int httm_unmerge_filtered(const httm_plan_t* p, const void* o_m, const void* o_out,
+                          const int32_t* assign_q, void* out, void* stream) {
+  if (!p || !o_m || !o_out || !assign_q || !out || o_m == out) return HTTM_E_INVALID_ARG;
+  if (p->outlier_cap <= 0) return HTTM_E_INVALID_ARG;
+  if (!aligned16(o_m) || !aligned16(o_out) || !aligned16(out) || !aligned16(assign_q)) return HTTM_E_INVALID_ARG;
+  HTTM_HIP(launch_unmerge(o_m, assign_q, p->d_pi, out, p->geom.H, p->sizes.N, p->sizes.M_q, 1,
+                          (hipStream_t)stream, o_out));
+  return HTTM_OK;
+}
+
+int httm_outlier_stats(const httm_plan_t* p, float* tau, int32_t* counts, void* stream) {
+  if (!p || !tau || !counts) return HTTM_E_INVALID_ARG;
+  if (p->outlier_cap <= 0) return HTTM_E_INVALID_ARG;
+  HTTM_HIP(hipStreamSynchronize((hipStream_t)stream));
+  SelectState st;
+  HTTM_HIP(hipMemcpy(&st, p->ob.state, sizeof(st), hipMemcpyDeviceToHost));
+  *tau = st.tau;
+  int32_t off[HTTM_MAX_HEADS + 1];
+  HTTM_HIP(hipMemcpy(off, p->ob.offsets, (size_t)(p->geom.H + 1) * 4, hipMemcpyDeviceToHost));
+  for (int h = 0; h < p->geom.H; ++h) counts[h] = off[h + 1] - off[h];
   return HTTM_OK;
 }
 

@@ -42,6 +42,7 @@
 // the step's true maximum and rescales its O and l accumulators - the classic online-softmax
 // update, taken only when needed.
 #include <cstdlib>
+#include <cstring>
 
 #include "dev_common.hpp"
 #include "kernels.hpp"
@@ -70,6 +71,11 @@ struct AttnArgs {
   int32_t ragged_head[kAttnMaxHeads];         // head of every partial tile
   int64_t q_off[kAttnMaxHeads + 1];
   int64_t k_off[kAttnMaxHeads + 1];
+  // When set, the query side comes from device memory instead: rows of head h are
+  // [dev_q_off[h], dev_q_off[h+1]) and workgroup t takes tile (head, first row) =
+  // (dev_tiles[1+2t], dev_tiles[2+2t]) for t < dev_tiles[0].
+  const int32_t* dev_q_off;
+  const int32_t* dev_tiles;
 };
 
 // position of key row `kv` (0..63) inside a transposed V row in LDS: bits 2 and 3 swapped
@@ -271,7 +277,15 @@ void attention_kernel(const AttnArgs a) {
   // range of full tiles.
   const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
   int h = 0, q0;
-  if (idx < a.ragged_per_xcd) {
+  int64_t q_base_dev = 0;
+  int mq_dev = 0;
+  if (a.dev_tiles) {
+    if ((int)blockIdx.x >= a.dev_tiles[0]) return;
+    h = a.dev_tiles[1 + 2 * blockIdx.x];
+    q0 = a.dev_tiles[2 + 2 * blockIdx.x];
+    q_base_dev = a.dev_q_off[h];
+    mq_dev = a.dev_q_off[h + 1] - a.dev_q_off[h];
+  } else if (idx < a.ragged_per_xcd) {
     const int i = idx * 8 + xcd;
     if (i >= a.n_ragged) return;
     h = a.ragged_head[i];
@@ -282,8 +296,8 @@ void attention_kernel(const AttnArgs a) {
     while (tile >= a.tile_start[h + 1]) ++h;
     q0 = (tile - a.tile_start[h]) * BQ;
   }
-  const int64_t q_base = a.q_off[h], k_base = a.k_off[h];
-  const int Mq = (int)(a.q_off[h + 1] - q_base);
+  const int64_t q_base = a.dev_tiles ? q_base_dev : a.q_off[h], k_base = a.k_off[h];
+  const int Mq = a.dev_tiles ? mq_dev : (int)(a.q_off[h + 1] - q_base);
   const int Mk = (int)(a.k_off[h + 1] - k_base);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -498,10 +512,33 @@ int attn_cfg() {
 
 }  // namespace
 
+hipError_t launch_attention_dev_tiles(const void* q, const void* k, const void* v, void* o,
+                                      const int32_t* q_off_dev, const int32_t* tiles, int max_tiles,
+                                      const int64_t* k_off_host, int H, float scale,
+                                      hipStream_t stream) {
+  static_assert(kAttnDevTileRows == 32 * 2 * 4, "the device tile list is cut for attention_kernel<2, 4>");
+  if (max_tiles <= 0) return hipSuccess;
+  AttnArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.q = (const bf16_t*)q;
+  a.k = (const bf16_t*)k;
+  a.v = (const bf16_t*)v;
+  a.o = (bf16_t*)o;
+  a.scale_log2 = scale * 1.4426950408889634f;
+  a.H = H;
+  for (int h = 0; h <= kAttnMaxHeads; ++h) a.k_off[h] = k_off_host[h < H ? h : H];
+  a.dev_q_off = q_off_dev;
+  a.dev_tiles = tiles;
+  hipLaunchKernelGGL((attention_kernel<2, 4>), dim3((unsigned)max_tiles), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_attention(const void* q, const void* k, const void* v, void* o,
                             const int64_t* q_off_host, const int64_t* k_off_host, int H,
                             float scale, hipStream_t stream) {
   AttnArgs a;
+  a.dev_q_off = nullptr;
+  a.dev_tiles = nullptr;
   a.q = (const bf16_t*)q;
   a.k = (const bf16_t*)k;
   a.v = (const bf16_t*)v;

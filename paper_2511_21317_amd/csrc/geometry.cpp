@@ -14,6 +14,7 @@ int check_geom(const httm_geom_t& g) {
       g.variant != HTTM_VARIANT_NONE)
     return HTTM_E_INVALID_ARG;
   if (g.flags & ~HTTM_FLAG_ANCHOR_FIRST_FRAME) return HTTM_E_INVALID_ARG;
+  if (!(g.outlier_frac >= 0.0 && g.outlier_frac <= HTTM_MAX_OUTLIER_FRAC)) return HTTM_E_INVALID_ARG;
   if (g.d_head != 64 || g.H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
   const int64_t tpf = (int64_t)g.n_special + (int64_t)g.Hp * g.Wp;
   const int64_t N = tpf * g.S;
@@ -31,6 +32,12 @@ int32_t clusters_kept(int32_t n, double rho, int32_t n0) {
   int32_t k = n - r;
   if (k < 1) k = 1;
   return k < n0 ? n0 : k;
+}
+
+int64_t outlier_budget(const httm_geom_t& g, int64_t N) {
+  // Sec. 3.4 step 3: "the top d % of tokens ... across all heads", rounded down
+  if (g.variant == HTTM_VARIANT_NONE || !(g.outlier_frac > 0.0)) return 0;
+  return (int64_t)std::floor(g.outlier_frac * (double)g.H * (double)N + 1e-9);
 }
 
 int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
@@ -121,6 +128,10 @@ int workspace_layout(const httm_geom_t& g, const HostTables& t, httm_workspace_l
   out->o_m = off;      off = align_up(off + (int64_t)g.H * t.M_q * row, 256);
   out->assign_q = off; off = align_up(off + (int64_t)g.H * t.N * 4, 256);
   out->assign_k = off; off = align_up(off + (int64_t)g.H * t.N * 4, 256);
+  const int64_t cap = outlier_budget(g, t.N);
+  out->eps_q = off;    off = align_up(off + (cap ? (int64_t)g.H * t.N * 4 : 0), 256);
+  out->q_out = off;    off = align_up(off + cap * row, 256);
+  out->o_out = off;    off = align_up(off + cap * row, 256);
   out->total = off;
   return HTTM_OK;
 }

@@ -41,6 +41,9 @@ int check_geom(const httm_geom_t& g);
 // Clusters kept by a block of n tokens at merge ratio rho, at least its n0 anchored tokens.
 int32_t clusters_kept(int32_t n, double rho, int32_t n0 = 0);
 
+// Outlier queries there can be at most (0 when the filter is off).
+int64_t outlier_budget(const httm_geom_t& g, int64_t N);
+
 // Build every table.  `with_pi` = false skips the O(N) permutation (sizes only).
 int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out);
 

@@ -26,6 +26,7 @@ struct MatchMergeStream {
   int64_t M;
   const int32_t* preset;  // [N] cluster slot per reordered token shared by all heads, or nullptr
   const float* preset_score;  // [N] or nullptr
+  float* eps;           // [H, N] out or nullptr: L2 distance of every token to its merged token
 };
 struct MatchMergeArgs {
   MatchMergeStream s[2];
@@ -36,6 +37,47 @@ struct MatchMergeArgs {
   int32_t max_block;
 };
 hipError_t launch_match_merge(const MatchMergeArgs& a, hipStream_t stream);
+
+// ---- adaptive outlier filtering of the merged queries (paper Sec. 3.4, Alg. 2) ---------------
+// State of the device-side selection of the threshold tau.
+struct SelectState {
+  uint32_t prefix;   // leading bits of tau's bit pattern decided so far
+  uint32_t rank;     // descending rank of tau among the values that share the prefix
+  float tau;         // the threshold: a deviation strictly above it marks an outlier
+  uint32_t pad;
+};
+struct OutlierBuffers {      // all device memory, owned by the plan
+  SelectState* state;
+  uint32_t* hist;            // [2048], zero between calls
+  int32_t* counts;           // [H], zero between calls
+  int32_t* offsets;          // [H + 1] first outlier row of every head in q_out / o_out
+  int32_t* cursors;          // [H] rows handed out so far
+  int32_t* tiles;            // [1 + 2 * max_tiles]: n, then (head, first row) per attention tile
+  int32_t max_tiles;
+};
+// tau = the largest of the H*N deviations that is not among the `budget` largest; then the
+// per-head outlier counts, their prefix offsets and the tile list of the second attention
+// (`tile_rows` query rows per tile).
+hipError_t launch_outlier_select(const float* eps, int H, int64_t N, int64_t budget,
+                                 const OutlierBuffers& b, int tile_rows, hipStream_t stream);
+// Un-merge the outliers: recompute the merged queries that lose a constituent, give every
+// outlier token a row in q_out and rewrite its assign_q entry as -1 - row.
+struct RefineArgs {
+  const void* x;          // [H, N, 64] bf16 queries (input order with pi, else reordered)
+  void* xm;               // [H, M, 64] merged queries, updated in place
+  int32_t* assign;        // [H, N], updated in place
+  const float* eps;       // [H, N]
+  void* q_out;            // [budget, 64] bf16
+  const WorkItem* items;
+  int32_t n_items;
+  int64_t M;
+  const int32_t* pi;
+  int64_t N;
+  int32_t H;
+  int32_t max_block;
+  OutlierBuffers b;
+};
+hipError_t launch_outlier_refine(const RefineArgs& a, hipStream_t stream);
 
 // Head-uniform variant: mean over heads of x[H, N, 64] (bf16) -> xbar[N, 64] (fp32), summed in
 // head order; then block-wise matching of the fp32 tokens -> slot[N], score[N].
@@ -49,11 +91,21 @@ constexpr int kAttnMaxHeads = HTTM_MAX_HEADS;
 hipError_t launch_attention(const void* q, const void* k, const void* v, void* o,
                             const int64_t* q_off_host, const int64_t* k_off_host, int H,
                             float scale, hipStream_t stream);
+// Query rows and tiles are described by device memory (the outlier queries of Sec. 3.4, whose
+// number per head is only known on the device): q / o rows of head h are
+// [q_off_dev[h], q_off_dev[h+1]); tiles[0] tiles follow in `tiles` as (head, first row) pairs.
+constexpr int kAttnDevTileRows = 256;
+hipError_t launch_attention_dev_tiles(const void* q, const void* k, const void* v, void* o,
+                                      const int32_t* q_off_dev, const int32_t* tiles, int max_tiles,
+                                      const int64_t* k_off_host, int H, float scale,
+                                      hipStream_t stream);
 
 // ---- stage 4 -------------------------------------------------------------------------------
 // fused != 0: out[pi[j]][h*64 + c] = o_m[h][assign[h][j]][c]  (out is [N, H*64])
 // fused == 0: out[h][j][c]         = o_m[h][assign[h][j]][c]  (out is [H, N, 64])
+// A negative assign entry a refers to row -1 - a of `o_out` (an outlier query's own output row).
 hipError_t launch_unmerge(const void* o_m, const int32_t* assign, const int32_t* pi_dev, void* out,
-                          int H, int64_t N, int64_t M_q, int fused, hipStream_t stream);
+                          int H, int64_t N, int64_t M_q, int fused, hipStream_t stream,
+                          const void* o_out = nullptr);
 
 }  // namespace httm

@@ -139,6 +139,7 @@ void match_merge_kernel(const MatchMergeArgs a) {
     if (tid < n) {
       assign[tid] = it.moff + tid;
       if (score) score[tid] = 1.0f;
+      if (s.eps) s.eps[h * N + it.start + tid] = 0.f;
     }
     return;
   }
@@ -327,11 +328,32 @@ void match_merge_kernel(const MatchMergeArgs a) {
       if (idx < end) add_row_chunk(acc, col + s_list[idx] * kLdsRowBytes, sel);
       const float cnt = (float)(end - beg);
       const float rcnt = 1.0f / cnt;
+      float mean[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) mean[q] = div_by_count(acc[q], cnt, rcnt);
       u32x4 o;
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        o[q] = pack_bf16x2(div_by_count(acc[2 * q], cnt, rcnt), div_by_count(acc[2 * q + 1], cnt, rcnt));
+      for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(mean[2 * q], mean[2 * q + 1]);
       out[mc] = o;
+      if (s.eps && pass == 0) {
+        // Sec. 3.4 step 2: L2 distance of every constituent to the merged token (the fp32 mean);
+        // zero where nothing was merged.  The 8 lanes of a cluster hold 8 channels each.
+        float* __restrict__ eps = s.eps + h * N + it.start;
+        for (int i2 = beg; i2 < end; ++i2) {
+          const int j = s_list[i2];
+          const bf16x8 w = *(const bf16x8*)(col + j * kLdsRowBytes);
+          float d2 = 0.f;
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const float df = (float)w[q] - mean[q];
+            d2 = fmaf(df, df, d2);
+          }
+          d2 += __shfl_xor(d2, 1);
+          d2 += __shfl_xor(d2, 2);
+          d2 += __shfl_xor(d2, 4);
+          if (c == 0) eps[j] = end - beg >= 2 ? sqrtf(d2) : 0.f;
+        }
+      }
     }
     if (pass == 1 || v == nullptr) break;
     __syncthreads();
@@ -342,6 +364,160 @@ void match_merge_kernel(const MatchMergeArgs a) {
       if (row < n) *(u32x4*)(tile + row * kLdsRowBytes + c * 16) = vr[i];
     }
     __syncthreads();
+  }
+}
+
+// ---- un-merging the outliers (Sec. 3.4 step 4; Alg. 2, second loop) ---------------------------------
+//
+// One workgroup per (work item, head), queries only.  Tokens whose deviation lies above tau leave
+// their cluster: the merged tokens that lose a constituent are recomputed from the constituents
+// that remain (dst first if it remains, then ascending position - the order of the first
+// aggregation), a merged token that loses all of them becomes a zero row, and every outlier gets a
+// row of its own in q_out; its assign entry becomes -1 - row.  Work items without an outlier
+// return before they load a single token row.
+template <int NW, int MAXN>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(4, 8)))
+void outlier_refine_kernel(const RefineArgs a) {
+  constexpr int NT = 64 * NW;
+  constexpr int ITER = MAXN * kRowChunks / NT;
+  static_assert(NT == MAXN, "one thread per token");
+  __shared__ __align__(16) unsigned char tile[MAXN * kLdsRowBytes];
+  __shared__ uint16_t s_list[MAXN];
+  __shared__ uint16_t s_off[MAXN + 4];
+  __shared__ uint8_t s_wcnt[NW * MAXN];
+  __shared__ uint16_t s_dpos[MAXN];
+  __shared__ uint8_t s_affected[MAXN];   // cluster m lost a constituent
+  __shared__ uint8_t s_dst_out[MAXN];    // the dst token of cluster m is an outlier
+  __shared__ int s_wout[NW];             // outliers per wave
+  __shared__ int s_base;
+
+  if ((int)blockIdx.x >= a.n_items) return;
+  const WorkItem it = a.items[blockIdx.x];
+  const int n = it.n, k = it.k;
+  if (k == n) return;                    // nothing was merged here: no deviation, no outlier
+  const int64_t h = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t N = a.N, M = a.M;
+  int32_t* __restrict__ assign = a.assign + h * N + it.start;
+  const float tau = a.b.state->tau;
+  int cl = tid < n ? assign[tid] - it.moff : -1;   // cluster before the filter
+  if (cl >= k) cl = -1;                            // (an entry that is not a slot of this item is left alone)
+  const bool is_out = cl >= 0 && a.eps[h * N + it.start + tid] > tau;
+  if (!__syncthreads_or(is_out)) return;
+
+  // ---- rows to LDS ---------------------------------------------------------------------------------
+  const char* __restrict__ x = (const char*)a.x + h * N * kRowBytes;
+  u32x4 xr[ITER];
+#pragma unroll
+  for (int i = 0; i < ITER; ++i) {
+    const int e = tid + i * NT;
+    const int row = e >> 3, c = e & 7;
+    if (row < n) {
+      const uint32_t src = a.pi ? (uint32_t)a.pi[it.start + row] : (uint32_t)(it.start + row);
+      xr[i] = __builtin_nontemporal_load((const u32x4*)(x + src * kRowBytes + c * 16));
+    }
+  }
+  for (int m = tid; m < k; m += NT) {
+    s_dpos[m] = (uint16_t)dst_position(m, n, k, it.n0);
+    s_affected[m] = 0;
+    s_dst_out[m] = 0;
+  }
+  for (int m = lane; m < k; m += 64) s_wcnt[wave * MAXN + m] = 0;
+#pragma unroll
+  for (int i = 0; i < ITER; ++i) {
+    const int e = tid + i * NT;
+    const int row = e >> 3, c = e & 7;
+    if (row < n) *(u32x4*)(tile + row * kLdsRowBytes + c * 16) = xr[i];
+  }
+  __syncthreads();
+
+  // ---- outliers: rows in q_out, new assign entries, affected clusters ----------------------------------
+  const unsigned long long ob = __ballot(is_out);
+  if (lane == 0) s_wout[wave] = __popcll(ob);
+  if (is_out) {
+    s_affected[cl] = 1;
+    if (s_dpos[cl] == tid) s_dst_out[cl] = 1;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int tot = 0;
+    for (int w = 0; w < NW; ++w) tot += s_wout[w];
+    s_base = a.b.offsets[h] + atomicAdd(&a.b.cursors[h], tot);
+  }
+  __syncthreads();
+  if (is_out) {
+    int r = __builtin_amdgcn_mbcnt_hi((uint32_t)(ob >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ob, 0u));
+    for (int w = 0; w < wave; ++w) r += s_wout[w];
+    const int row = s_base + r;
+    assign[tid] = -1 - row;
+    u32x4* __restrict__ dst = (u32x4*)a.q_out + (int64_t)row * kRowChunks;
+#pragma unroll
+    for (int c = 0; c < kRowChunks; ++c) dst[c] = *(const u32x4*)(tile + tid * kLdsRowBytes + c * 16);
+  }
+  const int my_cl = is_out ? -1 : cl;   // members that remain
+
+  // ---- stable counting sort of the remaining members by cluster (as in the first aggregation) ------
+  int my_rank = 0;
+  {
+    unsigned long long same = __ballot(my_cl >= 0);
+    for (int bit = 0; (1 << bit) < k; ++bit) {
+      const bool set = (my_cl >> bit) & 1;
+      const unsigned long long b = __ballot(set);
+      same &= set ? b : ~b;
+    }
+    if (my_cl >= 0) {
+      my_rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(same >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)same, 0u));
+      if (my_rank == 0) s_wcnt[wave * MAXN + my_cl] = (uint8_t)__popcll(same);
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    int carry = 0;
+    for (int m0 = 0; m0 < k; m0 += 64) {
+      const int m = m0 + lane;
+      int tot = 0;
+      if (m < k) {
+#pragma unroll
+        for (int w = 0; w < NW; ++w) tot += s_wcnt[w * MAXN + m];
+      }
+      const int excl = wave_exclusive_scan(tot, lane);
+      if (m < k) s_off[m] = (uint16_t)(carry + excl);
+      carry += __shfl(excl + tot, 63);
+    }
+    if (lane == 0) s_off[k] = (uint16_t)carry;
+  }
+  __syncthreads();
+  if (my_cl >= 0) {
+    int rank = my_rank;
+    for (int w = 0; w < wave; ++w) rank += s_wcnt[w * MAXN + my_cl];
+    const int dp = s_dpos[my_cl];
+    // dst first and the src tokens in ascending position; plain ascending if the dst has left
+    const int pos = s_dst_out[my_cl] ? rank : (tid == dp ? 0 : rank + (dp < tid ? 0 : 1));
+    s_list[s_off[my_cl] + pos] = (uint16_t)tid;
+  }
+  __syncthreads();
+
+  // ---- the affected merged tokens again ---------------------------------------------------------------------
+  const PairSelectors sel = make_pair_selectors();
+  u32x4* __restrict__ xm = (u32x4*)a.xm + (h * M + it.moff) * kRowChunks;
+  for (int mc = tid; mc < k * kRowChunks; mc += NT) {
+    const int m = mc >> 3, c = mc & 7;
+    if (!s_affected[m]) continue;
+    const int beg = s_off[m], end = s_off[m + 1];
+    float acc[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+    const unsigned char* col = tile + c * 16;
+    for (int idx = beg; idx < end; ++idx) add_row_chunk(acc, col + s_list[idx] * kLdsRowBytes, sel);
+    u32x4 o = {0, 0, 0, 0};
+    if (end > beg) {
+      const float cnt = (float)(end - beg);
+      const float rcnt = 1.0f / cnt;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        o[q] = pack_bf16x2(div_by_count(acc[2 * q], cnt, rcnt), div_by_count(acc[2 * q + 1], cnt, rcnt));
+    }
+    xm[mc] = o;
   }
 }
 
@@ -460,6 +636,18 @@ hipError_t launch_match_merge(const MatchMergeArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL((match_merge_kernel<4, 256>), grid, dim3(256), 0, stream, a);
   else
     hipLaunchKernelGGL((match_merge_kernel<8, 512>), grid, dim3(512), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_outlier_refine(const RefineArgs& a, hipStream_t stream) {
+  if (a.n_items == 0 || a.H == 0) return hipSuccess;
+  dim3 grid((unsigned)a.n_items, (unsigned)a.H);
+  if (a.max_block <= 64)
+    hipLaunchKernelGGL((outlier_refine_kernel<1, 64>), grid, dim3(64), 0, stream, a);
+  else if (a.max_block <= 256)
+    hipLaunchKernelGGL((outlier_refine_kernel<4, 256>), grid, dim3(256), 0, stream, a);
+  else
+    hipLaunchKernelGGL((outlier_refine_kernel<8, 512>), grid, dim3(512), 0, stream, a);
   return hipGetLastError();
 }
 

@@ -54,7 +54,8 @@ __global__ __launch_bounds__(kThreads) void reorder_kernel(const u32x4* __restri
 __global__ __launch_bounds__(kThreads) void unmerge_rows_kernel(const u32x4* __restrict__ o_m,
                                                                 const int32_t* __restrict__ assign,
                                                                 u32x4* __restrict__ out, int64_t N,
-                                                                int64_t M_q) {
+                                                                int64_t M_q,
+                                                                const u32x4* __restrict__ o_out) {
   const int c = threadIdx.x & 7;
   const int r = threadIdx.x >> 3;
   const int64_t h = blockIdx.y;
@@ -69,7 +70,9 @@ __global__ __launch_bounds__(kThreads) void unmerge_rows_kernel(const u32x4* __r
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const int64_t j = j0 + u * kRowsPerPass;
-    if (j < N) val[u] = o_m[(h * M_q + idx[u]) * kRowChunks + c];
+    if (j < N)
+      val[u] = idx[u] >= 0 ? o_m[(h * M_q + idx[u]) * kRowChunks + c]
+                           : o_out[(int64_t)(-1 - idx[u]) * kRowChunks + c];   // an outlier's own row
   }
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
@@ -89,7 +92,8 @@ __global__ __launch_bounds__(kThreads) void unmerge_fused_kernel(const u32x4* __
                                                                  const int32_t* __restrict__ assign,
                                                                  const int32_t* __restrict__ pi,
                                                                  u32x4* __restrict__ out, int H,
-                                                                 int64_t N, int64_t M_q) {
+                                                                 int64_t N, int64_t M_q,
+                                                                 const u32x4* __restrict__ o_out) {
   extern __shared__ int32_t lds[];
   int32_t* s_assign = lds;             // [H][kTok]
   int32_t* s_pi = lds + H * kTok;      // [kTok]
@@ -118,8 +122,11 @@ __global__ __launch_bounds__(kThreads) void unmerge_fused_kernel(const u32x4* __
       const int e = e0 + u * kRowsPerPass;
       if (e < total) {
         const int t = e / H, h = e % H;
-        if (j0 + t < N)
-          val[u] = o_m[((int64_t)h * M_q + s_assign[h * kTok + t]) * kRowChunks + c];
+        if (j0 + t < N) {
+          const int32_t sl = s_assign[h * kTok + t];   // negative: row -1 - sl of the outlier outputs
+          val[u] = sl >= 0 ? o_m[((int64_t)h * M_q + sl) * kRowChunks + c]
+                           : o_out[(int64_t)(-1 - sl) * kRowChunks + c];
+        }
       }
     }
 #pragma unroll
@@ -151,17 +158,18 @@ hipError_t launch_reorder(const void* src, void* dst, const int32_t* pi_dev, int
 }
 
 hipError_t launch_unmerge(const void* o_m, const int32_t* assign, const int32_t* pi_dev, void* out,
-                          int H, int64_t N, int64_t M_q, int fused, hipStream_t stream) {
+                          int H, int64_t N, int64_t M_q, int fused, hipStream_t stream,
+                          const void* o_out) {
   if (N == 0 || H == 0) return hipSuccess;
   if (fused) {
     dim3 grid((unsigned)(((N + kTok - 1) / kTok + 7) / 8 * 8));
     const size_t lds = (size_t)(H * kTok + kTok) * sizeof(int32_t);
     hipLaunchKernelGGL(unmerge_fused_kernel, grid, dim3(kThreads), lds, stream, (const u32x4*)o_m,
-                       assign, pi_dev, (u32x4*)out, H, N, M_q);
+                       assign, pi_dev, (u32x4*)out, H, N, M_q, (const u32x4*)o_out);
   } else {
     dim3 grid((unsigned)((N + kRowsPerWg - 1) / kRowsPerWg), (unsigned)H);
     hipLaunchKernelGGL(unmerge_rows_kernel, grid, dim3(kThreads), 0, stream, (const u32x4*)o_m,
-                       assign, (u32x4*)out, N, M_q);
+                       assign, (u32x4*)out, N, M_q, (const u32x4*)o_out);
   }
   return hipGetLastError();
 }

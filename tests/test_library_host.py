@@ -74,6 +74,28 @@ def test_merged_lengths_of_the_five_workloads():
     assert none.M_q == none.N == 10992
 
 
+def test_outlier_budget_and_workspace_regions():
+    """Sec. 3.4 step 3: the budget is floor(d * H * N); its three workspace regions exist only then."""
+    g0 = httm.make_geom(8, 37, 37, 4, 2, 0.5)
+    g1 = httm.make_geom(8, 37, 37, 4, 2, 0.5, outlier_frac=0.02)
+    s0, s1 = httm.geom_sizes(g0), httm.geom_sizes(g1)
+    assert s0.outlier_cap == 0 and s1.outlier_cap == orc.outlier_budget(16 * 10992, 0.02) == 3517
+    w0, w1 = httm.workspace_layout(g0), httm.workspace_layout(g1)
+    assert w0.eps_q == w0.q_out == w0.o_out == w0.total
+    assert w1.q_out - w1.eps_q >= 16 * 10992 * 4 and w1.o_out - w1.q_out >= 3517 * 128
+    assert w1.total - w1.o_out >= 3517 * 128 and w1.total == s1.workspace_bytes
+    assert httm.geom_sizes(httm.make_geom(8, 37, 37, 4, 2, 0.5, variant="none", outlier_frac=0.1)).outlier_cap == 0
+    L, s = httm.lib(), httm.Sizes()
+    for bad_frac in (-0.1, 0.6, float("nan")):
+        bad = httm.make_geom(8, 37, 37, 4, 2, 0.5, outlier_frac=bad_frac)
+        assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -1
+    # the filtered entry points refuse a missing plan before touching the GPU
+    assert L.httm_reorder_match_merge_filtered(None, None, None, None, None, None, None, None, None,
+                                               None, None, None) == -1
+    assert L.httm_attention_outliers(None, None, None, None, None, None) == -1
+    assert L.httm_unmerge_filtered(None, None, None, None, None, None) == -1
+
+
 def test_argument_errors_are_reported_not_crashed():
     L = httm.lib()
     s = httm.Sizes()
