@@ -245,8 +245,8 @@ HTTM_API int httm_workspace_layout(const httm_geom_t* g, httm_workspace_layout_t
  * assign_q : [H, N] int32 out; slot in 0..M_q-1, or -1 - r for an outlier whose query sits in row r
  *            of q_out.
  * eps_q    : [H, N] float out, the deviations.
- * q_out    : [outlier_cap, d_head] bf16 out; the outlier queries, grouped by head (the order inside
- *            a head is not fixed from run to run; results do not depend on it). */
+ * q_out    : [outlier_cap, d_head] bf16 out; the outlier queries, grouped by head and, inside a
+ *            head, in ascending reordered position. */
 HTTM_API int httm_reorder_match_merge_filtered(const httm_plan_t* plan, const void* q, const void* k,
                                                const void* v, void* q_m, void* k_m, void* v_m,
                                                int32_t* assign_q, int32_t* assign_k, float* eps_q,

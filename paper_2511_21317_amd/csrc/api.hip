@@ -113,8 +113,8 @@ int run_match_merge_filtered(const httm_plan_t* p, const void* q, const void* k,
   int rc = run_match_merge(p, p->d_pi, q, k, v, q_m, k_m, v_m, assign_q, assign_k, nullptr, nullptr,
                            st, eps_q);
   if (rc != HTTM_OK) return rc;
-  HTTM_HIP(launch_outlier_select(eps_q, p->geom.H, p->sizes.N, p->outlier_cap, p->ob,
-                                 kAttnDevTileRows, st));
+  HTTM_HIP(launch_outlier_select(eps_q, p->geom.H, p->sizes.N, p->outlier_cap, p->d_items_q,
+                                 p->n_items, p->ob, kAttnDevTileRows, st));
   RefineArgs r;
   std::memset(&r, 0, sizeof(r));
   r.x = q;
@@ -129,6 +129,7 @@ int run_match_merge_filtered(const httm_plan_t* p, const void* q, const void* k,
   r.N = p->sizes.N;
   r.H = p->geom.H;
   r.max_block = (int32_t)(p->sizes.max_block < kPrefixChunk ? kPrefixChunk : p->sizes.max_block);
+  r.eager = (double)p->outlier_cap * (double)p->sizes.max_block >= (double)p->geom.H * (double)p->sizes.N;
   r.b = p->ob;
   HTTM_HIP(launch_outlier_refine(r, st));
   return HTTM_OK;
@@ -228,7 +229,8 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
   if (rc == HTTM_OK && p->outlier_cap > 0) {
     OutlierBuffers& b = p->ob;
     b.max_tiles = (int32_t)(p->outlier_cap / kAttnDevTileRows + g->H);
-    const size_t words = sizeof(SelectState) / 4 + 2048 + (size_t)g->H * 3 + 1 + 1 + 2 * (size_t)b.max_tiles;
+    const size_t words = sizeof(SelectState) / 4 + 2048 + (size_t)g->H * 2 + 1 +
+                         (size_t)g->H * p->n_items + 1 + 2 * (size_t)b.max_tiles;
     uint32_t* base = nullptr;
     e = hipMalloc((void**)&base, words * 4);
     if (e == hipSuccess) e = hipMemset(base, 0, words * 4);
@@ -239,8 +241,8 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
       b.hist = base + sizeof(SelectState) / 4;
       b.counts = (int32_t*)(b.hist + 2048);
       b.offsets = b.counts + g->H;
-      b.cursors = b.offsets + g->H + 1;
-      b.tiles = b.cursors + g->H;
+      b.item_base = b.offsets + g->H + 1;
+      b.tiles = b.item_base + (size_t)g->H * p->n_items;
     }
   }
   if (rc != HTTM_OK) {

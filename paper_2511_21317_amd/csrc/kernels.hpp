@@ -49,17 +49,18 @@ struct SelectState {
 struct OutlierBuffers {      // all device memory, owned by the plan
   SelectState* state;
   uint32_t* hist;            // [2048], zero between calls
-  int32_t* counts;           // [H], zero between calls
+  int32_t* counts;           // [H] outliers per head
   int32_t* offsets;          // [H + 1] first outlier row of every head in q_out / o_out
-  int32_t* cursors;          // [H] rows handed out so far
+  int32_t* item_base;        // [H][n_items] first outlier row of a work item, relative to its head
   int32_t* tiles;            // [1 + 2 * max_tiles]: n, then (head, first row) per attention tile
   int32_t max_tiles;
 };
 // tau = the largest of the H*N deviations that is not among the `budget` largest; then the
-// per-head outlier counts, their prefix offsets and the tile list of the second attention
-// (`tile_rows` query rows per tile).
+// outlier counts per (work item, head), their prefix offsets and the tile list of the second
+// attention (`tile_rows` query rows per tile).
 hipError_t launch_outlier_select(const float* eps, int H, int64_t N, int64_t budget,
-                                 const OutlierBuffers& b, int tile_rows, hipStream_t stream);
+                                 const WorkItem* items, int n_items, const OutlierBuffers& b,
+                                 int tile_rows, hipStream_t stream);
 // Un-merge the outliers: recompute the merged queries that lose a constituent, give every
 // outlier token a row in q_out and rewrite its assign_q entry as -1 - row.
 struct RefineArgs {
@@ -75,6 +76,7 @@ struct RefineArgs {
   int64_t N;
   int32_t H;
   int32_t max_block;
+  int32_t eager;          // request the token rows before testing the item for outliers
   OutlierBuffers b;
 };
 hipError_t launch_outlier_refine(const RefineArgs& a, hipStream_t stream);

@@ -68,6 +68,19 @@ __device__ __forceinline__ void add_row_chunk(float (&acc)[8], const unsigned ch
   }
 }
 
+// Sum of x over the aligned group of 8 lanes a lane belongs to, returned in all 8 lanes; data-parallel
+// primitives only (no LDS): lane^1 and lane^2 inside a quad, then the mirrored lane of the other quad
+// (which by then holds that quad's sum).
+__device__ __forceinline__ float sum_over_8_lanes(float x) {
+  int v = __builtin_bit_cast(int, x);
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  v = __builtin_bit_cast(int, x);
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  v = __builtin_bit_cast(int, x);
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  return x;
+}
+
 // a / b for a small positive integer-valued b, correctly rounded: one Newton step on the product
 // with the hardware reciprocal (the residual is exact thanks to the fma).
 __device__ __forceinline__ float div_by_count(float a, float b, float rb) {
@@ -348,9 +361,7 @@ void match_merge_kernel(const MatchMergeArgs a) {
             const float df = (float)w[q] - mean[q];
             d2 = fmaf(df, df, d2);
           }
-          d2 += __shfl_xor(d2, 1);
-          d2 += __shfl_xor(d2, 2);
-          d2 += __shfl_xor(d2, 4);
+          d2 = sum_over_8_lanes(d2);
           if (c == 0) eps[j] = end - beg >= 2 ? sqrtf(d2) : 0.f;
         }
       }
@@ -389,7 +400,6 @@ void outlier_refine_kernel(const RefineArgs a) {
   __shared__ uint8_t s_affected[MAXN];   // cluster m lost a constituent
   __shared__ uint8_t s_dst_out[MAXN];    // the dst token of cluster m is an outlier
   __shared__ int s_wout[NW];             // outliers per wave
-  __shared__ int s_base;
 
   if ((int)blockIdx.x >= a.n_items) return;
   const WorkItem it = a.items[blockIdx.x];
@@ -399,24 +409,30 @@ void outlier_refine_kernel(const RefineArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t N = a.N, M = a.M;
   int32_t* __restrict__ assign = a.assign + h * N + it.start;
+  // The token rows are requested before it is known whether the item has an outlier at all when
+  // outliers are dense (`eager`: at least one per largest block on average), so that the row
+  // latency does not queue behind the latency of the deviations; otherwise after the test.
+  const char* __restrict__ x = (const char*)a.x + h * N * kRowBytes;
+  u32x4 xr[ITER];
+#define HTTM_REFINE_ISSUE_ROW_LOADS()                                                             \
+  _Pragma("unroll") for (int i = 0; i < ITER; ++i) {                                              \
+    const int e = tid + i * NT;                                                                   \
+    const int row = e >> 3, c = e & 7;                                                            \
+    if (row < n) {                                                                                \
+      const uint32_t src = a.pi ? (uint32_t)a.pi[it.start + row] : (uint32_t)(it.start + row);    \
+      xr[i] = __builtin_nontemporal_load((const u32x4*)(x + src * kRowBytes + c * 16));           \
+    }                                                                                             \
+  }
+  if (a.eager) HTTM_REFINE_ISSUE_ROW_LOADS()
   const float tau = a.b.state->tau;
   int cl = tid < n ? assign[tid] - it.moff : -1;   // cluster before the filter
   if (cl >= k) cl = -1;                            // (an entry that is not a slot of this item is left alone)
   const bool is_out = cl >= 0 && a.eps[h * N + it.start + tid] > tau;
   if (!__syncthreads_or(is_out)) return;
+  if (!a.eager) HTTM_REFINE_ISSUE_ROW_LOADS()
+#undef HTTM_REFINE_ISSUE_ROW_LOADS
 
   // ---- rows to LDS ---------------------------------------------------------------------------------
-  const char* __restrict__ x = (const char*)a.x + h * N * kRowBytes;
-  u32x4 xr[ITER];
-#pragma unroll
-  for (int i = 0; i < ITER; ++i) {
-    const int e = tid + i * NT;
-    const int row = e >> 3, c = e & 7;
-    if (row < n) {
-      const uint32_t src = a.pi ? (uint32_t)a.pi[it.start + row] : (uint32_t)(it.start + row);
-      xr[i] = __builtin_nontemporal_load((const u32x4*)(x + src * kRowBytes + c * 16));
-    }
-  }
   for (int m = tid; m < k; m += NT) {
     s_dpos[m] = (uint16_t)dst_position(m, n, k, it.n0);
     s_affected[m] = 0;
@@ -439,16 +455,11 @@ void outlier_refine_kernel(const RefineArgs a) {
     if (s_dpos[cl] == tid) s_dst_out[cl] = 1;
   }
   __syncthreads();
-  if (tid == 0) {
-    int tot = 0;
-    for (int w = 0; w < NW; ++w) tot += s_wout[w];
-    s_base = a.b.offsets[h] + atomicAdd(&a.b.cursors[h], tot);
-  }
-  __syncthreads();
   if (is_out) {
+    // rows of q_out: the head's range, then this work item's share of it, then ascending position
     int r = __builtin_amdgcn_mbcnt_hi((uint32_t)(ob >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ob, 0u));
     for (int w = 0; w < wave; ++w) r += s_wout[w];
-    const int row = s_base + r;
+    const int row = a.b.offsets[h] + a.b.item_base[h * a.n_items + blockIdx.x] + r;
     assign[tid] = -1 - row;
     u32x4* __restrict__ dst = (u32x4*)a.q_out + (int64_t)row * kRowChunks;
 #pragma unroll

@@ -7,8 +7,10 @@
 // of every value that matches the digits fixed so far (LDS atomics, then one global atomic per
 // non-empty bin) and a one-workgroup kernel walks the histogram from the top to the wanted
 // rank.  Integer counts only, so the result does not depend on the order of the atomics.
-// Then one pass counts the values above the threshold per head, and one small kernel turns
-// the counts into row offsets and into the tile list of the second attention.
+// Then one pass counts the values above the threshold per (work item, head), a prefix sum per
+// head gives every work item the first outlier row it owns (no atomics: the rows of q_out are
+// the same from run to run), and one wave turns the head totals into row offsets and into the
+// tile list of the second attention.
 #include "dev_common.hpp"
 #include "kernels.hpp"
 
@@ -102,69 +104,102 @@ __global__ __launch_bounds__(kSelThreads) void select_pick_kernel(uint32_t* __re
   }
 }
 
-// counts[h] += number of deviations of head h above tau
+// item_cnt[h][i] = number of deviations above tau among the tokens of work item i of head h.
+// One wave per (item, head).
 __global__ __launch_bounds__(256) void outlier_count_kernel(const float* __restrict__ eps, int64_t N,
+                                                            const WorkItem* __restrict__ items, int n_items,
                                                             const SelectState* __restrict__ st,
-                                                            int32_t* __restrict__ counts) {
+                                                            int32_t* __restrict__ item_cnt) {
+  const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= n_items) return;
+  const int lane = threadIdx.x & 63;
   const float tau = st->tau;
-  const float* e = eps + (int64_t)blockIdx.y * N;
+  const WorkItem it = items[item];
+  const float* e = eps + (int64_t)blockIdx.y * N + it.start;
   int c = 0;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < N; i += (int64_t)gridDim.x * 256)
-    c += e[i] > tau ? 1 : 0;
+  for (int t = lane; t < it.n; t += 64) c += e[t] > tau ? 1 : 0;
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d);
-  __shared__ int s_c[4];
-  if ((threadIdx.x & 63) == 0) s_c[threadIdx.x >> 6] = c;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const int tot = s_c[0] + s_c[1] + s_c[2] + s_c[3];
-    if (tot) atomicAdd(&counts[blockIdx.y], tot);
-  }
+  if (lane == 0) item_cnt[(int64_t)blockIdx.y * n_items + item] = c;
 }
 
-// One thread: row offsets per head, zeroed cursors and counts, and the (head, first row) list of
-// the second attention's query tiles.
-__global__ void outlier_offsets_kernel(int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
-                                       int32_t* __restrict__ cursors, int32_t* __restrict__ tiles,
-                                       int H, int tile_rows, int max_tiles) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  int32_t off = 0, nt = 0;
-  for (int h = 0; h < H; ++h) {
-    const int32_t c = counts[h];
-    counts[h] = 0;
-    cursors[h] = 0;
+// One workgroup per head: exclusive prefix sum of the head's item counts, in place, so that every
+// work item knows the first outlier row it owns (relative to its head); counts[h] = the head's total.
+__global__ __launch_bounds__(256) void outlier_scan_kernel(int32_t* __restrict__ item_cnt, int n_items,
+                                                           int32_t* __restrict__ counts) {
+  __shared__ int s_part[256];
+  int32_t* c = item_cnt + (int64_t)blockIdx.x * n_items;
+  const int t = threadIdx.x;
+  const int per = (n_items + 255) / 256;
+  const int i0 = t * per, i1 = i0 + per < n_items ? i0 + per : n_items;
+  int sum = 0;
+  for (int i = i0; i < i1; ++i) sum += c[i];
+  s_part[t] = sum;
+  __syncthreads();
+  int base = 0;
+  for (int u = 0; u < t; ++u) base += s_part[u];
+  for (int i = i0; i < i1; ++i) {
+    const int v = c[i];
+    c[i] = base;
+    base += v;
+  }
+  if (t == 255) counts[blockIdx.x] = base;
+}
+
+// One wave: first outlier row of every head, and the (head, first row) list of the second
+// attention's query tiles.  Lane h looks after head h (H <= 64).
+__global__ __launch_bounds__(64) void outlier_offsets_kernel(const int32_t* __restrict__ counts,
+                                                             int32_t* __restrict__ offsets,
+                                                             int32_t* __restrict__ tiles, int H,
+                                                             int tile_rows, int max_tiles) {
+  const int h = threadIdx.x;
+  int32_t off = 0, first_tile = 0, mine = 0;
+  for (int g = 0; g < H; ++g) {
+    const int32_t c = counts[g];
+    if (g < h) {
+      off += c;
+      first_tile += (c + tile_rows - 1) / tile_rows;
+    }
+    if (g == h) mine = c;
+  }
+  if (h < H) {
     offsets[h] = off;
-    for (int32_t r = 0; r < c && nt < max_tiles; r += tile_rows) {
+    int nt = first_tile;
+    for (int32_t r = 0; r < mine && nt < max_tiles; r += tile_rows, ++nt) {
       tiles[1 + 2 * nt] = h;
       tiles[2 + 2 * nt] = r;
-      ++nt;
     }
-    off += c;
+    if (h == H - 1) {
+      offsets[H] = off + mine;
+      tiles[0] = nt < max_tiles ? nt : max_tiles;
+    }
   }
-  offsets[H] = off;
-  tiles[0] = nt;
 }
 
 }  // namespace
 
 hipError_t launch_outlier_select(const float* eps, int H, int64_t N, int64_t budget,
-                                 const OutlierBuffers& b, int tile_rows, hipStream_t stream) {
+                                 const WorkItem* items, int n_items, const OutlierBuffers& b,
+                                 int tile_rows, hipStream_t stream) {
   const int64_t total = (int64_t)H * N;
   if (total == 0) return hipSuccess;
   const uint32_t* keys = (const uint32_t*)eps;
+  // Few workgroups: each ends with one global atomic per non-empty bin, and the values crowd into
+  // a handful of bins in the first pass, so the number of workgroups is what serialises there.
   int64_t want = (total / 4 + kSelThreads - 1) / kSelThreads;
-  const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+  const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 256 ? 256 : want));
   hipLaunchKernelGGL(select_hist_kernel<0>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist);
   hipLaunchKernelGGL(select_pick_kernel<0>, dim3(1), dim3(kSelThreads), 0, stream, b.hist, b.state, (uint32_t)budget);
   hipLaunchKernelGGL(select_hist_kernel<1>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist);
   hipLaunchKernelGGL(select_pick_kernel<1>, dim3(1), dim3(kSelThreads), 0, stream, b.hist, b.state, (uint32_t)budget);
   hipLaunchKernelGGL(select_hist_kernel<2>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist);
   hipLaunchKernelGGL(select_pick_kernel<2>, dim3(1), dim3(kSelThreads), 0, stream, b.hist, b.state, (uint32_t)budget);
-  int64_t cw = (N + 256 * 16 - 1) / (256 * 16);
-  const unsigned cgrid = (unsigned)(cw < 1 ? 1 : (cw > 256 ? 256 : cw));
-  hipLaunchKernelGGL(outlier_count_kernel, dim3(cgrid, (unsigned)H), dim3(256), 0, stream, eps, N, b.state, b.counts);
-  hipLaunchKernelGGL(outlier_offsets_kernel, dim3(1), dim3(64), 0, stream, b.counts, b.offsets, b.cursors,
-                     b.tiles, H, tile_rows, b.max_tiles);
+  hipLaunchKernelGGL(outlier_count_kernel, dim3((unsigned)((n_items + 3) / 4), (unsigned)H), dim3(256), 0,
+                     stream, eps, N, items, n_items, b.state, b.item_base);
+  hipLaunchKernelGGL(outlier_scan_kernel, dim3((unsigned)H), dim3(256), 0, stream, b.item_base, n_items,
+                     b.counts);
+  hipLaunchKernelGGL(outlier_offsets_kernel, dim3(1), dim3(64), 0, stream, b.counts, b.offsets, b.tiles, H,
+                     tile_rows, b.max_tiles);
   return hipGetLastError();
 }
 
