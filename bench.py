@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the r=0 and head-uniform runs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--stage-iters", type=int, default=10)
+    ap.add_argument("--outlier-frac", type=float, default=0.0,
+                    help="time the layer WITH the adaptive outlier filtering of the queries (Sec. 3.4) at "
+                         "this share of all query tokens; 0 (default) is the benchmark's configuration")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -117,7 +120,9 @@ def main():
     q, k, v = synth.make_qkv(w, device="cuda")
     torch.cuda.synchronize()
 
-    plan = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H, n_special=w.n_special))
+    filtered = args.outlier_frac > 0.0
+    plan = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H, n_special=w.n_special,
+                                    outlier_frac=args.outlier_frac))
     H, N, Mq, Mk = plan.H, plan.N, plan.M_q, plan.M_k
     out = torch.empty((N, H * 64), dtype=torch.bfloat16, device="cuda")
     ws = httm.alloc_workspace(plan)
@@ -143,17 +148,29 @@ def main():
     k_off = [h * Mk for h in range(H + 1)]
     qr = torch.empty_like(q)
     t_reorder = gpu_time_ms(lambda: httm.reorder(plan, q, qr, 0), it)
-    t_fused_merge = gpu_time_ms(lambda: httm.reorder_match_merge(
-        plan, q, k, v, views["q_m"], views["k_m"], views["v_m"], views["assign_q"], views["assign_k"]), it)
-    kr, vr = torch.empty_like(k), torch.empty_like(v)
-    httm.reorder(plan, k, kr, 0)
-    httm.reorder(plan, v, vr, 0)
-    t_merge = gpu_time_ms(lambda: httm.match_merge(
-        plan, qr, kr, vr, views["q_m"], views["k_m"], views["v_m"], views["assign_q"], views["assign_k"]), it)
-    del kr, vr
+    if filtered:
+        t_fused_merge = gpu_time_ms(lambda: httm.reorder_match_merge_filtered(
+            plan, q, k, v, views["q_m"], views["k_m"], views["v_m"], views["assign_q"], views["assign_k"],
+            views["eps_q"], views["q_out"]), it)
+        t_merge = float("nan")
+    else:
+        t_fused_merge = gpu_time_ms(lambda: httm.reorder_match_merge(
+            plan, q, k, v, views["q_m"], views["k_m"], views["v_m"], views["assign_q"], views["assign_k"]), it)
+        kr, vr = torch.empty_like(k), torch.empty_like(v)
+        httm.reorder(plan, k, kr, 0)
+        httm.reorder(plan, v, vr, 0)
+        t_merge = gpu_time_ms(lambda: httm.match_merge(
+            plan, qr, kr, vr, views["q_m"], views["k_m"], views["v_m"], views["assign_q"], views["assign_k"]), it)
+        del kr, vr
     t_attn = gpu_time_ms(lambda: httm.attention(views["q_m"], views["k_m"], views["v_m"], views["o_m"],
                                                 q_off, k_off, 0.125), it)
-    t_unmerge = gpu_time_ms(lambda: httm.unmerge(plan, views["o_m"], views["assign_q"], out, True), it)
+    if filtered:
+        t_attn2 = gpu_time_ms(lambda: httm.attention_outliers(plan, views["q_out"], views["k_m"],
+                                                              views["v_m"], views["o_out"]), it)
+        t_unmerge = gpu_time_ms(lambda: httm.unmerge_filtered(plan, views["o_m"], views["o_out"],
+                                                              views["assign_q"], out), it)
+    else:
+        t_unmerge = gpu_time_ms(lambda: httm.unmerge(plan, views["o_m"], views["assign_q"], out, True), it)
     del qr
 
     b_reorder = 2 * H * N * row                                   # one tensor, read + write
@@ -176,6 +193,14 @@ def main():
         "unmerge_inverse_reorder_fused": {"ms": t_unmerge, "GB/s": gbs(b_unmerge, t_unmerge),
                                           "frac_hbm": gbs(b_unmerge, t_unmerge) / PEAK_HBM_GBS},
     }
+    if filtered:
+        tau, counts = httm.outlier_stats(plan)
+        f2 = 4.0 * sum(counts) * Mk * 64
+        del stages["match_merge_on_reordered"]
+        stages["reorder_match_merge_fused"] = {"ms": t_fused_merge, "with_outlier_filter": True}
+        stages["outlier_attention"] = {"ms": t_attn2, "TFLOP/s": f2 / (t_attn2 * 1e-3) / 1e12,
+                                       "outliers": sum(counts), "tau": tau}
+        stages["unmerge_inverse_reorder_fused"] = {"ms": t_unmerge, "with_outlier_rows": True}
     for name, s in stages.items():
         log(f"[bench] {name}: " + ", ".join(f"{k_}={v_:.4g}" for k_, v_ in s.items()))
 
@@ -188,7 +213,7 @@ def main():
 
     # ---- extras: unmerged attention and the head-uniform variant on the same inputs -------------
     extras = {}
-    if not args.no_extras:
+    if not args.no_extras and not filtered:
         del ws, views, out
         torch.cuda.empty_cache()
         plan_u = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H,
@@ -251,7 +276,7 @@ def main():
         torch.cuda.empty_cache()
 
     cpu = None
-    if not args.no_cpu:
+    if not args.no_cpu and not filtered:   # the CPU leg times the benchmark's own configuration
         log("[bench] timing the CPU oracle on a bounded sample ...")
         cpu = cpu_oracle_baseline(w, q.cpu(), k.cpu(), v.cpu())
         log(f"[bench] cpu oracle: {cpu['value']:.4g} tokens/s on {cpu['cores']} threads ({cpu['sample']})")
@@ -270,7 +295,8 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "S": w.S, "grid": [w.Hp, w.Wp], "N": N, "H": H, "d_head": 64,
-                   "block": [w.b, w.b, w.T], "rho": w.rho, "M_q": Mq, "M_k": Mk},
+                   "block": [w.b, w.b, w.T], "rho": w.rho, "M_q": Mq, "M_k": Mk,
+                   "outlier_frac": args.outlier_frac},
         "roofline": roofline,
         "stages": stages,
         "extras": extras,

@@ -170,3 +170,76 @@ def test_filtered_layer_forward_matches_the_oracle(idx, frac):
     assert not torch.equal(out0, out)
     plain.close()
     plan.close()
+
+
+def test_filtered_layer_full_size_sampled():
+    """Workload 5 at the paper's setting (Sec. 4.1: 90 % of the queries merged, 10 % of all query
+    tokens filtered out again), in the launch configuration the benchmark times.  The threshold
+    needs the deviations of all heads, so the oracle matches and aggregates the queries of every
+    head; merged tokens, attention rows and outputs are then checked for one head on samples."""
+    require_gpu()
+    w, frac, h = synth.workload(5), 0.1, 3
+    print(f"[case] filtered layer {w.name} frac={frac}", flush=True)
+    q, k, v = synth.make_qkv(w, device="cuda")
+    plan = plan_for(w, outlier_frac=frac)
+    out = torch.empty((plan.N, plan.H * 64), dtype=torch.bfloat16, device="cuda")
+    ws = httm.alloc_workspace(plan)
+    httm.layer_forward(plan, q, k, v, out, ws)
+    tau_gpu, counts = httm.outlier_stats(plan)
+    views = httm.workspace_views(plan, ws)
+    g = oracle_geom(w)
+    pi, blocks = orc.temporal_reorder(g)
+    eps_all, keep = [], {}
+    for hh in range(w.H):
+        qr = orc.reorder(f32(q[hh]), pi)
+        aq, _, gap = orc.blockwise_tome(qr, g, blocks, w.rho)
+        qm0 = orc.block_aggregate(qr, aq, g, blocks, w.rho)
+        eps_all.append(orc.deviations(qr, aq, qm0))
+        if hh == h:
+            keep = dict(qr=qr, aq=aq, gap=gap, qm0=qm0)
+        print(f"[step] oracle deviations head {hh}", flush=True)
+    tau = orc.outlier_threshold(np.concatenate(eps_all), frac)
+    assert abs(tau_gpu - tau) <= 1e-5 * tau
+    assert sum(counts) <= plan.outlier_cap and sum(counts) >= plan.outlier_cap - 16
+    n_ref = [int((e > tau).sum()) for e in eps_all]
+    assert max(abs(a - b) for a, b in zip(counts, n_ref)) <= 8           # per-head split of the shared budget
+    # ---- head h in detail
+    qr, aq, gap = keep["qr"], keep["aq"], keep["gap"]
+    mask = eps_all[h] > tau
+    a_gpu = views["assign_q"][h].cpu().numpy()
+    m_gpu = a_gpu < 0
+    flip = np.flatnonzero(m_gpu != mask)
+    assert flip.size <= 1e-3 * a_gpu.size
+    if flip.size:
+        assert ((np.abs(eps_all[h][flip] - tau) <= NEAR_TAU * tau) | (gap[flip] < 1e-3)).all()
+    bad = check_assign(a_gpu[~m_gpu], aq[~m_gpu], gap[~m_gpu], "cfg5 filtered assign_q")
+    e_gpu = views["eps_q"][h].cpu().numpy()
+    same = m_gpu | (a_gpu == aq)
+    assert np.abs(e_gpu - eps_all[h])[same].max() <= 2e-5 * float(eps_all[h].max())
+    qm = orc.remove_outliers(qr, aq, keep["qm0"], mask, g, blocks, w.rho)
+    kr, vr = orc.reorder(f32(k[h]), pi), orc.reorder(f32(v[h]), pi)
+    ak, _, _ = orc.blockwise_tome(kr, g, blocks, w.rho)
+    km = orc.block_aggregate(kr, ak, g, blocks, w.rho)
+    vm = orc.block_aggregate(vr, ak, g, blocks, w.rho)
+    if flip.size == 0 and bad == 0:
+        assert (np.abs(f32(views["q_m"][h]) - qm) <= 2.0 ** -8 * np.abs(qm) + 1e-30).all()
+    rng = np.random.default_rng(55)
+    # merged rows that still have a constituent
+    alive = np.flatnonzero(np.bincount(aq[~mask], minlength=qm.shape[0]) > 0)
+    rows = np.sort(rng.choice(alive, size=512, replace=False))
+    want = orc.attention(qm, km, vm, rows=rows)
+    check_output(f32(views["o_m"][h][torch.from_numpy(rows).cuda()]), want, "cfg5 filtered o_m")
+    # outlier rows
+    pos = np.sort(rng.choice(np.flatnonzero(mask & m_gpu), size=512, replace=False))
+    want_o = orc.attention(qr[pos], km, vm)
+    got_o = f32(out[torch.from_numpy(pi[pos]).cuda(), h * 64:(h + 1) * 64])
+    err, rel = check_output(got_o, want_o, "cfg5 outlier output rows")
+    print(f"cfg5 d={frac}: tau {tau:.6g}, outliers {sum(counts)}, head {h} flips {flip.size}, "
+          f"outlier rows max_abs {err:.4g} rel_l2 {rel:.4g}", flush=True)
+    # tokens that stay merged read the row of their (recomputed) merged query
+    row_of = -np.ones(qm.shape[0], dtype=np.int64)
+    row_of[rows] = np.arange(rows.size)
+    sel = np.flatnonzero(~mask & ~m_gpu & (row_of[aq] >= 0) & (a_gpu == aq))
+    got_m = f32(out[torch.from_numpy(pi[sel]).cuda(), h * 64:(h + 1) * 64])
+    check_output(got_m, want[row_of[aq[sel]]], "cfg5 filtered merged output rows")
+    plan.close()
