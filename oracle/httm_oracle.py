@@ -72,6 +72,8 @@ class Geometry:
     T: int              # temporal block length (frames)
     n_special: int = 5  # special tokens at the front of each frame
     anchor: bool = False  # first-frame anchoring (App. C.2): every frame-0 token is a dst
+    chunked: bool = False  # spatial blocks are runs of b consecutive patch tokens of a frame (row-major)
+                           # instead of b x b windows: the paper's own setting n_s = 128 (Sec. 4.1)
 
     @property
     def tokens_per_frame(self) -> int:
@@ -95,12 +97,31 @@ def token_index(g: Geometry, frame: int, slot: int) -> int:
     return frame * g.tokens_per_frame + slot
 
 
+def spatial_windows(g: Geometry) -> list:
+    """Patch slots (row-major index y * Wp + x) of every spatial block of a frame, in block order.
+
+    Windowed form: b x b windows of the patch grid, row-major over windows, partial at the right /
+    bottom edge.  Chunked form (Sec. 4.1 "spatial block size n_s"): runs of b consecutive patch
+    tokens in the frame's own token order, the last run partial.
+    """
+    P = g.Hp * g.Wp
+    if g.chunked:
+        return [list(range(c, min(P, c + g.b))) for c in range(0, P, g.b)]
+    out = []
+    for by in range(-(-g.Hp // g.b)):
+        rows = range(by * g.b, min(g.Hp, (by + 1) * g.b))
+        for bx in range(-(-g.Wp // g.b)):
+            cols = range(bx * g.b, min(g.Wp, (bx + 1) * g.b))
+            out.append([y * g.Wp + x for y in rows for x in cols])
+    return out
+
+
 def temporal_reorder(g: Geometry):
     """Permutation pi and block list of the temporal reordering (Sec. 3.3).
 
     pi[j] is the input position of the token that sits at reordered position
     j.  `blocks` lists (start, n) in reordered coordinates: the same spatial
-    window of every frame of a temporal group, stacked.
+    block (see spatial_windows) of every frame of a temporal group, stacked.
     """
     pi = []
     for f in range(g.S):
@@ -108,20 +129,14 @@ def temporal_reorder(g: Geometry):
             pi.append(token_index(g, f, s))
     blocks = []
     n_groups = -(-g.S // g.T)
-    n_by = -(-g.Hp // g.b)
-    n_bx = -(-g.Wp // g.b)
     for grp in range(n_groups):
         frames = range(grp * g.T, min(g.S, (grp + 1) * g.T))
-        for by in range(n_by):
-            rows = range(by * g.b, min(g.Hp, (by + 1) * g.b))
-            for bx in range(n_bx):
-                cols = range(bx * g.b, min(g.Wp, (bx + 1) * g.b))
-                start = len(pi)
-                for f in frames:
-                    for y in rows:
-                        for x in cols:
-                            pi.append(token_index(g, f, g.n_special + y * g.Wp + x))
-                blocks.append((start, len(pi) - start))
+        for window in spatial_windows(g):
+            start = len(pi)
+            for f in frames:
+                for slot in window:
+                    pi.append(token_index(g, f, g.n_special + slot))
+            blocks.append((start, len(pi) - start))
     return np.asarray(pi, dtype=np.int64), blocks
 
 
@@ -134,15 +149,10 @@ def anchor_sizes(g: Geometry) -> list:
     every other block has none.
     """
     n_groups = -(-g.S // g.T)
-    n_by = -(-g.Hp // g.b)
-    n_bx = -(-g.Wp // g.b)
     out = []
     for grp in range(n_groups):
-        for by in range(n_by):
-            rows = min(g.Hp, (by + 1) * g.b) - by * g.b
-            for bx in range(n_bx):
-                cols = min(g.Wp, (bx + 1) * g.b) - bx * g.b
-                out.append(rows * cols if (g.anchor and grp == 0) else 0)
+        for window in spatial_windows(g):
+            out.append(len(window) if (g.anchor and grp == 0) else 0)
     return out
 
 

@@ -21,14 +21,17 @@ def _cos(a, b):
     return _dot(a, b) / (max(math.sqrt(_dot(a, a)), 1e-12) * max(math.sqrt(_dot(b, b)), 1e-12))
 
 
-def _blocks_bruteforce(S, Hp, Wp, b, T, n_special):
-    """Token sets per block, each listed in (frame, row, col) order, blocks in (group,by,bx) order."""
+def _blocks_bruteforce(S, Hp, Wp, b, T, n_special, chunked=False):
+    """Token sets per block, each listed in (frame, row, col) order, blocks in (group,by,bx) order.
+    chunked: a spatial block is a run of b consecutive patch tokens of the frame (Sec. 4.1, n_s)
+    instead of a b x b window."""
     tpf = n_special + Hp * Wp
     groups = {}
     for f in range(S):
         for y in range(Hp):
             for x in range(Wp):
-                groups.setdefault((f // T, y // b, x // b), []).append(f * tpf + n_special + y * Wp + x)
+                key = (f // T, (y * Wp + x) // b, 0) if chunked else (f // T, y // b, x // b)
+                groups.setdefault(key, []).append(f * tpf + n_special + y * Wp + x)
     specials = [f * tpf + s for f in range(S) for s in range(n_special)]
     return specials, [groups[key] for key in sorted(groups)]
 
@@ -69,9 +72,9 @@ def _mean(vectors):
     return [math.fsum(v[c] for v in vectors) / len(vectors) for c in range(E)]
 
 
-def _layer_bruteforce(q, k, v, S, Hp, Wp, b, T, n_special, rho_q, rho_kv, anchor=False):
+def _layer_bruteforce(q, k, v, S, Hp, Wp, b, T, n_special, rho_q, rho_kv, anchor=False, chunked=False):
     H, N, E = q.shape
-    specials, blocks = _blocks_bruteforce(S, Hp, Wp, b, T, n_special)
+    specials, blocks = _blocks_bruteforce(S, Hp, Wp, b, T, n_special, chunked)
     anchor_below = (n_special + Hp * Wp) if anchor else 0      # input indices of frame 0
     out = np.zeros((N, H * E))
     owners_q, owners_k = [], []
@@ -123,6 +126,33 @@ def test_oracle_equals_bruteforce(case, dtype):
         assert np.array_equal(orc.rep_map(res["assign_k"][h], pi, g, blocks, rho_kv), ref_rep_k[h])
     tol = 1e-5 if dtype == np.float32 else 1e-12
     assert np.abs(res["O"] - ref_out).max() < tol
+
+
+CHUNKED = [
+    # S, Hp, Wp, n_s, n_t, n_special, rho_q, rho_kv: spatial blocks are runs of n_s tokens (Sec. 4.1)
+    (3, 3, 4, 5, 2, 5, 0.5, 0.5),        # 12 patch tokens in runs of 5, 5, 2
+    (4, 3, 3, 4, 3, 1, 0.9, 0.7),
+    (5, 2, 5, 10, 4, 0, 0.75, 0.3),      # one run = the whole frame
+    (2, 4, 4, 7, 1, 2, 0.6, 0.6),        # n_t = 1: purely spatial blocks
+]
+
+
+@pytest.mark.parametrize("anchor", [False, True])
+@pytest.mark.parametrize("case", CHUNKED)
+def test_oracle_equals_bruteforce_with_chunked_blocks(case, anchor):
+    S, Hp, Wp, b, T, nsp, rho_q, rho_kv = case
+    g = orc.Geometry(S, Hp, Wp, b, T, n_special=nsp, anchor=anchor, chunked=True)
+    H, E = 2, 8
+    rng = np.random.default_rng(777 + S * 100 + Hp * 10 + Wp)
+    q, k, v = (rng.standard_normal((H, g.N, E)) for _ in range(3))
+    ref_out, ref_rep_q, ref_rep_k = _layer_bruteforce(q, k, v, S, Hp, Wp, b, T, nsp, rho_q, rho_kv,
+                                                      anchor=anchor, chunked=True)
+    res = orc.layer_forward(q, k, v, g, rho_q, rho_kv, dtype=np.float64)
+    pi, blocks = res["pi"], res["blocks"]
+    for h in range(H):
+        assert np.array_equal(orc.rep_map(res["assign_q"][h], pi, g, blocks, rho_q), ref_rep_q[h])
+        assert np.array_equal(orc.rep_map(res["assign_k"][h], pi, g, blocks, rho_kv), ref_rep_k[h])
+    assert np.abs(res["O"] - ref_out).max() < 1e-12
 
 
 ANCHORED = [

@@ -140,3 +140,28 @@ def test_anchored_dst_positions(n, k, n0):
         assert rest == orc.dst_positions(n - n0, k - n0)
     assert orc.cluster_count(n, 0.99, n0) == max(1, n0)
     assert orc.cluster_count(n, 0.0, n0) == n
+
+
+def test_chunked_blocks_at_the_papers_setting():
+    """Sec. 4.1: n_s = 128 consecutive tokens x n_t = 30 frames = blocks of 3840 tokens; a 37 x 37
+    frame has 10 full runs and one of 89; 90 % / 70 % merging keeps 384 / 1152 per full block."""
+    g = orc.Geometry(60, 37, 37, 128, 30, chunked=True)
+    pi, blocks = orc.temporal_reorder(g)
+    assert sorted(pi.tolist()) == list(range(g.N))
+    assert len(blocks) == 2 * 11
+    sizes = [n for _, n in blocks]
+    assert sizes == ([3840] * 10 + [89 * 30]) * 2
+    ks, offs, M = orc.merged_layout(g, blocks, 0.9)
+    assert ks[:11] == [384] * 10 + [267] and M == g.n_prefix + 2 * (3840 + 267)
+    assert orc.merged_layout(g, blocks, 0.7)[0][:11] == [1152] * 10 + [801]
+    # a block = the same run of every frame of the group, frames stacked
+    tpf = g.tokens_per_frame
+    start, n = blocks[12]                      # second group, second run
+    got = pi[start:start + n]
+    assert (got // tpf).tolist() == [f for f in range(30, 60) for _ in range(128)]
+    assert (got % tpf - g.n_special).tolist() == list(range(128, 256)) * 30
+    # windows and runs agree when the window is a full row strip: b x b with b = Wp = Hp is one block per frame
+    sq = orc.Geometry(4, 6, 6, 6, 2)
+    ch = orc.Geometry(4, 6, 6, 36, 2, chunked=True)
+    assert np.array_equal(orc.temporal_reorder(sq)[0], orc.temporal_reorder(ch)[0])
+    assert orc.temporal_reorder(sq)[1] == orc.temporal_reorder(ch)[1]
