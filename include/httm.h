@@ -80,6 +80,10 @@ enum {
  * frame 0 itself is never merged away.  A block of the first group keeps max(k, n0) clusters, n0 its
  * frame-0 tokens; its other dst tokens are strided over the rest of the block.  Applies to Q and K. */
 #define HTTM_FLAG_ANCHOR_FIRST_FRAME 1
+/* Chunked spatial blocks (Sec. 4.1, "spatial block size n_s"): a spatial block is a run of b
+ * consecutive patch tokens of a frame, in the frame's own (row-major) token order, the last run of a
+ * frame partial - instead of a b x b window of the patch grid.  The paper's setting is b = 128, T = 30. */
+#define HTTM_FLAG_CHUNKED_BLOCKS 2
 
 #define HTTM_MAX_OUTLIER_FRAC 0.5
 #define HTTM_MAX_BLOCK 512        /* largest merging block (b*b*T tokens) the kernels accept */
@@ -93,7 +97,7 @@ typedef struct httm_geom {
   int32_t n_special;  /* special tokens at the front of every frame (5 for VGGT); never merged */
   int32_t H;          /* attention heads */
   int32_t d_head;     /* channels per head; must be 64 */
-  int32_t b;          /* spatial block edge in patches (n_s = b*b) */
+  int32_t b;          /* spatial block edge in patches (n_s = b*b); with HTTM_FLAG_CHUNKED_BLOCKS: n_s itself */
   int32_t T;          /* temporal block length in frames (n_t) */
   double rho_q;       /* fraction of each block's query tokens merged away, 0 <= rho < 1 or 1 */
   double rho_kv;      /* the same for key/value tokens */

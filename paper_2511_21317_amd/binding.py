@@ -93,14 +93,15 @@ def _check(rc: int, what: str):
 
 
 FLAG_ANCHOR_FIRST_FRAME = 1
+FLAG_CHUNKED_BLOCKS = 2
 
 
 def make_geom(S, Hp, Wp, b, T, rho_q, rho_kv=None, *, H=16, d_head=64, n_special=5,
-              variant="headwise", anchor_first_frame=False, outlier_frac=0.0) -> Geom:
+              variant="headwise", anchor_first_frame=False, outlier_frac=0.0, chunked_blocks=False) -> Geom:
     if rho_kv is None:
         rho_kv = rho_q
     v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
-    flags = FLAG_ANCHOR_FIRST_FRAME if anchor_first_frame else 0
+    flags = (FLAG_ANCHOR_FIRST_FRAME if anchor_first_frame else 0) | (FLAG_CHUNKED_BLOCKS if chunked_blocks else 0)
     return Geom(S, Hp, Wp, n_special, H, d_head, b, T, float(rho_q), float(rho_kv), v, flags,
                 float(outlier_frac))
 

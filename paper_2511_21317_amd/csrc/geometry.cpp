@@ -13,14 +13,16 @@ int check_geom(const httm_geom_t& g) {
   if (g.variant != HTTM_VARIANT_HEADWISE && g.variant != HTTM_VARIANT_UNIFORM &&
       g.variant != HTTM_VARIANT_NONE)
     return HTTM_E_INVALID_ARG;
-  if (g.flags & ~HTTM_FLAG_ANCHOR_FIRST_FRAME) return HTTM_E_INVALID_ARG;
+  if (g.flags & ~(HTTM_FLAG_ANCHOR_FIRST_FRAME | HTTM_FLAG_CHUNKED_BLOCKS)) return HTTM_E_INVALID_ARG;
   if (!(g.outlier_frac >= 0.0 && g.outlier_frac <= HTTM_MAX_OUTLIER_FRAC)) return HTTM_E_INVALID_ARG;
   if (g.d_head != 64 || g.H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
   const int64_t tpf = (int64_t)g.n_special + (int64_t)g.Hp * g.Wp;
   const int64_t N = tpf * g.S;
   if (N >= (int64_t)1 << 25) return HTTM_E_UNSUPPORTED;  // per-head byte offsets (N*128) stay below 2^32
   const int64_t bh = g.b < g.Hp ? g.b : g.Hp, bw = g.b < g.Wp ? g.b : g.Wp, bt = g.T < g.S ? g.T : g.S;
-  if (bh * bw * bt > HTTM_MAX_BLOCK) return HTTM_E_UNSUPPORTED;
+  const int64_t P = (int64_t)g.Hp * g.Wp;
+  const int64_t ns = (g.flags & HTTM_FLAG_CHUNKED_BLOCKS) ? (g.b < P ? g.b : P) : bh * bw;
+  if (ns * bt > HTTM_MAX_BLOCK) return HTTM_E_UNSUPPORTED;
   return HTTM_OK;
 }
 
@@ -50,7 +52,14 @@ int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
   t.N = (int64_t)tpf * g.S;
   t.n_prefix = (int64_t)g.S * g.n_special;
   const int32_t groups = (g.S + g.T - 1) / g.T;
-  const int32_t wy = (g.Hp + g.b - 1) / g.b, wx = (g.Wp + g.b - 1) / g.b;
+  // Spatial blocks of a frame: b x b windows of the patch grid (row-major over windows), or runs of
+  // b consecutive patch tokens (Sec. 4.1) - then a "window" is one row of slots [x0, x1).
+  const bool chunked = (g.flags & HTTM_FLAG_CHUNKED_BLOCKS) != 0;
+  const int32_t P = g.Hp * g.Wp;
+  const int32_t wy = chunked ? 1 : (g.Hp + g.b - 1) / g.b;
+  const int32_t wx = chunked ? (P + g.b - 1) / g.b : (g.Wp + g.b - 1) / g.b;
+  const int32_t row_len = chunked ? P : g.Wp;    // slots per "row" of the loops below
+  const int32_t n_rows = chunked ? 1 : g.Hp;
   t.n_blocks = (int64_t)groups * wy * wx;
   t.block_start.resize(t.n_blocks);
   t.block_n.resize(t.n_blocks);
@@ -82,9 +91,10 @@ int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
   for (int32_t grp = 0; grp < groups; ++grp) {
     const int32_t f0 = grp * g.T, f1 = (f0 + g.T < g.S) ? f0 + g.T : g.S;
     for (int32_t by = 0; by < wy; ++by) {
-      const int32_t y0 = by * g.b, y1 = (y0 + g.b < g.Hp) ? y0 + g.b : g.Hp;
+      const int32_t y0 = chunked ? 0 : by * g.b;
+      const int32_t y1 = chunked ? 1 : ((y0 + g.b < n_rows) ? y0 + g.b : n_rows);
       for (int32_t bx = 0; bx < wx; ++bx, ++bi) {
-        const int32_t x0 = bx * g.b, x1 = (x0 + g.b < g.Wp) ? x0 + g.b : g.Wp;
+        const int32_t x0 = bx * g.b, x1 = (x0 + g.b < row_len) ? x0 + g.b : row_len;
         const int32_t n = (f1 - f0) * (y1 - y0) * (x1 - x0);
         t.block_start[bi] = (int32_t)pos;
         t.block_n[bi] = n;
@@ -93,7 +103,7 @@ int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
           int64_t w = pos;
           for (int32_t f = f0; f < f1; ++f)
             for (int32_t y = y0; y < y1; ++y) {
-              const int32_t row = f * tpf + g.n_special + y * g.Wp;
+              const int32_t row = f * tpf + g.n_special + y * row_len;
               for (int32_t x = x0; x < x1; ++x) t.pi[w++] = row + x;
             }
         }

@@ -48,6 +48,7 @@ class Workload:
     d_head: int = D_HEAD
     n_special: int = N_SPECIAL
     anchor: bool = False   # first-frame anchoring switched on for this workload
+    chunked: bool = False  # spatial blocks are runs of b consecutive tokens (the paper's n_s) instead of windows
 
     @property
     def tokens_per_frame(self) -> int:

@@ -31,7 +31,8 @@ def round_bf16(x: np.ndarray) -> np.ndarray:
 
 
 def oracle_geom(w) -> orc.Geometry:
-    return orc.Geometry(w.S, w.Hp, w.Wp, w.b, w.T, n_special=w.n_special, anchor=w.anchor)
+    return orc.Geometry(w.S, w.Hp, w.Wp, w.b, w.T, n_special=w.n_special, anchor=w.anchor,
+                        chunked=w.chunked)
 
 
 def plan_for(w, variant="headwise", rho_q=None, rho_kv=None, H=None, outlier_frac=0.0) -> httm.Plan:
@@ -39,7 +40,8 @@ def plan_for(w, variant="headwise", rho_q=None, rho_kv=None, H=None, outlier_fra
     rk = rq if rho_kv is None else rho_kv
     return httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, rq, rk, H=w.H if H is None else H,
                                     n_special=w.n_special, variant=variant,
-                                    anchor_first_frame=w.anchor, outlier_frac=outlier_frac))
+                                    anchor_first_frame=w.anchor, outlier_frac=outlier_frac,
+                                    chunked_blocks=w.chunked))
 
 
 def check_assign(gpu_assign: np.ndarray, ref_assign: np.ndarray, ref_gap: np.ndarray, what=""):

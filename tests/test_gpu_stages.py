@@ -26,6 +26,9 @@ ODD = [
     Workload("anchored_ratio_below_frame0", 18, 6, 13, 9, 4, 4, 0.9, 1, H=2, anchor=True),   # k = n0
     Workload("anchored_mixed_dst", 19, 5, 12, 15, 4, 3, 0.5, 1, H=3, anchor=True),            # k > n0
     Workload("anchored_block512", 20, 9, 10, 12, 8, 8, 0.75, 1, H=2, anchor=True),
+    # chunked spatial blocks (Sec. 4.1): runs of b consecutive tokens of a frame x T frames
+    Workload("chunked_ns50_nt5", 22, 7, 11, 13, 50, 5, 0.8, 1, H=2, chunked=True),          # 250-token blocks
+    Workload("chunked_ns128_nt4_anchored", 23, 6, 16, 20, 128, 4, 0.9, 1, H=2, chunked=True, anchor=True),
 ]
 
 

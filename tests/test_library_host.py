@@ -39,12 +39,20 @@ GEOMS = [
 ]
 
 
+CHUNKED_GEOMS = [
+    (8, 37, 37, 128, 4, 0.9, 0.7),      # runs of 128 tokens (Sec. 4.1), 10 full + one of 89 per frame
+    (5, 6, 7, 10, 2, 0.5, 0.5),
+    (3, 4, 4, 64, 3, 0.75, 0.25),       # a run longer than the frame
+]
+
+
 @pytest.mark.parametrize("anchor", [False, True], ids=["plain", "anchored"])
-@pytest.mark.parametrize("case", GEOMS)
+@pytest.mark.parametrize("case", GEOMS + CHUNKED_GEOMS)
 def test_host_tables_match_oracle(case, anchor):
     S, Hp, Wp, b, T, rq, rk = case
-    g = httm.make_geom(S, Hp, Wp, b, T, rq, rk, anchor_first_frame=anchor)
-    og = orc.Geometry(S, Hp, Wp, b, T, anchor=anchor)
+    chunked = case in CHUNKED_GEOMS
+    g = httm.make_geom(S, Hp, Wp, b, T, rq, rk, anchor_first_frame=anchor, chunked_blocks=chunked)
+    og = orc.Geometry(S, Hp, Wp, b, T, anchor=anchor, chunked=chunked)
     t = httm.geom_tables(g)
     s = httm.geom_sizes(g)
     pi, blocks = orc.temporal_reorder(og)
@@ -110,7 +118,7 @@ def test_argument_errors_are_reported_not_crashed():
     bad = httm.make_geom(0, 16, 16, 4, 2, 0.5)
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -1
     bad = httm.make_geom(2, 16, 16, 4, 2, 0.5)
-    bad.flags = 2                                            # a flag bit this library does not know
+    bad.flags = 4                                            # a flag bit this library does not know
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -1
     assert L.httm_geom_sizes(None, C.byref(s)) == -1
     # compute entry points reject null pointers before touching the GPU
