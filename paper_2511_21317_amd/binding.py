@@ -15,7 +15,7 @@ LIB_PATH = os.environ.get("HTTM_LIB_PATH") or os.path.join(PKG_DIR, "libhttm.so"
 
 VARIANT_HEADWISE, VARIANT_UNIFORM, VARIANT_NONE = 0, 1, 2
 VARIANTS = {"headwise": VARIANT_HEADWISE, "uniform": VARIANT_UNIFORM, "none": VARIANT_NONE}
-MAX_BLOCK = 512
+MAX_BLOCK = 4096
 MAX_HEADS = 64
 
 

@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libhttm.so")
 
-SOURCES = ["api.hip", "geometry.cpp", "reorder_unmerge.hip", "match_merge.hip", "outlier_filter.hip",
+SOURCES = ["api.hip", "geometry.cpp", "reorder_unmerge.hip", "match_merge.hip", "match_merge_big.hip", "outlier_filter.hip",
            "attention.hip"]
 
 HIPCC_FLAGS = [

@@ -37,6 +37,9 @@ struct MatchMergeArgs {
   int32_t max_block;
 };
 hipError_t launch_match_merge(const MatchMergeArgs& a, hipStream_t stream);
+// The same for blocks of more than kSmallBlockMax tokens (two kernels; no preset mode).
+constexpr int kSmallBlockMax = 512;
+hipError_t launch_match_merge_big(const MatchMergeArgs& a, hipStream_t stream);
 
 // ---- adaptive outlier filtering of the merged queries (paper Sec. 3.4, Alg. 2) ---------------
 // State of the device-side selection of the threshold tau.

@@ -640,6 +640,7 @@ hipError_t launch_match_merge(const MatchMergeArgs& a, hipStream_t stream) {
   int n_items = 0;
   for (int i = 0; i < a.n_streams; ++i) n_items = a.s[i].n_items > n_items ? a.s[i].n_items : n_items;
   if (n_items == 0 || a.H == 0) return hipSuccess;
+  if (a.max_block > kSmallBlockMax) return launch_match_merge_big(a, stream);
   dim3 grid((unsigned)n_items, (unsigned)a.H, (unsigned)a.n_streams);
   if (a.max_block <= 64)
     hipLaunchKernelGGL((match_merge_kernel<1, 64>), grid, dim3(64), 0, stream, a);

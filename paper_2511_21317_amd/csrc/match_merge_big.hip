@@ -1,0 +1,429 @@
+// Stage 2 for merging blocks that do not fit one LDS tile (more than 512 tokens; the paper's own
+// setting is n_b = n_s * n_t = 128 * 30 = 3840, Sec. 4.1).  Same computation as match_merge.hip
+// (Sec. 3.2 Eq. 1 and the best-match rule inside a block, Sec. 3.3; mean of the constituents,
+// Alg. 1 "BlockwiseToMe" / "BlockAggregate"), cut in two kernels:
+//
+//   big_match_kernel      one workgroup per (256 tokens of a work item, head, stream).  The tokens sit
+//                         in registers as MFMA B operands; the dst tokens of the item stream through
+//                         LDS in tiles of 64 (gathered through pi, double buffered), each tile giving
+//                         a [64 dst x 256 tokens] block of raw dot products on the matrix cores, scaled
+//                         by 1/||d|| and folded into a running (best score, lowest index) per token.
+//                         It is the score half of a flash-attention kernel with an arg-max in place
+//                         of the softmax.
+//   big_aggregate_kernel  one workgroup of 1024 threads per (work item, head, stream).  Cluster sizes
+//                         with integer LDS atomics, a prefix sum, then a stable counting sort in rounds
+//                         of 1024 tokens (wave ballots, no atomics: the member order is ascending
+//                         position, the same from run to run); the member LISTS fit in LDS even
+//                         though the rows do not, and one thread per (cluster, 16-byte chunk) gathers
+//                         its members' rows from global memory, adds them in fp32 and rounds once.
+#include "dev_common.hpp"
+#include "kernels.hpp"
+
+namespace httm {
+
+namespace {
+
+struct PairSel {
+  bf16x2 lo, hi;
+};
+__device__ __forceinline__ PairSel pair_selectors() {
+  // (1, 0) and (0, 1) as bf16 pairs, pinned in vector registers (see match_merge.hip)
+  uint32_t slo = 0x00003f80u, shi = 0x3f800000u;
+  asm volatile("" : "+v"(slo), "+v"(shi));
+  return {__builtin_bit_cast(bf16x2, slo), __builtin_bit_cast(bf16x2, shi)};
+}
+
+__device__ __forceinline__ float sum8(float x) {
+  int v = __builtin_bit_cast(int, x);
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false));
+  v = __builtin_bit_cast(int, x);
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false));
+  v = __builtin_bit_cast(int, x);
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false));
+  return x;
+}
+
+__device__ __forceinline__ float chunk_sumsq(const bf16x8 w, float ss) {
+  const bf16x2 pr[4] = {__builtin_shufflevector(w, w, 0, 1), __builtin_shufflevector(w, w, 2, 3),
+                        __builtin_shufflevector(w, w, 4, 5), __builtin_shufflevector(w, w, 6, 7)};
+#pragma unroll
+  for (int q = 0; q < 4; ++q) ss = __builtin_amdgcn_fdot2_f32_bf16(pr[q], pr[q], ss, false);
+  return ss;
+}
+
+// Cluster whose dst token sits at block position p, or -1 if p is a src position
+// (inverse of dst_position).
+__device__ __forceinline__ int cluster_at(int p, int n, int k, int n0) {
+  if (p < n0) return p;
+  if (k == n0) return -1;
+  const int m = n0 + ((p - n0) * (k - n0) + (n - n0) - 1) / (n - n0);
+  return (m < k && dst_position(m, n, k, n0) == p) ? m : -1;
+}
+
+constexpr int kBmWaves = 4;
+constexpr int kBmThreads = 64 * kBmWaves;
+constexpr int kBmTokens = 64 * kBmWaves;   // tokens per workgroup (two 32-token tiles per wave)
+constexpr int kBmDstTile = 64;
+
+__global__ __launch_bounds__(kBmThreads) __attribute__((amdgpu_waves_per_eu(2, 4)))
+void big_match_kernel(const MatchMergeArgs a) {
+  __shared__ __align__(16) unsigned char s_d[2][kBmDstTile * kLdsRowBytes];
+  __shared__ __align__(16) float s_dinv[2][kBmDstTile];
+
+  const int n_heads = a.H;
+  const int sidx = blockIdx.z / n_heads;
+  const int64_t h = blockIdx.z % n_heads;
+  const MatchMergeStream& s = a.s[sidx];
+  if ((int)blockIdx.x >= s.n_items) return;
+  const WorkItem it = s.items[blockIdx.x];
+  const int n = it.n, k = it.k, n0 = it.n0;
+  const int t0 = blockIdx.y * kBmTokens;
+  if (t0 >= n) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int64_t N = a.N;
+  const char* __restrict__ x = (const char*)s.x + h * N * kRowBytes;
+  const int32_t* __restrict__ pi = a.pi;
+  int32_t* __restrict__ assign = s.assign + h * N + it.start;
+  float* __restrict__ score = s.score ? s.score + h * N + it.start : nullptr;
+
+  if (k == n) {   // nothing to merge: every token is its own cluster
+    const int t = t0 + tid;
+    if (t < n) {
+      assign[t] = it.moff + t;
+      if (score) score[t] = 1.0f;
+    }
+    return;
+  }
+
+  // ---- this wave's 64 tokens as B operands: lane -> token column, 8 channels per k-step ---------
+  bf16x8 bx[2][4];
+  float invn[2];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    const int tok = t0 + wave * 64 + qt * 32 + l32;
+    const int tokc = tok < n ? tok : n - 1;
+    const uint32_t src = pi ? (uint32_t)pi[it.start + tokc] : (uint32_t)(it.start + tokc);
+    float ss = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bx[qt][ks] = *(const bf16x8*)(x + src * kRowBytes + ks * 32 + half * 16);
+      ss = chunk_sumsq(bx[qt][ks], ss);
+    }
+    ss += __shfl_xor(ss, 32);
+    invn[qt] = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
+  }
+
+  // ---- dst tiles: thread (row r0 / r0 + 32, chunk c) moves two 16-byte pieces per tile -----------
+  const int r0 = tid >> 3, c16 = (tid & 7) * 16;
+  const int n_tiles = (k + kBmDstTile - 1) / kBmDstTile;
+  u32x4 dreg[2];
+  auto dst_src_row = [&](int m) -> uint32_t {   // source row of the dst token of cluster m (clamped)
+    const int mc = m < k ? m : k - 1;
+    const int p = dst_position(mc, n, k, n0);
+    return pi ? (uint32_t)pi[it.start + p] : (uint32_t)(it.start + p);
+  };
+  uint32_t srow[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) srow[i] = dst_src_row(r0 + 32 * i);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) dreg[i] = *(const u32x4*)(x + srow[i] * kRowBytes + c16);
+  if (n_tiles > 1) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) srow[i] = dst_src_row(kBmDstTile + r0 + 32 * i);
+  }
+
+  float best[2] = {-INFINITY, -INFINITY};
+  int bm[2] = {0, 0};
+  for (int j = 0; j < n_tiles; ++j) {
+    const int buf = j & 1;
+    // rows of tile j: registers -> LDS, and 1/||d|| from the 8 lanes that share a row
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int r = r0 + 32 * i;
+      *(u32x4*)(&s_d[buf][r * kLdsRowBytes + c16]) = dreg[i];
+      const float ss = sum8(chunk_sumsq(__builtin_bit_cast(bf16x8, dreg[i]), 0.f));
+      if ((tid & 7) == 0)
+        s_dinv[buf][r] = j * kBmDstTile + r < k ? 1.0f / fmaxf(sqrtf(ss), 1e-12f) : __builtin_nanf("");
+    }
+    // tile j+1 on its way while tile j is used; the source rows of tile j+2 behind it
+    if (j + 1 < n_tiles) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) dreg[i] = *(const u32x4*)(x + srow[i] * kRowBytes + c16);
+      if (j + 2 < n_tiles) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) srow[i] = dst_src_row((j + 2) * kBmDstTile + r0 + 32 * i);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int step = 0; step < 2; ++step) {
+      const int d0 = j * kBmDstTile + step * 32;
+      if (d0 >= k) break;
+      bf16x8 ad[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        ad[ks] = *(const bf16x8*)(&s_d[buf][(step * 32 + l32) * kLdsRowBytes + ks * 32 + half * 16]);
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad[ks], bx[qt][ks], acc, 0, 0, 0);
+        // acc[r] = <dst d0 + 8*(r/4) + 4*half + r%4, token l32 of tile qt>; NaN-scaled rows (past k)
+        // never compare greater
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int mb = step * 32 + 8 * g + 4 * half;
+          const f32x4 dv = *(const f32x4*)(&s_dinv[buf][mb]);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const float sc = acc[4 * g + q] * dv[q];
+            if (sc > best[qt]) {
+              best[qt] = sc;
+              bm[qt] = j * kBmDstTile + mb + q;
+            }
+          }
+        }
+      }
+    }
+    // (the next iteration writes the other buffer; the one after it this buffer again, and by then
+    // every wave has passed the next barrier)
+  }
+
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    const float ob = __shfl_xor(best[qt], 32);
+    const int om = __shfl_xor(bm[qt], 32);
+    if (ob > best[qt] || (ob == best[qt] && om < bm[qt])) {
+      best[qt] = ob;
+      bm[qt] = om;
+    }
+    const int tok = t0 + wave * 64 + qt * 32 + l32;
+    if (half == 0 && tok < n) {
+      int c = cluster_at(tok, n, k, n0);
+      float sc = 1.0f;
+      if (c < 0) {
+        c = bm[qt];
+        sc = best[qt] * invn[qt];
+      }
+      assign[tok] = it.moff + c;
+      if (score) score[tok] = sc;
+    }
+  }
+}
+
+// ---- aggregation ---------------------------------------------------------------------------------
+
+constexpr int kBaWaves = 16;
+constexpr int kBaThreads = 64 * kBaWaves;
+
+// Dynamic LDS: s_src[nmax] int32 | s_off[kmax + 1] int32 | s_cur[kmax] int32 | s_list[nmax] u16 |
+//              s_wcnt[kBaWaves][kmax] u8
+__global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMergeArgs a, int nmax,
+                                                                   int kmax) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  int32_t* s_src = (int32_t*)lds;
+  int32_t* s_off = s_src + nmax;
+  int32_t* s_cur = s_off + kmax + 1;
+  uint16_t* s_list = (uint16_t*)(s_cur + kmax);
+  uint8_t* s_wcnt = (uint8_t*)(s_list + nmax + (nmax & 1));
+  __shared__ int s_part[kBaWaves];
+
+  const MatchMergeStream& s = a.s[blockIdx.z];
+  if ((int)blockIdx.x >= s.n_items) return;
+  const WorkItem it = s.items[blockIdx.x];
+  const int n = it.n, k = it.k;
+  const int64_t h = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t N = a.N, M = s.M;
+  const char* __restrict__ x = (const char*)s.x + h * N * kRowBytes;
+  const char* __restrict__ v = s.v ? (const char*)s.v + h * N * kRowBytes : nullptr;
+  u32x4* __restrict__ xm = (u32x4*)s.xm + (h * M + it.moff) * kRowChunks;
+  u32x4* __restrict__ vm = s.v ? (u32x4*)s.vm + (h * M + it.moff) * kRowChunks : nullptr;
+  const int32_t* __restrict__ assign = s.assign + h * N + it.start;
+
+  // ---- source rows and cluster sizes ------------------------------------------------------------------
+  for (int m = tid; m <= k; m += kBaThreads) s_off[m] = 0;
+  for (int e = tid; e < kBaWaves * k; e += kBaThreads) s_wcnt[(e / k) * kmax + e % k] = 0;
+  __syncthreads();
+  for (int t = tid; t < n; t += kBaThreads) {
+    s_src[t] = a.pi ? a.pi[it.start + t] : it.start + t;
+    atomicAdd(&s_off[assign[t] - it.moff + 1], 1);    // integer counts: order does not matter
+  }
+  __syncthreads();
+  // inclusive prefix over s_off[1..k]  ->  s_off[m] = first list entry of cluster m, s_off[k] = n
+  {
+    const int per = (k + kBaThreads - 1) / kBaThreads;
+    const int i0 = 1 + tid * per, i1 = i0 + per <= k + 1 ? i0 + per : k + 1;
+    int sum = 0;
+    for (int i = i0; i < i1; ++i) sum += s_off[i];
+    int incl = sum;   // inclusive scan over the wave, then over the 16 wave totals
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int up = __shfl_up(incl, d);
+      if (lane >= d) incl += up;
+    }
+    if (lane == 63) s_part[wave] = incl;
+    __syncthreads();
+    int base = incl - sum;
+    for (int w = 0; w < wave; ++w) base += s_part[w];
+    for (int i = i0; i < i1; ++i) {
+      base += s_off[i];
+      s_off[i] = base;
+    }
+  }
+  __syncthreads();
+  for (int m = tid; m < k; m += kBaThreads) s_cur[m] = s_off[m];
+  __syncthreads();
+
+  // ---- stable counting sort in rounds of kBaThreads tokens ------------------------------------------------
+  for (int base = 0; base < n; base += kBaThreads) {
+    const int t = base + tid;
+    const int my_cl = t < n ? assign[t] - it.moff : -1;
+    int my_rank = 0;
+    {
+      unsigned long long same = __ballot(my_cl >= 0);
+      for (int bit = 0; (1 << bit) < k; ++bit) {
+        const bool set = (my_cl >> bit) & 1;
+        const unsigned long long b = __ballot(set);
+        same &= set ? b : ~b;
+      }
+      if (my_cl >= 0) {
+        my_rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(same >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)same, 0u));
+        if (my_rank == 0) s_wcnt[wave * kmax + my_cl] = (uint8_t)__popcll(same);
+      }
+    }
+    __syncthreads();
+    if (my_cl >= 0) {
+      int pos = s_cur[my_cl] + my_rank;
+      for (int w = 0; w < wave; ++w) pos += s_wcnt[w * kmax + my_cl];
+      // ascending position, re-ordered so that the dst token comes first (the order of the sums
+      // in match_merge.hip)
+      const int first = s_off[my_cl];
+      const int dp = dst_position(my_cl, n, k, it.n0);
+      const int fin = t == dp ? 0 : (t < dp ? pos - first + 1 : pos - first);
+      s_list[first + fin] = (uint16_t)t;
+    }
+    __syncthreads();
+    // advance the cursors of the clusters touched in this round and clear the per-wave counts
+    if (my_cl >= 0 && my_rank == 0) {
+      // the first wave (lowest index) that saw the cluster does the update for all waves
+      bool first = true;
+      for (int w = 0; w < wave; ++w) first = first && s_wcnt[w * kmax + my_cl] == 0;
+      if (first) {
+        int tot = 0;
+        for (int w = wave; w < kBaWaves; ++w) tot += s_wcnt[w * kmax + my_cl];
+        s_cur[my_cl] += tot;
+      }
+    }
+    __syncthreads();
+    if (my_cl >= 0 && my_rank == 0) s_wcnt[wave * kmax + my_cl] = 0;
+    __syncthreads();
+  }
+
+  // ---- aggregation: thread (cluster m, 16-byte chunk c) gathers its members' rows ---------------------------
+  const PairSel sel = pair_selectors();
+  for (int pass = 0; pass < 2; ++pass) {
+    const char* __restrict__ src = pass == 0 ? x : v;
+    u32x4* __restrict__ out = pass == 0 ? xm : vm;
+    for (int mc = tid; mc < k * kRowChunks; mc += kBaThreads) {
+      const int m = mc >> 3, c = mc & 7;
+      const int beg = s_off[m], end = s_off[m + 1];
+      float acc[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+      int idx = beg;
+      for (; idx + 4 <= end; idx += 4) {
+        bf16x8 w[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          w[u] = *(const bf16x8*)(src + (uint32_t)s_src[s_list[idx + u]] * kRowBytes + c * 16);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const bf16x2 pr[4] = {__builtin_shufflevector(w[u], w[u], 0, 1), __builtin_shufflevector(w[u], w[u], 2, 3),
+                                __builtin_shufflevector(w[u], w[u], 4, 5), __builtin_shufflevector(w[u], w[u], 6, 7)};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            acc[2 * q] = __builtin_amdgcn_fdot2_f32_bf16(pr[q], sel.lo, acc[2 * q], false);
+            acc[2 * q + 1] = __builtin_amdgcn_fdot2_f32_bf16(pr[q], sel.hi, acc[2 * q + 1], false);
+          }
+        }
+      }
+      for (; idx < end; ++idx) {
+        const bf16x8 w = *(const bf16x8*)(src + (uint32_t)s_src[s_list[idx]] * kRowBytes + c * 16);
+        const bf16x2 pr[4] = {__builtin_shufflevector(w, w, 0, 1), __builtin_shufflevector(w, w, 2, 3),
+                              __builtin_shufflevector(w, w, 4, 5), __builtin_shufflevector(w, w, 6, 7)};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          acc[2 * q] = __builtin_amdgcn_fdot2_f32_bf16(pr[q], sel.lo, acc[2 * q], false);
+          acc[2 * q + 1] = __builtin_amdgcn_fdot2_f32_bf16(pr[q], sel.hi, acc[2 * q + 1], false);
+        }
+      }
+      const float cnt = (float)(end - beg);
+      const float rcnt = 1.0f / cnt;
+      float mean[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        // correctly rounded quotient: one Newton step on the product with the reciprocal
+        const float qv = acc[q] * rcnt;
+        mean[q] = fmaf(fmaf(-qv, cnt, acc[q]), rcnt, qv);
+      }
+      u32x4 o;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(mean[2 * q], mean[2 * q + 1]);
+      out[mc] = o;
+      if (s.eps && pass == 0) {
+        // Sec. 3.4 step 2: L2 distance of every constituent to the fp32 mean; zero if nothing was merged
+        float* __restrict__ eps = s.eps + h * N + it.start;
+        for (int i2 = beg; i2 < end; ++i2) {
+          const int j = s_list[i2];
+          const bf16x8 w = *(const bf16x8*)(src + (uint32_t)s_src[j] * kRowBytes + c * 16);
+          float d2 = 0.f;
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const float df = (float)w[q] - mean[q];
+            d2 = fmaf(df, df, d2);
+          }
+          d2 = sum8(d2);
+          if (c == 0) eps[j] = end - beg >= 2 ? sqrtf(d2) : 0.f;
+        }
+      }
+    }
+    if (pass == 1 || v == nullptr) break;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_match_merge_big(const MatchMergeArgs& a, hipStream_t stream) {
+  int n_items = 0, preset = 0;
+  for (int i = 0; i < a.n_streams; ++i) {
+    n_items = a.s[i].n_items > n_items ? a.s[i].n_items : n_items;
+    preset |= a.s[i].preset != nullptr;
+  }
+  if (n_items == 0 || a.H == 0) return hipSuccess;
+  if (preset) return hipErrorNotSupported;
+  const int nmax = a.max_block;
+  const int kmax = a.max_block;   // a block keeps at most all of its tokens
+  dim3 mgrid((unsigned)n_items, (unsigned)((nmax + kBmTokens - 1) / kBmTokens), (unsigned)(a.H * a.n_streams));
+  hipLaunchKernelGGL(big_match_kernel, mgrid, dim3(kBmThreads), 0, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const size_t lds = (size_t)nmax * 4 + ((size_t)kmax + 1) * 4 + (size_t)kmax * 4 +
+                     ((size_t)nmax + (nmax & 1)) * 2 + (size_t)kBaWaves * kmax;
+  static bool attr_set = false;
+  if (!attr_set) {
+    e = hipFuncSetAttribute((const void*)big_aggregate_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            150 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  dim3 agrid((unsigned)n_items, (unsigned)a.H, (unsigned)a.n_streams);
+  hipLaunchKernelGGL(big_aggregate_kernel, agrid, dim3(kBaThreads), lds, stream, a, nmax, kmax);
+  return hipGetLastError();
+}
+
+}  // namespace httm

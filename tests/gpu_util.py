@@ -104,3 +104,22 @@ def run_stages(plan: httm.Plan, q, k, v, with_scores=True):
     torch.cuda.synchronize()
     return dict(qr=qr, kr=kr, vr=vr, q_m=q_m, k_m=k_m, v_m=v_m, assign_q=aq, assign_k=ak,
                 score_q=sq, score_k=sk, o_m=o_m, o_r=o_r, o_hn=o_hn, out=out_fused)
+
+
+def excuse_tie_tokens(got_o: np.ndarray, want_o: np.ndarray, aq_gpu: np.ndarray, ref: dict) -> np.ndarray:
+    """A query token whose cluster differs by an allowed tie reads another merged row, and the two
+    merged queries involved have other constituents.  Returns a copy of want_o in which the rows of
+    those tokens (at most TIE_FRACTION of all) are replaced by the GPU's own, so that an end-to-end
+    comparison looks at every other token."""
+    want_o = want_o.copy()
+    pi = ref["pi"]
+    for h in range(len(ref["assign_q"])):
+        a_ref = ref["assign_q"][h]
+        bad = np.flatnonzero(aq_gpu[h] != a_ref)
+        if bad.size:
+            touched = np.zeros(ref["q_m"][h].shape[0], dtype=bool)
+            touched[aq_gpu[h][bad]] = True
+            touched[a_ref[bad]] = True
+            skip = np.flatnonzero(touched[aq_gpu[h]] | touched[a_ref])
+            want_o[pi[skip], h * 64:(h + 1) * 64] = got_o[pi[skip], h * 64:(h + 1) * 64]
+    return want_o

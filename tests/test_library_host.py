@@ -111,7 +111,13 @@ def test_argument_errors_are_reported_not_crashed():
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -2
     bad = httm.make_geom(2, 16, 16, 16, 4, 0.5)            # 16*16*2 = 512 ok; 4 frames clipped to S=2
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == 0
-    bad = httm.make_geom(8, 32, 32, 16, 4, 0.5)            # 1024-token block
+    big = httm.make_geom(8, 32, 32, 16, 4, 0.5)            # 1024-token block: the two-kernel path
+    assert L.httm_geom_sizes(C.byref(big), C.byref(s)) == 0
+    bad = httm.make_geom(32, 32, 32, 16, 32, 0.5)          # 8192-token block
+    assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -2
+    bad = httm.make_geom(8, 32, 32, 16, 4, 0.5, variant="uniform")   # no head-uniform matching of big blocks
+    assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -2
+    bad = httm.make_geom(8, 32, 32, 16, 4, 0.5, outlier_frac=0.1)    # nor outlier filtering (yet)
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -2
     bad = httm.make_geom(2, 16, 16, 4, 2, 1.5)
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -1
