@@ -88,7 +88,7 @@ enum {
 #define HTTM_MAX_OUTLIER_FRAC 0.5
 #define HTTM_MAX_BLOCK 4096       /* largest merging block (n_s*n_t tokens) the kernels accept; blocks of more
                                      than 512 tokens (the paper's 128 x 30 = 3840, Sec. 4.1) take a two-kernel path
-                                     and are not available with HTTM_VARIANT_UNIFORM or outlier filtering */
+                                     and are not available with HTTM_VARIANT_UNIFORM */
 #define HTTM_MAX_HEADS 64
 
 /* Problem description.  Plain data, filled by the caller. */

@@ -20,6 +20,7 @@ struct httm_plan {
   WorkItem* d_items_q = nullptr;
   WorkItem* d_items_k = nullptr;
   int32_t n_items = 0;
+  int32_t max_k = 0;   // most clusters any work item keeps (Q or K)
   // head-uniform variant only
   float* d_mean = nullptr;    // [2][N][64] fp32: head-averaged Q then K
   int32_t* d_slot = nullptr;  // [2][N] shared cluster slot of every reordered token
@@ -84,6 +85,7 @@ int run_match_merge(const httm_plan_t* p, const int32_t* pi, const void* q, cons
   a.N = p->sizes.N;
   a.H = g.H;
   a.max_block = (int32_t)(p->sizes.max_block < kPrefixChunk ? kPrefixChunk : p->sizes.max_block);
+  a.max_k = p->max_k;
   a.s[0] = {q, nullptr, q_m, nullptr, assign_q, score_q, p->d_items_q, p->n_items, p->sizes.M_q,
             nullptr, nullptr, eps_q};
   a.s[1] = {k, v, k_m, v_m, assign_k, score_k, p->d_items_k, p->n_items, p->sizes.M_k, nullptr,
@@ -131,7 +133,10 @@ int run_match_merge_filtered(const httm_plan_t* p, const void* q, const void* k,
   r.max_block = (int32_t)(p->sizes.max_block < kPrefixChunk ? kPrefixChunk : p->sizes.max_block);
   r.eager = (double)p->outlier_cap * (double)p->sizes.max_block >= (double)p->geom.H * (double)p->sizes.N;
   r.b = p->ob;
-  HTTM_HIP(launch_outlier_refine(r, st));
+  if (r.max_block > kSmallBlockMax)
+    HTTM_HIP(launch_outlier_refine_big(r, p->max_k, st));
+  else
+    HTTM_HIP(launch_outlier_refine(r, st));
   return HTTM_OK;
 }
 
@@ -211,6 +216,8 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
   p->geom = *g;
   fill_sizes(*g, t, &p->sizes, &p->ws);
   p->n_items = (int32_t)t.items_q.size();
+  for (const WorkItem& w : t.items_q) p->max_k = w.k > p->max_k ? w.k : p->max_k;
+  for (const WorkItem& w : t.items_k) p->max_k = w.k > p->max_k ? w.k : p->max_k;
   hipError_t e = hipGetDevice(&p->device);
   if (e != hipSuccess) {
     delete p;

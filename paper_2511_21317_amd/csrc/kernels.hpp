@@ -35,6 +35,7 @@ struct MatchMergeArgs {
   int64_t N;
   int32_t H;
   int32_t max_block;
+  int32_t max_k;        // most clusters any work item of any stream keeps
 };
 hipError_t launch_match_merge(const MatchMergeArgs& a, hipStream_t stream);
 // The same for blocks of more than kSmallBlockMax tokens (two kernels; no preset mode).
@@ -83,6 +84,8 @@ struct RefineArgs {
   OutlierBuffers b;
 };
 hipError_t launch_outlier_refine(const RefineArgs& a, hipStream_t stream);
+// The same for blocks of more than kSmallBlockMax tokens (max_k: most clusters a work item keeps).
+hipError_t launch_outlier_refine_big(const RefineArgs& a, int max_k, hipStream_t stream);
 
 // Head-uniform variant: mean over heads of x[H, N, 64] (bf16) -> xbar[N, 64] (fp32), summed in
 // head order; then block-wise matching of the fp32 tokens -> slot[N], score[N].

@@ -220,41 +220,117 @@ void big_match_kernel(const MatchMergeArgs a) {
 constexpr int kBaWaves = 16;
 constexpr int kBaThreads = 64 * kBaWaves;
 
+// What the REFINE instantiation needs on top of the stream description (Sec. 3.4 step 4).
+struct RefineExtra {
+  const SelectState* state;   // tau
+  const int32_t* offsets;     // [H + 1] first outlier row of a head
+  const int32_t* item_base;   // [H][n_items] first outlier row of a work item inside its head
+  void* q_out;                // [budget, 64] bf16
+};
+
 // Dynamic LDS: s_src[nmax] int32 | s_off[kmax + 1] int32 | s_cur[kmax] int32 | s_list[nmax] u16 |
-//              s_wcnt[kBaWaves][kmax] u8
-__global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMergeArgs a, int nmax,
-                                                                   int kmax) {
+//              s_cl[nmax] int16 | s_wcnt[kBaWaves][kmax] u8 | s_aff[kmax] u8 | s_dout[kmax] u8
+//
+// REFINE = false: first aggregation of stream blockIdx.z (X and, for the K stream, V).
+// REFINE = true : the un-merging of the outliers for the query stream a.s[0] (see
+//                 outlier_refine_kernel in match_merge.hip for the rules): tokens whose deviation lies
+//                 above tau get a row of q_out and a negative assign entry, and only the clusters that
+//                 lose a constituent are summed again.
+template <bool REFINE>
+__global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMergeArgs a, const RefineExtra rx,
+                                                                   int nmax, int kmax) {
   extern __shared__ __align__(16) unsigned char lds[];
   int32_t* s_src = (int32_t*)lds;
   int32_t* s_off = s_src + nmax;
   int32_t* s_cur = s_off + kmax + 1;
   uint16_t* s_list = (uint16_t*)(s_cur + kmax);
-  uint8_t* s_wcnt = (uint8_t*)(s_list + nmax + (nmax & 1));
+  int16_t* s_cl = (int16_t*)(s_list + nmax + (nmax & 1));
+  uint8_t* s_wcnt = (uint8_t*)(s_cl + nmax + (nmax & 1));
+  uint8_t* s_aff = s_wcnt + (size_t)kBaWaves * kmax;
+  uint8_t* s_dout = s_aff + kmax;
   __shared__ int s_part[kBaWaves];
 
-  const MatchMergeStream& s = a.s[blockIdx.z];
+  const MatchMergeStream& s = a.s[REFINE ? 0 : blockIdx.z];
   if ((int)blockIdx.x >= s.n_items) return;
   const WorkItem it = s.items[blockIdx.x];
   const int n = it.n, k = it.k;
+  if (REFINE && k == n) return;   // nothing was merged here: no deviation, no outlier
   const int64_t h = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t N = a.N, M = s.M;
   const char* __restrict__ x = (const char*)s.x + h * N * kRowBytes;
-  const char* __restrict__ v = s.v ? (const char*)s.v + h * N * kRowBytes : nullptr;
+  const char* __restrict__ v = (!REFINE && s.v) ? (const char*)s.v + h * N * kRowBytes : nullptr;
   u32x4* __restrict__ xm = (u32x4*)s.xm + (h * M + it.moff) * kRowChunks;
-  u32x4* __restrict__ vm = s.v ? (u32x4*)s.vm + (h * M + it.moff) * kRowChunks : nullptr;
-  const int32_t* __restrict__ assign = s.assign + h * N + it.start;
+  u32x4* __restrict__ vm = v ? (u32x4*)s.vm + (h * M + it.moff) * kRowChunks : nullptr;
+  int32_t* __restrict__ assign = s.assign + h * N + it.start;
 
-  // ---- source rows and cluster sizes ------------------------------------------------------------------
+  // ---- clusters of the tokens; in REFINE mode the outliers leave ---------------------------------------
+  if (REFINE) {
+    const float tau = rx.state->tau;
+    const float* __restrict__ eps = s.eps + h * N + it.start;
+    bool any = false;
+    for (int t = tid; t < n; t += kBaThreads) {
+      int cl = assign[t] - it.moff;
+      if (cl < 0 || cl >= k) cl = -1;              // not a slot of this item: left alone
+      const bool out = cl >= 0 && eps[t] > tau;
+      s_cl[t] = (int16_t)(out ? -2 - cl : cl);     // outliers remember the cluster they leave
+      any = any || out;
+    }
+    if (!__syncthreads_or(any)) return;
+  } else {
+    for (int t = tid; t < n; t += kBaThreads) s_cl[t] = (int16_t)(assign[t] - it.moff);
+  }
   for (int m = tid; m <= k; m += kBaThreads) s_off[m] = 0;
+  for (int m = tid; m < k; m += kBaThreads) {
+    s_aff[m] = 0;
+    s_dout[m] = 0;
+  }
   for (int e = tid; e < kBaWaves * k; e += kBaThreads) s_wcnt[(e / k) * kmax + e % k] = 0;
   __syncthreads();
   for (int t = tid; t < n; t += kBaThreads) {
     s_src[t] = a.pi ? a.pi[it.start + t] : it.start + t;
-    atomicAdd(&s_off[assign[t] - it.moff + 1], 1);    // integer counts: order does not matter
+    const int cl = s_cl[t];
+    if (cl >= 0) atomicAdd(&s_off[cl + 1], 1);    // integer counts: order does not matter
+    if (REFINE && cl <= -2) {
+      const int left = -2 - cl;
+      s_aff[left] = 1;
+      if (dst_position(left, n, k, it.n0) == t) s_dout[left] = 1;
+    }
   }
   __syncthreads();
-  // inclusive prefix over s_off[1..k]  ->  s_off[m] = first list entry of cluster m, s_off[k] = n
+
+  if (REFINE) {
+    // rows of q_out in ascending position: the head's range, then this item's share, then the rank
+    int base = rx.offsets[h] + rx.item_base[h * s.n_items + blockIdx.x];
+    for (int t0 = 0; t0 < n; t0 += kBaThreads) {
+      const int t = t0 + tid;
+      const bool out = t < n && s_cl[t] <= -2;
+      const unsigned long long ob = __ballot(out);
+      if (lane == 0) s_part[wave] = __popcll(ob);
+      __syncthreads();
+      int before = 0, total = 0;
+      for (int w = 0; w < kBaWaves; ++w) {
+        before += w < wave ? s_part[w] : 0;
+        total += s_part[w];
+      }
+      if (out) {
+        const int row = base + before +
+                        __builtin_amdgcn_mbcnt_hi((uint32_t)(ob >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ob, 0u));
+        assign[t] = -1 - row;
+        const u32x4* __restrict__ srcrow = (const u32x4*)(x + (uint32_t)s_src[t] * kRowBytes);
+        u32x4* __restrict__ dst = (u32x4*)rx.q_out + (int64_t)row * kRowChunks;
+        u32x4 r8[kRowChunks];
+#pragma unroll
+        for (int c = 0; c < kRowChunks; ++c) r8[c] = srcrow[c];
+#pragma unroll
+        for (int c = 0; c < kRowChunks; ++c) dst[c] = r8[c];
+      }
+      base += total;
+      __syncthreads();
+    }
+  }
+
+  // inclusive prefix over s_off[1..k]  ->  s_off[m] = first list entry of cluster m
   {
     const int per = (k + kBaThreads - 1) / kBaThreads;
     const int i0 = 1 + tid * per, i1 = i0 + per <= k + 1 ? i0 + per : k + 1;
@@ -282,7 +358,8 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
   // ---- stable counting sort in rounds of kBaThreads tokens ------------------------------------------------
   for (int base = 0; base < n; base += kBaThreads) {
     const int t = base + tid;
-    const int my_cl = t < n ? assign[t] - it.moff : -1;
+    int my_cl = t < n ? s_cl[t] : -1;
+    if (my_cl < 0) my_cl = -1;
     int my_rank = 0;
     {
       unsigned long long same = __ballot(my_cl >= 0);
@@ -301,10 +378,11 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
       int pos = s_cur[my_cl] + my_rank;
       for (int w = 0; w < wave; ++w) pos += s_wcnt[w * kmax + my_cl];
       // ascending position, re-ordered so that the dst token comes first (the order of the sums
-      // in match_merge.hip)
+      // in match_merge.hip); plain ascending if the dst token has left
       const int first = s_off[my_cl];
       const int dp = dst_position(my_cl, n, k, it.n0);
-      const int fin = t == dp ? 0 : (t < dp ? pos - first + 1 : pos - first);
+      const int fin = (REFINE && s_dout[my_cl]) ? pos - first
+                                                : (t == dp ? 0 : (t < dp ? pos - first + 1 : pos - first));
       s_list[first + fin] = (uint16_t)t;
     }
     __syncthreads();
@@ -325,75 +403,98 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
   }
 
   // ---- aggregation: thread (cluster m, 16-byte chunk c) gathers its members' rows ---------------------------
+  // Four members at a time, all loads of a batch (X and V) issued before the first add; a batch that
+  // runs past the end of the list loads nothing for the missing members and adds zeros.
   const PairSel sel = pair_selectors();
-  for (int pass = 0; pass < 2; ++pass) {
-    const char* __restrict__ src = pass == 0 ? x : v;
-    u32x4* __restrict__ out = pass == 0 ? xm : vm;
-    for (int mc = tid; mc < k * kRowChunks; mc += kBaThreads) {
-      const int m = mc >> 3, c = mc & 7;
-      const int beg = s_off[m], end = s_off[m + 1];
-      float acc[8];
+  auto add_chunk = [&](float (&acc)[8], const bf16x8 w) {
+    const bf16x2 pr[4] = {__builtin_shufflevector(w, w, 0, 1), __builtin_shufflevector(w, w, 2, 3),
+                          __builtin_shufflevector(w, w, 4, 5), __builtin_shufflevector(w, w, 6, 7)};
 #pragma unroll
-      for (int q = 0; q < 8; ++q) acc[q] = 0.f;
-      int idx = beg;
-      for (; idx + 4 <= end; idx += 4) {
-        bf16x8 w[4];
+    for (int q = 0; q < 4; ++q) {
+      acc[2 * q] = __builtin_amdgcn_fdot2_f32_bf16(pr[q], sel.lo, acc[2 * q], false);
+      acc[2 * q + 1] = __builtin_amdgcn_fdot2_f32_bf16(pr[q], sel.hi, acc[2 * q + 1], false);
+    }
+  };
+  auto finish = [&](const float (&acc)[8], float cnt, float (&mean)[8]) -> u32x4 {
+    const float rcnt = 1.0f / cnt;
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-          w[u] = *(const bf16x8*)(src + (uint32_t)s_src[s_list[idx + u]] * kRowBytes + c * 16);
+    for (int q = 0; q < 8; ++q) {
+      // correctly rounded quotient: one Newton step on the product with the reciprocal
+      const float qv = acc[q] * rcnt;
+      mean[q] = fmaf(fmaf(-qv, cnt, acc[q]), rcnt, qv);
+    }
+    u32x4 o;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const bf16x2 pr[4] = {__builtin_shufflevector(w[u], w[u], 0, 1), __builtin_shufflevector(w[u], w[u], 2, 3),
-                                __builtin_shufflevector(w[u], w[u], 4, 5), __builtin_shufflevector(w[u], w[u], 6, 7)};
+    for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(mean[2 * q], mean[2 * q + 1]);
+    return o;
+  };
+  const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+  for (int mc = tid; mc < k * kRowChunks; mc += kBaThreads) {
+    const int m = mc >> 3, c = mc & 7;
+    if (REFINE && !s_aff[m]) continue;
+    const int beg = s_off[m], end = s_off[m + 1];
+    float acc[8], accv[8];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            acc[2 * q] = __builtin_amdgcn_fdot2_f32_bf16(pr[q], sel.lo, acc[2 * q], false);
-            acc[2 * q + 1] = __builtin_amdgcn_fdot2_f32_bf16(pr[q], sel.hi, acc[2 * q + 1], false);
-          }
+    for (int q = 0; q < 8; ++q) acc[q] = accv[q] = 0.f;
+    for (int idx = beg; idx < end; idx += 4) {
+      bf16x8 w[4], wv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        w[u] = zero8;
+        wv[u] = zero8;
+        if (idx + u < end) {
+          const uint32_t off = (uint32_t)s_src[s_list[idx + u]] * kRowBytes + c * 16;
+          w[u] = *(const bf16x8*)(x + off);
+          if (v) wv[u] = *(const bf16x8*)(v + off);
         }
       }
-      for (; idx < end; ++idx) {
-        const bf16x8 w = *(const bf16x8*)(src + (uint32_t)s_src[s_list[idx]] * kRowBytes + c * 16);
-        const bf16x2 pr[4] = {__builtin_shufflevector(w, w, 0, 1), __builtin_shufflevector(w, w, 2, 3),
-                              __builtin_shufflevector(w, w, 4, 5), __builtin_shufflevector(w, w, 6, 7)};
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          acc[2 * q] = __builtin_amdgcn_fdot2_f32_bf16(pr[q], sel.lo, acc[2 * q], false);
-          acc[2 * q + 1] = __builtin_amdgcn_fdot2_f32_bf16(pr[q], sel.hi, acc[2 * q + 1], false);
-        }
-      }
-      const float cnt = (float)(end - beg);
-      const float rcnt = 1.0f / cnt;
-      float mean[8];
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        // correctly rounded quotient: one Newton step on the product with the reciprocal
-        const float qv = acc[q] * rcnt;
-        mean[q] = fmaf(fmaf(-qv, cnt, acc[q]), rcnt, qv);
-      }
-      u32x4 o;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(mean[2 * q], mean[2 * q + 1]);
-      out[mc] = o;
-      if (s.eps && pass == 0) {
-        // Sec. 3.4 step 2: L2 distance of every constituent to the fp32 mean; zero if nothing was merged
-        float* __restrict__ eps = s.eps + h * N + it.start;
-        for (int i2 = beg; i2 < end; ++i2) {
-          const int j = s_list[i2];
-          const bf16x8 w = *(const bf16x8*)(src + (uint32_t)s_src[j] * kRowBytes + c * 16);
-          float d2 = 0.f;
-#pragma unroll
-          for (int q = 0; q < 8; ++q) {
-            const float df = (float)w[q] - mean[q];
-            d2 = fmaf(df, df, d2);
-          }
-          d2 = sum8(d2);
-          if (c == 0) eps[j] = end - beg >= 2 ? sqrtf(d2) : 0.f;
-        }
+      for (int u = 0; u < 4; ++u) {
+        add_chunk(acc, w[u]);
+        if (v) add_chunk(accv, wv[u]);
       }
     }
-    if (pass == 1 || v == nullptr) break;
+    if (REFINE && end == beg) {   // every constituent has left: a zero row nobody reads
+      xm[mc] = u32x4{0, 0, 0, 0};
+      continue;
+    }
+    const float cnt = (float)(end - beg);
+    float mean[8], meanv[8];
+    xm[mc] = finish(acc, cnt, mean);
+    if (v) vm[mc] = finish(accv, cnt, meanv);
+    if (!REFINE && s.eps) {
+      // Sec. 3.4 step 2: L2 distance of every constituent to the fp32 mean; zero if nothing was merged
+      float* __restrict__ eps = s.eps + h * N + it.start;
+      for (int i2 = beg; i2 < end; ++i2) {
+        const int j = s_list[i2];
+        const bf16x8 w = *(const bf16x8*)(x + (uint32_t)s_src[j] * kRowBytes + c * 16);
+        float d2 = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const float df = (float)w[q] - mean[q];
+          d2 = fmaf(df, df, d2);
+        }
+        d2 = sum8(d2);
+        if (c == 0) eps[j] = end - beg >= 2 ? sqrtf(d2) : 0.f;
+      }
+    }
   }
+}
+
+size_t big_aggregate_lds(int nmax, int kmax) {
+  const size_t n2 = (size_t)nmax + (nmax & 1);
+  return (size_t)nmax * 4 + ((size_t)kmax + 1) * 4 + (size_t)kmax * 4 + n2 * 2 + n2 * 2 +
+         (size_t)kBaWaves * kmax + 2 * (size_t)kmax;
+}
+
+template <bool REFINE>
+hipError_t allow_big_lds() {
+  static bool done = false;
+  if (done) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute((const void*)big_aggregate_kernel<REFINE>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+  done = e == hipSuccess;
+  return e;
 }
 
 }  // namespace
@@ -407,22 +508,42 @@ hipError_t launch_match_merge_big(const MatchMergeArgs& a, hipStream_t stream) {
   if (n_items == 0 || a.H == 0) return hipSuccess;
   if (preset) return hipErrorNotSupported;
   const int nmax = a.max_block;
-  const int kmax = a.max_block;   // a block keeps at most all of its tokens
+  const int kmax = a.max_k > 0 ? a.max_k : a.max_block;
   dim3 mgrid((unsigned)n_items, (unsigned)((nmax + kBmTokens - 1) / kBmTokens), (unsigned)(a.H * a.n_streams));
   hipLaunchKernelGGL(big_match_kernel, mgrid, dim3(kBmThreads), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const size_t lds = (size_t)nmax * 4 + ((size_t)kmax + 1) * 4 + (size_t)kmax * 4 +
-                     ((size_t)nmax + (nmax & 1)) * 2 + (size_t)kBaWaves * kmax;
-  static bool attr_set = false;
-  if (!attr_set) {
-    e = hipFuncSetAttribute((const void*)big_aggregate_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            150 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  e = allow_big_lds<false>();
+  if (e != hipSuccess) return e;
   dim3 agrid((unsigned)n_items, (unsigned)a.H, (unsigned)a.n_streams);
-  hipLaunchKernelGGL(big_aggregate_kernel, agrid, dim3(kBaThreads), lds, stream, a, nmax, kmax);
+  hipLaunchKernelGGL(big_aggregate_kernel<false>, agrid, dim3(kBaThreads), big_aggregate_lds(nmax, kmax), stream,
+                     a, RefineExtra{}, nmax, kmax);
+  return hipGetLastError();
+}
+
+hipError_t launch_outlier_refine_big(const RefineArgs& r, int max_k, hipStream_t stream) {
+  if (r.n_items == 0 || r.H == 0) return hipSuccess;
+  MatchMergeArgs a = {};
+  a.n_streams = 1;
+  a.pi = r.pi;
+  a.N = r.N;
+  a.H = r.H;
+  a.max_block = r.max_block;
+  a.max_k = max_k;
+  a.s[0].x = r.x;
+  a.s[0].xm = r.xm;
+  a.s[0].assign = r.assign;
+  a.s[0].items = r.items;
+  a.s[0].n_items = r.n_items;
+  a.s[0].M = r.M;
+  a.s[0].eps = const_cast<float*>(r.eps);
+  const RefineExtra rx = {r.b.state, r.b.offsets, r.b.item_base, r.q_out};
+  const int nmax = r.max_block, kmax = max_k > 0 ? max_k : r.max_block;
+  hipError_t e = allow_big_lds<true>();
+  if (e != hipSuccess) return e;
+  dim3 grid((unsigned)r.n_items, (unsigned)r.H);
+  hipLaunchKernelGGL(big_aggregate_kernel<true>, grid, dim3(kBaThreads), big_aggregate_lds(nmax, kmax), stream, a,
+                     rx, nmax, kmax);
   return hipGetLastError();
 }
 

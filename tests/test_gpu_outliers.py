@@ -31,6 +31,10 @@ CASES = [
     (Workload("odd_block512_b8T8", 13, 9, 10, 12, 8, 8, 0.9, 1, H=2), 0.05),
     (Workload("odd_k_gt_32", 17, 4, 16, 16, 8, 4, 0.25, 1, H=2), 0.1),
     (Workload("anchored_mixed_dst", 19, 5, 12, 15, 4, 3, 0.5, 1, H=3, anchor=True), 0.1),
+    # blocks of more than 512 tokens (two-kernel path), incl. the paper's 128 x 30 at d = 0.1
+    (Workload("big_b16T8", 24, 8, 16, 20, 16, 8, 0.75, 1, H=2), 0.05),
+    (Workload("big_chunked_ns128_nt30", 25, 33, 12, 16, 128, 30, 0.9, 1, H=2, chunked=True), 0.1),
+    (Workload("big_chunked_ns128_nt30_dense", 25, 33, 12, 16, 128, 30, 0.9, 1, H=2, chunked=True), 0.4),
 ]
 
 
@@ -91,27 +95,36 @@ def test_filtered_stages_match_the_oracle(w, frac):
             keep = ~mask_gpu
             bad_idx = check_assign(slot_gpu[keep], ref["assign_q"][h][keep], ref["gap_q"][h][keep],
                                    f"{w.name} assign_q head {h}")
+        # A token whose cluster differs by an allowed tie changes the mean of the two clusters
+        # involved, hence the deviation of all their members: those clusters are left out below.
+        a_ref = ref["assign_q"][h]
+        moved = np.flatnonzero(~mask_gpu & (slot_gpu != a_ref))
+        touched = np.zeros(ref["q_m"][h].shape[0], dtype=bool)
+        touched[slot_gpu[moved]] = True
+        touched[a_ref[moved]] = True
+        clean = ~touched[a_ref]
         # deviations: fp32 on both sides, different summation order
-        same_cluster = mask_gpu | (slot_gpu == ref["assign_q"][h])
         e_ref = ref["eps"][h]
-        assert np.abs(eps_gpu[h] - e_ref)[same_cluster].max() <= 2e-5 * max(1.0, float(e_ref.max()))
+        assert np.abs(eps_gpu[h] - e_ref)[clean].max() <= 2e-5 * max(1.0, float(e_ref.max()))
         # the outlier decision
         flip = np.flatnonzero(mask_gpu != mask_ref)
         n_flip += flip.size
         if flip.size:
             near = np.abs(e_ref[flip] - tau_ref) <= NEAR_TAU * tau_ref
-            tied = ref["gap_q"][h][flip] < 1e-3
-            assert (near | tied).all(), f"head {h}: outlier decision differs away from the threshold"
+            assert (near | ~clean[flip]).all(), f"head {h}: outlier decision differs away from the threshold"
         # every outlier owns one row of q_out, inside its head's range, holding its query bit for bit
         rows = -1 - aq_gpu[h][mask_gpu]
         assert ((rows >= offs[h]) & (rows < offs[h + 1])).all()
         rows_seen.append(rows)
         assert np.array_equal(q_out[rows], qr_bits[h][mask_gpu])
         # merged queries: one bf16 rounding from the oracle's fp32 mean wherever the members agree
-        if flip.size == 0 and bad_idx == 0:
-            want = ref["q_m"][h]
-            g_qm = f32(got["q_m"][h])
-            assert (np.abs(g_qm - want) <= 2.0 ** -8 * np.abs(want) + 1e-30).all(), f"q_m head {h}"
+        # (clusters not touched by a tie, none of whose members has a flipped outlier decision)
+        rows_ok = ~touched
+        rows_ok[a_ref[flip]] = False
+        assert rows_ok.mean() > 0.9
+        want = ref["q_m"][h][rows_ok]
+        g_qm = f32(got["q_m"][h])[rows_ok]
+        assert (np.abs(g_qm - want) <= 2.0 ** -8 * np.abs(want) + 1e-30).all(), f"q_m head {h}"
     all_rows = np.concatenate(rows_seen)
     assert np.unique(all_rows).size == all_rows.size == offs[-1]
     assert n_flip <= max(2, int(1e-3 * H * N))

@@ -117,8 +117,8 @@ def test_argument_errors_are_reported_not_crashed():
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -2
     bad = httm.make_geom(8, 32, 32, 16, 4, 0.5, variant="uniform")   # no head-uniform matching of big blocks
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -2
-    bad = httm.make_geom(8, 32, 32, 16, 4, 0.5, outlier_frac=0.1)    # nor outlier filtering (yet)
-    assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -2
+    ok = httm.make_geom(8, 32, 32, 16, 4, 0.5, outlier_frac=0.1)     # outlier filtering of big blocks: fine
+    assert L.httm_geom_sizes(C.byref(ok), C.byref(s)) == 0
     bad = httm.make_geom(2, 16, 16, 4, 2, 1.5)
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -1
     bad = httm.make_geom(0, 16, 16, 4, 2, 0.5)
