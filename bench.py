@@ -260,24 +260,34 @@ def main():
         plan_f.close()
         del ws_f, vf
         torch.cuda.empty_cache()
-        # the paper's own block geometry and ratios on the same tokens (Sec. 4.1): runs of 128 tokens x
-        # 30 frames = blocks of 3840, 90 % of the queries and 70 % of the keys / values merged
-        plan_p = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, 128, 30, 0.9, 0.7, H=w.H, n_special=w.n_special,
-                                          chunked_blocks=True))
-        ws_p = httm.alloc_workspace(plan_p)
-        vp = httm.workspace_views(plan_p, ws_p)
-        t_pap = gpu_time_ms(lambda: httm.layer_forward(plan_p, q, k, v, out_u, ws_p), max(2, it // 2))
-        t_pmm = gpu_time_ms(lambda: httm.reorder_match_merge(
-            plan_p, q, k, v, vp["q_m"], vp["k_m"], vp["v_m"], vp["assign_q"], vp["assign_k"]), max(2, it // 2))
-        f_p = 4.0 * H * plan_p.M_q * plan_p.M_k * 64
-        extras["paper_blocks_ns128_nt30_rq0.9_rkv0.7_layer"] = {
-            "ms": t_pap, "tokens/s": N / (t_pap * 1e-3), "M_q": plan_p.M_q, "M_k": plan_p.M_k,
-            "reorder_match_merge_ms": t_pmm, "attention_flop": f_p}
-        log(f"[bench] paper-scale blocks (3840 tokens, 90 % / 70 %): layer {t_pap:.3f} ms, matching + merging "
-            f"{t_pmm:.3f} ms (M_q = {plan_p.M_q}, M_k = {plan_p.M_k})")
-        plan_p.close()
-        del ws_p, vp
-        torch.cuda.empty_cache()
+        # the paper's own configuration on the same tokens (Sec. 4.1): runs of 128 tokens x 30 frames =
+        # blocks of 3840, 90 % of the queries and 70 % of the keys / values merged, 10 % of all query
+        # tokens filtered out again as outliers
+        for frac_p, tag in ((0.0, "paper_blocks_ns128_nt30_rq0.9_rkv0.7_layer"),
+                            (0.1, "paper_configuration_ns128_nt30_rq0.9_rkv0.7_d0.1_layer")):
+            plan_p = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, 128, 30, 0.9, 0.7, H=w.H, n_special=w.n_special,
+                                              chunked_blocks=True, outlier_frac=frac_p))
+            ws_p = httm.alloc_workspace(plan_p)
+            vp = httm.workspace_views(plan_p, ws_p)
+            t_pap = gpu_time_ms(lambda: httm.layer_forward(plan_p, q, k, v, out_u, ws_p), max(2, it // 2))
+            if frac_p:
+                t_pmm = gpu_time_ms(lambda: httm.reorder_match_merge_filtered(
+                    plan_p, q, k, v, vp["q_m"], vp["k_m"], vp["v_m"], vp["assign_q"], vp["assign_k"],
+                    vp["eps_q"], vp["q_out"]), max(2, it // 2))
+                n_out = sum(httm.outlier_stats(plan_p)[1])
+            else:
+                t_pmm = gpu_time_ms(lambda: httm.reorder_match_merge(
+                    plan_p, q, k, v, vp["q_m"], vp["k_m"], vp["v_m"], vp["assign_q"], vp["assign_k"]),
+                    max(2, it // 2))
+                n_out = 0
+            f_p = 4.0 * (H * plan_p.M_q + n_out) * plan_p.M_k * 64
+            extras[tag] = {"ms": t_pap, "tokens/s": N / (t_pap * 1e-3), "M_q": plan_p.M_q, "M_k": plan_p.M_k,
+                           "outlier_queries": n_out, "stage2_ms": t_pmm, "attention_flop": f_p}
+            log(f"[bench] paper blocks (3840 tokens, 90 % / 70 %, d = {frac_p}): layer {t_pap:.3f} ms, stage 2 "
+                f"{t_pmm:.3f} ms (M_q = {plan_p.M_q}, M_k = {plan_p.M_k}, {n_out} outlier queries)")
+            plan_p.close()
+            del ws_p, vp
+            torch.cuda.empty_cache()
         plan_0 = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, 0.0, H=w.H,
                                           n_special=w.n_special, variant="none"))
         ws_0 = httm.alloc_workspace(plan_0)

@@ -111,7 +111,8 @@ def test_filtered_stages_match_the_oracle(w, frac):
         n_flip += flip.size
         if flip.size:
             near = np.abs(e_ref[flip] - tau_ref) <= NEAR_TAU * tau_ref
-            assert (near | ~clean[flip]).all(), f"head {h}: outlier decision differs away from the threshold"
+            tied = ref["gap_q"][h][flip] < 1e-3    # as an outlier a tied token does not show which cluster it left
+            assert (near | ~clean[flip] | tied).all(), f"head {h}: outlier decision differs away from the threshold"
         # every outlier owns one row of q_out, inside its head's range, holding its query bit for bit
         rows = -1 - aq_gpu[h][mask_gpu]
         assert ((rows >= offs[h]) & (rows < offs[h + 1])).all()
@@ -185,16 +186,23 @@ def test_filtered_layer_forward_matches_the_oracle(idx, frac):
     plan.close()
 
 
-def test_filtered_layer_full_size_sampled():
-    """Workload 5 at the paper's setting (Sec. 4.1: 90 % of the queries merged, 10 % of all query
-    tokens filtered out again), in the launch configuration the benchmark times.  The threshold
-    needs the deviations of all heads, so the oracle matches and aggregates the queries of every
-    head; merged tokens, attention rows and outputs are then checked for one head on samples."""
+@pytest.mark.parametrize("paper_blocks", [False, True], ids=["cfg5_blocks", "paper_blocks_ns128_nt30"])
+def test_filtered_layer_full_size_sampled(paper_blocks):
+    """Workload 5's tokens at the paper's setting (Sec. 4.1: 90 % of the queries merged, 10 % of all
+    query tokens filtered out again), in the launch configuration the benchmark times - once with
+    the benchmark's 8 x 8 x 4 blocks, once with the paper's own runs of 128 tokens x 30 frames and
+    70 % of the keys / values merged.  The threshold needs the deviations of all heads, so the oracle
+    matches and aggregates the queries of every head; merged tokens, attention rows and outputs are
+    then checked for one head on samples."""
     require_gpu()
     w, frac, h = synth.workload(5), 0.1, 3
+    rho_kv = w.rho
+    if paper_blocks:
+        w = dataclasses.replace(w, name="paper_S200_37x37_ns128_nt30", b=128, T=30, chunked=True)
+        rho_kv = 0.7
     print(f"[case] filtered layer {w.name} frac={frac}", flush=True)
     q, k, v = synth.make_qkv(w, device="cuda")
-    plan = plan_for(w, outlier_frac=frac)
+    plan = plan_for(w, rho_kv=rho_kv, outlier_frac=frac)
     out = torch.empty((plan.N, plan.H * 64), dtype=torch.bfloat16, device="cuda")
     ws = httm.alloc_workspace(plan)
     httm.layer_forward(plan, q, k, v, out, ws)
@@ -215,7 +223,7 @@ def test_filtered_layer_full_size_sampled():
     assert abs(tau_gpu - tau) <= 1e-5 * tau
     assert sum(counts) <= plan.outlier_cap and sum(counts) >= plan.outlier_cap - 16
     n_ref = [int((e > tau).sum()) for e in eps_all]
-    assert max(abs(a - b) for a, b in zip(counts, n_ref)) <= 8           # per-head split of the shared budget
+    assert max(abs(a - b) for a, b in zip(counts, n_ref)) <= 32          # per-head split of the shared budget
     # ---- head h in detail
     qr, aq, gap = keep["qr"], keep["aq"], keep["gap"]
     mask = eps_all[h] > tau
@@ -223,22 +231,38 @@ def test_filtered_layer_full_size_sampled():
     m_gpu = a_gpu < 0
     flip = np.flatnonzero(m_gpu != mask)
     assert flip.size <= 1e-3 * a_gpu.size
-    if flip.size:
-        assert ((np.abs(eps_all[h][flip] - tau) <= NEAR_TAU * tau) | (gap[flip] < 1e-3)).all()
     bad = check_assign(a_gpu[~m_gpu], aq[~m_gpu], gap[~m_gpu], "cfg5 filtered assign_q")
     e_gpu = views["eps_q"][h].cpu().numpy()
-    same = m_gpu | (a_gpu == aq)
-    assert np.abs(e_gpu - eps_all[h])[same].max() <= 2e-5 * float(eps_all[h].max())
     qm = orc.remove_outliers(qr, aq, keep["qm0"], mask, g, blocks, w.rho)
     kr, vr = orc.reorder(f32(k[h]), pi), orc.reorder(f32(v[h]), pi)
-    ak, _, _ = orc.blockwise_tome(kr, g, blocks, w.rho)
-    km = orc.block_aggregate(kr, ak, g, blocks, w.rho)
-    vm = orc.block_aggregate(vr, ak, g, blocks, w.rho)
-    if flip.size == 0 and bad == 0:
-        assert (np.abs(f32(views["q_m"][h]) - qm) <= 2.0 ** -8 * np.abs(qm) + 1e-30).all()
+    ak, _, _ = orc.blockwise_tome(kr, g, blocks, rho_kv)
+    km = orc.block_aggregate(kr, ak, g, blocks, rho_kv)
+    vm = orc.block_aggregate(vr, ak, g, blocks, rho_kv)
+    # the GPU's clusters before the filter (an outlier's entry no longer shows the cluster it left):
+    # the same stage 2 on a plan without the filter
+    plan0 = plan_for(w, rho_kv=rho_kv)
+    v0 = httm.workspace_views(plan0, httm.alloc_workspace(plan0))
+    httm.reorder_match_merge(plan0, q, k, v, v0["q_m"], v0["k_m"], v0["v_m"], v0["assign_q"], v0["assign_k"])
+    torch.cuda.synchronize()
+    a_pre = v0["assign_q"][h].cpu().numpy()
+    plan0.close()
+    del v0
+    assert np.array_equal(a_pre[~m_gpu], a_gpu[~m_gpu])
+    touched = np.zeros(qm.shape[0], dtype=bool)          # clusters a tie or a flipped decision changed
+    moved = np.flatnonzero(a_pre != aq)
+    touched[a_pre[moved]] = True
+    touched[aq[moved]] = True
+    # flipped decisions: near tau, or in a cluster that a tie had already changed, or a token that is
+    # itself tied between two clusters (as an outlier it does not show which one it left)
+    near = np.abs(eps_all[h][flip] - tau) <= NEAR_TAU * tau
+    assert (near | touched[aq[flip]] | (gap[flip] < 1e-3)).all()
+    touched[aq[flip]] = True
+    assert touched.mean() < 0.05
+    assert (np.abs(f32(views["q_m"][h]) - qm) <= 2.0 ** -8 * np.abs(qm) + 1e-30)[~touched].all()
     rng = np.random.default_rng(55)
     # merged rows that still have a constituent
-    alive = np.flatnonzero(np.bincount(aq[~mask], minlength=qm.shape[0]) > 0)
+    assert np.abs(e_gpu - eps_all[h])[~touched[aq]].max() <= 2e-5 * float(eps_all[h].max())
+    alive = np.flatnonzero((np.bincount(aq[~mask], minlength=qm.shape[0]) > 0) & ~touched)
     rows = np.sort(rng.choice(alive, size=512, replace=False))
     want = orc.attention(qm, km, vm, rows=rows)
     check_output(f32(views["o_m"][h][torch.from_numpy(rows).cuda()]), want, "cfg5 filtered o_m")
@@ -247,7 +271,7 @@ def test_filtered_layer_full_size_sampled():
     want_o = orc.attention(qr[pos], km, vm)
     got_o = f32(out[torch.from_numpy(pi[pos]).cuda(), h * 64:(h + 1) * 64])
     err, rel = check_output(got_o, want_o, "cfg5 outlier output rows")
-    print(f"cfg5 d={frac}: tau {tau:.6g}, outliers {sum(counts)}, head {h} flips {flip.size}, "
+    print(f"{w.name} d={frac}: tau {tau:.6g}, outliers {sum(counts)}, head {h} flips {flip.size}, "
           f"outlier rows max_abs {err:.4g} rel_l2 {rel:.4g}", flush=True)
     # tokens that stay merged read the row of their (recomputed) merged query
     row_of = -np.ones(qm.shape[0], dtype=np.int64)
