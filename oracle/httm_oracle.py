@@ -40,6 +40,9 @@ Readings taken where the paper is silent (all listed in the design notes):
     exact ties);
   * means are taken over the raw (un-normalised) tokens; V uses K's matches;
   * no size-weighted attention bias (Eq. 3 has none);
+  * general rule (dst_frac > 0): floor(dst_frac * n) strided dst per block; the r = min(floor(rho * n),
+    number of src) src with the highest best-match similarity merge (ties: lower position), the others
+    stay clusters of their own behind the dst clusters, in ascending position;
   * outlier filtering: the deviation is taken to the fp32 mean; "top d %" is a
     budget of floor(d * H * N) tokens and the threshold is the largest deviation
     outside that budget (strictly greater = outlier); Alg. 2's "append retained
@@ -72,6 +75,9 @@ class Geometry:
     T: int              # temporal block length (frames)
     n_special: int = 5  # special tokens at the front of each frame
     anchor: bool = False  # first-frame anchoring (App. C.2): every frame-0 token is a dst
+    dst_frac: float = 0.0  # > 0: the general rule of Sec. 3.2 - this share of a block's tokens are dst and
+                           # only the top-r src (by best similarity) merge; 0: Alg. 1's "k clusters per
+                           # block", where every src merges
     chunked: bool = False  # spatial blocks are runs of b consecutive patch tokens of a frame (row-major)
                            # instead of b x b windows: the paper's own setting n_s = 128 (Sec. 4.1)
 
@@ -172,12 +178,24 @@ def inverse_reorder(xr: np.ndarray, pi: np.ndarray) -> np.ndarray:
 # Sec. 3.2 "Merging" restricted to blocks (Sec. 3.3); Alg. 1 "BlockwiseToMe"
 # --------------------------------------------------------------------------
 
-def cluster_count(n: int, rho: float, n0: int = 0) -> int:
+def dst_count(n: int, rho: float, n0: int = 0, dst_frac: float = 0.0) -> int:
+    """Number of dst tokens of a block.  Alg. 1's rule (dst_frac = 0): as many as the block keeps.
+    General rule (Sec. 3.2, "partitioned into src and dst"; the 25 % / 75 % example of Sec. 3.3):
+    floor(dst_frac * n), at least one, at least the n0 anchored tokens."""
+    if dst_frac <= 0.0:
+        return cluster_count(n, rho, n0)
+    return max(1, int(math.floor(dst_frac * n + 1e-9)), n0)
+
+
+def cluster_count(n: int, rho: float, n0: int = 0, dst_frac: float = 0.0) -> int:
     """Tokens a block of n keeps when a fraction rho is merged away (M = N - r).
 
-    With n0 anchored tokens (all of them dst) the block keeps at least those.
+    With n0 anchored tokens (all of them dst) the block keeps at least those.  Under the general
+    rule only src tokens can be merged away: r = min(floor(rho * n), number of src).
     """
     r = int(math.floor(rho * n + 1e-9))
+    if dst_frac > 0.0:
+        return n - min(r, n - dst_count(n, rho, n0, dst_frac))
     return max(1, n - r, n0)
 
 
@@ -198,33 +216,61 @@ def row_norm(x: np.ndarray) -> np.ndarray:
     return x / np.maximum(nrm, x.dtype.type(EPS_NORM))[:, None]
 
 
-def match_block(xb: np.ndarray, k: int, n0: int = 0):
-    """Bipartite matching inside one block (Eq. 1 and the best-match rule).
+def match_block(xb: np.ndarray, k: int, n0: int = 0, kd: int = None):
+    """Bipartite matching inside one block (Eq. 1, the best-match rule and the top-r selection).
 
-    xb: [n, E] tokens of the block.  Returns
+    xb: [n, E] tokens of the block, which keeps k clusters of which the first kd (default: all k)
+    are its dst tokens.  The r = n - k src tokens with the highest best-match similarity (ties:
+    lower position first) merge into their best dst; every other src token stays a cluster of its
+    own, numbered kd, kd+1, ... in ascending position.  Returns
       cluster[n]  cluster id m in 0..k-1 of every token (a dst is its own cluster),
       score[n]    cosine similarity of a src to its best dst (1.0 for dst tokens),
-      gap[n]      best minus second-best similarity (inf for dst tokens / k = 1).
+      gap[n]      how far the token is from deciding otherwise: best minus second-best similarity,
+                  and (when not every src merges) the distance of its score to the score on the
+                  other side of the selection boundary; inf for dst tokens.
     """
     n = xb.shape[0]
-    dpos = dst_positions(n, k, n0)
+    kd = k if kd is None else kd
+    dpos = dst_positions(n, kd, n0)
     is_dst = np.zeros(n, dtype=bool)
     is_dst[dpos] = True
     spos = np.flatnonzero(~is_dst)
     cluster = np.empty(n, dtype=np.int64)
     score = np.ones(n, dtype=xb.dtype)
     gap = np.full(n, np.inf, dtype=xb.dtype)
-    cluster[dpos] = np.arange(k)
+    cluster[dpos] = np.arange(kd)
     if spos.size:
         sim = row_norm(xb[spos]) @ row_norm(xb[dpos]).T           # Eq. 1, [n_src, n_dst]
         best = np.argmax(sim, axis=1)                            # first maximum = lowest m
         cluster[spos] = best
         score[spos] = sim[np.arange(spos.size), best]
-        if k > 1:
+        if kd > 1:
             rest = sim.copy()
             rest[np.arange(spos.size), best] = -np.inf
             gap[spos] = score[spos] - rest.max(axis=1)
+        r = n - k
+        if r < spos.size:
+            # "merge the top-r src tokens with the highest similarity scores" (Sec. 3.2)
+            order = np.lexsort((spos, -score[spos]))              # score descending, then position
+            merged = np.zeros(spos.size, dtype=bool)
+            merged[order[:r]] = True
+            stay = spos[~merged]                                 # ascending position
+            cluster[stay] = kd + np.arange(stay.size)
+            s_sorted = score[spos][order]
+            if 0 < r:
+                other = np.where(merged, s_sorted[r], s_sorted[r - 1])   # first score across the boundary
+                gap[spos] = np.minimum(gap[spos], np.abs(score[spos] - other))
     return cluster, score, gap
+
+
+def cluster_owners(cluster: np.ndarray, n: int, k: int, kd: int, n0: int) -> list:
+    """Block-local position of the token every cluster starts from: the dst token of clusters
+    0..kd-1, the (single) unmerged src token of clusters kd..k-1."""
+    owners = dst_positions(n, kd, n0)
+    if k > kd:
+        pos = {int(c): j for j, c in enumerate(cluster) if c >= kd}
+        owners = owners + [pos[m] for m in range(kd, k)]
+    return owners
 
 
 def merged_layout(g: Geometry, blocks, rho: float):
@@ -236,11 +282,16 @@ def merged_layout(g: Geometry, blocks, rho: float):
     ks, offs = [], []
     pos = g.n_prefix
     for (_, n), n0 in zip(blocks, anchor_sizes(g)):
-        k = cluster_count(n, rho, n0)
+        k = cluster_count(n, rho, n0, g.dst_frac)
         ks.append(k)
         offs.append(pos)
         pos += k
     return ks, offs, pos
+
+
+def dst_counts(g: Geometry, blocks, rho: float) -> list:
+    """Per block: how many of its clusters are dst tokens (all of them under Alg. 1's rule)."""
+    return [dst_count(n, rho, n0, g.dst_frac) for (_, n), n0 in zip(blocks, anchor_sizes(g))]
 
 
 def blockwise_tome(xr: np.ndarray, g: Geometry, blocks, rho: float):
@@ -256,8 +307,8 @@ def blockwise_tome(xr: np.ndarray, g: Geometry, blocks, rho: float):
     score = np.ones(L, dtype=xr.dtype)
     gap = np.full(L, np.inf, dtype=xr.dtype)
     assign[:g.n_prefix] = np.arange(g.n_prefix)        # specials pass through
-    for (start, n), k, off, n0 in zip(blocks, ks, offs, anchor_sizes(g)):
-        c, s, gp = match_block(xr[start:start + n], k, n0)
+    for (start, n), k, off, n0, kd in zip(blocks, ks, offs, anchor_sizes(g), dst_counts(g, blocks, rho)):
+        c, s, gp = match_block(xr[start:start + n], k, n0, kd)
         assign[start:start + n] = off + c
         score[start:start + n] = s
         gap[start:start + n] = gp
@@ -279,8 +330,8 @@ def block_aggregate(xr: np.ndarray, assign: np.ndarray, g: Geometry, blocks, rho
     count = np.zeros(M, dtype=np.int64)
     out[:g.n_prefix] = xr[:g.n_prefix]
     count[:g.n_prefix] = 1
-    for (start, n), k, off, n0 in zip(blocks, ks, offs, anchor_sizes(g)):
-        dpos = dst_positions(n, k, n0)
+    for (start, n), k, off, n0, kd in zip(blocks, ks, offs, anchor_sizes(g), dst_counts(g, blocks, rho)):
+        dpos = cluster_owners(assign[start:start + n] - off, n, k, kd, n0)
         dset = set(dpos)
         for m, j in enumerate(dpos):
             out[off + m] = xr[start + j]
@@ -338,10 +389,10 @@ def remove_outliers(xr: np.ndarray, assign: np.ndarray, xm: np.ndarray, mask: np
     aff[affected] = True
     acc = np.zeros((M, xr.shape[1]), dtype=xr.dtype)
     cnt = np.zeros(M, dtype=np.int64)
-    for (start, n), k, off, n0 in zip(blocks, ks, offs, anchor_sizes(g)):
+    for (start, n), k, off, n0, kd in zip(blocks, ks, offs, anchor_sizes(g), dst_counts(g, blocks, rho)):
         if not aff[off:off + k].any():
             continue
-        dpos = dst_positions(n, k, n0)
+        dpos = cluster_owners(assign[start:start + n] - off, n, k, kd, n0)
         dset = set(dpos)
         for m, j in enumerate(dpos):
             if aff[off + m] and not mask[start + j]:
@@ -500,8 +551,8 @@ def rep_map(assign: np.ndarray, pi: np.ndarray, g: Geometry, blocks, rho: float)
     ks, offs, M = merged_layout(g, blocks, rho)
     slot_owner = np.empty(M, dtype=np.int64)
     slot_owner[:g.n_prefix] = pi[:g.n_prefix]
-    for (start, n), k, off, n0 in zip(blocks, ks, offs, anchor_sizes(g)):
-        for m, j in enumerate(dst_positions(n, k, n0)):
+    for (start, n), k, off, n0, kd in zip(blocks, ks, offs, anchor_sizes(g), dst_counts(g, blocks, rho)):
+        for m, j in enumerate(cluster_owners(assign[start:start + n] - off, n, k, kd, n0)):
             slot_owner[off + m] = pi[start + j]
     rep = np.empty(g.N, dtype=np.int64)
     rep[pi] = slot_owner[assign]

@@ -36,24 +36,33 @@ def _blocks_bruteforce(S, Hp, Wp, b, T, n_special, chunked=False):
     return specials, [groups[key] for key in sorted(groups)]
 
 
-def _merge_head(x, specials, blocks, rho, anchor_below=0):
+def _merge_head(x, specials, blocks, rho, anchor_below=0, dst_frac=0.0):
     """x: list of N vectors.  Returns (clusters, owner): clusters = list of member lists (input
     indices, dst first), in merged order; owner[i] = index into clusters for input token i.
     Tokens with input index < anchor_below (= the tokens of frame 0 under first-frame anchoring,
-    App. C.2) are always dst; the other dst are strided over the rest of the block."""
+    App. C.2) are always dst; the other dst are strided over the rest of the block.
+    dst_frac > 0: the general rule of Sec. 3.2 - that share of the block are dst, and only the r src
+    tokens with the highest best-match similarity merge (ties: earlier token first)."""
     clusters = [[i] for i in specials]
     owner = {i: c for c, i in enumerate(specials)}
     for toks in blocks:
         n = len(toks)
         anchored = [p for p, i in enumerate(toks) if i < anchor_below]
         others = [p for p, i in enumerate(toks) if i >= anchor_below]
-        k = max(1, n - int(math.floor(rho * n + 1e-9)), len(anchored))
-        free = k - len(anchored)
+        r = int(math.floor(rho * n + 1e-9))
+        if dst_frac > 0.0:
+            kd = max(1, int(math.floor(dst_frac * n + 1e-9)), len(anchored))
+            r = min(r, n - kd)
+        else:
+            kd = max(1, n - r, len(anchored))
+            r = n - kd
+        free = kd - len(anchored)
         dpos = anchored + [others[(m * len(others)) // free] for m in range(free)]
         base = len(clusters)
         for m, p in enumerate(dpos):
             clusters.append([toks[p]])
             owner[toks[p]] = base + m
+        matches = []                                   # (score, position, best cluster) of every src token
         for p, i in enumerate(toks):
             if p in dpos:
                 continue
@@ -62,8 +71,15 @@ def _merge_head(x, specials, blocks, rho, anchor_below=0):
                 s = _cos(x[i], x[toks[dp]])
                 if s > best_s:                       # strict: lowest m wins exact ties
                     best_m, best_s = m, s
-            clusters[base + best_m].append(i)
-            owner[i] = base + best_m
+            matches.append((best_s, p, best_m))
+        chosen = {p for _, p, _ in sorted(matches, key=lambda t: (-t[0], t[1]))[:r]}
+        for s_, p, m in matches:                       # in ascending position
+            if p in chosen:
+                clusters[base + m].append(toks[p])
+                owner[toks[p]] = base + m
+            else:
+                owner[toks[p]] = len(clusters)
+                clusters.append([toks[p]])
     return clusters, owner
 
 
@@ -72,7 +88,8 @@ def _mean(vectors):
     return [math.fsum(v[c] for v in vectors) / len(vectors) for c in range(E)]
 
 
-def _layer_bruteforce(q, k, v, S, Hp, Wp, b, T, n_special, rho_q, rho_kv, anchor=False, chunked=False):
+def _layer_bruteforce(q, k, v, S, Hp, Wp, b, T, n_special, rho_q, rho_kv, anchor=False, chunked=False,
+                      dst_frac=0.0):
     H, N, E = q.shape
     specials, blocks = _blocks_bruteforce(S, Hp, Wp, b, T, n_special, chunked)
     anchor_below = (n_special + Hp * Wp) if anchor else 0      # input indices of frame 0
@@ -80,8 +97,8 @@ def _layer_bruteforce(q, k, v, S, Hp, Wp, b, T, n_special, rho_q, rho_kv, anchor
     owners_q, owners_k = [], []
     for h in range(H):
         qh, kh, vh = q[h].tolist(), k[h].tolist(), v[h].tolist()
-        cq, own_q = _merge_head(qh, specials, blocks, rho_q, anchor_below)
-        ck, own_k = _merge_head(kh, specials, blocks, rho_kv, anchor_below)
+        cq, own_q = _merge_head(qh, specials, blocks, rho_q, anchor_below, dst_frac)
+        ck, own_k = _merge_head(kh, specials, blocks, rho_kv, anchor_below, dst_frac)
         qm = [_mean([qh[i] for i in mem]) for mem in cq]
         km = [_mean([kh[i] for i in mem]) for mem in ck]
         vm = [_mean([vh[i] for i in mem]) for mem in ck]      # V follows K's matches
@@ -153,6 +170,52 @@ def test_oracle_equals_bruteforce_with_chunked_blocks(case, anchor):
         assert np.array_equal(orc.rep_map(res["assign_q"][h], pi, g, blocks, rho_q), ref_rep_q[h])
         assert np.array_equal(orc.rep_map(res["assign_k"][h], pi, g, blocks, rho_kv), ref_rep_k[h])
     assert np.abs(res["O"] - ref_out).max() < 1e-12
+
+
+TOP_R = [
+    # S, Hp, Wp, b, T, n_special, rho_q, rho_kv, dst_frac, anchor, chunked
+    (3, 3, 4, 2, 2, 5, 0.5, 0.5, 0.25, False, False),
+    (4, 4, 4, 2, 3, 1, 0.6, 0.3, 0.25, False, False),
+    (2, 4, 4, 4, 2, 0, 0.9, 0.9, 0.25, False, False),      # the ratio asks for more than there are src
+    (3, 2, 6, 5, 3, 2, 0.4, 0.7, 0.5, False, True),
+    (4, 3, 3, 2, 2, 2, 0.5, 0.5, 0.25, True, False),       # with first-frame anchoring
+    (3, 3, 4, 2, 2, 5, 0.0, 0.5, 0.25, False, False),      # queries not merged at all
+]
+
+
+@pytest.mark.parametrize("case", TOP_R)
+def test_oracle_equals_bruteforce_with_top_r_selection(case):
+    """Sec. 3.2 as written: a fixed share of dst tokens, and only the r most similar src merge."""
+    S, Hp, Wp, b, T, nsp, rho_q, rho_kv, dst_frac, anchor, chunked = case
+    g = orc.Geometry(S, Hp, Wp, b, T, n_special=nsp, anchor=anchor, chunked=chunked, dst_frac=dst_frac)
+    H, E = 2, 8
+    rng = np.random.default_rng(31 + S * 100 + Hp * 10 + Wp)
+    q, k, v = (rng.standard_normal((H, g.N, E)) for _ in range(3))
+    ref_out, ref_rep_q, ref_rep_k = _layer_bruteforce(q, k, v, S, Hp, Wp, b, T, nsp, rho_q, rho_kv,
+                                                      anchor=anchor, chunked=chunked, dst_frac=dst_frac)
+    res = orc.layer_forward(q, k, v, g, rho_q, rho_kv, dtype=np.float64)
+    pi, blocks = res["pi"], res["blocks"]
+    for h in range(H):
+        assert np.array_equal(orc.rep_map(res["assign_q"][h], pi, g, blocks, rho_q), ref_rep_q[h])
+        assert np.array_equal(orc.rep_map(res["assign_k"][h], pi, g, blocks, rho_kv), ref_rep_k[h])
+    assert np.abs(res["O"] - ref_out).max() < 1e-12
+    # sizes: a block of n tokens keeps n - min(floor(rho n), n - kd)
+    ks, _, M = orc.merged_layout(g, blocks, rho_q)
+    kds = orc.dst_counts(g, blocks, rho_q)
+    for (_, n), k_, kd in zip(blocks, ks, kds):
+        assert k_ == n - min(int(math.floor(rho_q * n + 1e-9)), n - kd) and 1 <= kd <= k_
+    assert res["q_m"][0].shape[0] == M
+
+
+def test_top_r_rule_reduces_to_alg1_when_every_src_merges():
+    """With dst_frac = 1 - rho (and no rounding trouble) the two rules describe the same partition."""
+    g0 = orc.Geometry(2, 4, 4, 2, 2)
+    g1 = orc.Geometry(2, 4, 4, 2, 2, dst_frac=0.25)
+    rng = np.random.default_rng(3)
+    q, k, v = (rng.standard_normal((2, g0.N, 8)) for _ in range(3))
+    a = orc.layer_forward(q, k, v, g0, 0.75, 0.75, dtype=np.float64)
+    b_ = orc.layer_forward(q, k, v, g1, 0.75, 0.75, dtype=np.float64)
+    assert np.array_equal(a["O"], b_["O"]) and all(np.array_equal(x, y) for x, y in zip(a["assign_q"], b_["assign_q"]))
 
 
 ANCHORED = [
