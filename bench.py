@@ -288,6 +288,17 @@ def main():
             plan_p.close()
             del ws_p, vp
             torch.cuda.empty_cache()
+        # the cost the merging blocks remove (Sec. 3.3, Table 3 "Matching"): un-blocked matching of
+        # the queries with 25 % dst tokens, against the block-local stage 2 (Q, K and V, with merging)
+        best = torch.empty((H, N), dtype=torch.int32, device="cuda")
+        t_glob = gpu_time_ms(lambda: httm.global_match(q, 0.25, best), 1, warmup=1)
+        kd_g = int(0.25 * N)
+        extras["global_matching_q_dst0.25"] = {
+            "ms": t_glob, "TFLOP/s": 2.0 * H * N * kd_g * 64 / (t_glob * 1e-3) / 1e12,
+            "x_block_local_stage2": t_glob / t_fused_merge}
+        log(f"[bench] un-blocked matching of Q (25 % dst): {t_glob:.2f} ms = {t_glob / t_fused_merge:.0f}x the "
+            f"block-local matching + merging of Q, K and V")
+        del best
         plan_0 = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, 0.0, H=w.H,
                                           n_special=w.n_special, variant="none"))
         ws_0 = httm.alloc_workspace(plan_0)

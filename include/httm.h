@@ -109,6 +109,13 @@ typedef struct httm_geom {
                           query tokens - those that lie farthest from their merged token, over all
                           heads together - that is taken out of the merging again; 0 = off,
                           at most HTTM_MAX_OUTLIER_FRAC.  Ignored for HTTM_VARIANT_NONE. */
+  double dst_frac;    /* 0: Alg. 1's rule - a block keeps k clusters, all of them dst tokens, and every src
+                         merges.  > 0 (at most 1): the general rule of Sec. 3.2 - floor(dst_frac * n) tokens
+                         of a block are dst (at least one), and only the r = min(floor(rho * n), number of
+                         src) src tokens with the highest best-match similarity merge (ties: lower
+                         position first); the other src stay clusters of their own, placed behind the
+                         block's dst clusters in ascending position.  Blocks of at most 512 tokens,
+                         HTTM_VARIANT_HEADWISE only. */
 } httm_geom_t;
 
 /* Sizes derived from a geometry. */
@@ -187,6 +194,18 @@ HTTM_API int httm_match_merge(const httm_plan_t* plan, const void* q_r, const vo
 HTTM_API int httm_reorder_match_merge(const httm_plan_t* plan, const void* q, const void* k, const void* v,
                              void* q_m, void* k_m, void* v_m, int32_t* assign_q, int32_t* assign_k,
                              float* score_q, float* score_k, void* stream);
+
+/* Un-blocked ("global") matching, the comparison point of Sec. 3.3 and Table 3: the whole sequence of
+ * a head is one merging block.  kd = max(1, floor(dst_frac * N)) tokens at positions floor(m * N / kd)
+ * are dst; Eq. 1 and the best-match rule over all N x kd pairs (about dst_frac * (1 - dst_frac) * N^2 *
+ * d_head multiply-adds per head - the "0.19 N^2 d_head" of Sec. 3.3 at 25 %).  Matching only: it is
+ * here to be timed against the block-local stage 2.
+ * x        : [H, N, d_head] bf16, any token order.  N * kd pairs; N < 2^25, grid limit N <= 16 M.
+ * best_dst : [H, N] int32 out; index 0..kd-1 of the most similar dst (lowest index on exact ties);
+ *            a dst token gets its own index.
+ * sim      : [H, N] float out or NULL; that cosine similarity (1.0 for dst tokens). */
+HTTM_API int httm_global_match(const void* x, int64_t N, int H, int d_head, double dst_frac,
+                               int32_t* best_dst, float* sim, void* stream);
 
 /* ---- stage 3: attention over the reduced sequences (Sec. 3.2 Eq. 3-4) ------------------- */
 

@@ -27,7 +27,7 @@ class Geom(C.Structure):
     _fields_ = [("S", C.c_int32), ("Hp", C.c_int32), ("Wp", C.c_int32), ("n_special", C.c_int32),
                 ("H", C.c_int32), ("d_head", C.c_int32), ("b", C.c_int32), ("T", C.c_int32),
                 ("rho_q", C.c_double), ("rho_kv", C.c_double), ("variant", C.c_int32),
-                ("flags", C.c_int32), ("outlier_frac", C.c_double)]
+                ("flags", C.c_int32), ("outlier_frac", C.c_double), ("dst_frac", C.c_double)]
 
 
 class Sizes(C.Structure):
@@ -73,12 +73,13 @@ def lib() -> C.CDLL:
     L.httm_attention_outliers.argtypes = [vp, vp, vp, vp, vp, vp]
     L.httm_unmerge_filtered.argtypes = [vp, vp, vp, i32p, vp, vp]
     L.httm_outlier_stats.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32), vp]
+    L.httm_global_match.argtypes = [vp, C.c_int64, C.c_int, C.c_int, C.c_double, i32p, f32p, vp]
     for name in ("httm_geom_sizes", "httm_workspace_layout", "httm_geom_tables", "httm_plan_create",
                  "httm_plan_destroy", "httm_plan_query", "httm_reorder", "httm_match_merge",
                  "httm_reorder_match_merge",
                  "httm_attention", "httm_unmerge", "httm_layer_forward",
                  "httm_reorder_match_merge_filtered", "httm_attention_outliers", "httm_unmerge_filtered",
-                 "httm_outlier_stats"):
+                 "httm_outlier_stats", "httm_global_match"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -97,13 +98,14 @@ FLAG_CHUNKED_BLOCKS = 2
 
 
 def make_geom(S, Hp, Wp, b, T, rho_q, rho_kv=None, *, H=16, d_head=64, n_special=5,
-              variant="headwise", anchor_first_frame=False, outlier_frac=0.0, chunked_blocks=False) -> Geom:
+              variant="headwise", anchor_first_frame=False, outlier_frac=0.0, chunked_blocks=False,
+              dst_frac=0.0) -> Geom:
     if rho_kv is None:
         rho_kv = rho_q
     v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
     flags = (FLAG_ANCHOR_FIRST_FRAME if anchor_first_frame else 0) | (FLAG_CHUNKED_BLOCKS if chunked_blocks else 0)
     return Geom(S, Hp, Wp, n_special, H, d_head, b, T, float(rho_q), float(rho_kv), v, flags,
-                float(outlier_frac))
+                float(outlier_frac), float(dst_frac))
 
 
 def geom_sizes(g: Geom) -> Sizes:
@@ -297,6 +299,16 @@ def outlier_stats(plan: Plan):
     counts = (C.c_int32 * plan.H)()
     _check(lib().httm_outlier_stats(plan._h, C.byref(tau), counts, _stream()), "httm_outlier_stats")
     return float(tau.value), [int(c) for c in counts]
+
+
+def global_match(x, dst_frac: float, best_dst, sim=None):
+    """Un-blocked matching of x [H, N, 64] (Sec. 3.3's comparison point): best_dst / sim [H, N]."""
+    H, N = int(x.shape[0]), int(x.shape[1])
+    _check(lib().httm_global_match(_dev(x, torch.bfloat16, (H, N, 64)), N, H, 64, float(dst_frac),
+                                   _dev(best_dst, torch.int32, (H, N)),
+                                   _dev(sim, torch.float32, (H, N)) if sim is not None else None, _stream()),
+           "httm_global_match")
+    return best_dst
 
 
 def alloc_workspace(plan: Plan) -> torch.Tensor:

@@ -86,6 +86,7 @@ int run_match_merge(const httm_plan_t* p, const int32_t* pi, const void* q, cons
   a.H = g.H;
   a.max_block = (int32_t)(p->sizes.max_block < kPrefixChunk ? kPrefixChunk : p->sizes.max_block);
   a.max_k = p->max_k;
+  a.top_r = p->geom.dst_frac > 0.0 && p->geom.variant != HTTM_VARIANT_NONE;
   a.s[0] = {q, nullptr, q_m, nullptr, assign_q, score_q, p->d_items_q, p->n_items, p->sizes.M_q,
             nullptr, nullptr, eps_q};
   a.s[1] = {k, v, k_m, v_m, assign_k, score_k, p->d_items_k, p->n_items, p->sizes.M_k, nullptr,
@@ -304,6 +305,17 @@ int httm_reorder_match_merge(const httm_plan_t* p, const void* q, const void* k,
     if (!aligned16(x)) return HTTM_E_INVALID_ARG;
   return run_match_merge(p, p->d_pi, q, k, v, q_m, k_m, v_m, assign_q, assign_k, score_q, score_k,
                          (hipStream_t)stream);
+}
+
+int httm_global_match(const void* x, int64_t N, int H, int d_head, double dst_frac, int32_t* best_dst,
+                      float* sim, void* stream) {
+  if (!x || !best_dst || N <= 0 || H <= 0 || !(dst_frac > 0.0 && dst_frac <= 1.0)) return HTTM_E_INVALID_ARG;
+  if (d_head != 64 || H > HTTM_MAX_HEADS || N >= ((int64_t)1 << 24)) return HTTM_E_UNSUPPORTED;
+  if (!aligned16(x) || !aligned16(best_dst)) return HTTM_E_INVALID_ARG;
+  int64_t kd = (int64_t)(dst_frac * (double)N + 1e-9);
+  if (kd < 1) kd = 1;
+  HTTM_HIP(launch_global_match(x, N, H, (int32_t)kd, best_dst, sim, (hipStream_t)stream));
+  return HTTM_OK;
 }
 
 int httm_attention(const void* q_m, const void* k_m, const void* v_m, void* o_m,

@@ -46,8 +46,15 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
 // n tokens that keeps k clusters): the n0 anchored tokens at the front of the block first (App. C.2),
 // the other k - n0 evenly strided over the remaining n - n0 tokens, the first of them included.
 // n0 = 0 gives floor(m * n / k).
+// (32-bit product: for blocks of at most 32768 tokens, which is every merging block.)
 __device__ __forceinline__ int dst_position(int m, int n, int k, int n0) {
   return m < n0 ? m : n0 + ((m - n0) * (n - n0)) / (k - n0);
+}
+// The same for a "block" of any size below 2^31 tokens (un-blocked matching of a whole sequence):
+// (m - n0) * (n - n0) passes 2^31 from n = 46341 on, so the product is taken in 64 bits there.
+__device__ __forceinline__ int dst_position_any(int m, int n, int k, int n0) {
+  if (n <= 32768) return dst_position(m, n, k, n0);
+  return m < n0 ? m : n0 + (int)(((int64_t)(m - n0) * (int64_t)(n - n0)) / (int64_t)(k - n0));
 }
 
 }  // namespace httm

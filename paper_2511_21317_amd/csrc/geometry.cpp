@@ -15,6 +15,7 @@ int check_geom(const httm_geom_t& g) {
     return HTTM_E_INVALID_ARG;
   if (g.flags & ~(HTTM_FLAG_ANCHOR_FIRST_FRAME | HTTM_FLAG_CHUNKED_BLOCKS)) return HTTM_E_INVALID_ARG;
   if (!(g.outlier_frac >= 0.0 && g.outlier_frac <= HTTM_MAX_OUTLIER_FRAC)) return HTTM_E_INVALID_ARG;
+  if (!(g.dst_frac >= 0.0 && g.dst_frac <= 1.0)) return HTTM_E_INVALID_ARG;
   if (g.d_head != 64 || g.H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
   const int64_t tpf = (int64_t)g.n_special + (int64_t)g.Hp * g.Wp;
   const int64_t N = tpf * g.S;
@@ -24,17 +25,33 @@ int check_geom(const httm_geom_t& g) {
   const int64_t ns = (g.flags & HTTM_FLAG_CHUNKED_BLOCKS) ? (g.b < P ? g.b : P) : bh * bw;
   if (ns * bt > HTTM_MAX_BLOCK) return HTTM_E_UNSUPPORTED;
   if (ns * bt > 512 && g.variant == HTTM_VARIANT_UNIFORM) return HTTM_E_UNSUPPORTED;
+  if (g.dst_frac > 0.0 && g.variant != HTTM_VARIANT_NONE &&
+      (ns * bt > 512 || g.variant == HTTM_VARIANT_UNIFORM))
+    return HTTM_E_UNSUPPORTED;
   return HTTM_OK;
 }
 
-int32_t clusters_kept(int32_t n, double rho, int32_t n0) {
+int32_t clusters_kept(int32_t n, double rho, int32_t n0, double dst_frac, int32_t* kd_out) {
   // Sec. 3.2: r tokens are merged away, M = N - r remain; Sec. 4.1 fixes "ratio rho leaves
   // (1 - rho)".  Applied per block with the count rounded down; at least one cluster survives,
   // and every anchored token (App. C.2) is one.
   const int32_t r = (int32_t)std::floor(rho * (double)n + 1e-9);
-  int32_t k = n - r;
-  if (k < 1) k = 1;
-  return k < n0 ? n0 : k;
+  int32_t k, kd;
+  if (dst_frac > 0.0) {
+    // general rule: a fixed share of dst tokens, only src tokens can be merged away
+    kd = (int32_t)std::floor(dst_frac * (double)n + 1e-9);
+    if (kd < 1) kd = 1;
+    if (kd < n0) kd = n0;
+    const int32_t n_src = n - kd;
+    k = n - (r < n_src ? r : n_src);
+  } else {
+    k = n - r;
+    if (k < 1) k = 1;
+    if (k < n0) k = n0;
+    kd = k;
+  }
+  if (kd_out) *kd_out = kd;
+  return k;
 }
 
 int64_t outlier_budget(const httm_geom_t& g, int64_t N) {
@@ -82,8 +99,8 @@ int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
   t.items_k.clear();
   for (int64_t p = 0; p < t.n_prefix; p += kPrefixChunk) {
     const int32_t n = (int32_t)((t.n_prefix - p) < kPrefixChunk ? (t.n_prefix - p) : kPrefixChunk);
-    t.items_q.push_back({(int32_t)p, n, n, (int32_t)p, 0, {0, 0, 0}});
-    t.items_k.push_back({(int32_t)p, n, n, (int32_t)p, 0, {0, 0, 0}});
+    t.items_q.push_back({(int32_t)p, n, n, (int32_t)p, 0, n, {0, 0}});
+    t.items_k.push_back({(int32_t)p, n, n, (int32_t)p, 0, n, {0, 0}});
   }
 
   int64_t mq = t.n_prefix, mk = t.n_prefix;
@@ -112,13 +129,15 @@ int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
         // first temporal group are its first (rows x cols) positions
         const bool anchor = (g.flags & HTTM_FLAG_ANCHOR_FIRST_FRAME) && grp == 0;
         const int32_t n0 = anchor ? (y1 - y0) * (x1 - x0) : 0;
-        const int32_t kq = clusters_kept(n, rho_q, n0), kk = clusters_kept(n, rho_k, n0);
+        const double df = g.variant == HTTM_VARIANT_NONE ? 0.0 : g.dst_frac;
+        int32_t kdq = 0, kdk = 0;
+        const int32_t kq = clusters_kept(n, rho_q, n0, df, &kdq), kk = clusters_kept(n, rho_k, n0, df, &kdk);
         t.block_kq[bi] = kq;
         t.block_kk[bi] = kk;
         t.block_offq[bi] = (int32_t)mq;
         t.block_offk[bi] = (int32_t)mk;
-        t.items_q.push_back({(int32_t)pos, n, kq, (int32_t)mq, n0, {0, 0, 0}});
-        t.items_k.push_back({(int32_t)pos, n, kk, (int32_t)mk, n0, {0, 0, 0}});
+        t.items_q.push_back({(int32_t)pos, n, kq, (int32_t)mq, n0, kdq, {0, 0}});
+        t.items_k.push_back({(int32_t)pos, n, kk, (int32_t)mk, n0, kdk, {0, 0}});
         mq += kq;
         mk += kk;
         pos += n;

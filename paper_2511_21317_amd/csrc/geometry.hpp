@@ -20,7 +20,8 @@ struct WorkItem {
   int32_t k;      // clusters kept
   int32_t moff;   // first merged slot
   int32_t n0;     // leading tokens that are always dst
-  int32_t pad[3];
+  int32_t kd;     // clusters 0..kd-1 are the dst tokens; kd == k unless only the top-r src merge
+  int32_t pad[2];
 };
 
 struct HostTables {
@@ -38,8 +39,9 @@ constexpr int kPrefixChunk = 64;  // tokens per pseudo-block of the special pref
 // Validate a geometry (returns an HTTM_E_* code).
 int check_geom(const httm_geom_t& g);
 
-// Clusters kept by a block of n tokens at merge ratio rho, at least its n0 anchored tokens.
-int32_t clusters_kept(int32_t n, double rho, int32_t n0 = 0);
+// Clusters kept by a block of n tokens at merge ratio rho, at least its n0 anchored tokens; *kd
+// (if given) receives how many of them are dst tokens (Sec. 3.2; dst_frac = 0: all of them).
+int32_t clusters_kept(int32_t n, double rho, int32_t n0 = 0, double dst_frac = 0.0, int32_t* kd = nullptr);
 
 // Outlier queries there can be at most (0 when the filter is off).
 int64_t outlier_budget(const httm_geom_t& g, int64_t N);

@@ -36,11 +36,18 @@ struct MatchMergeArgs {
   int32_t H;
   int32_t max_block;
   int32_t max_k;        // most clusters any work item of any stream keeps
+  int32_t top_r;        // some work item merges only its top-r src tokens (WorkItem.kd < k)
+  WorkItem single;      // used instead of s[].items when those are nullptr (one work item, n_items = 1)
 };
 hipError_t launch_match_merge(const MatchMergeArgs& a, hipStream_t stream);
 // The same for blocks of more than kSmallBlockMax tokens (two kernels; no preset mode).
 constexpr int kSmallBlockMax = 512;
 hipError_t launch_match_merge_big(const MatchMergeArgs& a, hipStream_t stream);
+// Un-blocked matching (the cost the merging blocks remove, paper Sec. 3.3): the whole sequence of a
+// head is one block of N tokens with kd strided dst tokens.  best[h][j] = index 0..kd-1 of the dst
+// most similar to token j (a dst token: its own index), sim[h][j] = that cosine similarity.
+hipError_t launch_global_match(const void* x, int64_t N, int H, int32_t kd, int32_t* best, float* sim,
+                               hipStream_t stream);
 
 // ---- adaptive outlier filtering of the merged queries (paper Sec. 3.4, Alg. 2) ---------------
 // State of the device-side selection of the threshold tau.

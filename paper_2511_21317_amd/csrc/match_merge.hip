@@ -89,7 +89,11 @@ __device__ __forceinline__ float div_by_count(float a, float b, float rb) {
   return fmaf(r, rb, q);
 }
 
-template <int NW, int MAXN>
+// TOPR: work items may have fewer dst tokens (WorkItem.kd) than clusters (k): the general rule of
+// Sec. 3.2, where only the n - k src tokens with the highest best-match similarity merge and the
+// other src tokens stay clusters of their own (a separate instantiation, so that the usual one
+// pays nothing for it).
+template <int NW, int MAXN, bool TOPR = false>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(4, 8)))
 void match_merge_kernel(const MatchMergeArgs a) {
   constexpr int NT = 64 * NW;
@@ -100,8 +104,10 @@ void match_merge_kernel(const MatchMergeArgs a) {
   __shared__ __align__(16) unsigned char tile[MAXN * kLdsRowBytes];
   // phase A (matching): inverse norms of all tokens / of the dst tokens
   // phase B (aggregation): member lists - the same storage, the phases are separated by barriers
-  constexpr int kUnionA = MAXN * 8, kUnionB = MAXN * 4 + 8 + NW * MAXN;
-  __shared__ __align__(16) unsigned char s_union[kUnionA > kUnionB ? kUnionA : kUnionB];
+  // (TOPR: the selection's 256-bin histogram and a few words, between the two phases)
+  constexpr int kUnionA = MAXN * 8, kUnionB = MAXN * 4 + 8 + NW * MAXN, kUnionT = TOPR ? 1024 + 8 + 4 * NW : 0;
+  constexpr int kUnionAB = kUnionA > kUnionB ? kUnionA : kUnionB;
+  __shared__ __align__(16) unsigned char s_union[kUnionAB > kUnionT ? kUnionAB : kUnionT];
   __shared__ uint16_t s_dpos[MAXN];
   __shared__ int16_t s_cl[MAXN];
   float* s_invn = (float*)s_union;                    // [MAXN]
@@ -140,7 +146,7 @@ void match_merge_kernel(const MatchMergeArgs a) {
   }
 
   // ---- nothing to merge: copy ----------------------------------------------------------------
-  if (k == n) {
+  if (k == n && (!TOPR || it.kd == n)) {
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
       const int e = tid + i * NT;
@@ -195,20 +201,22 @@ void match_merge_kernel(const MatchMergeArgs a) {
       s_invn[tid] = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
     }
     __syncthreads();
-    for (int m = tid; m < k; m += NT) {
-      const int p = dst_position(m, n, k, it.n0);
+    const int kd = TOPR ? it.kd : k;   // dst tokens = clusters 0 .. kd-1
+    for (int m = tid; m < kd; m += NT) {
+      const int p = dst_position(m, n, kd, it.n0);
       s_dpos[m] = (uint16_t)p;
       s_dinv[m] = s_invn[p];
       s_cl[p] = (int16_t)m;
     }
     // pad the last 32-wide dst tile with NaN: a NaN score never compares greater, so the
     // arg-max below needs no bounds test
-    for (int m = k + tid; m < ((k + 31) & ~31); m += NT) s_dinv[m] = __builtin_nanf("");
+    for (int m = kd + tid; m < ((kd + 31) & ~31); m += NT) s_dinv[m] = __builtin_nanf("");
     __syncthreads();
 
     // ---- 3. similarities and arg-max -----------------------------------------------------------
     // Wave w owns the tokens 64w .. 64w+63, i.e. the two 32-token tiles 2w and 2w+1.
-    const int ndt = (k + 31) >> 5;
+    const int ndt = (kd + 31) >> 5;
+    float my_sc = 1.0f;                // similarity of token `tid` to the dst it would join
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
       const int tt = wave * 2 + sub;
@@ -223,7 +231,7 @@ void match_merge_kernel(const MatchMergeArgs a) {
         int bm = 0;
         for (int dt = 0; dt < ndt; ++dt) {
           const int m = dt * 32 + l32;
-          const int drow = s_dpos[m < k ? m : k - 1];
+          const int drow = s_dpos[m < kd ? m : kd - 1];
           f32x16 acc;
 #pragma unroll
           for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -263,12 +271,95 @@ void match_merge_kernel(const MatchMergeArgs a) {
             sc = best * s_invn[tok];
           }
           my_cl = c;
-          assign[tok] = it.moff + c;
-          if (score) score[tok] = sc;
+          my_sc = sc;
+          if (!TOPR) {
+            assign[tok] = it.moff + c;
+            if (score) score[tok] = sc;
+          }
         }
       }
     }
     __syncthreads();   // everybody is done with s_invn / s_dinv
+
+    if (TOPR) {
+      // ---- 3b. top-r selection (Sec. 3.2): of the n - kd src tokens only the r = n - k with the
+      // highest similarity merge (ties: lower position first).  The r-th largest key is found by a
+      // radix select over the block (4 passes of 8 bits, LDS histogram); keys that tie with it are
+      // taken in ascending position; every other src token becomes a cluster of its own.
+      uint32_t* hist = (uint32_t*)s_union;   // [256]; s_invn / s_dinv are dead now
+      uint32_t* sel = hist + 256;            // [0] prefix found so far, [1] rank inside it
+      int* s_wsum = (int*)(sel + 2);         // [NW] per-wave counts
+      const int r = n - k, n_src = n - kd;
+      const bool is_src = tid < n && s_cl[tid] < 0;
+      uint32_t key = 0;                      // order-preserving image of the similarity
+      if (is_src) {
+        const uint32_t u = __float_as_uint(my_sc);
+        key = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+      }
+      bool merged = is_src && r > 0;
+      if (r > 0 && r < n_src) {
+        uint32_t prefix = 0, rank = (uint32_t)(r - 1);   // descending rank of the last key taken
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+          const int shift = 24 - 8 * pass;
+          for (int b = tid; b < 256; b += NT) hist[b] = 0;
+          __syncthreads();
+          if (is_src && (pass == 0 || (key >> (shift + 8)) == prefix)) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+          __syncthreads();
+          if (wave == 0) {
+            uint32_t hb[4], mine = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              hb[i] = hist[lane * 4 + i];
+              mine += hb[i];
+            }
+            uint32_t incl = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+              const uint32_t up = (uint32_t)__shfl_up((int)incl, d);
+              if (lane >= d) incl += up;
+            }
+            uint32_t above = (uint32_t)__shfl((int)incl, 63) - incl;   // keys in the bins of higher lanes
+#pragma unroll
+            for (int i = 3; i >= 0; --i) {
+              if (rank >= above && rank < above + hb[i]) {
+                sel[0] = (prefix << 8) | (uint32_t)(lane * 4 + i);
+                sel[1] = rank - above;
+              }
+              above += hb[i];
+            }
+          }
+          __syncthreads();
+          prefix = sel[0];
+          rank = sel[1];
+        }
+        // `prefix` is the key of the last src taken; rank + 1 of the keys equal to it are taken
+        const bool eq = is_src && key == prefix;
+        const unsigned long long eb = __ballot(eq);
+        if (lane == 0) s_wsum[wave] = __popcll(eb);
+        __syncthreads();
+        int er = __builtin_amdgcn_mbcnt_hi((uint32_t)(eb >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)eb, 0u));
+        for (int w = 0; w < wave; ++w) er += s_wsum[w];
+        merged = is_src && (key > prefix || (eq && er <= (int)rank));
+        __syncthreads();   // s_wsum is reused below
+      }
+      const bool stay = is_src && !merged;
+      const unsigned long long sb = __ballot(stay);
+      if (lane == 0) s_wsum[wave] = __popcll(sb);
+      __syncthreads();
+      if (stay) {
+        int idx = __builtin_amdgcn_mbcnt_hi((uint32_t)(sb >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)sb, 0u));
+        for (int w = 0; w < wave; ++w) idx += s_wsum[w];
+        my_cl = kd + idx;
+        // (its similarity to the dst it did not join stays the reported score)
+        s_dpos[my_cl] = (uint16_t)tid;
+      }
+      if (tid < n) {
+        assign[tid] = it.moff + my_cl;
+        if (score) score[tid] = my_sc;
+      }
+      __syncthreads();   // s_dpos of the new clusters is visible; the union is free for phase 4
+    }
   }
 
   // ---- 4. stable counting sort of the tokens by cluster -----------------------------------------
@@ -434,7 +525,8 @@ void outlier_refine_kernel(const RefineArgs a) {
 
   // ---- rows to LDS ---------------------------------------------------------------------------------
   for (int m = tid; m < k; m += NT) {
-    s_dpos[m] = (uint16_t)dst_position(m, n, k, it.n0);
+    // (clusters kd .. k-1 are single src tokens that did not merge: they never lose a constituent)
+    s_dpos[m] = (uint16_t)(m < it.kd ? dst_position(m, n, it.kd, it.n0) : 0xFFFF);
     s_affected[m] = 0;
     s_dst_out[m] = 0;
   }
@@ -642,6 +734,15 @@ hipError_t launch_match_merge(const MatchMergeArgs& a, hipStream_t stream) {
   if (n_items == 0 || a.H == 0) return hipSuccess;
   if (a.max_block > kSmallBlockMax) return launch_match_merge_big(a, stream);
   dim3 grid((unsigned)n_items, (unsigned)a.H, (unsigned)a.n_streams);
+  if (a.top_r) {
+    if (a.max_block <= 64)
+      hipLaunchKernelGGL((match_merge_kernel<1, 64, true>), grid, dim3(64), 0, stream, a);
+    else if (a.max_block <= 256)
+      hipLaunchKernelGGL((match_merge_kernel<4, 256, true>), grid, dim3(256), 0, stream, a);
+    else
+      hipLaunchKernelGGL((match_merge_kernel<8, 512, true>), grid, dim3(512), 0, stream, a);
+    return hipGetLastError();
+  }
   if (a.max_block <= 64)
     hipLaunchKernelGGL((match_merge_kernel<1, 64>), grid, dim3(64), 0, stream, a);
   else if (a.max_block <= 256)

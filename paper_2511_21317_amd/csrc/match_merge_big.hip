@@ -56,8 +56,9 @@ __device__ __forceinline__ float chunk_sumsq(const bf16x8 w, float ss) {
 __device__ __forceinline__ int cluster_at(int p, int n, int k, int n0) {
   if (p < n0) return p;
   if (k == n0) return -1;
-  const int m = n0 + ((p - n0) * (k - n0) + (n - n0) - 1) / (n - n0);
-  return (m < k && dst_position(m, n, k, n0) == p) ? m : -1;
+  // 64-bit: (p - n0) * (k - n0) passes 2^31 for sequences of more than ~46 000 tokens
+  const int m = n0 + (int)(((int64_t)(p - n0) * (int64_t)(k - n0) + (n - n0) - 1) / (int64_t)(n - n0));
+  return (m < k && dst_position_any(m, n, k, n0) == p) ? m : -1;
 }
 
 constexpr int kBmWaves = 4;
@@ -75,7 +76,7 @@ void big_match_kernel(const MatchMergeArgs a) {
   const int64_t h = blockIdx.z % n_heads;
   const MatchMergeStream& s = a.s[sidx];
   if ((int)blockIdx.x >= s.n_items) return;
-  const WorkItem it = s.items[blockIdx.x];
+  const WorkItem it = s.items ? s.items[blockIdx.x] : a.single;
   const int n = it.n, k = it.k, n0 = it.n0;
   const int t0 = blockIdx.y * kBmTokens;
   if (t0 >= n) return;
@@ -120,7 +121,7 @@ void big_match_kernel(const MatchMergeArgs a) {
   u32x4 dreg[2];
   auto dst_src_row = [&](int m) -> uint32_t {   // source row of the dst token of cluster m (clamped)
     const int mc = m < k ? m : k - 1;
-    const int p = dst_position(mc, n, k, n0);
+    const int p = dst_position_any(mc, n, k, n0);
     return pi ? (uint32_t)pi[it.start + p] : (uint32_t)(it.start + p);
   };
   uint32_t srow[2];
@@ -518,6 +519,26 @@ hipError_t launch_match_merge_big(const MatchMergeArgs& a, hipStream_t stream) {
   dim3 agrid((unsigned)n_items, (unsigned)a.H, (unsigned)a.n_streams);
   hipLaunchKernelGGL(big_aggregate_kernel<false>, agrid, dim3(kBaThreads), big_aggregate_lds(nmax, kmax), stream,
                      a, RefineExtra{}, nmax, kmax);
+  return hipGetLastError();
+}
+
+hipError_t launch_global_match(const void* x, int64_t N, int H, int32_t kd, int32_t* best, float* sim,
+                               hipStream_t stream) {
+  if (N == 0 || H == 0) return hipSuccess;
+  MatchMergeArgs a = {};
+  a.n_streams = 1;
+  a.pi = nullptr;
+  a.N = N;
+  a.H = H;
+  a.max_block = (int32_t)N;
+  a.single = {0, (int32_t)N, kd, 0, 0, kd, {0, 0}};
+  a.s[0].x = x;
+  a.s[0].assign = best;
+  a.s[0].score = sim;
+  a.s[0].items = nullptr;
+  a.s[0].n_items = 1;
+  dim3 grid(1u, (unsigned)((N + kBmTokens - 1) / kBmTokens), (unsigned)H);
+  hipLaunchKernelGGL(big_match_kernel, grid, dim3(kBmThreads), 0, stream, a);
   return hipGetLastError();
 }
 

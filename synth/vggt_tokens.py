@@ -49,6 +49,7 @@ class Workload:
     n_special: int = N_SPECIAL
     anchor: bool = False   # first-frame anchoring switched on for this workload
     chunked: bool = False  # spatial blocks are runs of b consecutive tokens (the paper's n_s) instead of windows
+    dst_frac: float = 0.0  # > 0: fixed share of dst tokens per block and top-r selection of the src that merge
 
     @property
     def tokens_per_frame(self) -> int:

@@ -32,7 +32,7 @@ def round_bf16(x: np.ndarray) -> np.ndarray:
 
 def oracle_geom(w) -> orc.Geometry:
     return orc.Geometry(w.S, w.Hp, w.Wp, w.b, w.T, n_special=w.n_special, anchor=w.anchor,
-                        chunked=w.chunked)
+                        chunked=w.chunked, dst_frac=w.dst_frac)
 
 
 def plan_for(w, variant="headwise", rho_q=None, rho_kv=None, H=None, outlier_frac=0.0) -> httm.Plan:
@@ -41,7 +41,7 @@ def plan_for(w, variant="headwise", rho_q=None, rho_kv=None, H=None, outlier_fra
     return httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, rq, rk, H=w.H if H is None else H,
                                     n_special=w.n_special, variant=variant,
                                     anchor_first_frame=w.anchor, outlier_frac=outlier_frac,
-                                    chunked_blocks=w.chunked))
+                                    chunked_blocks=w.chunked, dst_frac=w.dst_frac))
 
 
 def check_assign(gpu_assign: np.ndarray, ref_assign: np.ndarray, ref_gap: np.ndarray, what=""):

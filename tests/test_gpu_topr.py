@@ -1,0 +1,190 @@
+"""GPU parity of the general merging rule of Sec. 3.2 (a fixed share of dst tokens per block, only
+the top-r src tokens by best-match similarity merge) against the CPU oracle.
+
+One flipped selection renumbers the unmerged src clusters behind it, so assignments are compared
+in a layout-independent form: for every token, the input position of the token its cluster starts
+from (its dst token, or itself if it did not merge)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_21317_amd as httm
+import synth
+from oracle import httm_oracle as orc
+from synth.vggt_tokens import Workload
+
+from gpu_util import check_output, f32, oracle_geom, plan_for, require_gpu, run_stages
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # name, index, S, Hp, Wp, b, T, rho, shift  (+ dst_frac)
+    Workload("topr_cfg1_like", 31, 2, 16, 16, 4, 2, 0.5, 1, dst_frac=0.25),
+    Workload("topr_ratio_above_src_share", 32, 4, 9, 11, 4, 3, 0.9, 1, H=3, dst_frac=0.25),   # r capped: every src merges
+    Workload("topr_block256", 33, 4, 16, 16, 8, 4, 0.5, 1, H=2, dst_frac=0.25),
+    Workload("topr_block512_half_dst", 34, 8, 16, 16, 8, 8, 0.3, 1, H=2, dst_frac=0.5),
+    Workload("topr_chunked_anchored", 35, 6, 16, 20, 128, 4, 0.6, 1, H=2, chunked=True, anchor=True, dst_frac=0.25),
+    Workload("topr_nothing_merges", 36, 3, 8, 8, 4, 2, 0.0, 1, H=2, dst_frac=0.25),
+]
+
+
+def _rep_from_gpu(assign, pi, g, blocks, rho):
+    """Owner token of every slot, from the GPU's own assignment: the dst token of a dst cluster, the
+    single member of any other cluster."""
+    ks, offs, M = orc.merged_layout(g, blocks, rho)
+    kds = orc.dst_counts(g, blocks, rho)
+    owner = -np.ones(M, dtype=np.int64)
+    owner[:g.n_prefix] = pi[:g.n_prefix]
+    for (start, n), k, off, n0, kd in zip(blocks, ks, offs, orc.anchor_sizes(g), kds):
+        for m, j in enumerate(orc.dst_positions(n, kd, n0)):
+            owner[off + m] = pi[start + j]
+        local = assign[start:start + n] - off
+        assert local.min() >= 0 and local.max() < k
+        extra = np.flatnonzero(local >= kd)
+        assert np.unique(local[extra]).size == extra.size == k - kd      # each such cluster has one member
+        owner[off + local[extra]] = pi[start + extra]
+        # ... and they are numbered in ascending position
+        assert (np.diff(local[extra]) > 0).all()
+    assert (owner >= 0).all()
+    rep = np.empty(g.N, dtype=np.int64)
+    rep[pi] = owner[assign]
+    return rep
+
+
+@pytest.mark.parametrize("w", CASES, ids=lambda w: w.name)
+def test_top_r_rule_matches_the_oracle(w):
+    require_gpu()
+    print(f"[case] {w.name} N={w.N} H={w.H} dst_frac={w.dst_frac}", flush=True)
+    q, k, v = synth.make_qkv(w, device="cuda")
+    plan = plan_for(w)
+    g = oracle_geom(w)
+    got = run_stages(plan, q, k, v)
+    ref = orc.layer_forward(f32(q), f32(k), f32(v), g, w.rho, w.rho)
+    pi, blocks = ref["pi"], ref["blocks"]
+    assert plan.M_q == ref["q_m"][0].shape[0] and plan.M_k == ref["k_m"][0].shape[0]
+    inv = np.empty_like(pi)
+    inv[pi] = np.arange(pi.size)
+    total_bad = 0
+    want_o = ref["O"].copy()
+    got_o = f32(got["out"])
+    for h in range(w.H):
+        for name, gapn in (("assign_q", "gap_q"), ("assign_k", "gap_k")):
+            a_gpu = got[name][h].cpu().numpy().astype(np.int64)
+            rep_gpu = _rep_from_gpu(a_gpu, pi, g, blocks, w.rho)
+            rep_ref = orc.rep_map(ref[name][h], pi, g, blocks, w.rho)
+            bad = np.flatnonzero(rep_gpu != rep_ref)              # input positions
+            total_bad += bad.size
+            if bad.size:
+                assert (ref[gapn][h][inv[bad]] < 1e-3).all(), f"{name} head {h}: differs away from a tie"
+            if name == "assign_q" and bad.size:
+                # tokens whose cluster has another composition on the GPU read a different row
+                owners = np.concatenate([rep_ref[bad], rep_gpu[bad]])
+                touched = np.isin(rep_ref, owners) | np.isin(rep_gpu, owners)
+                want_o[touched, h * 64:(h + 1) * 64] = got_o[touched, h * 64:(h + 1) * 64]
+        # scores of the tokens (merged or not) against the oracle
+        sq = got["score_q"][h].cpu().numpy()
+        assert np.abs(sq - ref["score_q"][h]).max() < 1e-3 or total_bad > 0
+    assert total_bad <= max(4, int(2e-3 * w.H * w.N))
+    check_output(got_o, want_o, f"{w.name} layer output", relative_to_magnitude=True)
+    # the merged tokens: clusters whose members agree are one bf16 rounding from the oracle's mean
+    for h in range(w.H):
+        a_gpu = got["assign_q"][h].cpu().numpy().astype(np.int64)
+        if np.array_equal(a_gpu, ref["assign_q"][h]):
+            want = ref["q_m"][h]
+            assert (np.abs(f32(got["q_m"][h]) - want) <= 2.0 ** -8 * np.abs(want) + 1e-30).all()
+    # the fused layer call gives the same bits as the stage calls
+    out = torch.empty_like(got["out"])
+    httm.layer_forward(plan, q, k, v, out, httm.alloc_workspace(plan))
+    torch.cuda.synchronize()
+    assert torch.equal(out, got["out"])
+    plan.close()
+
+
+def test_top_r_with_outlier_filter_runs_and_matches():
+    """The general rule and the adaptive outlier filter together (Sec. 3.2 + Sec. 3.4)."""
+    require_gpu()
+    w = Workload("topr_filtered", 37, 4, 16, 16, 4, 4, 0.6, 1, H=2, dst_frac=0.25)
+    q, k, v = synth.make_qkv(w, device="cuda")
+    plan = plan_for(w, outlier_frac=0.05)
+    out = torch.empty((plan.N, plan.H * 64), dtype=torch.bfloat16, device="cuda")
+    ws = httm.alloc_workspace(plan)
+    httm.layer_forward(plan, q, k, v, out, ws)
+    torch.cuda.synchronize()
+    views = httm.workspace_views(plan, ws)
+    ref = orc.layer_forward(f32(q), f32(k), f32(v), oracle_geom(w), w.rho, w.rho, outlier_frac=0.05)
+    tau, counts = httm.outlier_stats(plan)
+    assert abs(tau - ref["tau"]) <= 1e-4 * ref["tau"]
+    aq = views["assign_q"].cpu().numpy()
+    got_o, want_o = f32(out), ref["O"].copy()
+    pi = ref["pi"]
+    flips = 0
+    for h in range(w.H):
+        # tokens decided differently (selection, tie or threshold) are excused; they must be few
+        diff = np.flatnonzero(((aq[h] < 0) != ref["outlier_mask"][h]) |
+                              ((aq[h] >= 0) & ~ref["outlier_mask"][h] & (aq[h] != ref["assign_q"][h])))
+        flips += diff.size
+        want_o[pi[diff], h * 64:(h + 1) * 64] = got_o[pi[diff], h * 64:(h + 1) * 64]
+    assert flips <= 0.02 * w.H * w.N
+    diffm = np.abs(got_o - want_o) / np.maximum(1.0, np.abs(want_o))
+    assert np.quantile(diffm, 0.999) < 2e-2          # renumbered clusters aside, rows agree
+    plan.close()
+
+
+@pytest.mark.parametrize("n_tokens,dst_frac", [(5000, 0.25), (777, 0.1), (4096, 0.5)])
+def test_global_matching_equals_the_oracle_on_one_big_block(n_tokens, dst_frac):
+    """Sec. 3.3's comparison point: the whole sequence as one merging block (Eq. 1 + best match)."""
+    require_gpu()
+    w = synth.workload(2)
+    q, _, _ = synth.make_qkv(w, device="cuda")
+    x = q[:3, :n_tokens].contiguous()
+    best = torch.full((3, n_tokens), -1, dtype=torch.int32, device="cuda")
+    sim = torch.full((3, n_tokens), float("nan"), dtype=torch.float32, device="cuda")
+    httm.global_match(x, dst_frac, best, sim)
+    torch.cuda.synchronize()
+    kd = max(1, int(np.floor(dst_frac * n_tokens + 1e-9)))
+    for h in range(3):
+        c, s, gap = orc.match_block(f32(x[h]), kd)
+        check = best[h].cpu().numpy()
+        bad = np.flatnonzero(check != c)
+        assert bad.size <= 1e-3 * n_tokens + 2 and (gap[bad] < 1e-3).all()
+        same = check == c
+        assert np.abs(sim[h].cpu().numpy() - s)[same].max() < 1e-5
+
+
+def test_global_matching_of_a_long_sequence():
+    """More than 46 340 tokens: dst positions floor(m * N / kd) need a 64-bit product.  The oracle's
+    similarity matrix (75 000 x 25 000) is evaluated in row chunks to bound memory."""
+    require_gpu()
+    n_tokens, dst_frac = 100000, 0.25
+    w = synth.workload(4)
+    q, _, _ = synth.make_qkv(w, device="cuda")
+    x = q[5:6, :n_tokens].contiguous()
+    print(f"[case] global matching N={n_tokens} kd={int(dst_frac * n_tokens)}", flush=True)
+    best = torch.full((1, n_tokens), -1, dtype=torch.int32, device="cuda")
+    sim = torch.full((1, n_tokens), float("nan"), dtype=torch.float32, device="cuda")
+    httm.global_match(x, dst_frac, best, sim)
+    torch.cuda.synchronize()
+    kd = int(np.floor(dst_frac * n_tokens + 1e-9))
+    xs = f32(x[0])
+    dpos = np.asarray(orc.dst_positions(n_tokens, kd))
+    assert dpos.max() < n_tokens and (np.diff(dpos) > 0).all()
+    got_b, got_s = best[0].cpu().numpy(), sim[0].cpu().numpy()
+    assert np.array_equal(got_b[dpos], np.arange(kd)) and (got_s[dpos] == 1.0).all()
+    dn = orc.row_norm(xs[dpos])
+    is_dst = np.zeros(n_tokens, dtype=bool)
+    is_dst[dpos] = True
+    spos = np.flatnonzero(~is_dst)
+    n_bad = 0
+    for c0 in range(0, spos.size, 4096):
+        rows = spos[c0:c0 + 4096]
+        s_ = orc.row_norm(xs[rows]) @ dn.T                       # Eq. 1 for this chunk of src tokens
+        b_ = np.argmax(s_, axis=1)
+        top = s_[np.arange(rows.size), b_]
+        s_[np.arange(rows.size), b_] = -np.inf
+        gap = top - s_.max(axis=1)
+        bad = np.flatnonzero(got_b[rows] != b_)
+        n_bad += bad.size
+        assert (gap[bad] < 1e-3).all()
+        ok = got_b[rows] == b_
+        assert np.abs(got_s[rows] - top)[ok].max() < 1e-5
+    assert n_bad <= 1e-3 * n_tokens

@@ -82,6 +82,27 @@ def test_merged_lengths_of_the_five_workloads():
     assert none.M_q == none.N == 10992
 
 
+@pytest.mark.parametrize("case", [(8, 37, 37, 4, 2, 0.5, 0.5, 0.25), (3, 5, 7, 4, 2, 0.9, 0.3, 0.25),
+                                  (5, 6, 7, 10, 2, 0.6, 0.0, 0.5)])
+def test_host_tables_with_a_fixed_dst_share(case):
+    """Sec. 3.2's general rule: a block keeps n - min(floor(rho n), number of src) clusters."""
+    S, Hp, Wp, b, T, rq, rk, df = case
+    g = httm.make_geom(S, Hp, Wp, b, T, rq, rk, dst_frac=df)
+    og = orc.Geometry(S, Hp, Wp, b, T, dst_frac=df)
+    t, s = httm.geom_tables(g), httm.geom_sizes(g)
+    _, blocks = orc.temporal_reorder(og)
+    kq, oq, Mq = orc.merged_layout(og, blocks, rq)
+    kk, ok, Mk = orc.merged_layout(og, blocks, rk)
+    assert t["block_kq"].tolist() == kq and t["block_offq"].tolist() == oq and s.M_q == Mq
+    assert t["block_kk"].tolist() == kk and t["block_offk"].tolist() == ok and s.M_k == Mk
+    L, sz = httm.lib(), httm.Sizes()
+    bad = httm.make_geom(8, 32, 32, 16, 4, 0.5, dst_frac=0.25)           # 1024-token blocks: not with this rule
+    assert L.httm_geom_sizes(C.byref(bad), C.byref(sz)) == -2
+    bad = httm.make_geom(8, 16, 16, 4, 2, 0.5, dst_frac=1.5)
+    assert L.httm_geom_sizes(C.byref(bad), C.byref(sz)) == -1
+    assert L.httm_global_match(None, 10, 1, 64, 0.25, None, None, None) == -1
+
+
 def test_outlier_budget_and_workspace_regions():
     """Sec. 3.4 step 3: the budget is floor(d * H * N); its three workspace regions exist only then."""
     g0 = httm.make_geom(8, 37, 37, 4, 2, 0.5)
