@@ -377,11 +377,12 @@ int httm_layer_forward(const httm_plan_t* p, const void* q, const void* k, const
     q_off[h] = (int64_t)h * p->sizes.M_q;
     k_off[h] = (int64_t)h * p->sizes.M_k;
   }
-  HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_off, k_off, H, 0.125f, st));
   if (filtered) {
-    // Alg. 1: the outlier queries attend on their own
-    rc = run_attention_outliers(p, q_out, k_m, v_m, o_out, st);
-    if (rc != HTTM_OK) return rc;
+    // Alg. 1: the outlier queries attend on their own - same launch, workgroups appended to the grid
+    HTTM_HIP(launch_attention_both(q_m, k_m, v_m, o_m, q_off, k_off, H, 0.125f, q_out, o_out, p->ob.offsets,
+                                   p->ob.tiles, p->ob.max_tiles, st));
+  } else {
+    HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_off, k_off, H, 0.125f, st));
   }
   // Stage 4 with the inverse reorder fused.
   HTTM_HIP(launch_unmerge(o_m, assign_q, p->d_pi, out, H, p->sizes.N, p->sizes.M_q, 1, st,

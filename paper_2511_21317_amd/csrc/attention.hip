@@ -71,11 +71,15 @@ struct AttnArgs {
   int32_t ragged_head[kAttnMaxHeads];         // head of every partial tile
   int64_t q_off[kAttnMaxHeads + 1];
   int64_t k_off[kAttnMaxHeads + 1];
-  // When set, the query side comes from device memory instead: rows of head h are
+  // When set, a second set of query tiles is described by device memory: rows of head h are
   // [dev_q_off[h], dev_q_off[h+1]) and workgroup t takes tile (head, first row) =
   // (dev_tiles[1+2t], dev_tiles[2+2t]) for t < dev_tiles[0].
+  // Workgroups from dev_first_block on take these tiles; their queries and outputs are q2 / o2.
   const int32_t* dev_q_off;
   const int32_t* dev_tiles;
+  const bf16_t* q2;
+  bf16_t* o2;
+  int32_t dev_first_block;
 };
 
 // position of key row `kv` (0..63) inside a transposed V row in LDS: bits 2 and 3 swapped
@@ -279,10 +283,12 @@ void attention_kernel(const AttnArgs a) {
   int h = 0, q0;
   int64_t q_base_dev = 0;
   int mq_dev = 0;
-  if (a.dev_tiles) {
-    if ((int)blockIdx.x >= a.dev_tiles[0]) return;
-    h = a.dev_tiles[1 + 2 * blockIdx.x];
-    q0 = a.dev_tiles[2 + 2 * blockIdx.x];
+  const bool dev_tile = a.dev_tiles && (int)blockIdx.x >= a.dev_first_block;
+  if (dev_tile) {
+    const int t = (int)blockIdx.x - a.dev_first_block;
+    if (t >= a.dev_tiles[0]) return;
+    h = a.dev_tiles[1 + 2 * t];
+    q0 = a.dev_tiles[2 + 2 * t];
     q_base_dev = a.dev_q_off[h];
     mq_dev = a.dev_q_off[h + 1] - a.dev_q_off[h];
   } else if (idx < a.ragged_per_xcd) {
@@ -296,8 +302,10 @@ void attention_kernel(const AttnArgs a) {
     while (tile >= a.tile_start[h + 1]) ++h;
     q0 = (tile - a.tile_start[h]) * BQ;
   }
-  const int64_t q_base = a.dev_tiles ? q_base_dev : a.q_off[h], k_base = a.k_off[h];
-  const int Mq = a.dev_tiles ? mq_dev : (int)(a.q_off[h + 1] - q_base);
+  const int64_t q_base = dev_tile ? q_base_dev : a.q_off[h], k_base = a.k_off[h];
+  const int Mq = dev_tile ? mq_dev : (int)(a.q_off[h + 1] - q_base);
+  const bf16_t* __restrict__ q_rows = dev_tile ? a.q2 : a.q;
+  bf16_t* __restrict__ o_rows = dev_tile ? a.o2 : a.o;
   const int Mk = (int)(a.k_off[h + 1] - k_base);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -311,7 +319,7 @@ void attention_kernel(const AttnArgs a) {
     // softmax over an empty key set: defined as zero output
     for (int e = tid; e < BQ * kRowChunks; e += NT) {
       const int row = q0 + (e >> 3);
-      if (row < Mq) ((u32x4*)a.o)[(q_base + row) * kRowChunks + (e & 7)] = u32x4{0, 0, 0, 0};
+      if (row < Mq) ((u32x4*)o_rows)[(q_base + row) * kRowChunks + (e & 7)] = u32x4{0, 0, 0, 0};
     }
     return;
   }
@@ -322,7 +330,7 @@ void attention_kernel(const AttnArgs a) {
   for (int qt = 0; qt < QT; ++qt) {
     int row = wq0 + qt * 32 + l32;
     row = row < Mq ? row : Mq - 1;
-    const bf16_t* p = a.q + (q_base + row) * kDHead + half * 8;
+    const bf16_t* p = q_rows + (q_base + row) * kDHead + half * 8;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) w.qf[qt][ks] = *(const bf16x8*)(p + ks * 16);
     w.mc[qt] = 0.f;
@@ -457,7 +465,7 @@ void attention_kernel(const AttnArgs a) {
     const float inv = 1.0f / l_tot;
     const int row = wq0 + qt * 32 + l32;
     if (row < Mq) {
-      bf16_t* orow = a.o + (q_base + row) * kDHead;
+      bf16_t* orow = o_rows + (q_base + row) * kDHead;
 #pragma unroll
       for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
@@ -471,9 +479,10 @@ void attention_kernel(const AttnArgs a) {
   }
 }
 
+// `extra_tiles` workgroups are appended for the device-side tile list (a.dev_tiles), if any.
 template <int QT, int NW>
 hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_off_host, int H,
-                      hipStream_t stream) {
+                      hipStream_t stream, int extra_tiles = 0) {
   constexpr int BQ = 32 * QT * NW;
   int64_t full = 0;
   int ragged = 0;
@@ -495,8 +504,9 @@ hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_o
   a.n_ragged = ragged;
   a.full_per_xcd = (int32_t)((full + 7) / 8);
   a.ragged_per_xcd = (ragged + 7) / 8;
-  if (full + ragged == 0) return hipSuccess;
-  const unsigned grid = 8u * (unsigned)(a.full_per_xcd + a.ragged_per_xcd);
+  if (full + ragged + extra_tiles == 0) return hipSuccess;
+  a.dev_first_block = 8 * (a.full_per_xcd + a.ragged_per_xcd);
+  const unsigned grid = (unsigned)a.dev_first_block + (unsigned)extra_tiles;
   hipLaunchKernelGGL((attention_kernel<QT, NW>), dim3(grid), dim3(64 * NW), 0, stream, a);
   return hipGetLastError();
 }
@@ -529,8 +539,30 @@ hipError_t launch_attention_dev_tiles(const void* q, const void* k, const void* 
   for (int h = 0; h <= kAttnMaxHeads; ++h) a.k_off[h] = k_off_host[h < H ? h : H];
   a.dev_q_off = q_off_dev;
   a.dev_tiles = tiles;
+  a.q2 = a.q;
+  a.o2 = a.o;
+  a.dev_first_block = 0;
   hipLaunchKernelGGL((attention_kernel<2, 4>), dim3((unsigned)max_tiles), dim3(256), 0, stream, a);
   return hipGetLastError();
+}
+
+hipError_t launch_attention_both(const void* q, const void* k, const void* v, void* o,
+                                 const int64_t* q_off_host, const int64_t* k_off_host, int H, float scale,
+                                 const void* q2, void* o2, const int32_t* q2_off_dev, const int32_t* tiles,
+                                 int max_tiles, hipStream_t stream) {
+  AttnArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.q = (const bf16_t*)q;
+  a.k = (const bf16_t*)k;
+  a.v = (const bf16_t*)v;
+  a.o = (bf16_t*)o;
+  a.scale_log2 = scale * 1.4426950408889634f;
+  a.H = H;
+  a.dev_q_off = q2_off_dev;
+  a.dev_tiles = max_tiles > 0 ? tiles : nullptr;
+  a.q2 = (const bf16_t*)q2;
+  a.o2 = (bf16_t*)o2;
+  return launch_cfg<2, 4>(a, q_off_host, k_off_host, H, stream, max_tiles > 0 ? max_tiles : 0);
 }
 
 hipError_t launch_attention(const void* q, const void* k, const void* v, void* o,
@@ -539,6 +571,9 @@ hipError_t launch_attention(const void* q, const void* k, const void* v, void* o
   AttnArgs a;
   a.dev_q_off = nullptr;
   a.dev_tiles = nullptr;
+  a.q2 = nullptr;
+  a.o2 = nullptr;
+  a.dev_first_block = 0;
   a.q = (const bf16_t*)q;
   a.k = (const bf16_t*)k;
   a.v = (const bf16_t*)v;

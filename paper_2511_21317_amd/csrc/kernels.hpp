@@ -110,6 +110,12 @@ hipError_t launch_attention(const void* q, const void* k, const void* v, void* o
 // number per head is only known on the device): q / o rows of head h are
 // [q_off_dev[h], q_off_dev[h+1]); tiles[0] tiles follow in `tiles` as (head, first row) pairs.
 constexpr int kAttnDevTileRows = 256;
+// Both in one launch: the host-described sequences (q, o) and, appended to the grid, the
+// device-described query rows (q2, o2) against the same keys / values.
+hipError_t launch_attention_both(const void* q, const void* k, const void* v, void* o,
+                                 const int64_t* q_off_host, const int64_t* k_off_host, int H, float scale,
+                                 const void* q2, void* o2, const int32_t* q2_off_dev, const int32_t* tiles,
+                                 int max_tiles, hipStream_t stream);
 hipError_t launch_attention_dev_tiles(const void* q, const void* k, const void* v, void* o,
                                       const int32_t* q_off_dev, const int32_t* tiles, int max_tiles,
                                       const int64_t* k_off_host, int H, float scale,
