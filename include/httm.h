@@ -3,9 +3,14 @@
  * layer for AMD MI355X (gfx950).  C ABI.
  *
  * The library computes the hot path of the paper's Algorithm 1 (App. D.1) between the QKV
- * projection and the output projection, without the outlier filter:
+ * projection and the output projection:
  *
  *   temporal reorder -> block-wise matching -> aggregation -> attention -> unmerge -> inverse reorder
+ *
+ * and, switched on through the geometry, the adaptive outlier filtering of the queries (Sec. 3.4,
+ * Alg. 2: httm_geom_t.outlier_frac), first-frame anchoring (App. C.2), the paper's own block shape
+ * (runs of n_s tokens x n_t frames, Sec. 4.1) and the general src/dst rule of Sec. 3.2 with top-r
+ * selection (httm_geom_t.dst_frac).
  *
  * Conventions common to every call
  *   - All tensor pointers are DEVICE pointers unless a parameter says "host".  Tensors are
@@ -15,7 +20,9 @@
  *     httm_plan_destroy).  No other call allocates, frees or synchronises.
  *   - Every compute call is asynchronous on the HIP stream passed as `stream`
  *     (a hipStream_t cast to void*; NULL is the default stream).
- *   - Inputs are never modified.  In-place operation is not supported.
+ *   - Inputs are never modified.  In-place operation is not supported.  A plan with
+ *     outlier_frac > 0 keeps the threshold and the outlier row offsets in its own device memory:
+ *     calls that use such a plan must not overlap in time.
  *   - Return value: 0 (HTTM_OK) on success, a negative HTTM_E_* code otherwise.  Nothing
  *     aborts or throws across this boundary.  Argument checks happen on the host before
  *     any kernel is launched; a call that returns an error has launched nothing.
@@ -30,6 +37,7 @@
  *   A merging block is a b x b window of patches stacked over T consecutive frames, blocks are
  *   ordered (frame group, window row, window col), tokens inside a block (frame, row, col).
  *   Windows at the right/bottom edge and the last frame group may be partial.
+ *   (HTTM_FLAG_CHUNKED_BLOCKS: runs of b consecutive patch tokens of a frame instead of windows.)
  *
  * Merged layout (Sec. 3.2, "Merging", restricted to blocks as in Sec. 3.3 / Alg. 1):
  *   a block of n tokens keeps k = max(1, n - floor(rho*n + 1e-9)) clusters; its dst tokens are
@@ -39,6 +47,8 @@
  *   [ specials, unmerged ] ++ [ the k clusters of block 0 ] ++ [ block 1 ] ...
  *   with length M = S*n_special + sum of k.  Q and K are matched independently per head
  *   (Eq. 2); V follows K's matches.
+ *   (HTTM_FLAG_ANCHOR_FIRST_FRAME and dst_frac > 0 change which tokens are dst and how many
+ *   clusters a block keeps; see there.)
  */
 #ifndef HTTM_H
 #define HTTM_H
