@@ -99,7 +99,7 @@ void big_match_kernel(const MatchMergeArgs a) {
 
   // ---- this wave's 64 tokens as B operands: lane -> token column, 8 channels per k-step ---------
   bf16x8 bx[2][4];
-  float invn[2];
+  float invn[2], bias[2];
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
     const int tok = t0 + wave * 64 + qt * 32 + l32;
@@ -112,7 +112,9 @@ void big_match_kernel(const MatchMergeArgs a) {
       ss = chunk_sumsq(bx[qt][ks], ss);
     }
     ss += __shfl_xor(ss, 32);
-    invn[qt] = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
+    const float nrm = sqrtf(ss);
+    invn[qt] = 1.0f / fmaxf(nrm, 1e-12f);
+    bias[qt] = nrm * 1.001f;   // score + bias >= 0 for every dst: |<x, d>| / ||d|| <= ||x||
   }
 
   // ---- dst tiles: thread (row r0 / r0 + 32, chunk c) moves two 16-byte pieces per tile -----------
@@ -134,8 +136,13 @@ void big_match_kernel(const MatchMergeArgs a) {
     for (int i = 0; i < 2; ++i) srow[i] = dst_src_row(kBmDstTile + r0 + 32 * i);
   }
 
-  float best[2] = {-INFINITY, -INFINITY};
-  int bm[2] = {0, 0};
+  // Running arg-max.  A score s = <x, d> / ||d|| is kept as the key (s + bias) with its four lowest
+  // mantissa bits replaced by 15 - r, r the accumulator register it came from: the keys are
+  // non-negative floats, so a plain float maximum orders them by score and, among scores that agree
+  // to 2^-19, by the lower dst index - two vector instructions per score (fma, and-or) plus the
+  // maximum tree, instead of scale, compare and two selects.
+  float bestk[2] = {-1.0f, -1.0f};
+  int bd0[2] = {0, 0};
   for (int j = 0; j < n_tiles; ++j) {
     const int buf = j & 1;
     // rows of tile j: registers -> LDS, and 1/||d|| from the 8 lanes that share a row
@@ -173,20 +180,22 @@ void big_match_kernel(const MatchMergeArgs a) {
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
           acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad[ks], bx[qt][ks], acc, 0, 0, 0);
-        // acc[r] = <dst d0 + 8*(r/4) + 4*half + r%4, token l32 of tile qt>; NaN-scaled rows (past k)
-        // never compare greater
+        // acc[r] = <dst d0 + 8*(r/4) + 4*half + r%4, token l32 of tile qt>; rows past k have a NaN
+        // scale, and a maximum never returns the NaN operand
+        float stepk = -1.0f;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int mb = step * 32 + 8 * g + 4 * half;
-          const f32x4 dv = *(const f32x4*)(&s_dinv[buf][mb]);
+          const f32x4 dv = *(const f32x4*)(&s_dinv[buf][step * 32 + 8 * g + 4 * half]);
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            const float sc = acc[4 * g + q] * dv[q];
-            if (sc > best[qt]) {
-              best[qt] = sc;
-              bm[qt] = j * kBmDstTile + mb + q;
-            }
+            const uint32_t u = __float_as_uint(fmaf(acc[4 * g + q], dv[q], bias[qt]));
+            stepk = fmaxf(stepk, __uint_as_float((u & ~15u) | (uint32_t)(15 - (4 * g + q))));
           }
+        }
+        // strict comparison of the scores without the index bits: an earlier step keeps a tie
+        if (__uint_as_float(__float_as_uint(stepk) & ~15u) > __uint_as_float(__float_as_uint(bestk[qt]) & ~15u)) {
+          bestk[qt] = stepk;
+          bd0[qt] = d0;
         }
       }
     }
@@ -196,19 +205,22 @@ void big_match_kernel(const MatchMergeArgs a) {
 
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
-    const float ob = __shfl_xor(best[qt], 32);
-    const int om = __shfl_xor(bm[qt], 32);
-    if (ob > best[qt] || (ob == best[qt] && om < bm[qt])) {
-      best[qt] = ob;
-      bm[qt] = om;
+    const int r = 15 - (int)(__float_as_uint(bestk[qt]) & 15u);
+    int bmq = bd0[qt] + 8 * (r >> 2) + 4 * half + (r & 3);
+    float bestq = __uint_as_float(__float_as_uint(bestk[qt]) & ~15u);
+    const float ob = __shfl_xor(bestq, 32);
+    const int om = __shfl_xor(bmq, 32);
+    if (ob > bestq || (ob == bestq && om < bmq)) {
+      bestq = ob;
+      bmq = om;
     }
     const int tok = t0 + wave * 64 + qt * 32 + l32;
     if (half == 0 && tok < n) {
       int c = cluster_at(tok, n, k, n0);
       float sc = 1.0f;
       if (c < 0) {
-        c = bm[qt];
-        sc = best[qt] * invn[qt];
+        c = bmq;
+        sc = (bestq - bias[qt]) * invn[qt];
       }
       assign[tok] = it.moff + c;
       if (score) score[tok] = sc;

@@ -75,8 +75,22 @@ def test_filtered_stages_match_the_oracle(w, frac):
     pi = ref["pi"]
 
     tau_ref = ref["tau"]
-    assert abs(got["tau"] - tau_ref) <= 1e-5 * max(tau_ref, 1e-30), (got["tau"], tau_ref)
     aq_gpu = got["assign_q"].cpu().numpy()
+    # the GPU's clusters before the filter (an outlier's entry no longer shows the cluster it left):
+    # the same stage 2 on a plan without the filter
+    plan0 = plan_for(w)
+    pre = {n_: torch.empty_like(got[n_]) for n_ in ("q_m", "k_m", "v_m", "assign_q", "assign_k")}
+    httm.reorder_match_merge(plan0, q, k, v, pre["q_m"], pre["k_m"], pre["v_m"], pre["assign_q"], pre["assign_k"])
+    torch.cuda.synchronize()
+    a_pre = pre["assign_q"].cpu().numpy()
+    plan0.close()
+    assert all(np.array_equal(a_pre[h][aq_gpu[h] >= 0], aq_gpu[h][aq_gpu[h] >= 0]) for h in range(H))
+    # tau is an order statistic of the deviations: with identical clusters it agrees to rounding; a
+    # token that joined another cluster by an allowed tie changes a few deviations and can move it
+    # by the spacing of neighbouring order statistics
+    n_moved = sum(int((a_pre[h] != ref["assign_q"][h]).sum()) for h in range(H))
+    tau_tol = 1e-5 if n_moved == 0 else 1e-3
+    assert abs(got["tau"] - tau_ref) <= tau_tol * max(tau_ref, 1e-30), (got["tau"], tau_ref, n_moved)
     eps_gpu = got["eps"].cpu().numpy()
     q_out = got["q_out"].cpu().view(torch.int16).numpy()
     qr_bits = [orc.reorder(q[h].cpu().view(torch.int16).numpy(), pi) for h in range(H)]
@@ -98,9 +112,9 @@ def test_filtered_stages_match_the_oracle(w, frac):
         # A token whose cluster differs by an allowed tie changes the mean of the two clusters
         # involved, hence the deviation of all their members: those clusters are left out below.
         a_ref = ref["assign_q"][h]
-        moved = np.flatnonzero(~mask_gpu & (slot_gpu != a_ref))
+        moved = np.flatnonzero(a_pre[h] != a_ref)
         touched = np.zeros(ref["q_m"][h].shape[0], dtype=bool)
-        touched[slot_gpu[moved]] = True
+        touched[a_pre[h][moved]] = True
         touched[a_ref[moved]] = True
         clean = ~touched[a_ref]
         # deviations: fp32 on both sides, different summation order
