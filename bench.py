@@ -105,6 +105,10 @@ def main():
     ap.add_argument("--outlier-frac", type=float, default=0.0,
                     help="time the layer WITH the adaptive outlier filtering of the queries (Sec. 3.4) at "
                          "this share of all query tokens; 0 (default) is the benchmark's configuration")
+    ap.add_argument("--plain-keys", action="store_true",
+                    help="merged keys without the logit scale and the general stage-3 kernel (the default is "
+                         "HTTM_FLAG_LOG2_KEYS: stage 2 folds log2(e)/sqrt(d) into the merged keys, stage 3 skips "
+                         "the multiplication per score)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -125,11 +129,15 @@ def main():
     torch.cuda.synchronize()
 
     filtered = args.outlier_frac > 0.0
+    LK = not args.plain_keys
+
+    def mk_geom(*a, **kw):
+        return httm.make_geom(*a, log2_keys=LK, **kw)
     if args.paper_blocks:
-        plan = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, 128, 30, 0.9, 0.7, H=w.H, n_special=w.n_special,
+        plan = httm.Plan(mk_geom(w.S, w.Hp, w.Wp, 128, 30, 0.9, 0.7, H=w.H, n_special=w.n_special,
                                         chunked_blocks=True, outlier_frac=args.outlier_frac))
     else:
-        plan = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H, n_special=w.n_special,
+        plan = httm.Plan(mk_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H, n_special=w.n_special,
                                         outlier_frac=args.outlier_frac))
     H, N, Mq, Mk = plan.H, plan.N, plan.M_q, plan.M_k
     out = torch.empty((N, H * 64), dtype=torch.bfloat16, device="cuda")
@@ -170,8 +178,12 @@ def main():
         t_merge = gpu_time_ms(lambda: httm.match_merge(
             plan, qr, kr, vr, views["q_m"], views["k_m"], views["v_m"], views["assign_q"], views["assign_k"]), it)
         del kr, vr
-    t_attn = gpu_time_ms(lambda: httm.attention(views["q_m"], views["k_m"], views["v_m"], views["o_m"],
-                                                q_off, k_off, 0.125), it)
+    if LK:
+        t_attn = gpu_time_ms(lambda: httm.attention_log2(views["q_m"], views["k_m"], views["v_m"], views["o_m"],
+                                                         q_off, k_off), it)
+    else:
+        t_attn = gpu_time_ms(lambda: httm.attention(views["q_m"], views["k_m"], views["v_m"], views["o_m"],
+                                                    q_off, k_off, 0.125), it)
     if filtered:
         t_attn2 = gpu_time_ms(lambda: httm.attention_outliers(plan, views["q_out"], views["k_m"],
                                                               views["v_m"], views["o_out"]), it)
@@ -224,7 +236,7 @@ def main():
     if not args.no_extras and not filtered and not args.paper_blocks:
         del ws, views, out
         torch.cuda.empty_cache()
-        plan_u = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H,
+        plan_u = httm.Plan(mk_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H,
                                           n_special=w.n_special, variant="uniform"))
         out_u = torch.empty((N, H * 64), dtype=torch.bfloat16, device="cuda")
         ws_u = httm.alloc_workspace(plan_u)
@@ -234,7 +246,7 @@ def main():
         plan_u.close()
         del ws_u
         torch.cuda.empty_cache()
-        plan_a = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H, n_special=w.n_special,
+        plan_a = httm.Plan(mk_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H, n_special=w.n_special,
                                           anchor_first_frame=True))
         ws_a = httm.alloc_workspace(plan_a)
         t_anc = gpu_time_ms(lambda: httm.layer_forward(plan_a, q, k, v, out_u, ws_a), max(2, it // 2))
@@ -246,7 +258,7 @@ def main():
         torch.cuda.empty_cache()
         # adaptive outlier filtering of the queries at the paper's setting (Sec. 4.1: 10 % of all
         # query tokens are taken out of the merging again and attend on their own)
-        plan_f = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H, n_special=w.n_special,
+        plan_f = httm.Plan(mk_geom(w.S, w.Hp, w.Wp, w.b, w.T, w.rho, H=w.H, n_special=w.n_special,
                                           outlier_frac=0.1))
         ws_f = httm.alloc_workspace(plan_f)
         t_fil = gpu_time_ms(lambda: httm.layer_forward(plan_f, q, k, v, out_u, ws_f), max(2, it // 2))
@@ -273,7 +285,7 @@ def main():
         # tokens filtered out again as outliers
         for frac_p, tag in ((0.0, "paper_blocks_ns128_nt30_rq0.9_rkv0.7_layer"),
                             (0.1, "paper_configuration_ns128_nt30_rq0.9_rkv0.7_d0.1_layer")):
-            plan_p = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, 128, 30, 0.9, 0.7, H=w.H, n_special=w.n_special,
+            plan_p = httm.Plan(mk_geom(w.S, w.Hp, w.Wp, 128, 30, 0.9, 0.7, H=w.H, n_special=w.n_special,
                                               chunked_blocks=True, outlier_frac=frac_p))
             ws_p = httm.alloc_workspace(plan_p)
             vp = httm.workspace_views(plan_p, ws_p)
@@ -307,7 +319,7 @@ def main():
         log(f"[bench] un-blocked matching of Q (25 % dst): {t_glob:.2f} ms = {t_glob / t_fused_merge:.0f}x the "
             f"block-local matching + merging of Q, K and V")
         del best
-        plan_0 = httm.Plan(httm.make_geom(w.S, w.Hp, w.Wp, w.b, w.T, 0.0, H=w.H,
+        plan_0 = httm.Plan(mk_geom(w.S, w.Hp, w.Wp, w.b, w.T, 0.0, H=w.H,
                                           n_special=w.n_special, variant="none"))
         ws_0 = httm.alloc_workspace(plan_0)
         big = N > 100000
@@ -343,7 +355,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "S": w.S, "grid": [w.Hp, w.Wp], "N": N, "H": H, "d_head": 64,
                    "block": [w.b, w.b, w.T], "rho": w.rho, "M_q": Mq, "M_k": Mk,
-                   "outlier_frac": args.outlier_frac,
+                   "outlier_frac": args.outlier_frac, "log2_keys": LK,
                    "paper_blocks_ns128_nt30_rq0.9_rkv0.7": bool(args.paper_blocks)},
         "roofline": roofline,
         "stages": stages,

@@ -94,6 +94,13 @@ enum {
  * consecutive patch tokens of a frame, in the frame's own (row-major) token order, the last run of a
  * frame partial - instead of a b x b window of the patch grid.  The paper's setting is b = 128, T = 30. */
 #define HTTM_FLAG_CHUNKED_BLOCKS 2
+/* Log2 keys: stage 2 multiplies the fp32 mean of every key cluster by log2(e) / sqrt(d_head) before
+ * its one rounding to bf16, so that q . k' is the logit of Eq. 3 in base-2 units and stage 3 can use
+ * the weights 2^(q . k') without a multiplication per score (httm_attention_log2; the same softmax,
+ * Eq. 3-4).  A key that is a cluster of its own is rounded once where it would otherwise be copied.
+ * With the flag, k_m of the stage-2 calls and of the layer's workspace holds these scaled keys, and
+ * httm_layer_forward / httm_attention_outliers take the faster stage-3 path. */
+#define HTTM_FLAG_LOG2_KEYS 4
 
 #define HTTM_MAX_OUTLIER_FRAC 0.5
 #define HTTM_MAX_BLOCK 4096       /* largest merging block (n_s*n_t tokens) the kernels accept; blocks of more
@@ -230,6 +237,15 @@ HTTM_API int httm_attention(const void* q_m, const void* k_m, const void* v_m, v
                    const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
                    float scale, void* stream);
 
+/* The same attention for keys that carry the logit scale (HTTM_FLAG_LOG2_KEYS):
+ *   o = sum_j 2^(q . k'_j) v_j / sum_j 2^(q . k'_j)      (= Eq. 3-4 for k' = k * log2(e) / sqrt(d_head)).
+ * Arguments and layout as for httm_attention, without `scale`.  Rows whose weights would leave the
+ * fp32 range without a per-row shift are detected and recomputed with one, so the result is defined
+ * for any finite input; the fast path covers row sums between 2^-80 and 2^90. */
+HTTM_API int httm_attention_log2(const void* q_m, const void* k_log2, const void* v_m, void* o_m,
+                                 const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
+                                 void* stream);
+
 /* ---- stage 4: unmerge (Sec. 3.2 Eq. 5-7) and inverse reorder (Sec. 3.3) ------------------ */
 
 /* o_m      : [H, M_q, d_head] bf16, attention output per merged query.
@@ -287,7 +303,8 @@ HTTM_API int httm_reorder_match_merge_filtered(const httm_plan_t* plan, const vo
                                                int32_t* assign_q, int32_t* assign_k, float* eps_q,
                                                void* q_out, void* stream);
 
-/* o_out[r] = softmax(q_out[r] k_m[h]^T / 8) v_m[h] for every outlier row r, h the head it belongs to.
+/* o_out[r] = softmax(q_out[r] k_m[h]^T / 8) v_m[h] for every outlier row r, h the head it belongs to
+ * (k_m as stage 2 of this plan wrote it: scaled keys with HTTM_FLAG_LOG2_KEYS).
  * k_m, v_m: [H, M_k, d_head] bf16; o_out: [outlier_cap, d_head] bf16 out. */
 HTTM_API int httm_attention_outliers(const httm_plan_t* plan, const void* q_out, const void* k_m,
                                      const void* v_m, void* o_out, void* stream);

@@ -67,6 +67,7 @@ def lib() -> C.CDLL:
     L.httm_match_merge.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, i32p, f32p, f32p, vp]
     L.httm_reorder_match_merge.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, i32p, f32p, f32p, vp]
     L.httm_attention.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, C.c_float, vp]
+    L.httm_attention_log2.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, vp]
     L.httm_unmerge.argtypes = [vp, vp, i32p, vp, C.c_int, vp]
     L.httm_layer_forward.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     L.httm_reorder_match_merge_filtered.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, i32p, f32p, vp, vp]
@@ -77,7 +78,7 @@ def lib() -> C.CDLL:
     for name in ("httm_geom_sizes", "httm_workspace_layout", "httm_geom_tables", "httm_plan_create",
                  "httm_plan_destroy", "httm_plan_query", "httm_reorder", "httm_match_merge",
                  "httm_reorder_match_merge",
-                 "httm_attention", "httm_unmerge", "httm_layer_forward",
+                 "httm_attention", "httm_attention_log2", "httm_unmerge", "httm_layer_forward",
                  "httm_reorder_match_merge_filtered", "httm_attention_outliers", "httm_unmerge_filtered",
                  "httm_outlier_stats", "httm_global_match"):
         getattr(L, name).restype = C.c_int
@@ -95,15 +96,18 @@ def _check(rc: int, what: str):
 
 FLAG_ANCHOR_FIRST_FRAME = 1
 FLAG_CHUNKED_BLOCKS = 2
+FLAG_LOG2_KEYS = 4
+LOG2_KEY_SCALE = 0.125 * 1.4426950408889634   # log2(e) / sqrt(64): the factor the scaled keys carry
 
 
 def make_geom(S, Hp, Wp, b, T, rho_q, rho_kv=None, *, H=16, d_head=64, n_special=5,
               variant="headwise", anchor_first_frame=False, outlier_frac=0.0, chunked_blocks=False,
-              dst_frac=0.0) -> Geom:
+              dst_frac=0.0, log2_keys=False) -> Geom:
     if rho_kv is None:
         rho_kv = rho_q
     v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
-    flags = (FLAG_ANCHOR_FIRST_FRAME if anchor_first_frame else 0) | (FLAG_CHUNKED_BLOCKS if chunked_blocks else 0)
+    flags = ((FLAG_ANCHOR_FIRST_FRAME if anchor_first_frame else 0) | (FLAG_CHUNKED_BLOCKS if chunked_blocks else 0)
+             | (FLAG_LOG2_KEYS if log2_keys else 0))
     return Geom(S, Hp, Wp, n_special, H, d_head, b, T, float(rho_q), float(rho_kv), v, flags,
                 float(outlier_frac), float(dst_frac))
 
@@ -182,6 +186,8 @@ class Plan:
     def H(self): return int(self.geom.H)
     @property
     def outlier_cap(self): return int(self.sizes.outlier_cap)
+    @property
+    def log2_keys(self): return bool(self.geom.flags & FLAG_LOG2_KEYS)
 
 
 def reorder(plan: Plan, src: torch.Tensor, dst: torch.Tensor, direction: int = 0):
@@ -221,6 +227,17 @@ def attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, scale: float = 0.125):
     bf = torch.bfloat16
     _check(lib().httm_attention(_dev(q_m, bf), _dev(k_m, bf), _dev(v_m, bf), _dev(o_m, bf), qo, ko,
                                 H, 64, float(scale), _stream()), "httm_attention")
+    return o_m
+
+
+def attention_log2(q_m, k_log2, v_m, o_m, q_offsets, k_offsets):
+    """As attention(), for keys that carry the factor LOG2_KEY_SCALE (a plan with log2_keys)."""
+    H = len(q_offsets) - 1
+    qo = (C.c_int64 * (H + 1))(*[int(x) for x in q_offsets])
+    ko = (C.c_int64 * (H + 1))(*[int(x) for x in k_offsets])
+    bf = torch.bfloat16
+    _check(lib().httm_attention_log2(_dev(q_m, bf), _dev(k_log2, bf), _dev(v_m, bf), _dev(o_m, bf), qo, ko,
+                                     H, 64, _stream()), "httm_attention_log2")
     return o_m
 
 

@@ -71,6 +71,8 @@ int upload(const std::vector<T>& host, T** dev) {
   return HTTM_OK;
 }
 
+bool log2_keys(const httm_plan_t* p) { return (p->geom.flags & HTTM_FLAG_LOG2_KEYS) != 0; }
+
 // Matching + aggregation on `q,k,v`, which are in input order when `pi` is given and in
 // reordered order when it is nullptr.
 int run_match_merge(const httm_plan_t* p, const int32_t* pi, const void* q, const void* k,
@@ -88,9 +90,9 @@ int run_match_merge(const httm_plan_t* p, const int32_t* pi, const void* q, cons
   a.max_k = p->max_k;
   a.top_r = p->geom.dst_frac > 0.0 && p->geom.variant != HTTM_VARIANT_NONE;
   a.s[0] = {q, nullptr, q_m, nullptr, assign_q, score_q, p->d_items_q, p->n_items, p->sizes.M_q,
-            nullptr, nullptr, eps_q};
+            nullptr, nullptr, eps_q, 1.0f};
   a.s[1] = {k, v, k_m, v_m, assign_k, score_k, p->d_items_k, p->n_items, p->sizes.M_k, nullptr,
-            nullptr, nullptr};
+            nullptr, nullptr, log2_keys(p) ? kLog2KeyScale : 1.0f};
   if (g.variant == HTTM_VARIANT_UNIFORM) {
     const int64_t N = p->sizes.N;
     const void* src[2] = {q, k};
@@ -146,7 +148,7 @@ int run_attention_outliers(const httm_plan_t* p, const void* q_out, const void* 
   int64_t k_off[HTTM_MAX_HEADS + 1];
   for (int h = 0; h <= p->geom.H; ++h) k_off[h] = (int64_t)h * p->sizes.M_k;
   HTTM_HIP(launch_attention_dev_tiles(q_out, k_m, v_m, o_out, p->ob.offsets, p->ob.tiles,
-                                      p->ob.max_tiles, k_off, p->geom.H, 0.125f, st));
+                                      p->ob.max_tiles, k_off, p->geom.H, 0.125f, log2_keys(p), st));
   return HTTM_OK;
 }
 
@@ -333,7 +335,26 @@ int httm_attention(const void* q_m, const void* k_m, const void* v_m, void* o_m,
   if (any_q && (!q_m || !o_m)) return HTTM_E_INVALID_ARG;
   if (any_q && any_k && (!k_m || !v_m)) return HTTM_E_INVALID_ARG;
   if (!aligned16(q_m) || !aligned16(k_m) || !aligned16(v_m) || !aligned16(o_m)) return HTTM_E_INVALID_ARG;
-  HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, H, scale, (hipStream_t)stream));
+  HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, H, scale, false, (hipStream_t)stream));
+  return HTTM_OK;
+}
+
+int httm_attention_log2(const void* q_m, const void* k_log2, const void* v_m, void* o_m,
+                        const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
+                        void* stream) {
+  if (!q_offsets || !k_offsets || H <= 0) return HTTM_E_INVALID_ARG;
+  if (d_head != 64 || H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
+  for (int h = 0; h < H; ++h)
+    if (q_offsets[h + 1] < q_offsets[h] || k_offsets[h + 1] < k_offsets[h] ||
+        q_offsets[h + 1] - q_offsets[h] >= ((int64_t)1 << 24) ||
+        k_offsets[h + 1] - k_offsets[h] >= ((int64_t)1 << 24))
+      return HTTM_E_INVALID_ARG;
+  if (q_offsets[0] < 0 || k_offsets[0] < 0) return HTTM_E_INVALID_ARG;
+  const bool any_q = q_offsets[H] > q_offsets[0], any_k = k_offsets[H] > k_offsets[0];
+  if (any_q && (!q_m || !o_m)) return HTTM_E_INVALID_ARG;
+  if (any_q && any_k && (!k_log2 || !v_m)) return HTTM_E_INVALID_ARG;
+  if (!aligned16(q_m) || !aligned16(k_log2) || !aligned16(v_m) || !aligned16(o_m)) return HTTM_E_INVALID_ARG;
+  HTTM_HIP(launch_attention(q_m, k_log2, v_m, o_m, q_offsets, k_offsets, H, 1.0f, true, (hipStream_t)stream));
   return HTTM_OK;
 }
 
@@ -380,9 +401,9 @@ int httm_layer_forward(const httm_plan_t* p, const void* q, const void* k, const
   if (filtered) {
     // Alg. 1: the outlier queries attend on their own - same launch, workgroups appended to the grid
     HTTM_HIP(launch_attention_both(q_m, k_m, v_m, o_m, q_off, k_off, H, 0.125f, q_out, o_out, p->ob.offsets,
-                                   p->ob.tiles, p->ob.max_tiles, st));
+                                   p->ob.tiles, p->ob.max_tiles, log2_keys(p), st));
   } else {
-    HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_off, k_off, H, 0.125f, st));
+    HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_off, k_off, H, 0.125f, log2_keys(p), st));
   }
   // Stage 4 with the inverse reorder fused.
   HTTM_HIP(launch_unmerge(o_m, assign_q, p->d_pi, out, H, p->sizes.N, p->sizes.M_q, 1, st,

@@ -41,6 +41,15 @@
 // below 2^60 (this also catches inf / NaN), the wave redoes that step's softmax with m raised to
 // the step's true maximum and rescales its O and l accumulators - the classic online-softmax
 // update, taken only when needed.
+//
+// Two kernels.  The one described so far (SHIFT = true) takes any keys and any scale.  When stage 2
+// has left the merged keys multiplied by scale * log2(e) ("log2 keys": the factor goes into the
+// fp32 mean before its one rounding to bf16, so nothing is rounded twice), the raw MFMA scores are
+// the base-2 logits, and the fast kernel (SHIFT = false) uses the weights exp2(s) as they are: no
+// fma, no shift - a quarter of the vector work per score gone.  That is safe while a row's sum
+// stays well inside the fp32 range; every workgroup checks its final row sums against
+// [2^-80, 2^90] and, if a row is outside (or inf / NaN), writes a mark instead of its tile.  The
+// SHIFT kernel is launched right behind on the same grid and redoes exactly the marked tiles.
 #include <cstdlib>
 #include <cstring>
 
@@ -61,7 +70,8 @@ struct AttnArgs {
   const bf16_t* k;
   const bf16_t* v;
   bf16_t* o;
-  float scale_log2;  // scale * log2(e)
+  float scale_log2;  // scale * log2(e); 1 when the keys carry that factor already
+  int32_t marked_only;  // the kernel with per-row shifts redoes only the tiles the fast kernel marked
   int32_t H;
   int32_t n_full;                             // tiles with all BQ query rows
   int32_t n_ragged;                           // heads whose last tile is partial
@@ -108,10 +118,12 @@ struct WaveState {
   f32x16 s_cur[QT];      // raw scores of the current step
   u32x4 p_old[QT][2];    // bf16 P^T of the previous step, packed as MFMA B operands
   float mc[QT];          // shift m in log2 units
+  float c;               // factor from raw scores to log2 units (kernel with per-row shifts only)
   float l_run[QT];       // per-lane partial row sums
 };
 
-// exp2(s*c - m), bf16 pack and row sum of one query tile.
+// exp2(s*c - m) (SHIFT) or exp2(s), bf16 pack and row sum of one query tile.
+template <bool SHIFT>
 __device__ __forceinline__ float exp_pack(const f32x16& s, float c, float m, u32x4 (&p)[2]) {
   const bf16x2 ones2 = {(bf16_t)1.0f, (bf16_t)1.0f};
   float ps = 0.f;
@@ -119,8 +131,8 @@ __device__ __forceinline__ float exp_pack(const f32x16& s, float c, float m, u32
   for (int j = 0; j < 2; ++j)
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const float p0 = __builtin_amdgcn_exp2f(fmaf(s[8 * j + 2 * e], c, -m));
-      const float p1 = __builtin_amdgcn_exp2f(fmaf(s[8 * j + 2 * e + 1], c, -m));
+      const float p0 = __builtin_amdgcn_exp2f(SHIFT ? fmaf(s[8 * j + 2 * e], c, -m) : s[8 * j + 2 * e]);
+      const float p1 = __builtin_amdgcn_exp2f(SHIFT ? fmaf(s[8 * j + 2 * e + 1], c, -m) : s[8 * j + 2 * e + 1]);
       const uint32_t w = pack_bf16x2(p0, p1);
       p[j][e] = w;
       ps = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones2, ps, false);
@@ -163,10 +175,10 @@ __device__ __forceinline__ void load_v_operands(StepOperands& op, const bf16_t* 
 //   PRELOADED : `op` already holds this step's operands (otherwise they are read here)
 //   PREFETCH  : after the MFMAs are issued, `op` is refilled from sk_next / svt_next, so that the
 //               LDS latency of the following step hides behind this step's softmax
-template <int QT, bool DO_QK, bool DO_PV, bool DO_SM, bool MASK, bool FIRST, bool PRELOADED = false,
+template <int QT, bool SHIFT, bool DO_QK, bool DO_PV, bool DO_SM, bool MASK, bool FIRST, bool PRELOADED = false,
           bool PREFETCH = false>
 __device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk, const bf16_t* svt,
-                                              float c, int kv_first, int Mk, int l32, int half,
+                                              int kv_first, int Mk, int l32, int half,
                                               StepOperands* opp = nullptr, const bf16_t* sk_next = nullptr,
                                               const bf16_t* svt_next = nullptr) {
   StepOperands local;
@@ -210,21 +222,24 @@ __device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk
     }
     u32x4 p_new[QT][2];
     float psum[QT];
-    if (FIRST) {
+    if (!SHIFT) {
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) psum[qt] = exp_pack<false>(w.s_cur[qt], 1.f, 0.f, p_new[qt]);
+    } else if (FIRST) {
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt) {
         float tmax = w.s_cur[qt][0];
 #pragma unroll
         for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, w.s_cur[qt][r]);
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        w.mc[qt] = tmax * c;
-        psum[qt] = exp_pack(w.s_cur[qt], c, w.mc[qt], p_new[qt]);
+        w.mc[qt] = tmax * w.c;
+        psum[qt] = exp_pack<true>(w.s_cur[qt], w.c, w.mc[qt], p_new[qt]);
       }
     } else {
       bool redo = false;
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt) {
-        psum[qt] = exp_pack(w.s_cur[qt], c, w.mc[qt], p_new[qt]);
+        psum[qt] = exp_pack<true>(w.s_cur[qt], w.c, w.mc[qt], p_new[qt]);
         redo = redo || !(psum[qt] < kSumLimit);
       }
       // rare: raise m to this step's maximum where needed and redo the step's softmax
@@ -235,7 +250,7 @@ __device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk
 #pragma unroll
           for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, w.s_cur[qt][r]);
           tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-          const float rel = fmaf(tmax, c, -w.mc[qt]);  // log2 units above the current m
+          const float rel = fmaf(tmax, w.c, -w.mc[qt]);  // log2 units above the current m
           const float delta = rel > kShiftLimit ? rel : 0.f;
           const float sc = __builtin_amdgcn_exp2f(-delta);
           w.l_run[qt] *= sc;
@@ -244,7 +259,7 @@ __device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk
 #pragma unroll
             for (int r = 0; r < 16; ++r) w.o_acc[dt][qt][r] *= sc;
           w.mc[qt] += delta;
-          psum[qt] = exp_pack(w.s_cur[qt], c, w.mc[qt], p_new[qt]);
+          psum[qt] = exp_pack<true>(w.s_cur[qt], w.c, w.mc[qt], p_new[qt]);
         }
       }
     }
@@ -261,7 +276,18 @@ __device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk
   }
 }
 
-template <int QT, int NW>
+// bf16 bit pattern (a NaN with a payload that arithmetic does not produce) that the fast kernel
+// leaves in channel 0 of a tile's first output row when the tile has to be redone.
+constexpr uint16_t kRedoMark = 0x7FA5;
+// Row sums the fast kernel accepts: below 2^-80 the weights of the row's best keys are close to the
+// bottom of the fp32 range, above 2^90 close to the top (inf and NaN fail the test as well).
+constexpr float kFastSumMin = 8.271806125530277e-25f;   // 2^-80
+constexpr float kFastSumMax = 1.2379400392853803e27f;   // 2^90
+
+// SHIFT = false: the fast kernel (keys carry the logit scale; weights exp2(s)).  SHIFT = true: per-row
+// shifts and the overflow guard; with a.marked_only it is launched right after the fast kernel on
+// the same grid and a workgroup leaves at once unless the fast kernel marked its tile.
+template <int QT, int NW, bool SHIFT>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attention_kernel(const AttnArgs a) {
   constexpr int NT = 64 * NW;
@@ -307,6 +333,8 @@ void attention_kernel(const AttnArgs a) {
   const bf16_t* __restrict__ q_rows = dev_tile ? a.q2 : a.q;
   bf16_t* __restrict__ o_rows = dev_tile ? a.o2 : a.o;
   const int Mk = (int)(a.k_off[h + 1] - k_base);
+  uint16_t* mark = (uint16_t*)(o_rows + (q_base + q0) * kDHead);
+  if (SHIFT && a.marked_only && (Mk == 0 || *(volatile const uint16_t*)mark != kRedoMark)) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
@@ -387,7 +415,7 @@ void attention_kernel(const AttnArgs a) {
     }
   };
 
-  const float c = a.scale_log2;
+  w.c = a.scale_log2;
   const int n_tiles = (Mk + kKvTile - 1) / kKvTile;
 
   // Steps are numbered t = 0 .. 2*n_tiles-1 (32 keys each).  Outer iteration j runs the pipeline
@@ -402,12 +430,12 @@ void attention_kernel(const AttnArgs a) {
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the global->LDS loads have landed
   __syncthreads();
   if (active) {
-    pipeline_step<QT, true, false, false, false, false>(w, &s_k[0][0], nullptr, c, 0, Mk, l32, half);
+    pipeline_step<QT, SHIFT, true, false, false, false, false>(w, &s_k[0][0], nullptr, 0, Mk, l32, half);
     if (n_tiles > 1)
-      pipeline_step<QT, true, false, true, false, true>(w, &s_k[0][kStep * kDHead], nullptr, c, 0,
+      pipeline_step<QT, SHIFT, true, false, true, false, true>(w, &s_k[0][kStep * kDHead], nullptr, 0,
                                                         Mk, l32, half);
     else
-      pipeline_step<QT, true, false, true, true, true>(w, &s_k[0][kStep * kDHead], nullptr, c, 0,
+      pipeline_step<QT, SHIFT, true, false, true, true, true>(w, &s_k[0][kStep * kDHead], nullptr, 0,
                                                        Mk, l32, half);
   }
   store_v(0);
@@ -426,9 +454,9 @@ void attention_kernel(const AttnArgs a) {
     load_k((j + 1) * kKvTile, (j + 1) & 1);
     load_v(j * kKvTile);
     if (active) {
-      pipeline_step<QT, true, true, true, false, false, true, true>(
-          w, nullptr, nullptr, c, 0, Mk, l32, half, &op, kb + kStep * kDHead, vb + kStep);
-      pipeline_step<QT, true, true, true, false, false, true, false>(w, nullptr, nullptr, c, 0, Mk,
+      pipeline_step<QT, SHIFT, true, true, true, false, false, true, true>(
+          w, nullptr, nullptr, 0, Mk, l32, half, &op, kb + kStep * kDHead, vb + kStep);
+      pipeline_step<QT, SHIFT, true, true, true, false, false, true, false>(w, nullptr, nullptr, 0, Mk,
                                                                      l32, half, &op);
     }
     store_v(j & 1);
@@ -442,8 +470,8 @@ void attention_kernel(const AttnArgs a) {
     const bf16_t* kb = &s_k[j & 1][0];
     const bf16_t* vb = &s_vt[(j - 1) & 1][0];
     if (active) {
-      pipeline_step<QT, true, true, true, false, false>(w, kb, vb, c, 0, Mk, l32, half);
-      pipeline_step<QT, true, true, true, true, false>(w, kb + kStep * kDHead, vb + kStep, c,
+      pipeline_step<QT, SHIFT, true, true, true, false, false>(w, kb, vb, 0, Mk, l32, half);
+      pipeline_step<QT, SHIFT, true, true, true, true, false>(w, kb + kStep * kDHead, vb + kStep,
                                                        2 * j * kStep, Mk, l32, half);
     }
     store_v(j & 1);
@@ -453,16 +481,30 @@ void attention_kernel(const AttnArgs a) {
   // ---- j = n_tiles: drain ---------------------------------------------------------------------------
   if (active) {
     const bf16_t* vb = &s_vt[(n_tiles - 1) & 1][0];
-    pipeline_step<QT, false, true, true, true, false>(w, nullptr, vb, c, (2 * n_tiles - 1) * kStep, Mk,
+    pipeline_step<QT, SHIFT, false, true, true, true, false>(w, nullptr, vb, (2 * n_tiles - 1) * kStep, Mk,
                                                       l32, half);
-    pipeline_step<QT, false, true, false, false, false>(w, nullptr, vb + kStep, c, 0, Mk, l32, half);
+    pipeline_step<QT, SHIFT, false, true, false, false, false>(w, nullptr, vb + kStep, 0, Mk, l32, half);
+  }
+
+  float l_tot[QT];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) l_tot[qt] = w.l_run[qt] + __shfl_xor(w.l_run[qt], 32);
+  if (!SHIFT) {
+    // Rare: a row of this tile left the range in which unshifted weights are safe.  The whole
+    // workgroup (its tiles are staged together) leaves the tile to the kernel with per-row shifts.
+    bool bad = false;
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) bad = bad || !(l_tot[qt] >= kFastSumMin && l_tot[qt] <= kFastSumMax);
+    if (__syncthreads_or(active && bad)) {
+      if (tid == 0) *mark = kRedoMark;
+      return;
+    }
   }
 
   // ---- normalise and store ---------------------------------------------------------------------
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
-    const float l_tot = w.l_run[qt] + __shfl_xor(w.l_run[qt], 32);
-    const float inv = 1.0f / l_tot;
+    const float inv = 1.0f / l_tot[qt];
     const int row = wq0 + qt * 32 + l32;
     if (row < Mq) {
       bf16_t* orow = o_rows + (q_base + row) * kDHead;
@@ -480,6 +522,7 @@ void attention_kernel(const AttnArgs a) {
 }
 
 // `extra_tiles` workgroups are appended for the device-side tile list (a.dev_tiles), if any.
+// a.marked_only != 0: the fast kernel, then the kernel with per-row shifts on the marked tiles.
 template <int QT, int NW>
 hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_off_host, int H,
                       hipStream_t stream, int extra_tiles = 0) {
@@ -507,7 +550,9 @@ hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_o
   if (full + ragged + extra_tiles == 0) return hipSuccess;
   a.dev_first_block = 8 * (a.full_per_xcd + a.ragged_per_xcd);
   const unsigned grid = (unsigned)a.dev_first_block + (unsigned)extra_tiles;
-  hipLaunchKernelGGL((attention_kernel<QT, NW>), dim3(grid), dim3(64 * NW), 0, stream, a);
+  if (a.marked_only)
+    hipLaunchKernelGGL((attention_kernel<QT, NW, false>), dim3(grid), dim3(64 * NW), 0, stream, a);
+  hipLaunchKernelGGL((attention_kernel<QT, NW, true>), dim3(grid), dim3(64 * NW), 0, stream, a);
   return hipGetLastError();
 }
 
@@ -524,7 +569,7 @@ int attn_cfg() {
 
 hipError_t launch_attention_dev_tiles(const void* q, const void* k, const void* v, void* o,
                                       const int32_t* q_off_dev, const int32_t* tiles, int max_tiles,
-                                      const int64_t* k_off_host, int H, float scale,
+                                      const int64_t* k_off_host, int H, float scale, bool log2_keys,
                                       hipStream_t stream) {
   static_assert(kAttnDevTileRows == 32 * 2 * 4, "the device tile list is cut for attention_kernel<2, 4>");
   if (max_tiles <= 0) return hipSuccess;
@@ -534,7 +579,8 @@ hipError_t launch_attention_dev_tiles(const void* q, const void* k, const void* 
   a.k = (const bf16_t*)k;
   a.v = (const bf16_t*)v;
   a.o = (bf16_t*)o;
-  a.scale_log2 = scale * 1.4426950408889634f;
+  a.scale_log2 = log2_keys ? 1.0f : scale * 1.4426950408889634f;
+  a.marked_only = log2_keys ? 1 : 0;
   a.H = H;
   for (int h = 0; h <= kAttnMaxHeads; ++h) a.k_off[h] = k_off_host[h < H ? h : H];
   a.dev_q_off = q_off_dev;
@@ -542,21 +588,24 @@ hipError_t launch_attention_dev_tiles(const void* q, const void* k, const void* 
   a.q2 = a.q;
   a.o2 = a.o;
   a.dev_first_block = 0;
-  hipLaunchKernelGGL((attention_kernel<2, 4>), dim3((unsigned)max_tiles), dim3(256), 0, stream, a);
+  if (a.marked_only)
+    hipLaunchKernelGGL((attention_kernel<2, 4, false>), dim3((unsigned)max_tiles), dim3(256), 0, stream, a);
+  hipLaunchKernelGGL((attention_kernel<2, 4, true>), dim3((unsigned)max_tiles), dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
 hipError_t launch_attention_both(const void* q, const void* k, const void* v, void* o,
                                  const int64_t* q_off_host, const int64_t* k_off_host, int H, float scale,
                                  const void* q2, void* o2, const int32_t* q2_off_dev, const int32_t* tiles,
-                                 int max_tiles, hipStream_t stream) {
+                                 int max_tiles, bool log2_keys, hipStream_t stream) {
   AttnArgs a;
   std::memset(&a, 0, sizeof(a));
   a.q = (const bf16_t*)q;
   a.k = (const bf16_t*)k;
   a.v = (const bf16_t*)v;
   a.o = (bf16_t*)o;
-  a.scale_log2 = scale * 1.4426950408889634f;
+  a.scale_log2 = log2_keys ? 1.0f : scale * 1.4426950408889634f;
+  a.marked_only = log2_keys ? 1 : 0;
   a.H = H;
   a.dev_q_off = q2_off_dev;
   a.dev_tiles = max_tiles > 0 ? tiles : nullptr;
@@ -567,7 +616,7 @@ hipError_t launch_attention_both(const void* q, const void* k, const void* v, vo
 
 hipError_t launch_attention(const void* q, const void* k, const void* v, void* o,
                             const int64_t* q_off_host, const int64_t* k_off_host, int H,
-                            float scale, hipStream_t stream) {
+                            float scale, bool log2_keys, hipStream_t stream) {
   AttnArgs a;
   a.dev_q_off = nullptr;
   a.dev_tiles = nullptr;
@@ -578,7 +627,8 @@ hipError_t launch_attention(const void* q, const void* k, const void* v, void* o
   a.k = (const bf16_t*)k;
   a.v = (const bf16_t*)v;
   a.o = (bf16_t*)o;
-  a.scale_log2 = scale * 1.4426950408889634f;
+  a.scale_log2 = log2_keys ? 1.0f : scale * 1.4426950408889634f;
+  a.marked_only = log2_keys ? 1 : 0;
   a.H = H;
   switch (attn_cfg()) {
     case 14: return launch_cfg<1, 4>(a, q_off_host, k_off_host, H, stream);

@@ -13,7 +13,8 @@ int check_geom(const httm_geom_t& g) {
   if (g.variant != HTTM_VARIANT_HEADWISE && g.variant != HTTM_VARIANT_UNIFORM &&
       g.variant != HTTM_VARIANT_NONE)
     return HTTM_E_INVALID_ARG;
-  if (g.flags & ~(HTTM_FLAG_ANCHOR_FIRST_FRAME | HTTM_FLAG_CHUNKED_BLOCKS)) return HTTM_E_INVALID_ARG;
+  if (g.flags & ~(HTTM_FLAG_ANCHOR_FIRST_FRAME | HTTM_FLAG_CHUNKED_BLOCKS | HTTM_FLAG_LOG2_KEYS))
+    return HTTM_E_INVALID_ARG;
   if (!(g.outlier_frac >= 0.0 && g.outlier_frac <= HTTM_MAX_OUTLIER_FRAC)) return HTTM_E_INVALID_ARG;
   if (!(g.dst_frac >= 0.0 && g.dst_frac <= 1.0)) return HTTM_E_INVALID_ARG;
   if (g.d_head != 64 || g.H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;

@@ -27,6 +27,7 @@ struct MatchMergeStream {
   const int32_t* preset;  // [N] cluster slot per reordered token shared by all heads, or nullptr
   const float* preset_score;  // [N] or nullptr
   float* eps;           // [H, N] out or nullptr: L2 distance of every token to its merged token
+  float xm_scale;       // factor on the fp32 means of x before they are rounded to bf16 (1 = plain)
 };
 struct MatchMergeArgs {
   MatchMergeStream s[2];
@@ -103,9 +104,12 @@ hipError_t launch_match_f32(const float* xbar, const int32_t* pi, const WorkItem
 
 // ---- stage 3 -------------------------------------------------------------------------------
 constexpr int kAttnMaxHeads = HTTM_MAX_HEADS;
+// log2_keys: the keys carry the factor scale * log2(e) already (stage 2 with
+// MatchMergeStream.xm_scale), `scale` is ignored and the fast kernel runs first.
+constexpr float kLog2KeyScale = 0.125f * 1.4426950408889634f;   // log2(e) / sqrt(d_head)
 hipError_t launch_attention(const void* q, const void* k, const void* v, void* o,
                             const int64_t* q_off_host, const int64_t* k_off_host, int H,
-                            float scale, hipStream_t stream);
+                            float scale, bool log2_keys, hipStream_t stream);
 // Query rows and tiles are described by device memory (the outlier queries of Sec. 3.4, whose
 // number per head is only known on the device): q / o rows of head h are
 // [q_off_dev[h], q_off_dev[h+1]); tiles[0] tiles follow in `tiles` as (head, first row) pairs.
@@ -115,10 +119,10 @@ constexpr int kAttnDevTileRows = 256;
 hipError_t launch_attention_both(const void* q, const void* k, const void* v, void* o,
                                  const int64_t* q_off_host, const int64_t* k_off_host, int H, float scale,
                                  const void* q2, void* o2, const int32_t* q2_off_dev, const int32_t* tiles,
-                                 int max_tiles, hipStream_t stream);
+                                 int max_tiles, bool log2_keys, hipStream_t stream);
 hipError_t launch_attention_dev_tiles(const void* q, const void* k, const void* v, void* o,
                                       const int32_t* q_off_dev, const int32_t* tiles, int max_tiles,
-                                      const int64_t* k_off_host, int H, float scale,
+                                      const int64_t* k_off_host, int H, float scale, bool log2_keys,
                                       hipStream_t stream);
 
 // ---- stage 4 -------------------------------------------------------------------------------

@@ -89,6 +89,15 @@ __device__ __forceinline__ float div_by_count(float a, float b, float rb) {
   return fmaf(r, rb, q);
 }
 
+// 8 bf16 values times f, rounded to bf16 again.
+__device__ __forceinline__ u32x4 scale_chunk(u32x4 w, float f) {
+  u32x4 o;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    o[q] = pack_bf16x2(__uint_as_float(w[q] << 16) * f, __uint_as_float(w[q] & 0xFFFF0000u) * f);
+  return o;
+}
+
 // TOPR: work items may have fewer dst tokens (WorkItem.kd) than clusters (k): the general rule of
 // Sec. 3.2, where only the n - k src tokens with the highest best-match similarity merge and the
 // other src tokens stay clusters of their own (a separate instantiation, so that the usual one
@@ -151,7 +160,7 @@ void match_merge_kernel(const MatchMergeArgs a) {
     for (int i = 0; i < ITER; ++i) {
       const int e = tid + i * NT;
       if ((e >> 3) < n) {
-        xm[e] = xr[i];
+        xm[e] = s.xm_scale == 1.0f ? xr[i] : scale_chunk(xr[i], s.xm_scale);
         if (v) vm[e] = vr[i];
       }
     }
@@ -435,9 +444,10 @@ void match_merge_kernel(const MatchMergeArgs a) {
       float mean[8];
 #pragma unroll
       for (int q = 0; q < 8; ++q) mean[q] = div_by_count(acc[q], cnt, rcnt);
+      const float f = pass == 0 ? s.xm_scale : 1.0f;   // 1 unless the keys carry the logit scale
       u32x4 o;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(mean[2 * q], mean[2 * q + 1]);
+      for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(mean[2 * q] * f, mean[2 * q + 1] * f);
       out[mc] = o;
       if (s.eps && pass == 0) {
         // Sec. 3.4 step 2: L2 distance of every constituent to the merged token (the fp32 mean);

@@ -428,7 +428,7 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
       acc[2 * q + 1] = __builtin_amdgcn_fdot2_f32_bf16(pr[q], sel.hi, acc[2 * q + 1], false);
     }
   };
-  auto finish = [&](const float (&acc)[8], float cnt, float (&mean)[8]) -> u32x4 {
+  auto finish = [&](const float (&acc)[8], float cnt, float (&mean)[8], float f) -> u32x4 {
     const float rcnt = 1.0f / cnt;
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
@@ -438,7 +438,7 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
     }
     u32x4 o;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(mean[2 * q], mean[2 * q + 1]);
+    for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(mean[2 * q] * f, mean[2 * q + 1] * f);
     return o;
   };
   const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
@@ -473,8 +473,8 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
     }
     const float cnt = (float)(end - beg);
     float mean[8], meanv[8];
-    xm[mc] = finish(acc, cnt, mean);
-    if (v) vm[mc] = finish(accv, cnt, meanv);
+    xm[mc] = finish(acc, cnt, mean, REFINE ? 1.0f : s.xm_scale);
+    if (v) vm[mc] = finish(accv, cnt, meanv, 1.0f);
     if (!REFINE && s.eps) {
       // Sec. 3.4 step 2: L2 distance of every constituent to the fp32 mean; zero if nothing was merged
       float* __restrict__ eps = s.eps + h * N + it.start;

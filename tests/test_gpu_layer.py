@@ -14,7 +14,7 @@ import paper_2511_21317_amd as httm
 import synth
 from oracle import httm_oracle as orc
 
-from gpu_util import (check_assign, check_output, f32, oracle_geom, plan_for, require_gpu, round_bf16,
+from gpu_util import (check_assign, check_output, f32, key_scale, oracle_geom, plan_for, require_gpu, round_bf16,
                       run_layer, run_stages)
 
 pytestmark = pytest.mark.gpu
@@ -54,7 +54,7 @@ def test_layer_forward_matches_oracle_in_full(idx, anchor):
     plan.close()
 
 
-def _sampled_head_check(w, q, k, v, out, views, heads, n_rows, tag, rho_q, rho_kv):
+def _sampled_head_check(w, q, k, v, out, views, heads, n_rows, tag, rho_q, rho_kv, kscale):
     g = oracle_geom(w)
     pi, blocks = orc.temporal_reorder(g)
     rng = np.random.default_rng(w.index)
@@ -69,7 +69,7 @@ def _sampled_head_check(w, q, k, v, out, views, heads, n_rows, tag, rho_q, rho_k
         vm = orc.block_aggregate(vr, ak, g, blocks, rho_kv)
         ok_k = (views["assign_k"][h].cpu().numpy() == ak).all()
         if ok_k:     # no tie mismatch in this head: merged rows are one bf16 rounding from the fp32 mean
-            assert (np.abs(f32(views["k_m"][h]) - km) <= 2.0 ** -8 * np.abs(km) + 1e-30).all()
+            assert (np.abs(f32(views["k_m"][h]) - km * kscale) <= 2.0 ** -8 * np.abs(km * kscale) + 1e-30).all()
             assert (np.abs(f32(views["v_m"][h]) - vm) <= 2.0 ** -8 * np.abs(vm) + 1e-30).all()
         rows = np.sort(rng.choice(qm.shape[0], size=min(n_rows, qm.shape[0]), replace=False))
         om_rows = orc.attention(qm, km, vm, rows=rows)
@@ -93,7 +93,7 @@ def test_layer_forward_full_size_sampled(idx):
     out, views = run_layer(plan, q, k, v)
     assert plan.M_q == {4: 28650, 5: 28700}[idx]
     _sampled_head_check(w, q, k, v, out, views, heads=[0, 11], n_rows=1024, tag=f"cfg{idx}",
-                        rho_q=w.rho, rho_kv=w.rho)
+                        rho_q=w.rho, rho_kv=w.rho, kscale=key_scale(plan))
     # properties that hold at any size: constituents of one merged query share identical output rows
     h = 5
     aq = views["assign_q"][h].long()

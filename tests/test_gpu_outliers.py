@@ -16,7 +16,8 @@ import synth
 from oracle import httm_oracle as orc
 from synth.vggt_tokens import Workload
 
-from gpu_util import check_assign, check_output, f32, oracle_geom, plan_for, require_gpu, round_bf16
+from gpu_util import (check_assign, check_output, f32, merged_attention, oracle_geom, plain_keys, plan_for,
+                      require_gpu, round_bf16)
 
 pytestmark = pytest.mark.gpu
 
@@ -51,8 +52,7 @@ def _run_filtered_stages(plan, q, k, v):
     httm.reorder_match_merge_filtered(plan, q, k, v, q_m, k_m, v_m, aq, ak, eps, q_out)
     tau, counts = httm.outlier_stats(plan)
     o_m = torch.empty_like(q_m)
-    httm.attention(q_m, k_m, v_m, o_m, [h * plan.M_q for h in range(H + 1)],
-                   [h * plan.M_k for h in range(H + 1)], 0.125)
+    merged_attention(plan, q_m, k_m, v_m, o_m)
     o_out = torch.full((cap, 64), float("nan"), dtype=bf, device=dev)
     httm.attention_outliers(plan, q_out, k_m, v_m, o_out)
     out = torch.empty((N, H * 64), dtype=bf, device=dev)
@@ -148,7 +148,7 @@ def test_filtered_stages_match_the_oracle(w, frac):
     for h in range(H):
         rows = rows_seen[h]
         if rows.size:
-            want = orc.attention(f32(got["q_out"])[rows], f32(got["k_m"][h]), f32(got["v_m"][h]))
+            want = orc.attention(f32(got["q_out"])[rows], plain_keys(plan, f32(got["k_m"][h])), f32(got["v_m"][h]))
             check_output(o_out[rows], want, f"{w.name} outlier attention head {h}",
                          relative_to_magnitude=w.index > 5)
     # unmerge: bit-exact copies of o_m / o_out rows at the right places

@@ -8,8 +8,8 @@ import synth
 from oracle import httm_oracle as orc
 from synth.vggt_tokens import Workload
 
-from gpu_util import (check_assign, check_output, excuse_tie_tokens, f32, oracle_geom, plan_for, require_gpu,
-                      round_bf16, run_stages)
+from gpu_util import (check_assign, check_output, excuse_tie_tokens, f32, oracle_geom, plain_keys, plan_for, require_gpu,
+                      round_bf16, run_layer, run_stages)
 
 pytestmark = pytest.mark.gpu
 
@@ -95,14 +95,16 @@ def test_every_stage_matches_the_oracle(w):
             keep = np.ones(g_all[h].shape[0], dtype=bool)
             keep[a_all[h][bad]] = False
             keep[ref[asg][h][bad]] = False
-            want = round_bf16(ref[name][h])
+            # (merged keys: times the plan's factor, in fp32, before the one rounding)
+            mean = ref[name][h] * (got["key_scale"] if name == "k_m" else np.float32(1.0))
+            want = round_bf16(mean)
             exact = (g_all[h] == want).all(axis=1)[keep]
             assert exact.mean() > 0.999, f"{name} head {h}: {1 - exact.mean():.3g} rows differ"
             # never further than one bf16 rounding (half an ulp = 2^-9 relative) from the fp32 mean
-            assert (np.abs(g_all[h] - ref[name][h]) <= 2.0 ** -8 * np.abs(ref[name][h]) + 1e-30)[keep].all()
+            assert (np.abs(g_all[h] - mean) <= 2.0 ** -8 * np.abs(mean) + 1e-30)[keep].all()
     # attention on the GPU's own merged tokens vs the oracle's attention on the same tokens
     for h in range(H):
-        want = orc.attention(f32(got["q_m"][h]), f32(got["k_m"][h]), f32(got["v_m"][h]))
+        want = orc.attention(f32(got["q_m"][h]), plain_keys(plan, f32(got["k_m"][h])), f32(got["v_m"][h]))
         check_output(f32(got["o_m"][h]), want, f"{w.name} attention head {h}", relative_to_magnitude=w.index > 5)
     # unmerge: bit-exact copies of the GPU's o_m rows
     om_bits = got["o_m"].cpu().view(torch.int16).numpy()
@@ -157,7 +159,7 @@ def test_paper_scale_blocks_with_separate_ratios():
         check_assign(got["assign_k"].cpu().numpy()[h], ref["assign_k"][h], ref["gap_k"][h], "paper-scale assign_k")
         for name, asg in (("q_m", "assign_q"), ("k_m", "assign_k"), ("v_m", "assign_k")):
             if np.array_equal(got[asg].cpu().numpy()[h], ref[asg][h]):
-                want = ref[name][h]
+                want = ref[name][h] * (got["key_scale"] if name == "k_m" else np.float32(1.0))
                 assert (np.abs(f32(got[name][h]) - want) <= 2.0 ** -8 * np.abs(want) + 1e-30).all(), name
     got_o = f32(got["out"])
     want_o = excuse_tie_tokens(got_o, ref["O"], got["assign_q"].cpu().numpy().astype(np.int64), ref)
@@ -295,6 +297,133 @@ def test_attention_shift_is_raised_when_later_keys_dominate(where):
     got = f32(om)
     assert np.isfinite(got).all()
     check_output(got, want, f"shift raise ({where})", relative_to_magnitude=True)
+
+
+def _log2_keys(km: torch.Tensor) -> torch.Tensor:
+    """bf16 keys times log2(e)/8, rounded to bf16: what stage 2 hands to httm_attention_log2."""
+    return (km.float() * float(np.float32(httm.LOG2_KEY_SCALE))).to(torch.bfloat16)
+
+
+def _check_log2_attention(qm, k2, vm, qo, ko, what, relative=False):
+    """httm_attention_log2 against the oracle's attention on the keys the kernel was given,
+    their factor divided out again."""
+    om = torch.full_like(qm, float("nan"))
+    httm.attention_log2(qm, k2, vm, om, qo, ko)
+    torch.cuda.synchronize()
+    got = f32(om)
+    assert np.isfinite(got).all(), what
+    for h in range(len(qo) - 1):
+        if qo[h + 1] == qo[h] or ko[h + 1] == ko[h]:
+            continue
+        kk = f32(k2[ko[h]:ko[h + 1]]) / np.float32(httm.LOG2_KEY_SCALE)
+        want = orc.attention(f32(qm[qo[h]:qo[h + 1]]), kk, f32(vm[ko[h]:ko[h + 1]]))
+        check_output(got[qo[h]:qo[h + 1]], want, f"{what} head {h}", relative_to_magnitude=relative)
+    return got
+
+
+@pytest.mark.parametrize("mq,mk", RAGGED + [([700, 1030, 256, 1, 300], [70, 130, 64, 200, 90])])
+def test_log2_key_attention_on_ragged_heads(mq, mk):
+    require_gpu()
+    print(f"[case] ragged log2-key attention mq={mq} mk={mk}", flush=True)
+    gen = torch.Generator().manual_seed(2000 + sum(mq))
+    qo = [int(x) for x in np.concatenate([[0], np.cumsum(mq)])]
+    ko = [int(x) for x in np.concatenate([[0], np.cumsum(mk)])]
+    qm = torch.randn((qo[-1], 64), generator=gen).to(torch.bfloat16).cuda()
+    k2 = _log2_keys(torch.randn((ko[-1], 64), generator=gen)).cuda()
+    vm = torch.randn((ko[-1], 64), generator=gen).to(torch.bfloat16).cuda()
+    om = torch.full_like(qm, float("nan"))
+    httm.attention_log2(qm, k2, vm, om, qo, ko)
+    torch.cuda.synchronize()
+    for h in range(len(mq)):
+        got = f32(om[qo[h]:qo[h + 1]])
+        if mq[h] == 0:
+            continue
+        if mk[h] == 0:
+            assert (got == 0).all()
+            continue
+        kk = f32(k2[ko[h]:ko[h + 1]]) / np.float32(httm.LOG2_KEY_SCALE)
+        want = orc.attention(f32(qm[qo[h]:qo[h + 1]]), kk, f32(vm[ko[h]:ko[h + 1]]))
+        check_output(got, want, f"ragged log2-key head {h} ({mq[h]}x{mk[h]})")
+
+
+@pytest.mark.parametrize("case", ["huge_positive", "huge_negative", "growing", "one_head_of_three", "nan_free_zero_keys"])
+def test_log2_key_attention_leaves_the_unshifted_range(case):
+    """Rows whose sum of 2^(q.k') is not inside [2^-80, 2^90] cannot use unshifted weights: their
+    tiles are marked by the fast kernel and redone with per-row shifts.  The result must match the
+    oracle whichever kernel computed a tile."""
+    require_gpu()
+    gen = torch.Generator().manual_seed(4100)
+    mq, mk = 600, 900
+    q = torch.randn((mq, 64), generator=gen)
+    k = torch.randn((mk, 64), generator=gen)
+    v = torch.randn((mk, 64), generator=gen)
+    qo, ko = [0, mq], [0, mk]
+    if case == "huge_positive":          # logits of several hundred log2 units
+        q, k = q * 6, k * 6
+    elif case == "huge_negative":        # every logit far below zero: the row sums underflow unshifted
+        k = -q[:1].repeat(mk, 1) * 3 + 0.05 * k
+        q = q[:1].repeat(mq, 1) * 4 + 0.05 * q
+    elif case == "growing":
+        k = k * torch.linspace(0.01, 60, mk)[:, None]
+        q = q * 3
+    elif case == "one_head_of_three":    # ordinary heads around a head that leaves the range
+        q = torch.cat([q, q * 8, q])
+        k = torch.cat([k, k * 8, k])
+        v = torch.cat([v, v, v])
+        qo, ko = [0, mq, 2 * mq, 3 * mq], [0, mk, 2 * mk, 3 * mk]
+    else:                                # zero keys: every weight is exactly 1
+        k = torch.zeros_like(k)
+    qm = q.to(torch.bfloat16).cuda()
+    k2 = _log2_keys(k).cuda()
+    vm = v.to(torch.bfloat16).cuda()
+    logits2 = f32(qm[:mq]) @ f32(k2[:mk]).T
+    sums = np.log2(np.exp2(logits2 - logits2.max(axis=1, keepdims=True)).sum(axis=1)) + logits2.max(axis=1)
+    outside = (sums < -80) | (sums > 90)
+    if case in ("huge_positive", "huge_negative", "growing"):
+        assert outside.mean() > 0.5, "the case must actually leave the unshifted range"
+    elif case == "nan_free_zero_keys":
+        assert not outside.any()
+    _check_log2_attention(qm, k2, vm, qo, ko, f"log2 keys ({case})", relative=True)
+
+
+def test_log2_key_attention_rewrites_a_buffer_that_holds_old_marks():
+    """The output buffer of an earlier call, marks included, must not influence the next call."""
+    require_gpu()
+    gen = torch.Generator().manual_seed(4200)
+    mq, mk = 512, 300
+    qm = torch.randn((mq, 64), generator=gen).to(torch.bfloat16).cuda()
+    k2 = _log2_keys(torch.randn((mk, 64), generator=gen)).cuda()
+    vm = torch.randn((mk, 64), generator=gen).to(torch.bfloat16).cuda()
+    om = torch.empty_like(qm)
+    om.view(torch.int16).fill_(0x7FA5)               # every element looks like the redo mark
+    httm.attention_log2(qm, k2, vm, om, [0, mq], [0, mk])
+    torch.cuda.synchronize()
+    kk = f32(k2) / np.float32(httm.LOG2_KEY_SCALE)
+    check_output(f32(om), orc.attention(f32(qm), kk, f32(vm)), "old marks")
+
+
+@pytest.mark.parametrize("w", [synth.workload(1), synth.workload(2)] + ODD[:2], ids=lambda w: w.name)
+def test_plain_key_plans_take_the_general_kernel(w):
+    """Without HTTM_FLAG_LOG2_KEYS the merged keys are the plain means and stage 3 scales in fp32."""
+    require_gpu()
+    q, k, v = _inputs(w)
+    plan = plan_for(w, log2_keys=False)
+    assert not plan.log2_keys
+    got = run_stages(plan, q, k, v)
+    ref = _oracle_stages(w, q, k, v)
+    for h in range(w.H):
+        check_assign(got["assign_k"][h].cpu().numpy(), ref["assign_k"][h], ref["gap_k"][h], f"{w.name} assign_k")
+        if np.array_equal(got["assign_k"][h].cpu().numpy(), ref["assign_k"][h]):
+            assert (f32(got["k_m"][h]) == round_bf16(ref["k_m"][h])).all(axis=1).mean() > 0.999
+        want = orc.attention(f32(got["q_m"][h]), f32(got["k_m"][h]), f32(got["v_m"][h]))
+        check_output(f32(got["o_m"][h]), want, f"{w.name} attention head {h}", relative_to_magnitude=w.index > 5)
+    aq = got["assign_q"].cpu().numpy().astype(np.int64)
+    got_o = f32(got["out"])
+    check_output(got_o, excuse_tie_tokens(got_o, ref["O"], aq, ref), f"{w.name} plain keys, stage by stage",
+                 relative_to_magnitude=w.index > 5)
+    out, _ = run_layer(plan, q, k, v)
+    assert torch.equal(out, got["out"])                   # the layer call = the four stages
+    plan.close()
 
 
 def test_bad_arguments_launch_nothing():

@@ -145,7 +145,7 @@ def test_argument_errors_are_reported_not_crashed():
     bad = httm.make_geom(0, 16, 16, 4, 2, 0.5)
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -1
     bad = httm.make_geom(2, 16, 16, 4, 2, 0.5)
-    bad.flags = 4                                            # a flag bit this library does not know
+    bad.flags = 64                                           # a flag bit this library does not know
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -1
     assert L.httm_geom_sizes(None, C.byref(s)) == -1
     # compute entry points reject null pointers before touching the GPU
