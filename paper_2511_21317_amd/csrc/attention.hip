@@ -21,9 +21,13 @@
 // the very end, and every per-row quantity is a per-lane scalar for the O^T = V^T P^T
 // accumulators as well.  P^T goes from the accumulator registers straight into the B operand of
 // the second MFMA (fp32 -> bf16 in registers, no LDS round trip).  That fixes which 8 keys a lane
-// supplies per MFMA step: {16j + 4*half + 0..3, 16j + 8 + 4*half + 0..3}; V is therefore stored
-// transposed in LDS with key positions 2 and 3 bit-swapped, so that the matching A operand
-// (V^T rows = channels) is one aligned 16-byte read.
+// supplies per MFMA step: {16j + 4*half + 0..3, 16j + 8 + 4*half + 0..3}.  The matching A operand
+// (V^T: a lane's channel, those 8 keys) comes out of the row-major V tile through two transposing
+// LDS reads (ds_read_b64_tr_b16), so V is never transposed in memory or in registers.
+//
+// Both tiles go from global memory straight into LDS (global_load_lds_dwordx4: no registers, no
+// LDS store instructions); every lane fetches the 16-byte chunk that belongs at its position
+// under the tile's swizzle, which keeps the operand reads free of bank conflicts.
 //
 // Software pipeline.  Work is cut into steps of 32 keys.  In step t a wave issues, in one
 // basic block, the QK^T MFMAs of step t+1, the PV MFMAs of step t-1 and the softmax of step t:
@@ -46,7 +50,8 @@
 // has left the merged keys multiplied by scale * log2(e) ("log2 keys": the factor goes into the
 // fp32 mean before its one rounding to bf16, so nothing is rounded twice), the raw MFMA scores are
 // the base-2 logits, and the fast kernel (SHIFT = false) uses the weights exp2(s) as they are: no
-// fma, no shift - a quarter of the vector work per score gone.  That is safe while a row's sum
+// fma, no shift - a quarter of the vector work per score gone - and takes the row sums from the
+// matrix cores as well (row_sum_operand()).  That is safe while a row's sum
 // stays well inside the fp32 range; every workgroup checks its final row sums against
 // [2^-80, 2^90] and, if a row is outside (or inf / NaN), writes a mark instead of its tile.  The
 // SHIFT kernel is launched right behind on the same grid and redoes exactly the marked tiles.
@@ -92,16 +97,10 @@ struct AttnArgs {
   int32_t dev_first_block;
 };
 
-// position of key row `kv` (0..63) inside a transposed V row in LDS: bits 2 and 3 swapped
-__device__ __forceinline__ int vt_pos(int kv) {
-  return (kv & ~0xC) | ((kv & 4) << 1) | ((kv & 8) >> 1);
-}
-// element offset of channel row d of the transposed V tile: 144-byte rows, and every group of 16
-// rows is skewed by another 32 bytes so that the 4-byte transposing stores of a wave (8 channel
-// groups x 8 key pairs) fall into 64 distinct banks; the 16-byte operand reads stay aligned and
-// conflict-free.
-__device__ __forceinline__ int vt_row(int d) { return d * kLdsRowElems + (d >> 4) * 16; }
-constexpr int kVtTileElems = kDHead * kLdsRowElems + (kDHead / 16) * 16;
+// V tile in LDS: 64 rows of 128 bytes, written by global->LDS loads like the K tile; the 16-byte
+// chunk c of row r sits at chunk position c ^ (2 * (r & 3)), so that the four rows a transposing read
+// touches (32 bytes each, same channels) fall into four different 32-byte bank groups.
+__device__ __forceinline__ int v_swizzle(int row) { return (row & 3) << 1; }
 
 __device__ __forceinline__ f32x16 splat16(float x) {
   f32x16 r;
@@ -119,8 +118,23 @@ struct WaveState {
   u32x4 p_old[QT][2];    // bf16 P^T of the previous step, packed as MFMA B operands
   float mc[QT];          // shift m in log2 units
   float c;               // factor from raw scores to log2 units (kernel with per-row shifts only)
-  float l_run[QT];       // per-lane partial row sums
+  float l_run[QT];       // per-lane partial row sums (kernel with per-row shifts)
+  f32x4 l_acc[QT];       // row sums of the fast kernel, from the matrix cores: see row_sum_operand()
+  bf16x8 ones_a;
 };
+
+// Row sums on the matrix cores (fast kernel).  The P^T registers of a lane (query l%32, keys of
+// half l/32) read as the B operand of a 16x16x32 MFMA put query l%32 in column l%16 and its
+// 8 keys in k-group l/16: column n collects query n from k-groups 0 and 2 and query n+16 from
+// k-groups 1 and 3.  An A operand with ones in row 0 over k-groups {0, 2} and in row 1 over {1, 3}
+// therefore gives D[0][n] = sum over the 16 keys of query n and D[1][n] = the same for query n+16:
+// registers 0 and 1 of lanes 0..15.
+__device__ __forceinline__ bf16x8 row_sum_operand(int lane) {
+  const int m = lane & 15, kg = lane >> 4;
+  const bool one = (m == 0 && (kg & 1) == 0) || (m == 1 && (kg & 1) == 1);
+  const uint32_t w = one ? 0x3F803F80u : 0u;
+  return __builtin_bit_cast(bf16x8, u32x4{w, w, w, w});
+}
 
 // exp2(s*c - m) (SHIFT) or exp2(s), bf16 pack and row sum of one query tile.
 template <bool SHIFT>
@@ -135,7 +149,7 @@ __device__ __forceinline__ float exp_pack(const f32x16& s, float c, float m, u32
       const float p1 = __builtin_amdgcn_exp2f(SHIFT ? fmaf(s[8 * j + 2 * e + 1], c, -m) : s[8 * j + 2 * e + 1]);
       const uint32_t w = pack_bf16x2(p0, p1);
       p[j][e] = w;
-      ps = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones2, ps, false);
+      if (SHIFT) ps = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones2, ps, false);
     }
   return ps;
 }
@@ -159,12 +173,30 @@ __device__ __forceinline__ void load_k_operands(StepOperands& op, const bf16_t* 
   for (int ks = 0; ks < 4; ++ks)
     op.ak[ks] = *(const bf16x8*)(sk + l32 * kDHead + ((ks * 2 + half) ^ sw) * 8);
 }
-__device__ __forceinline__ void load_v_operands(StepOperands& op, const bf16_t* svt, int l32, int half) {
+// A operands of O^T += V^T P^T from the row-major V tile: ds_read_b64_tr_b16 hands lane 4a+e of a
+// 16-lane group element e of the 8 bytes that lane 4r+a of the group addressed, as its r-th value.
+// Lane 4r+a addresses key k0+r, channels c0+4a..c0+4a+3, so lane i receives keys k0..k0+3 of channel
+// c0+i - four consecutive keys of one V^T row.  Two reads (k0 = 16j + 4*half and 8 keys further)
+// give the 8 keys a lane's P^T registers hold; the four groups of a wave are (half, 16 channels).
+// `sv` points at the first of the 32 key rows of this step.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ void load_v_operands(StepOperands& op, const bf16_t* sv, int l32, int half) {
+  const int i = l32 & 15, chalf = l32 >> 4;
+  const int krow = 4 * half + (i >> 2);
 #pragma unroll
-  for (int dt = 0; dt < 2; ++dt)
+  for (int dt = 0; dt < 2; ++dt) {
+    const int chunk = (4 * dt + 2 * chalf + ((i & 3) >> 1)) ^ v_swizzle(krow);
+    const bf16_t* base = sv + krow * kDHead + chunk * 8 + 4 * (i & 1);
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      op.av[dt * 2 + j] = *(const bf16x8*)(svt + vt_row(dt * 32 + l32) + j * 16 + half * 8);
+    for (int j = 0; j < 2; ++j) {
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4*)(base + (16 * j) * kDHead));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4*)(base + (16 * j + 8) * kDHead));
+      op.av[dt * 2 + j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+  }
 }
 
 // One pipeline step of a wave.
@@ -203,6 +235,14 @@ __device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk
         for (int qt = 0; qt < QT; ++qt)
           w.o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
               op.av[dt * 2 + j], __builtin_bit_cast(bf16x8, w.p_old[qt][j]), w.o_acc[dt][qt], 0, 0, 0);
+    if (!SHIFT) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt)
+          w.l_acc[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+              w.ones_a, __builtin_bit_cast(bf16x8, w.p_old[qt][j]), w.l_acc[qt], 0, 0, 0);
+    }
   }
   if (PREFETCH) {
     load_k_operands(op, sk_next, l32, half);
@@ -265,7 +305,7 @@ __device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk
     }
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
-      w.l_run[qt] += psum[qt];
+      if (SHIFT) w.l_run[qt] += psum[qt];
 #pragma unroll
       for (int j = 0; j < 2; ++j) w.p_old[qt][j] = p_new[qt][j];
     }
@@ -293,13 +333,11 @@ void attention_kernel(const AttnArgs a) {
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * QT * NW;
   constexpr int LD_ITER = kKvTile * kRowChunks / NT;       // 16-byte K chunks per thread per tile
-  constexpr int LDV_ITER = LD_ITER / 2;                    // V row pairs per thread per tile
-  constexpr int ROWS_PER_PASS = NT / 8;
   static_assert(LD_ITER >= 2 && LD_ITER % 2 == 0, "tile staging needs an even chunk count");
   constexpr int kTileElems = kKvTile * kDHead;
   constexpr int LDK = 8 / NW;                              // 1 KB global->LDS loads per wave per tile
   __shared__ __align__(16) bf16_t s_k[2][kTileElems];    // [kv][d], 128-byte rows, chunk-swizzled
-  __shared__ __align__(16) bf16_t s_vt[2][kVtTileElems]; // [d][kv position], skewed 144-byte rows
+  __shared__ __align__(16) bf16_t s_v[2][kTileElems];    // [kv][d], 128-byte rows, chunk-swizzled
 
   // blockIdx -> (head, first query row).  Workgroups go round-robin to the 8 XCDs, and in
   // blockIdx order to free slots; the partial last tiles of the heads come first (they are
@@ -363,6 +401,7 @@ void attention_kernel(const AttnArgs a) {
     for (int ks = 0; ks < 4; ++ks) w.qf[qt][ks] = *(const bf16x8*)(p + ks * 16);
     w.mc[qt] = 0.f;
     w.l_run[qt] = 0.f;
+    w.l_acc[qt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt) w.o_acc[dt][qt] = splat16(0.f);
   }
@@ -370,8 +409,6 @@ void attention_kernel(const AttnArgs a) {
   // ---- K/V tile staging: global -> registers -> LDS ---------------------------------------------
   const char* kg = (const char*)(a.k + k_base * kDHead);   // wave-uniform bases; per-lane offsets
   const char* vg = (const char*)(a.v + k_base * kDHead);   // below fit 32 bits (rows < 2^24 here)
-  const int ld_c = tid & 7, ld_r = tid >> 3;  // chunk, row-in-pass
-  u32x4 vreg[LD_ITER];
   // K: straight from global memory into LDS, no registers.  Lane l of a wave instruction fills
   // bytes [16 l, 16 l + 16) of a 1 KB block = rows 8*blk .. 8*blk+7; it fetches the chunk that
   // belongs at its position under the swizzle.
@@ -389,33 +426,24 @@ void attention_kernel(const AttnArgs a) {
                                        (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
     }
   };
-  auto load_v = [&](int kv0) {
+  // V the same way, under its own swizzle
+  auto load_v = [&](int kv0, int buf) {
 #pragma unroll
-    for (int i = 0; i < LDV_ITER; ++i)
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        int row = kv0 + 2 * (ld_r + ROWS_PER_PASS * i) + u;
-        row = row < Mk ? row : Mk - 1;
-        vreg[2 * i + u] = *(const u32x4*)(vg + (uint32_t)(row * kRowBytes + ld_c * 16));
-      }
-  };
-  auto store_v = [&](int buf) {
-    // V rows 2r and 2r+1, channels ld_c*8 .. +7  ->  V^T[channel][pos], two keys per 32-bit word
-#pragma unroll
-    for (int i = 0; i < LDV_ITER; ++i) {
-      const int pos = vt_pos(2 * (ld_r + ROWS_PER_PASS * i));
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const uint32_t w0 = vreg[2 * i][e], w1 = vreg[2 * i + 1][e];
-        const uint32_t lo = __builtin_amdgcn_perm(w1, w0, 0x05040100u);  // channel 2e   of both keys
-        const uint32_t hi = __builtin_amdgcn_perm(w1, w0, 0x07060302u);  // channel 2e+1 of both keys
-        *(uint32_t*)(&s_vt[buf][vt_row(ld_c * 8 + 2 * e) + pos]) = lo;
-        *(uint32_t*)(&s_vt[buf][vt_row(ld_c * 8 + 2 * e + 1) + pos]) = hi;
-      }
+    for (int i = 0; i < LDK; ++i) {
+      const int blk = wave * LDK + i;
+      const int r = blk * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ v_swizzle(r);
+      int row = kv0 + r;
+      row = row < Mk ? row : Mk - 1;
+      const char* src = vg + (uint32_t)(row * kRowBytes + c * 16);
+      bf16_t* dst = &s_v[buf][blk * 512];
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
     }
   };
 
   w.c = a.scale_log2;
+  w.ones_a = row_sum_operand(lane);
   const int n_tiles = (Mk + kKvTile - 1) / kKvTile;
 
   // Steps are numbered t = 0 .. 2*n_tiles-1 (32 keys each).  Outer iteration j runs the pipeline
@@ -425,7 +453,7 @@ void attention_kernel(const AttnArgs a) {
 
   // ---- j = 0 ---------------------------------------------------------------------------------------
   load_k(0, 0);
-  load_v(0);
+  load_v(0, 0);
   if (n_tiles > 1) load_k(kKvTile, 1);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the global->LDS loads have landed
   __syncthreads();
@@ -438,7 +466,6 @@ void attention_kernel(const AttnArgs a) {
       pipeline_step<QT, SHIFT, true, false, true, true, true>(w, &s_k[0][kStep * kDHead], nullptr, 0,
                                                        Mk, l32, half);
   }
-  store_v(0);
   __syncthreads();
 
   // ---- j = 1 .. n_tiles-2: steady state, no masking ------------------------------------------------
@@ -446,49 +473,55 @@ void attention_kernel(const AttnArgs a) {
   StepOperands op;
   for (; j < n_tiles - 1; ++j) {
     const bf16_t* kb = &s_k[j & 1][0];
-    const bf16_t* vb = &s_vt[(j - 1) & 1][0];
+    const bf16_t* vb = &s_v[(j - 1) & 1][0];
     if (active) {
       load_k_operands(op, kb, l32, half);
       load_v_operands(op, vb, l32, half);
     }
     load_k((j + 1) * kKvTile, (j + 1) & 1);
-    load_v(j * kKvTile);
+    load_v(j * kKvTile, j & 1);
     if (active) {
       pipeline_step<QT, SHIFT, true, true, true, false, false, true, true>(
-          w, nullptr, nullptr, 0, Mk, l32, half, &op, kb + kStep * kDHead, vb + kStep);
+          w, nullptr, nullptr, 0, Mk, l32, half, &op, kb + kStep * kDHead, vb + kStep * kDHead);
       pipeline_step<QT, SHIFT, true, true, true, false, false, true, false>(w, nullptr, nullptr, 0, Mk,
                                                                      l32, half, &op);
     }
-    store_v(j & 1);
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): K tile j+1 is in LDS
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): K tile j+1 and V tile j are in LDS
     __syncthreads();
   }
 
   // ---- j = n_tiles-1 (if it is not j = 0): the last K tile, its first step may be ragged ---------
   if (j == n_tiles - 1) {
-    load_v(j * kKvTile);
+    load_v(j * kKvTile, j & 1);
     const bf16_t* kb = &s_k[j & 1][0];
-    const bf16_t* vb = &s_vt[(j - 1) & 1][0];
+    const bf16_t* vb = &s_v[(j - 1) & 1][0];
     if (active) {
       pipeline_step<QT, SHIFT, true, true, true, false, false>(w, kb, vb, 0, Mk, l32, half);
-      pipeline_step<QT, SHIFT, true, true, true, true, false>(w, kb + kStep * kDHead, vb + kStep,
+      pipeline_step<QT, SHIFT, true, true, true, true, false>(w, kb + kStep * kDHead, vb + kStep * kDHead,
                                                        2 * j * kStep, Mk, l32, half);
     }
-    store_v(j & 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the last V tile is in LDS
     __syncthreads();
   }
 
   // ---- j = n_tiles: drain ---------------------------------------------------------------------------
   if (active) {
-    const bf16_t* vb = &s_vt[(n_tiles - 1) & 1][0];
+    const bf16_t* vb = &s_v[(n_tiles - 1) & 1][0];
     pipeline_step<QT, SHIFT, false, true, true, true, false>(w, nullptr, vb, (2 * n_tiles - 1) * kStep, Mk,
                                                       l32, half);
-    pipeline_step<QT, SHIFT, false, true, false, false, false>(w, nullptr, vb + kStep, 0, Mk, l32, half);
+    pipeline_step<QT, SHIFT, false, true, false, false, false>(w, nullptr, vb + kStep * kDHead, 0, Mk, l32, half);
   }
 
   float l_tot[QT];
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt) l_tot[qt] = w.l_run[qt] + __shfl_xor(w.l_run[qt], 32);
+  for (int qt = 0; qt < QT; ++qt) {
+    if (SHIFT) {
+      l_tot[qt] = w.l_run[qt] + __shfl_xor(w.l_run[qt], 32);
+    } else {
+      const float s0 = __shfl(w.l_acc[qt][0], l32 & 15), s1 = __shfl(w.l_acc[qt][1], l32 & 15);
+      l_tot[qt] = l32 < 16 ? s0 : s1;
+    }
+  }
   if (!SHIFT) {
     // Rare: a row of this tile left the range in which unshifted weights are safe.  The whole
     // workgroup (its tiles are staged together) leaves the tile to the kernel with per-row shifts.
