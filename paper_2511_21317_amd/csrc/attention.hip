@@ -316,6 +316,72 @@ __device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk
   }
 }
 
+// The steady-state step of the fast kernel with the order of issue written out: one MFMA, then its
+// share of the softmax of the current step (two exp2, one bf16 pack of the pair before), fenced so
+// that the compiler keeps the interleave.  QK^T of step t+1 first (the K operands retire, their
+// successors are requested), then PV of step t-1 with the row sums, then the V operands.
+template <int QT, bool PREFETCH>
+__device__ __forceinline__ void steady_step(WaveState<QT>& w, StepOperands& op, const bf16_t* sk_next,
+                                            const bf16_t* sv_next, int l32, int half) {
+  static_assert(QT == 2, "written for two query tiles per wave");
+  f32x16 s_next[QT];
+  float ex[32];
+  u32x4 p_new[QT][2];
+  auto soft = [&](int g) {   // values 2g, 2g+1 of the 32 scores of this lane; pack pair g-1
+    // (the empty asm after a result only pins where the instruction is issued)
+    ex[2 * g] = __builtin_amdgcn_exp2f(w.s_cur[g >> 3][(2 * g) & 15]);
+    asm volatile("" : "+v"(ex[2 * g]));
+    ex[2 * g + 1] = __builtin_amdgcn_exp2f(w.s_cur[g >> 3][(2 * g + 1) & 15]);
+    asm volatile("" : "+v"(ex[2 * g + 1]));
+  };
+  auto pack = [&](int p) {
+    uint32_t r = pack_bf16x2(ex[2 * p], ex[2 * p + 1]);
+    asm volatile("" : "+v"(r));
+    p_new[p >> 3][(p & 7) >> 2][p & 3] = r;
+  };
+#pragma unroll
+  for (int g = 0; g < 8; ++g) {
+    const int ks = g >> 1, qt = g & 1;
+    s_next[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op.ak[ks], w.qf[qt][ks],
+                                                         ks == 0 ? splat16(0.f) : s_next[qt], 0, 0, 0);
+    soft(g);
+    if (g > 0) pack(g - 1);
+    if ((g & 3) == 3) {
+      const int rq = (g >> 2) & 1, rj = 0;
+      w.l_acc[rq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+          w.ones_a, __builtin_bit_cast(bf16x8, w.p_old[rq][rj]), w.l_acc[rq], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (PREFETCH) {
+    load_k_operands(op, sk_next, l32, half);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+#pragma unroll
+  for (int g = 8; g < 16; ++g) {
+    const int i = g - 8, j = i >> 2, dt = (i >> 1) & 1, qt = i & 1;
+    w.o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+        op.av[dt * 2 + j], __builtin_bit_cast(bf16x8, w.p_old[qt][j]), w.o_acc[dt][qt], 0, 0, 0);
+    soft(g);
+    pack(g - 1);
+    if ((g & 3) == 3) {   // a row-sum MFMA after every fourth product
+      const int rq = (g >> 2) & 1, rj = 1;
+      w.l_acc[rq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+          w.ones_a, __builtin_bit_cast(bf16x8, w.p_old[rq][rj]), w.l_acc[rq], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  pack(15);
+  if (PREFETCH) load_v_operands(op, sv_next, l32, half);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    w.s_cur[qt] = s_next[qt];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) w.p_old[qt][j] = p_new[qt][j];
+  }
+}
+
 // bf16 bit pattern (a NaN with a payload that arithmetic does not produce) that the fast kernel
 // leaves in channel 0 of a tile's first output row when the tile has to be redone.
 constexpr uint16_t kRedoMark = 0x7FA5;
@@ -481,10 +547,15 @@ void attention_kernel(const AttnArgs a) {
     load_k((j + 1) * kKvTile, (j + 1) & 1);
     load_v(j * kKvTile, j & 1);
     if (active) {
-      pipeline_step<QT, SHIFT, true, true, true, false, false, true, true>(
-          w, nullptr, nullptr, 0, Mk, l32, half, &op, kb + kStep * kDHead, vb + kStep * kDHead);
-      pipeline_step<QT, SHIFT, true, true, true, false, false, true, false>(w, nullptr, nullptr, 0, Mk,
-                                                                     l32, half, &op);
+      if constexpr (!SHIFT && QT == 2) {
+        steady_step<2, true>(w, op, kb + kStep * kDHead, vb + kStep * kDHead, l32, half);
+        steady_step<2, false>(w, op, nullptr, nullptr, l32, half);
+      } else {
+        pipeline_step<QT, SHIFT, true, true, true, false, false, true, true>(
+            w, nullptr, nullptr, 0, Mk, l32, half, &op, kb + kStep * kDHead, vb + kStep * kDHead);
+        pipeline_step<QT, SHIFT, true, true, true, false, false, true, false>(w, nullptr, nullptr, 0, Mk,
+                                                                       l32, half, &op);
+      }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): K tile j+1 and V tile j are in LDS
     __syncthreads();
