@@ -57,6 +57,7 @@
 // SHIFT kernel is launched right behind on the same grid and redoes exactly the marked tiles.
 #include <cstdlib>
 #include <cstring>
+#include <type_traits>
 
 #include "dev_common.hpp"
 #include "kernels.hpp"
@@ -440,7 +441,8 @@ void attention_kernel(const AttnArgs a) {
   uint16_t* mark = (uint16_t*)(o_rows + (q_base + q0) * kDHead);
   if (SHIFT && a.marked_only && (Mk == 0 || *(volatile const uint16_t*)mark != kRedoMark)) return;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS destinations stay scalar
   const int l32 = lane & 31, half = lane >> 5;
   const int wq0 = q0 + wave * 32 * QT;  // first query row of this wave
   // A wave of a partial tile that owns no valid row only helps to stage K/V and to keep the
@@ -478,14 +480,14 @@ void attention_kernel(const AttnArgs a) {
   // K: straight from global memory into LDS, no registers.  Lane l of a wave instruction fills
   // bytes [16 l, 16 l + 16) of a 1 KB block = rows 8*blk .. 8*blk+7; it fetches the chunk that
   // belongs at its position under the swizzle.
-  auto load_k = [&](int kv0, int buf) {
+  auto load_k = [&](int kv0, int buf, bool inside = false) {   // inside: the whole tile lies below Mk
 #pragma unroll
     for (int i = 0; i < LDK; ++i) {
       const int blk = wave * LDK + i;
       const int r = blk * 8 + (lane >> 3);
       const int c = (lane & 7) ^ k_swizzle(r);
       int row = kv0 + r;
-      row = row < Mk ? row : Mk - 1;
+      if (!inside) row = row < Mk ? row : Mk - 1;
       const char* src = kg + (uint32_t)(row * kRowBytes + c * 16);
       bf16_t* dst = &s_k[buf][blk * 512];
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
@@ -493,14 +495,14 @@ void attention_kernel(const AttnArgs a) {
     }
   };
   // V the same way, under its own swizzle
-  auto load_v = [&](int kv0, int buf) {
+  auto load_v = [&](int kv0, int buf, bool inside = false) {
 #pragma unroll
     for (int i = 0; i < LDK; ++i) {
       const int blk = wave * LDK + i;
       const int r = blk * 8 + (lane >> 3);
       const int c = (lane & 7) ^ v_swizzle(r);
       int row = kv0 + r;
-      row = row < Mk ? row : Mk - 1;
+      if (!inside) row = row < Mk ? row : Mk - 1;
       const char* src = vg + (uint32_t)(row * kRowBytes + c * 16);
       bf16_t* dst = &s_v[buf][blk * 512];
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
@@ -537,15 +539,21 @@ void attention_kernel(const AttnArgs a) {
   // ---- j = 1 .. n_tiles-2: steady state, no masking ------------------------------------------------
   int j = 1;
   StepOperands op;
-  for (; j < n_tiles - 1; ++j) {
-    const bf16_t* kb = &s_k[j & 1][0];
-    const bf16_t* vb = &s_v[(j - 1) & 1][0];
+  // Two tiles per trip with the buffer indices as constants (j is odd at the top): the LDS
+  // addresses become instruction offsets instead of a dozen vector adds per tile.
+  auto steady_tile = [&](auto parity, int jt) {
+    constexpr int P = decltype(parity)::value;        // jt & 1
+    const bf16_t* kb = &s_k[P][0];
+    const bf16_t* vb = &s_v[P ^ 1][0];
     if (active) {
       load_k_operands(op, kb, l32, half);
       load_v_operands(op, vb, l32, half);
     }
-    load_k((j + 1) * kKvTile, (j + 1) & 1);
-    load_v(j * kKvTile, j & 1);
+    if ((jt + 2) * kKvTile <= Mk)
+      load_k((jt + 1) * kKvTile, P ^ 1, true);
+    else
+      load_k((jt + 1) * kKvTile, P ^ 1);
+    load_v(jt * kKvTile, P, true);                     // jt < n_tiles - 1: a full tile
     if (active) {
       if constexpr (!SHIFT && QT == 2) {
         steady_step<2, true>(w, op, kb + kStep * kDHead, vb + kStep * kDHead, l32, half);
@@ -557,8 +565,16 @@ void attention_kernel(const AttnArgs a) {
                                                                        l32, half, &op);
       }
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): K tile j+1 and V tile j are in LDS
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): K tile jt+1 and V tile jt are in LDS
     __syncthreads();
+  };
+  for (; j + 1 < n_tiles - 1; j += 2) {
+    steady_tile(std::integral_constant<int, 1>{}, j);
+    steady_tile(std::integral_constant<int, 0>{}, j + 1);
+  }
+  if (j < n_tiles - 1) {
+    steady_tile(std::integral_constant<int, 1>{}, j);
+    ++j;
   }
 
   // ---- j = n_tiles-1 (if it is not j = 0): the last K tile, its first step may be ragged ---------
