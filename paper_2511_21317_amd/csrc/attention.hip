@@ -319,16 +319,19 @@ __device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk
 
 // The steady-state step of the fast kernel with the order of issue written out: one MFMA, then its
 // share of the softmax of the current step (two exp2, one bf16 pack of the pair before), fenced so
-// that the compiler keeps the interleave.  QK^T of step t+1 first (the K operands retire, their
-// successors are requested), then PV of step t-1 with the row sums, then the V operands.
-template <int QT, bool PREFETCH>
+// that the compiler keeps the interleave.  PV of step t-1 first (the V operands retire, their
+// successors are requested), then QK^T of step t+1 and the K operands; a row-sum MFMA after every
+// fourth product.  `between` runs after the step's last LDS read: the global->LDS requests of the
+// iteration go there, because the compiler makes every LDS read wait for all requests issued
+// before it in program order.
+template <int QT, bool PREFETCH, typename Between>
 __device__ __forceinline__ void steady_step(WaveState<QT>& w, StepOperands& op, const bf16_t* sk_next,
-                                            const bf16_t* sv_next, int l32, int half) {
+                                            const bf16_t* sv_next, int l32, int half, Between between) {
   static_assert(QT == 2, "written for two query tiles per wave");
   f32x16 s_next[QT];
   float ex[32];
   u32x4 p_new[QT][2];
-  auto soft = [&](int g) {   // values 2g, 2g+1 of the 32 scores of this lane; pack pair g-1
+  auto soft = [&](int g) {   // values 2g, 2g+1 of the 32 scores of this lane
     // (the empty asm after a result only pins where the instruction is issued)
     ex[2 * g] = __builtin_amdgcn_exp2f(w.s_cur[g >> 3][(2 * g) & 15]);
     asm volatile("" : "+v"(ex[2 * g]));
@@ -340,14 +343,15 @@ __device__ __forceinline__ void steady_step(WaveState<QT>& w, StepOperands& op, 
     asm volatile("" : "+v"(r));
     p_new[p >> 3][(p & 7) >> 2][p & 3] = r;
   };
+  // PV of step t-1 first: the V operands retire and their successors are requested ...
 #pragma unroll
   for (int g = 0; g < 8; ++g) {
-    const int ks = g >> 1, qt = g & 1;
-    s_next[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op.ak[ks], w.qf[qt][ks],
-                                                         ks == 0 ? splat16(0.f) : s_next[qt], 0, 0, 0);
+    const int j = g >> 2, dt = (g >> 1) & 1, qt = g & 1;
+    w.o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+        op.av[dt * 2 + j], __builtin_bit_cast(bf16x8, w.p_old[qt][j]), w.o_acc[dt][qt], 0, 0, 0);
     soft(g);
     if (g > 0) pack(g - 1);
-    if ((g & 3) == 3) {
+    if ((g & 3) == 3) {   // a row-sum MFMA after every fourth product
       const int rq = (g >> 2) & 1, rj = 0;
       w.l_acc[rq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
           w.ones_a, __builtin_bit_cast(bf16x8, w.p_old[rq][rj]), w.l_acc[rq], 0, 0, 0);
@@ -355,17 +359,18 @@ __device__ __forceinline__ void steady_step(WaveState<QT>& w, StepOperands& op, 
     __builtin_amdgcn_sched_barrier(0);
   }
   if (PREFETCH) {
-    load_k_operands(op, sk_next, l32, half);
+    load_v_operands(op, sv_next, l32, half);
     __builtin_amdgcn_sched_barrier(0);
   }
+  // ... then QK^T of step t+1
 #pragma unroll
   for (int g = 8; g < 16; ++g) {
-    const int i = g - 8, j = i >> 2, dt = (i >> 1) & 1, qt = i & 1;
-    w.o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-        op.av[dt * 2 + j], __builtin_bit_cast(bf16x8, w.p_old[qt][j]), w.o_acc[dt][qt], 0, 0, 0);
+    const int i = g - 8, ks = i >> 1, qt = i & 1;
+    s_next[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op.ak[ks], w.qf[qt][ks],
+                                                         ks == 0 ? splat16(0.f) : s_next[qt], 0, 0, 0);
     soft(g);
     pack(g - 1);
-    if ((g & 3) == 3) {   // a row-sum MFMA after every fourth product
+    if ((g & 3) == 3) {
       const int rq = (g >> 2) & 1, rj = 1;
       w.l_acc[rq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
           w.ones_a, __builtin_bit_cast(bf16x8, w.p_old[rq][rj]), w.l_acc[rq], 0, 0, 0);
@@ -373,7 +378,9 @@ __device__ __forceinline__ void steady_step(WaveState<QT>& w, StepOperands& op, 
     __builtin_amdgcn_sched_barrier(0);
   }
   pack(15);
-  if (PREFETCH) load_v_operands(op, sv_next, l32, half);
+  if (PREFETCH) load_k_operands(op, sk_next, l32, half);
+  __builtin_amdgcn_sched_barrier(0);
+  between();        // requests that must follow the step's last LDS read in program order
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
@@ -447,7 +454,7 @@ void attention_kernel(const AttnArgs a) {
   const int wq0 = q0 + wave * 32 * QT;  // first query row of this wave
   // A wave of a partial tile that owns no valid row only helps to stage K/V and to keep the
   // barriers; it issues no MFMA and no softmax.
-  const bool active = wq0 < Mq;
+  const bool active = __builtin_amdgcn_readfirstlane((int)(wq0 < Mq)) != 0;   // wave-uniform, and known to be
 
   if (Mk == 0) {
     // softmax over an empty key set: defined as zero output
@@ -545,20 +552,27 @@ void attention_kernel(const AttnArgs a) {
     constexpr int P = decltype(parity)::value;        // jt & 1
     const bf16_t* kb = &s_k[P][0];
     const bf16_t* vb = &s_v[P ^ 1][0];
-    if (active) {
+    auto request = [&]() {
+      if ((jt + 2) * kKvTile <= Mk)
+        load_k((jt + 1) * kKvTile, P ^ 1, true);
+      else
+        load_k((jt + 1) * kKvTile, P ^ 1);
+      load_v(jt * kKvTile, P, true);                     // jt < n_tiles - 1: a full tile
+    };
+    if constexpr (!SHIFT && QT == 2) {
+      // (a wave without valid rows runs the loop below instead: no global->LDS request may precede
+      // an LDS read on the path of an active wave, the compiler would wait for it before the read)
       load_k_operands(op, kb, l32, half);
       load_v_operands(op, vb, l32, half);
-    }
-    if ((jt + 2) * kKvTile <= Mk)
-      load_k((jt + 1) * kKvTile, P ^ 1, true);
-    else
-      load_k((jt + 1) * kKvTile, P ^ 1);
-    load_v(jt * kKvTile, P, true);                     // jt < n_tiles - 1: a full tile
-    if (active) {
-      if constexpr (!SHIFT && QT == 2) {
-        steady_step<2, true>(w, op, kb + kStep * kDHead, vb + kStep * kDHead, l32, half);
-        steady_step<2, false>(w, op, nullptr, nullptr, l32, half);
-      } else {
+      steady_step<2, true>(w, op, kb + kStep * kDHead, vb + kStep * kDHead, l32, half, request);
+      steady_step<2, false>(w, op, nullptr, nullptr, l32, half, [] {});
+    } else {
+      if (active) {
+        load_k_operands(op, kb, l32, half);
+        load_v_operands(op, vb, l32, half);
+      }
+      request();
+      if (active) {
         pipeline_step<QT, SHIFT, true, true, true, false, false, true, true>(
             w, nullptr, nullptr, 0, Mk, l32, half, &op, kb + kStep * kDHead, vb + kStep * kDHead);
         pipeline_step<QT, SHIFT, true, true, true, false, false, true, false>(w, nullptr, nullptr, 0, Mk,
@@ -568,13 +582,23 @@ void attention_kernel(const AttnArgs a) {
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): K tile jt+1 and V tile jt are in LDS
     __syncthreads();
   };
-  for (; j + 1 < n_tiles - 1; j += 2) {
-    steady_tile(std::integral_constant<int, 1>{}, j);
-    steady_tile(std::integral_constant<int, 0>{}, j + 1);
-  }
-  if (j < n_tiles - 1) {
-    steady_tile(std::integral_constant<int, 1>{}, j);
-    ++j;
+  if (!SHIFT && QT == 2 && !active) {
+    // a wave of a partial tile without valid rows: it only stages its share of K / V
+    for (; j < n_tiles - 1; ++j) {
+      load_k((j + 1) * kKvTile, (j + 1) & 1);
+      load_v(j * kKvTile, j & 1);
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+    }
+  } else {
+    for (; j + 1 < n_tiles - 1; j += 2) {
+      steady_tile(std::integral_constant<int, 1>{}, j);
+      steady_tile(std::integral_constant<int, 0>{}, j + 1);
+    }
+    if (j < n_tiles - 1) {
+      steady_tile(std::integral_constant<int, 1>{}, j);
+      ++j;
+    }
   }
 
   // ---- j = n_tiles-1 (if it is not j = 0): the last K tile, its first step may be ragged ---------
