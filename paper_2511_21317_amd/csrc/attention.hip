@@ -317,31 +317,39 @@ __device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk
   }
 }
 
-// The steady-state step of the fast kernel with the order of issue written out: one MFMA, then its
+// The steady-state step (of both kernels) with the order of issue written out: one MFMA, then its
 // share of the softmax of the current step (two exp2, one bf16 pack of the pair before), fenced so
 // that the compiler keeps the interleave.  PV of step t-1 first (the V operands retire, their
 // successors are requested), then QK^T of step t+1 and the K operands; a row-sum MFMA after every
 // fourth product.  `between` runs after the step's last LDS read: the global->LDS requests of the
 // iteration go there, because the compiler makes every LDS read wait for all requests issued
 // before it in program order.
-template <int QT, bool PREFETCH, typename Between>
+template <int QT, bool SHIFT, bool PREFETCH, typename Between>
 __device__ __forceinline__ void steady_step(WaveState<QT>& w, StepOperands& op, const bf16_t* sk_next,
                                             const bf16_t* sv_next, int l32, int half, Between between) {
   static_assert(QT == 2, "written for two query tiles per wave");
   f32x16 s_next[QT];
   float ex[32];
   u32x4 p_new[QT][2];
+  float psum[QT] = {0.f, 0.f};
+  const bf16x2 ones2 = {(bf16_t)1.0f, (bf16_t)1.0f};
   auto soft = [&](int g) {   // values 2g, 2g+1 of the 32 scores of this lane
     // (the empty asm after a result only pins where the instruction is issued)
-    ex[2 * g] = __builtin_amdgcn_exp2f(w.s_cur[g >> 3][(2 * g) & 15]);
+    const int qt = g >> 3;
+    const float x0 = w.s_cur[qt][(2 * g) & 15], x1 = w.s_cur[qt][(2 * g + 1) & 15];
+    ex[2 * g] = __builtin_amdgcn_exp2f(SHIFT ? fmaf(x0, w.c, -w.mc[qt]) : x0);
     asm volatile("" : "+v"(ex[2 * g]));
-    ex[2 * g + 1] = __builtin_amdgcn_exp2f(w.s_cur[g >> 3][(2 * g + 1) & 15]);
+    ex[2 * g + 1] = __builtin_amdgcn_exp2f(SHIFT ? fmaf(x1, w.c, -w.mc[qt]) : x1);
     asm volatile("" : "+v"(ex[2 * g + 1]));
   };
   auto pack = [&](int p) {
     uint32_t r = pack_bf16x2(ex[2 * p], ex[2 * p + 1]);
     asm volatile("" : "+v"(r));
     p_new[p >> 3][(p & 7) >> 2][p & 3] = r;
+    if (SHIFT) {
+      psum[p >> 3] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, r), ones2, psum[p >> 3], false);
+      asm volatile("" : "+v"(psum[p >> 3]));
+    }
   };
   // PV of step t-1 first: the V operands retire and their successors are requested ...
 #pragma unroll
@@ -351,7 +359,7 @@ __device__ __forceinline__ void steady_step(WaveState<QT>& w, StepOperands& op, 
         op.av[dt * 2 + j], __builtin_bit_cast(bf16x8, w.p_old[qt][j]), w.o_acc[dt][qt], 0, 0, 0);
     soft(g);
     if (g > 0) pack(g - 1);
-    if ((g & 3) == 3) {   // a row-sum MFMA after every fourth product
+    if (!SHIFT && (g & 3) == 3) {   // a row-sum MFMA after every fourth product
       const int rq = (g >> 2) & 1, rj = 0;
       w.l_acc[rq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
           w.ones_a, __builtin_bit_cast(bf16x8, w.p_old[rq][rj]), w.l_acc[rq], 0, 0, 0);
@@ -370,7 +378,7 @@ __device__ __forceinline__ void steady_step(WaveState<QT>& w, StepOperands& op, 
                                                          ks == 0 ? splat16(0.f) : s_next[qt], 0, 0, 0);
     soft(g);
     pack(g - 1);
-    if ((g & 3) == 3) {
+    if (!SHIFT && (g & 3) == 3) {
       const int rq = (g >> 2) & 1, rj = 1;
       w.l_acc[rq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
           w.ones_a, __builtin_bit_cast(bf16x8, w.p_old[rq][rj]), w.l_acc[rq], 0, 0, 0);
@@ -382,6 +390,33 @@ __device__ __forceinline__ void steady_step(WaveState<QT>& w, StepOperands& op, 
   __builtin_amdgcn_sched_barrier(0);
   between();        // requests that must follow the step's last LDS read in program order
   __builtin_amdgcn_sched_barrier(0);
+  if (SHIFT) {
+    // rare: raise m to this step's maximum where a row sum left the range, redo the step's weights
+    bool redo = false;
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) redo = redo || !(psum[qt] < kSumLimit);
+    if (__any(redo)) {
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) {
+        float tmax = w.s_cur[qt][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, w.s_cur[qt][r]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float rel = fmaf(tmax, w.c, -w.mc[qt]);
+        const float delta = rel > kShiftLimit ? rel : 0.f;
+        const float sc = __builtin_amdgcn_exp2f(-delta);
+        w.l_run[qt] *= sc;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) w.o_acc[dt][qt][r] *= sc;
+        w.mc[qt] += delta;
+        psum[qt] = exp_pack<true>(w.s_cur[qt], w.c, w.mc[qt], p_new[qt]);
+      }
+    }
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) w.l_run[qt] += psum[qt];
+  }
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
     w.s_cur[qt] = s_next[qt];
@@ -559,13 +594,13 @@ void attention_kernel(const AttnArgs a) {
         load_k((jt + 1) * kKvTile, P ^ 1);
       load_v(jt * kKvTile, P, true);                     // jt < n_tiles - 1: a full tile
     };
-    if constexpr (!SHIFT && QT == 2) {
+    if constexpr (QT == 2) {
       // (a wave without valid rows runs the loop below instead: no global->LDS request may precede
       // an LDS read on the path of an active wave, the compiler would wait for it before the read)
       load_k_operands(op, kb, l32, half);
       load_v_operands(op, vb, l32, half);
-      steady_step<2, true>(w, op, kb + kStep * kDHead, vb + kStep * kDHead, l32, half, request);
-      steady_step<2, false>(w, op, nullptr, nullptr, l32, half, [] {});
+      steady_step<2, SHIFT, true>(w, op, kb + kStep * kDHead, vb + kStep * kDHead, l32, half, request);
+      steady_step<2, SHIFT, false>(w, op, nullptr, nullptr, l32, half, [] {});
     } else {
       if (active) {
         load_k_operands(op, kb, l32, half);
@@ -582,7 +617,7 @@ void attention_kernel(const AttnArgs a) {
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): K tile jt+1 and V tile jt are in LDS
     __syncthreads();
   };
-  if (!SHIFT && QT == 2 && !active) {
+  if (QT == 2 && !active) {
     // a wave of a partial tile without valid rows: it only stages its share of K / V
     for (; j < n_tiles - 1; ++j) {
       load_k((j + 1) * kKvTile, (j + 1) & 1);
