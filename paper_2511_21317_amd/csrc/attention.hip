@@ -33,7 +33,10 @@
 // basic block, the QK^T MFMAs of step t+1, the PV MFMAs of step t-1 and the softmax of step t:
 // the 16 MFMAs do not depend on the ~100 vector instructions next to them, so the matrix core
 // and the vector ALU overlap inside a single wave (two waves per SIMD then fill what is left).
-// V lags K by one tile in LDS because of the t-1.
+// V lags K by one tile in LDS because of the t-1.  In the steady state the order of issue is
+// written out (steady_step(): one MFMA, then two exp2 and a pack, behind a scheduling fence), the
+// loop runs two tiles per trip so that the LDS buffer indices are constants, and the global->LDS
+// requests of an iteration are issued behind the last LDS read of its first step.
 //
 // Softmax without a running maximum.  softmax is invariant to the per-row shift m, and fp32 /
 // bf16 keep their relative precision over the whole exponent range, so m only has to keep
@@ -55,7 +58,6 @@
 // stays well inside the fp32 range; every workgroup checks its final row sums against
 // [2^-80, 2^90] and, if a row is outside (or inf / NaN), writes a mark instead of its tile.  The
 // SHIFT kernel is launched right behind on the same grid and redoes exactly the marked tiles.
-#include <cstdlib>
 #include <cstring>
 #include <type_traits>
 
@@ -200,25 +202,19 @@ __device__ __forceinline__ void load_v_operands(StepOperands& op, const bf16_t* 
   }
 }
 
-// One pipeline step of a wave.
+// One pipeline step of a wave outside the steady state (first tile, last tile, drain); the order of
+// issue is the compiler's.
 //   DO_QK : scores of the NEXT step from the 32 K rows at `sk`           -> becomes s_cur
-//   DO_PV : O^T += V^T P^T of the PREVIOUS step, V^T columns at `svt`
+//   DO_PV : O^T += V^T P^T of the PREVIOUS step, V rows at `svt`
 //   DO_SM : softmax of the CURRENT step (s_cur -> p_old); its first key is `kv_first`
 //   MASK  : keys >= Mk get weight 0;  FIRST : this is step 0 and fixes m
-//   PRELOADED : `op` already holds this step's operands (otherwise they are read here)
-//   PREFETCH  : after the MFMAs are issued, `op` is refilled from sk_next / svt_next, so that the
-//               LDS latency of the following step hides behind this step's softmax
-template <int QT, bool SHIFT, bool DO_QK, bool DO_PV, bool DO_SM, bool MASK, bool FIRST, bool PRELOADED = false,
-          bool PREFETCH = false>
+template <int QT, bool SHIFT, bool DO_QK, bool DO_PV, bool DO_SM, bool MASK, bool FIRST>
 __device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk, const bf16_t* svt,
-                                              int kv_first, int Mk, int l32, int half,
-                                              StepOperands* opp = nullptr, const bf16_t* sk_next = nullptr,
-                                              const bf16_t* svt_next = nullptr) {
-  StepOperands local;
-  StepOperands& op = PRELOADED || PREFETCH ? *opp : local;
+                                              int kv_first, int Mk, int l32, int half) {
+  StepOperands op;
   f32x16 s_next[QT];
   if (DO_QK) {
-    if (!PRELOADED) load_k_operands(op, sk, l32, half);
+    load_k_operands(op, sk, l32, half);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
@@ -227,7 +223,7 @@ __device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk
             op.ak[ks], w.qf[qt][ks], ks == 0 ? splat16(0.f) : s_next[qt], 0, 0, 0);
   }
   if (DO_PV) {
-    if (!PRELOADED) load_v_operands(op, svt, l32, half);
+    load_v_operands(op, svt, l32, half);
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
@@ -244,10 +240,6 @@ __device__ __forceinline__ void pipeline_step(WaveState<QT>& w, const bf16_t* sk
           w.l_acc[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
               w.ones_a, __builtin_bit_cast(bf16x8, w.p_old[qt][j]), w.l_acc[qt], 0, 0, 0);
     }
-  }
-  if (PREFETCH) {
-    load_k_operands(op, sk_next, l32, half);
-    load_v_operands(op, svt_next, l32, half);
   }
   if (DO_SM) {
     // s_cur[qt][r]: key kv_first + 8*(r/4) + 4*half + r%4, query column l32 of tile qt
@@ -594,30 +586,16 @@ void attention_kernel(const AttnArgs a) {
         load_k((jt + 1) * kKvTile, P ^ 1);
       load_v(jt * kKvTile, P, true);                     // jt < n_tiles - 1: a full tile
     };
-    if constexpr (QT == 2) {
-      // (a wave without valid rows runs the loop below instead: no global->LDS request may precede
-      // an LDS read on the path of an active wave, the compiler would wait for it before the read)
-      load_k_operands(op, kb, l32, half);
-      load_v_operands(op, vb, l32, half);
-      steady_step<2, SHIFT, true>(w, op, kb + kStep * kDHead, vb + kStep * kDHead, l32, half, request);
-      steady_step<2, SHIFT, false>(w, op, nullptr, nullptr, l32, half, [] {});
-    } else {
-      if (active) {
-        load_k_operands(op, kb, l32, half);
-        load_v_operands(op, vb, l32, half);
-      }
-      request();
-      if (active) {
-        pipeline_step<QT, SHIFT, true, true, true, false, false, true, true>(
-            w, nullptr, nullptr, 0, Mk, l32, half, &op, kb + kStep * kDHead, vb + kStep * kDHead);
-        pipeline_step<QT, SHIFT, true, true, true, false, false, true, false>(w, nullptr, nullptr, 0, Mk,
-                                                                       l32, half, &op);
-      }
-    }
+    // (a wave without valid rows runs the loop below instead: no global->LDS request may precede
+    // an LDS read on the path of an active wave, the compiler would wait for it before the read)
+    load_k_operands(op, kb, l32, half);
+    load_v_operands(op, vb, l32, half);
+    steady_step<QT, SHIFT, true>(w, op, kb + kStep * kDHead, vb + kStep * kDHead, l32, half, request);
+    steady_step<QT, SHIFT, false>(w, op, nullptr, nullptr, l32, half, [] {});
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): K tile jt+1 and V tile jt are in LDS
     __syncthreads();
   };
-  if (QT == 2 && !active) {
+  if (!active) {
     // a wave of a partial tile without valid rows: it only stages its share of K / V
     for (; j < n_tiles - 1; ++j) {
       load_k((j + 1) * kKvTile, (j + 1) & 1);
@@ -735,15 +713,6 @@ hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_o
   return hipGetLastError();
 }
 
-// Tuning knob for experiments (not part of the ABI): HTTM_ATTN_CFG=<QT><NW>, e.g. 24.
-int attn_cfg() {
-  static int cfg = [] {
-    const char* e = std::getenv("HTTM_ATTN_CFG");
-    return e ? std::atoi(e) : 24;
-  }();
-  return cfg;
-}
-
 }  // namespace
 
 hipError_t launch_attention_dev_tiles(const void* q, const void* k, const void* v, void* o,
@@ -809,10 +778,7 @@ hipError_t launch_attention(const void* q, const void* k, const void* v, void* o
   a.scale_log2 = log2_keys ? 1.0f : scale * 1.4426950408889634f;
   a.marked_only = log2_keys ? 1 : 0;
   a.H = H;
-  switch (attn_cfg()) {
-    case 14: return launch_cfg<1, 4>(a, q_off_host, k_off_host, H, stream);
-    default: return launch_cfg<2, 4>(a, q_off_host, k_off_host, H, stream);
-  }
+  return launch_cfg<2, 4>(a, q_off_host, k_off_host, H, stream);
 }
 
 }  // namespace httm
