@@ -10,7 +10,8 @@
  * and, switched on through the geometry, the adaptive outlier filtering of the queries (Sec. 3.4,
  * Alg. 2: httm_geom_t.outlier_frac), first-frame anchoring (App. C.2), the paper's own block shape
  * (runs of n_s tokens x n_t frames, Sec. 4.1) and the general src/dst rule of Sec. 3.2 with top-r
- * selection (httm_geom_t.dst_frac).
+ * selection (httm_geom_t.dst_frac).  HTTM_FLAG_LOG2_KEYS selects the faster stage-3 path: the
+ * merged keys leave stage 2 with the logit scale folded in (same softmax, Eq. 3-4).
  *
  * Conventions common to every call
  *   - All tensor pointers are DEVICE pointers unless a parameter says "host".  Tensors are
