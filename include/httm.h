@@ -242,7 +242,7 @@ HTTM_API int httm_attention(const void* q_m, const void* k_m, const void* v_m, v
  *   o = sum_j 2^(q . k'_j) v_j / sum_j 2^(q . k'_j)      (= Eq. 3-4 for k' = k * log2(e) / sqrt(d_head)).
  * Arguments and layout as for httm_attention, without `scale`.  Rows whose weights would leave the
  * fp32 range without a per-row shift are detected and recomputed with one, so the result is defined
- * for any finite input; the fast path covers row sums between 2^-80 and 2^90. */
+ * for any finite input; the fast path covers row sums between 2^-64 and 2^64. */
 HTTM_API int httm_attention_log2(const void* q_m, const void* k_log2, const void* v_m, void* o_m,
                                  const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
                                  void* stream);

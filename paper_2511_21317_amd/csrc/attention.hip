@@ -56,7 +56,7 @@
 // fma, no shift - a quarter of the vector work per score gone - and takes the row sums from the
 // matrix cores as well (row_sum_operand()).  That is safe while a row's sum
 // stays well inside the fp32 range; every workgroup checks its final row sums against
-// [2^-80, 2^90] and, if a row is outside (or inf / NaN), writes a mark instead of its tile.  The
+// [2^-64, 2^64] and, if a row is outside (or inf / NaN), writes a mark instead of its tile.  The
 // SHIFT kernel is launched right behind on the same grid and redoes exactly the marked tiles.
 #include <cstring>
 #include <type_traits>
@@ -420,10 +420,11 @@ __device__ __forceinline__ void steady_step(WaveState<QT>& w, StepOperands& op, 
 // bf16 bit pattern (a NaN with a payload that arithmetic does not produce) that the fast kernel
 // leaves in channel 0 of a tile's first output row when the tile has to be redone.
 constexpr uint16_t kRedoMark = 0x7FA5;
-// Row sums the fast kernel accepts: below 2^-80 the weights of the row's best keys are close to the
-// bottom of the fp32 range, above 2^90 close to the top (inf and NaN fail the test as well).
-constexpr float kFastSumMin = 8.271806125530277e-25f;   // 2^-80
-constexpr float kFastSumMax = 1.2379400392853803e27f;   // 2^90
+// Row sums the fast kernel accepts (inf and NaN fail the test as well): inside, the weights of a
+// row's best keys are far from both ends of the fp32 range, and no weight exceeds 2^64, so that the
+// unnormalised products with V stay finite for |v| below 1e19.
+constexpr float kFastSumMin = 5.421010862427522e-20f;    // 2^-64
+constexpr float kFastSumMax = 1.8446744073709552e19f;    // 2^64
 
 // SHIFT = false: the fast kernel (keys carry the logit scale; weights exp2(s)).  SHIFT = true: per-row
 // shifts and the overflow guard; with a.marked_only it is launched right after the fast kernel on

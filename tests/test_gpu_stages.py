@@ -348,7 +348,7 @@ def test_log2_key_attention_on_ragged_heads(mq, mk):
 
 @pytest.mark.parametrize("case", ["huge_positive", "huge_negative", "growing", "one_head_of_three", "nan_free_zero_keys"])
 def test_log2_key_attention_leaves_the_unshifted_range(case):
-    """Rows whose sum of 2^(q.k') is not inside [2^-80, 2^90] cannot use unshifted weights: their
+    """Rows whose sum of 2^(q.k') is not inside [2^-64, 2^64] cannot use unshifted weights: their
     tiles are marked by the fast kernel and redone with per-row shifts.  The result must match the
     oracle whichever kernel computed a tile."""
     require_gpu()
@@ -378,7 +378,7 @@ def test_log2_key_attention_leaves_the_unshifted_range(case):
     vm = v.to(torch.bfloat16).cuda()
     logits2 = f32(qm[:mq]) @ f32(k2[:mk]).T
     sums = np.log2(np.exp2(logits2 - logits2.max(axis=1, keepdims=True)).sum(axis=1)) + logits2.max(axis=1)
-    outside = (sums < -80) | (sums > 90)
+    outside = (sums < -64) | (sums > 64)
     if case in ("huge_positive", "huge_negative", "growing"):
         assert outside.mean() > 0.5, "the case must actually leave the unshifted range"
     elif case == "nan_free_zero_keys":
