@@ -304,7 +304,7 @@ def _log2_keys(km: torch.Tensor) -> torch.Tensor:
     return (km.float() * float(np.float32(httm.LOG2_KEY_SCALE))).to(torch.bfloat16)
 
 
-def _check_log2_attention(qm, k2, vm, qo, ko, what, relative=False):
+def _check_log2_attention(qm, k2, vm, qo, ko, what, relative=False, value_scale=1.0):
     """httm_attention_log2 against the oracle's attention on the keys the kernel was given,
     their factor divided out again."""
     om = torch.full_like(qm, float("nan"))
@@ -317,7 +317,9 @@ def _check_log2_attention(qm, k2, vm, qo, ko, what, relative=False):
             continue
         kk = f32(k2[ko[h]:ko[h + 1]]) / np.float32(httm.LOG2_KEY_SCALE)
         want = orc.attention(f32(qm[qo[h]:qo[h + 1]]), kk, f32(vm[ko[h]:ko[h + 1]]))
-        check_output(got[qo[h]:qo[h + 1]], want, f"{what} head {h}", relative_to_magnitude=relative)
+        # (values of another magnitude: the bar is read in units of that magnitude)
+        check_output(got[qo[h]:qo[h + 1]] / value_scale, want / value_scale, f"{what} head {h}",
+                     relative_to_magnitude=relative)
     return got
 
 
@@ -346,7 +348,8 @@ def test_log2_key_attention_on_ragged_heads(mq, mk):
         check_output(got, want, f"ragged log2-key head {h} ({mq[h]}x{mk[h]})")
 
 
-@pytest.mark.parametrize("case", ["huge_positive", "huge_negative", "growing", "one_head_of_three", "nan_free_zero_keys"])
+@pytest.mark.parametrize("case", ["huge_positive", "huge_negative", "growing", "one_head_of_three", "nan_free_zero_keys",
+                                  "large_values"])
 def test_log2_key_attention_leaves_the_unshifted_range(case):
     """Rows whose sum of 2^(q.k') is not inside [2^-64, 2^64] cannot use unshifted weights: their
     tiles are marked by the fast kernel and redone with per-row shifts.  The result must match the
@@ -371,6 +374,9 @@ def test_log2_key_attention_leaves_the_unshifted_range(case):
         k = torch.cat([k, k * 8, k])
         v = torch.cat([v, v, v])
         qo, ko = [0, mq, 2 * mq, 3 * mq], [0, mk, 2 * mk, 3 * mk]
+    elif case == "large_values":         # row sums near the top of the accepted range, values of 1e12
+        q, k = q * 2.2, k * 2.2
+        v = v * 1e12
     else:                                # zero keys: every weight is exactly 1
         k = torch.zeros_like(k)
     qm = q.to(torch.bfloat16).cuda()
@@ -383,7 +389,10 @@ def test_log2_key_attention_leaves_the_unshifted_range(case):
         assert outside.mean() > 0.5, "the case must actually leave the unshifted range"
     elif case == "nan_free_zero_keys":
         assert not outside.any()
-    _check_log2_attention(qm, k2, vm, qo, ko, f"log2 keys ({case})", relative=True)
+    elif case == "large_values":
+        assert (~outside).mean() > 0.5 and sums.max() > 30, "most rows must stay on the fast path, some near its top"
+    _check_log2_attention(qm, k2, vm, qo, ko, f"log2 keys ({case})", relative=True,
+                          value_scale=1e12 if case == "large_values" else 1.0)
 
 
 def test_log2_key_attention_rewrites_a_buffer_that_holds_old_marks():
