@@ -30,6 +30,9 @@ namespace httm {
 
 namespace {
 
+// members of a cluster whose LDS reads the aggregation keeps in flight together (2, 6 and 8 measured slower)
+constexpr int kAggBatch = 4;
+
 // exclusive prefix sum over 64 lanes of a wave (lane i gets the sum of lanes < i)
 __device__ __forceinline__ int wave_exclusive_scan(int v, int lane) {
   int incl = v;
@@ -55,9 +58,7 @@ __device__ __forceinline__ PairSelectors make_pair_selectors() {
 
 // acc[0..7] += the 8 bf16 channels of one 16-byte row chunk.  One v_dot2 per channel: the pair
 // (x_lo, x_hi) against (1, 0) or (0, 1) adds exactly one bf16 value to the fp32 accumulator.
-__device__ __forceinline__ void add_row_chunk(float (&acc)[8], const unsigned char* row_chunk,
-                                              const PairSelectors& sel) {
-  const bf16x8 w = *(const bf16x8*)row_chunk;
+__device__ __forceinline__ void add_row_chunk(float (&acc)[8], const bf16x8 w, const PairSelectors& sel) {
   const bf16x2 sel_lo = sel.lo, sel_hi = sel.hi;
   const bf16x2 pr[4] = {__builtin_shufflevector(w, w, 0, 1), __builtin_shufflevector(w, w, 2, 3),
                         __builtin_shufflevector(w, w, 4, 5), __builtin_shufflevector(w, w, 6, 7)};
@@ -430,15 +431,19 @@ void match_merge_kernel(const MatchMergeArgs a) {
       for (int q = 0; q < 8; ++q) acc[q] = 0.f;
       // members in list order: the dst token, then its src tokens in ascending position
       const unsigned char* col = tile + c * 16;
-      int idx = beg;
-      for (; idx + 2 <= end; idx += 2) {
-        const int j0 = s_list[idx], j1 = s_list[idx + 1];
-        const unsigned char* r0 = col + j0 * kLdsRowBytes;
-        const unsigned char* r1 = col + j1 * kLdsRowBytes;
-        add_row_chunk(acc, r0, sel);
-        add_row_chunk(acc, r1, sel);
+      // kAggBatch members per round: their list entries, then their rows, are requested together, so a
+      // round costs two LDS round trips; a slot past the end adds a zero row
+      const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+      for (int idx = beg; idx < end; idx += kAggBatch) {
+        int jj[kAggBatch];
+#pragma unroll
+        for (int u = 0; u < kAggBatch; ++u) jj[u] = s_list[idx + u < end ? idx + u : end - 1];
+        bf16x8 w[kAggBatch];
+#pragma unroll
+        for (int u = 0; u < kAggBatch; ++u) w[u] = *(const bf16x8*)(col + jj[u] * kLdsRowBytes);
+#pragma unroll
+        for (int u = 0; u < kAggBatch; ++u) add_row_chunk(acc, idx + u < end ? w[u] : zero8, sel);
       }
-      if (idx < end) add_row_chunk(acc, col + s_list[idx] * kLdsRowBytes, sel);
       const float cnt = (float)(end - beg);
       const float rcnt = 1.0f / cnt;
       float mean[8];
@@ -621,7 +626,8 @@ void outlier_refine_kernel(const RefineArgs a) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) acc[q] = 0.f;
     const unsigned char* col = tile + c * 16;
-    for (int idx = beg; idx < end; ++idx) add_row_chunk(acc, col + s_list[idx] * kLdsRowBytes, sel);
+    for (int idx = beg; idx < end; ++idx)
+      add_row_chunk(acc, *(const bf16x8*)(col + s_list[idx] * kLdsRowBytes), sel);
     u32x4 o = {0, 0, 0, 0};
     if (end > beg) {
       const float cnt = (float)(end - beg);
