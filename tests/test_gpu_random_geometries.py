@@ -1,0 +1,100 @@
+"""GPU parity of the layer on seeded random geometries: odd grids, block shapes that do not divide
+them, both block kinds, anchoring, separate ratios, both key conventions, the head-uniform variant.
+Every case is small enough for the oracle to evaluate in full."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_21317_amd as httm
+import synth
+from oracle import httm_oracle as orc
+from synth.vggt_tokens import Workload
+
+from gpu_util import (TIE_FRACTION, TIE_GAP, check_output, excuse_tie_tokens, f32, oracle_geom, plain_keys, plan_for,
+                      require_gpu, run_layer, run_stages)
+
+pytestmark = pytest.mark.gpu
+
+RHOS = [0.0, 0.3, 0.5, 0.75, 0.9, 1.0]
+
+
+def _draw(seed):
+    """A geometry and its options from one seed (plain Python / NumPy integers, no method arithmetic)."""
+    rng = np.random.default_rng(7000 + seed)
+    chunked = bool(rng.integers(0, 2))
+    S = int(rng.integers(1, 10))
+    Hp, Wp = int(rng.integers(3, 21)), int(rng.integers(3, 21))
+    T = int(rng.integers(1, 6))
+    b = int(rng.integers(5, 260)) if chunked else int(rng.integers(2, 9))
+    n_special = int(rng.choice([0, 1, 5]))
+    H = int(rng.integers(1, 4))
+    w = Workload(f"rand{seed}_S{S}_{Hp}x{Wp}_b{b}T{T}{'_chunked' if chunked else ''}", 100 + seed, S, Hp, Wp, b, T,
+                 float(rng.choice(RHOS)), 1, H=H, n_special=n_special, anchor=bool(rng.integers(0, 2)),
+                 chunked=chunked)
+    rho_kv = float(rng.choice(RHOS))
+    variant = "uniform" if rng.integers(0, 4) == 0 else "headwise"
+    log2_keys = bool(rng.integers(0, 2))
+    return w, rho_kv, variant, log2_keys
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_layer_on_a_random_geometry(seed):
+    require_gpu()
+    w, rho_kv, variant, log2_keys = _draw(seed)
+    g = oracle_geom(w)
+    _, blocks = orc.temporal_reorder(g)
+    max_block = max((n for _, n in blocks), default=0)
+    print(f"[case] {w.name} N={w.N} H={w.H} rho_q={w.rho} rho_kv={rho_kv} {variant} anchor={w.anchor} "
+          f"log2_keys={log2_keys} largest block {max_block}", flush=True)
+    if w.N > 6000:
+        pytest.skip("larger than the oracle should evaluate in full here")
+    if variant == "uniform" and max_block > 512:
+        with pytest.raises(httm.HttmError):       # no head-uniform matching of big blocks
+            plan_for(w, variant=variant, rho_kv=rho_kv, log2_keys=log2_keys)
+        return
+    q, k, v = synth.make_qkv(w, device="cuda")
+    plan = plan_for(w, variant=variant, rho_kv=rho_kv, log2_keys=log2_keys)
+    got = run_stages(plan, q, k, v, with_scores=False)
+    ref = orc.layer_forward(f32(q), f32(k), f32(v), g, w.rho, rho_kv, variant=variant)
+    assert plan.M_q == ref["q_m"][0].shape[0] and plan.M_k == ref["k_m"][0].shape[0]
+    aq, ak = got["assign_q"].cpu().numpy(), got["assign_k"].cpu().numpy()
+    pi = ref["pi"]
+    for h in range(w.H):
+        # indices: equal except at near-ties (the oracle's best-vs-second gap below 1e-3).  The 0.1 %
+        # allowance of the workloads is not applied: these inputs have a few dozen to a few thousand
+        # tokens of a smooth field, and on the smallest grids near-ties are the rule, not the exception
+        # - there the count is bounded by the number of near-tie tokens the oracle itself reports.
+        for a_gpu, name, gap in ((aq[h], "assign_q", "gap_q"), (ak[h], "assign_k", "gap_k")):
+            bad = np.flatnonzero(a_gpu != ref[name][h])
+            assert (ref[gap][h][bad] < TIE_GAP).all(), f"{w.name} {name} head {h}: differs at gap {ref[gap][h][bad].max()}"
+            near = int((ref[gap][h] < TIE_GAP).sum())
+            assert bad.size <= max(TIE_FRACTION * a_gpu.size, near), f"{w.name} {name} head {h}: {bad.size} indices differ"
+        # merged tokens: one bf16 rounding from the oracle's fp32 mean, outside clusters touched by a tie
+        for name, asg, a_gpu in (("q_m", "assign_q", aq), ("k_m", "assign_k", ak), ("v_m", "assign_k", ak)):
+            bad = np.flatnonzero(a_gpu[h] != ref[asg][h])
+            keep = np.ones(ref[name][h].shape[0], dtype=bool)
+            keep[a_gpu[h][bad]] = False
+            keep[ref[asg][h][bad]] = False
+            mean = ref[name][h] * (got["key_scale"] if name == "k_m" else np.float32(1.0))
+            assert (np.abs(f32(got[name][h]) - mean) <= 2.0 ** -8 * np.abs(mean) + 1e-30)[keep].all(), (w.name, name, h)
+        # stage 3 on the GPU's own merged tokens against the oracle's attention on the same tokens
+        want = orc.attention(f32(got["q_m"][h]), plain_keys(plan, f32(got["k_m"][h])), f32(got["v_m"][h]))
+        check_output(f32(got["o_m"][h]), want, f"{w.name} attention head {h}", relative_to_magnitude=True)
+        # stage 4: bit-exact copies of the merged outputs
+        want_r = orc.unmerge_by_cluster(got["o_m"][h].cpu().view(torch.int16).numpy(), aq[h].astype(np.int64))
+        assert np.array_equal(got["out"].cpu().view(torch.int16).numpy()[:, h * 64:(h + 1) * 64],
+                              orc.inverse_reorder(want_r, pi))
+    # end to end against the all-fp32 oracle.  The bar of the five workloads (2e-2) assumes thousands of
+    # keys per row; with a few hundred the roundings of the merged tokens (2^-9 each on q, k, v) are not
+    # averaged over keys, so small cases are read against three times that.
+    out_f = f32(got["out"])
+    assert np.isfinite(out_f).all()
+    if all(np.array_equal(ak[h], ref["assign_k"][h]) for h in range(w.H)):
+        want = excuse_tie_tokens(out_f, ref["O"], aq.astype(np.int64), ref)
+        diff = np.abs(out_f - want) / np.maximum(1.0, np.abs(want))
+        rel = float(np.linalg.norm(out_f - want) / max(np.linalg.norm(want), 1e-30))
+        bar = 2e-2 if plan.M_k >= 1024 else 6e-2
+        assert diff.max() < bar and rel < 1e-2, f"{w.name} layer output: max_abs={diff.max():.4g} rel_l2={rel:.4g}"
+    out, _ = run_layer(plan, q, k, v)
+    assert torch.equal(out, got["out"])                  # the layer call = the four stages, bit for bit
+    plan.close()
