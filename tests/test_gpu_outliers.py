@@ -39,6 +39,21 @@ CASES = [
 ]
 
 
+def _random_case(seed):
+    """A seeded random geometry with a merge ratio that leaves something to filter."""
+    rng = np.random.default_rng(9000 + seed)
+    chunked = bool(rng.integers(0, 2))
+    S, Hp, Wp = int(rng.integers(2, 9)), int(rng.integers(5, 19)), int(rng.integers(5, 19))
+    b = int(rng.integers(20, 260)) if chunked else int(rng.integers(3, 9))
+    w = Workload(f"rand{seed}_S{S}_{Hp}x{Wp}_b{b}{'_chunked' if chunked else ''}", 200 + seed, S, Hp, Wp, b,
+                 int(rng.integers(1, 5)), float(rng.choice([0.5, 0.75, 0.9])), 1, H=int(rng.integers(1, 4)),
+                 n_special=int(rng.choice([0, 1, 5])), anchor=bool(rng.integers(0, 2)), chunked=chunked)
+    return w, float(rng.choice([0.02, 0.1, 0.3]))
+
+
+CASES += [_random_case(s) for s in range(8)]
+
+
 def _run_filtered_stages(plan, q, k, v):
     H, N, cap = plan.H, plan.N, plan.outlier_cap
     bf, i32, dev = torch.bfloat16, torch.int32, "cuda"

@@ -28,6 +28,22 @@ CASES = [
 ]
 
 
+def _random_case(seed):
+    """A seeded random geometry for the general rule (blocks of at most 512 tokens)."""
+    rng = np.random.default_rng(9500 + seed)
+    chunked = bool(rng.integers(0, 2))
+    S, Hp, Wp = int(rng.integers(2, 9)), int(rng.integers(6, 19)), int(rng.integers(6, 19))
+    T = int(rng.integers(1, 4))
+    b = int(rng.integers(16, 512 // T + 1)) if chunked else int(rng.integers(3, 9))
+    return Workload(f"topr_rand{seed}_S{S}_{Hp}x{Wp}_b{b}T{T}{'_chunked' if chunked else ''}", 300 + seed, S, Hp, Wp,
+                    b, T, float(rng.choice([0.3, 0.5, 0.75, 0.9])), 1, H=int(rng.integers(1, 4)),
+                    n_special=int(rng.choice([0, 1, 5])), anchor=bool(rng.integers(0, 2)), chunked=chunked,
+                    dst_frac=float(rng.choice([0.1, 0.25, 0.5])))
+
+
+CASES += [_random_case(s) for s in range(8)]
+
+
 def _rep_from_gpu(assign, pi, g, blocks, rho):
     """Owner token of every slot, from the GPU's own assignment: the dst token of a dst cluster, the
     single member of any other cluster."""
