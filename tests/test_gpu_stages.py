@@ -227,6 +227,49 @@ def test_attention_on_ragged_heads(mq, mk):
         check_output(got, want, f"ragged head {h} ({mq[h]}x{mk[h]})")
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_attention_on_random_ragged_heads(seed):
+    """Both stage-3 entry points on seeded random head lengths: empty heads, lengths around the tile
+    sizes (32, 64, 128, 256), problems on either side of the choice between 128- and 256-row tiles."""
+    require_gpu()
+    rng = np.random.default_rng(8000 + seed)
+    H = int(rng.integers(1, 7))
+    pick = lambda: int(rng.choice([0, 1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, int(rng.integers(1, 3000))]))
+    mq, mk = [pick() for _ in range(H)], [pick() for _ in range(H)]
+    if seed % 4 == 3:                     # many tiles: the 256-row configuration
+        mq = [int(rng.integers(20000, 30000)) for _ in range(H)]
+        mk = [int(rng.integers(1, 400)) for _ in range(H)]
+    print(f"[case] random ragged attention seed {seed} mq={mq} mk={mk}", flush=True)
+    gen = torch.Generator().manual_seed(8000 + seed)
+    qo = [int(x) for x in np.concatenate([[0], np.cumsum(mq)])]
+    ko = [int(x) for x in np.concatenate([[0], np.cumsum(mk)])]
+    qm = torch.randn((max(qo[-1], 1), 64), generator=gen).to(torch.bfloat16).cuda()
+    kf = torch.randn((max(ko[-1], 1), 64), generator=gen)
+    vm = torch.randn((max(ko[-1], 1), 64), generator=gen).to(torch.bfloat16).cuda()
+    for log2 in (False, True):
+        km = (_log2_keys(kf) if log2 else kf.to(torch.bfloat16)).cuda()
+        om = torch.full_like(qm, float("nan"))
+        if log2:
+            httm.attention_log2(qm, km, vm, om, qo, ko)
+        else:
+            httm.attention(qm, km, vm, om, qo, ko, 0.125)
+        torch.cuda.synchronize()
+        for h in range(H):
+            got = f32(om[qo[h]:qo[h + 1]])
+            if mq[h] == 0:
+                continue
+            if mk[h] == 0:
+                assert (got == 0).all()
+                continue
+            kk = f32(km[ko[h]:ko[h + 1]])
+            if log2:
+                kk = kk / np.float32(httm.LOG2_KEY_SCALE)
+            rows = np.arange(mq[h]) if mq[h] <= 4000 else np.sort(rng.choice(mq[h], size=2000, replace=False))
+            want = orc.attention(f32(qm[qo[h]:qo[h + 1]])[rows], kk, f32(vm[ko[h]:ko[h + 1]]))
+            check_output(got[rows], want, f"random ragged head {h} ({mq[h]}x{mk[h]}, log2={log2})")
+        assert torch.isnan(om[qo[-1]:].float()).all()       # nothing written past the last head
+
+
 def test_attention_partial_tiles_in_a_large_grid():
     """In a grid of many workgroups a short partial tile is computed by the workgroup of the head's
     last full tile (second pass); longer partial tiles and heads that are a whole number of tiles
