@@ -200,6 +200,7 @@ RAGGED = [
     ([1, 63, 64, 65, 129, 300], [7, 64, 1, 200, 513, 65]),
     ([128, 0, 5, 257], [64, 33, 0, 1000]),            # a head without queries, a head without keys
     ([2000], [3001]),
+    ([90 + 3 * h for h in range(64)], [70 + 5 * h for h in range(64)]),   # the largest head count the ABI takes
 ]
 
 
