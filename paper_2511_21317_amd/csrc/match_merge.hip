@@ -142,16 +142,36 @@ void match_merge_kernel(const MatchMergeArgs a) {
   float* __restrict__ score = s.score ? s.score + h * N + it.start : nullptr;
 
   // ---- all global loads up front -----------------------------------------------------------
-  u32x4 xr[ITER], vr[ITER];
+  // First the source rows of all of this thread's chunks (one index load each when the tokens are
+  // still in the caller's order), then all row loads back to back: a wait for an index placed
+  // between the row loads would wait for the rows requested before it as well (the counter of
+  // outstanding loads is kept in issue order), and the rows would arrive one round trip after the other.
+  uint32_t off[ITER];
+  if (a.pi) {
 #pragma unroll
-  for (int i = 0; i < ITER; ++i) {
-    const int e = tid + i * NT;
-    const int row = e >> 3, c = e & 7;
-    if (row < n) {
-      const uint32_t src = a.pi ? (uint32_t)a.pi[it.start + row] : (uint32_t)(it.start + row);
-      const uint32_t off = src * kRowBytes + c * 16;
-      xr[i] = __builtin_nontemporal_load((const u32x4*)(x + off));
-      if (v) vr[i] = __builtin_nontemporal_load((const u32x4*)(v + off));
+    for (int i = 0; i < ITER; ++i) {
+      const int row = (tid + i * NT) >> 3;
+      off[i] = row < n ? (uint32_t)a.pi[it.start + row] : 0u;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) off[i] = (uint32_t)(it.start + ((tid + i * NT) >> 3));
+  }
+#pragma unroll
+  for (int i = 0; i < ITER; ++i) off[i] = off[i] * kRowBytes + (tid & 7) * 16;
+  u32x4 xr[ITER], vr[ITER];
+  if (v) {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      if (((tid + i * NT) >> 3) < n) {
+        xr[i] = __builtin_nontemporal_load((const u32x4*)(x + off[i]));
+        vr[i] = __builtin_nontemporal_load((const u32x4*)(v + off[i]));
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      if (((tid + i * NT) >> 3) < n) xr[i] = __builtin_nontemporal_load((const u32x4*)(x + off[i]));
     }
   }
 
@@ -173,7 +193,7 @@ void match_merge_kernel(const MatchMergeArgs a) {
     return;
   }
 
-  // ---- 1. rows to LDS ------------------------------------------------------------------------
+  // ---- 1. rows to LDS, and their inverse norms ---------------------------------------------------
 #pragma unroll
   for (int i = 0; i < ITER; ++i) {
     const int e = tid + i * NT;
@@ -181,6 +201,26 @@ void match_merge_kernel(const MatchMergeArgs a) {
     if (row < n) *(u32x4*)(tile + row * kLdsRowBytes + c * 16) = xr[i];
   }
   s_cl[tid] = -1;
+  if (!s.preset) {
+    // ---- 2. inverse norms, from the registers: the 8 lanes that hold the chunks of a row add their
+    // sums of squares; of the ITER rows a group of 8 lanes holds, lane c finishes the c-th (one
+    // square root and one division per thread)
+    static_assert(ITER == kRowChunks, "one row per lane of a group");
+    float mine = 0.f;
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      const bf16x8 w = __builtin_bit_cast(bf16x8, xr[i]);
+      const bf16x2 pr[4] = {__builtin_shufflevector(w, w, 0, 1), __builtin_shufflevector(w, w, 2, 3),
+                            __builtin_shufflevector(w, w, 4, 5), __builtin_shufflevector(w, w, 6, 7)};
+      float ss = 0.f;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) ss = __builtin_amdgcn_fdot2_f32_bf16(pr[q], pr[q], ss, false);
+      ss = sum_over_8_lanes(ss);
+      if ((tid & 7) == i) mine = ss;
+    }
+    const int row = (tid >> 3) + (NT >> 3) * (tid & 7);
+    if (row < n) s_invn[row] = 1.0f / fmaxf(sqrtf(mine), 1e-12f);
+  }
   __syncthreads();
 
   const int l32 = lane & 31, half = lane >> 5;
@@ -197,20 +237,6 @@ void match_merge_kernel(const MatchMergeArgs a) {
     }
     __syncthreads();
   } else {
-    // ---- 2. inverse norms --------------------------------------------------------------------
-    if (tid < n) {
-      float ss = 0.f;
-#pragma unroll
-      for (int c = 0; c < kRowChunks; ++c) {
-        const bf16x8 w = *(const bf16x8*)(tile + tid * kLdsRowBytes + c * 16);
-        const bf16x2 pr[4] = {__builtin_shufflevector(w, w, 0, 1), __builtin_shufflevector(w, w, 2, 3),
-                              __builtin_shufflevector(w, w, 4, 5), __builtin_shufflevector(w, w, 6, 7)};
-#pragma unroll
-        for (int q = 0; q < 4; ++q) ss = __builtin_amdgcn_fdot2_f32_bf16(pr[q], pr[q], ss, false);
-      }
-      s_invn[tid] = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
-    }
-    __syncthreads();
     const int kd = TOPR ? it.kd : k;   // dst tokens = clusters 0 .. kd-1
     for (int m = tid; m < kd; m += NT) {
       const int p = dst_position(m, n, kd, it.n0);
@@ -225,67 +251,77 @@ void match_merge_kernel(const MatchMergeArgs a) {
 
     // ---- 3. similarities and arg-max -----------------------------------------------------------
     // Wave w owns the tokens 64w .. 64w+63, i.e. the two 32-token tiles 2w and 2w+1.
+    // The two tiles go through the dst tiles side by side: they share the dst operand and the dst
+    // norms, and their dependent chains of LDS reads overlap.  (The token operands are read again
+    // for every dst tile: registers are scarce, the V rows wait in them.)
     const int ndt = (kd + 31) >> 5;
     float my_sc = 1.0f;                // similarity of token `tid` to the dst it would join
+    if (wave * 64 < n) {
+      int tok[2];
+      const unsigned char* xrow[2];
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      const int tt = wave * 2 + sub;
-      if (tt * 32 < n) {
-        const int tok = tt * 32 + l32;
-        const int tokc = tok < n ? tok : n - 1;
-        bf16x8 bx[4];
+      for (int sub = 0; sub < 2; ++sub) {
+        tok[sub] = (wave * 2 + sub) * 32 + l32;
+        xrow[sub] = tile + (tok[sub] < n ? tok[sub] : n - 1) * kLdsRowBytes + half * 16;
+      }
+      float best[2] = {-INFINITY, -INFINITY};
+      int bm[2] = {0, 0};
+      for (int dt = 0; dt < ndt; ++dt) {
+        asm volatile("" ::: "memory");   // keeps the reads of the token operands inside the loop
+        const int m = dt * 32 + l32;
+        const int drow = s_dpos[m < kd ? m : kd - 1];
+        f32x16 acc[2];
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-          bx[ks] = *(const bf16x8*)(tile + tokc * kLdsRowBytes + ks * 32 + half * 16);
-        float best = -INFINITY;
-        int bm = 0;
-        for (int dt = 0; dt < ndt; ++dt) {
-          const int m = dt * 32 + l32;
-          const int drow = s_dpos[m < kd ? m : kd - 1];
-          f32x16 acc;
+        for (int r = 0; r < 16; ++r) acc[0][r] = acc[1][r] = 0.f;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        for (int ks = 0; ks < 4; ++ks) {
+          const bf16x8 ad = *(const bf16x8*)(tile + drow * kLdsRowBytes + ks * 32 + half * 16);
 #pragma unroll
-          for (int ks = 0; ks < 4; ++ks) {
-            const bf16x8 ad = *(const bf16x8*)(tile + drow * kLdsRowBytes + ks * 32 + half * 16);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad, bx[ks], acc, 0, 0, 0);
-          }
-          // acc[r] = <dst row, token>, dst row = dt*32 + 8*(r/4) + 4*half + r%4, token = l32.
+          for (int sub = 0; sub < 2; ++sub)
+            acc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad, *(const bf16x8*)(xrow[sub] + ks * 32), acc[sub], 0, 0, 0);
+        }
+        // acc[sub][r] = <dst row, token>, dst row = dt*32 + 8*(r/4) + 4*half + r%4, token = l32 of the tile.
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int mb = dt * 32 + 8 * g + 4 * half;
-            const f32x4 dv = *(const f32x4*)(s_dinv + mb);   // mb is a multiple of 4: aligned
+        for (int g = 0; g < 4; ++g) {
+          const int mb = dt * 32 + 8 * g + 4 * half;
+          const f32x4 dv = *(const f32x4*)(s_dinv + mb);   // mb is a multiple of 4: aligned
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const float sc = acc[4 * g + q] * dv[q];
-              if (sc > best) {
-                best = sc;
-                bm = mb + q;
+          for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+              const float sc = acc[sub][4 * g + q] * dv[q];
+              if (sc > best[sub]) {
+                best[sub] = sc;
+                bm[sub] = mb + q;
               }
             }
           }
         }
-        const float ob = __shfl_xor(best, 32);
-        const int om = __shfl_xor(bm, 32);
-        if (ob > best || (ob == best && om < bm)) {
-          best = ob;
-          bm = om;
+      }
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        const float ob = __shfl_xor(best[sub], 32);
+        const int om = __shfl_xor(bm[sub], 32);
+        if (ob > best[sub] || (ob == best[sub] && om < bm[sub])) {
+          best[sub] = ob;
+          bm[sub] = om;
         }
-        // lanes 0..31 of sub-tile 0 and lanes 32..63 of sub-tile 1 publish, so that afterwards
-        // thread `tid` holds the result of token `tid`
-        if (half == sub && tok < n) {
-          int c = s_cl[tok];
-          float sc = 1.0f;
-          if (c < 0) {
-            c = bm;
-            sc = best * s_invn[tok];
-          }
-          my_cl = c;
-          my_sc = sc;
-          if (!TOPR) {
-            assign[tok] = it.moff + c;
-            if (score) score[tok] = sc;
-          }
+      }
+      // lanes 0..31 publish tile 0 and lanes 32..63 tile 1, so that afterwards thread `tid` holds
+      // the result of token `tid`
+      const int t = half ? tok[1] : tok[0];
+      if (t < n) {
+        int c = s_cl[t];
+        float sc = 1.0f;
+        if (c < 0) {
+          c = half ? bm[1] : bm[0];
+          sc = (half ? best[1] : best[0]) * s_invn[t];
+        }
+        my_cl = c;
+        my_sc = sc;
+        if (!TOPR) {
+          assign[t] = it.moff + c;
+          if (score) score[t] = sc;
         }
       }
     }
