@@ -33,15 +33,17 @@ namespace {
 // members of a cluster whose LDS reads the aggregation keeps in flight together (2, 6 and 8 measured slower)
 constexpr int kAggBatch = 4;
 
-// exclusive prefix sum over 64 lanes of a wave (lane i gets the sum of lanes < i)
-__device__ __forceinline__ int wave_exclusive_scan(int v, int lane) {
-  int incl = v;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const int up = __shfl_up(incl, d);
-    if (lane >= d) incl += up;
-  }
-  return incl - v;
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel primitives only (no LDS round
+// trips): shifts by 1, 2, 4 and 8 inside each row of 16 lanes (a lane without a source adds 0), then
+// the last lane of row 0 / 2 is added to row 1 / 3, and the last lane of row 1 to rows 2 and 3.
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);   // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);   // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);   // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);   // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);   // row_bcast:15 -> rows 1, 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);   // row_bcast:31 -> rows 2, 3
+  return v;
 }
 
 // Selectors (1, 0) and (0, 1) as bf16 pairs, pinned in vector registers: as an instruction
@@ -428,7 +430,10 @@ void match_merge_kernel(const MatchMergeArgs a) {
     if (my_cl >= 0 && my_rank == 0) s_wcnt[wave * MAXN + my_cl] = (uint8_t)__popcll(same);
   }
   __syncthreads();
-  if (wave == 0) {
+  {
+    // First list entry of every cluster.  Every wave computes all of them and writes them (the same
+    // values from every wave): a wave reads back only what it wrote itself, so no barrier is needed
+    // before the lists are filled, and nobody waits for one wave's scan.
     int carry = 0;
     for (int m0 = 0; m0 < k; m0 += 64) {
       const int m = m0 + lane;
@@ -437,13 +442,13 @@ void match_merge_kernel(const MatchMergeArgs a) {
 #pragma unroll
         for (int w = 0; w < NW; ++w) tot += s_wcnt[w * MAXN + m];
       }
-      const int excl = wave_exclusive_scan(tot, lane);
-      if (m < k) s_off[m] = (uint16_t)(carry + excl);
-      carry += __shfl(excl + tot, 63);
+      const int incl = wave_inclusive_scan(tot);
+      if (m < k) s_off[m] = (uint16_t)(carry + incl - tot);
+      carry += __builtin_amdgcn_readlane(incl, 63);
     }
     if (lane == 0) s_off[k] = (uint16_t)carry;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   }
-  __syncthreads();
   if (my_cl >= 0) {
     // position among the members of the cluster in ascending token order ...
     int rank = my_rank;
@@ -467,16 +472,22 @@ void match_merge_kernel(const MatchMergeArgs a) {
       for (int q = 0; q < 8; ++q) acc[q] = 0.f;
       // members in list order: the dst token, then its src tokens in ascending position
       const unsigned char* col = tile + c * 16;
-      // kAggBatch members per round: their list entries, then their rows, are requested together, so a
-      // round costs two LDS round trips; a slot past the end adds a zero row
+      // kAggBatch members per round: their rows are requested together, and with them the list
+      // entries of the next round, so that a round costs one LDS round trip; a slot past the end
+      // adds a zero row
       const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
-      for (int idx = beg; idx < end; idx += kAggBatch) {
-        int jj[kAggBatch];
+      int jj[kAggBatch];
 #pragma unroll
-        for (int u = 0; u < kAggBatch; ++u) jj[u] = s_list[idx + u < end ? idx + u : end - 1];
+      for (int u = 0; u < kAggBatch; ++u) jj[u] = s_list[beg + u < end ? beg + u : end - 1];
+      for (int idx = beg; idx < end; idx += kAggBatch) {
         bf16x8 w[kAggBatch];
 #pragma unroll
         for (int u = 0; u < kAggBatch; ++u) w[u] = *(const bf16x8*)(col + jj[u] * kLdsRowBytes);
+#pragma unroll
+        for (int u = 0; u < kAggBatch; ++u) {
+          const int nx = idx + kAggBatch + u;
+          jj[u] = s_list[nx < end ? nx : end - 1];
+        }
 #pragma unroll
         for (int u = 0; u < kAggBatch; ++u) add_row_chunk(acc, idx + u < end ? w[u] : zero8, sel);
       }
@@ -625,7 +636,10 @@ void outlier_refine_kernel(const RefineArgs a) {
     }
   }
   __syncthreads();
-  if (wave == 0) {
+  {
+    // First list entry of every cluster.  Every wave computes all of them and writes them (the same
+    // values from every wave): a wave reads back only what it wrote itself, so no barrier is needed
+    // before the lists are filled, and nobody waits for one wave's scan.
     int carry = 0;
     for (int m0 = 0; m0 < k; m0 += 64) {
       const int m = m0 + lane;
@@ -634,13 +648,13 @@ void outlier_refine_kernel(const RefineArgs a) {
 #pragma unroll
         for (int w = 0; w < NW; ++w) tot += s_wcnt[w * MAXN + m];
       }
-      const int excl = wave_exclusive_scan(tot, lane);
-      if (m < k) s_off[m] = (uint16_t)(carry + excl);
-      carry += __shfl(excl + tot, 63);
+      const int incl = wave_inclusive_scan(tot);
+      if (m < k) s_off[m] = (uint16_t)(carry + incl - tot);
+      carry += __builtin_amdgcn_readlane(incl, 63);
     }
     if (lane == 0) s_off[k] = (uint16_t)carry;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   }
-  __syncthreads();
   if (my_cl >= 0) {
     int rank = my_rank;
     for (int w = 0; w < wave; ++w) rank += s_wcnt[w * MAXN + my_cl];
