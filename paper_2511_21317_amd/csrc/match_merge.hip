@@ -30,6 +30,11 @@ namespace httm {
 
 namespace {
 
+// last word of a raw buffer descriptor on gfx9-family targets (32-bit data format, no swizzle, no
+// stride), and the cache-policy bit of a buffer load that marks it non-temporal
+constexpr int kRawBufferWord3 = 0x00020000;
+constexpr int kBufferNonTemporal = 2;
+
 // members of a cluster whose LDS reads the aggregation keeps in flight together (2, 6 and 8 measured slower)
 constexpr int kAggBatch = 4;
 
@@ -143,11 +148,17 @@ void match_merge_kernel(const MatchMergeArgs a) {
   int32_t* __restrict__ assign = s.assign + h * N + it.start;
   float* __restrict__ score = s.score ? s.score + h * N + it.start : nullptr;
 
-  // ---- all global loads up front -----------------------------------------------------------
+  // ---- the rows of x, all requested up front ---------------------------------------------------
   // First the source rows of all of this thread's chunks (one index load each when the tokens are
-  // still in the caller's order), then all row loads back to back: a wait for an index placed
-  // between the row loads would wait for the rows requested before it as well (the counter of
-  // outstanding loads is kept in issue order), and the rows would arrive one round trip after the other.
+  // still in the caller's order), then all row loads back to back: the counter of outstanding loads
+  // is kept in issue order, so a wait for an index placed between the row loads would make the rows
+  // arrive one round trip after the other.  The rows are read with buffer loads - a descriptor of
+  // the head's tensor in scalar registers plus a 32-bit byte offset per lane - because a slot past
+  // the item's last row can then be given the offset N * 128, which the descriptor's range check
+  // turns into zeros without a memory access: the requests are straight-line code.
+  // The rows of v are requested after the matching (their registers are free until then) and
+  // arrive while the clusters are sorted and x is aggregated.
+  const uint32_t head_bytes = (uint32_t)N * (uint32_t)kRowBytes;   // N < 2^25 is checked on the host
   uint32_t off[ITER];
   if (a.pi) {
 #pragma unroll
@@ -160,25 +171,23 @@ void match_merge_kernel(const MatchMergeArgs a) {
     for (int i = 0; i < ITER; ++i) off[i] = (uint32_t)(it.start + ((tid + i * NT) >> 3));
   }
 #pragma unroll
-  for (int i = 0; i < ITER; ++i) off[i] = off[i] * kRowBytes + (tid & 7) * 16;
+  for (int i = 0; i < ITER; ++i)
+    off[i] = ((tid + i * NT) >> 3) < n ? off[i] * kRowBytes + (tid & 7) * 16 : head_bytes;
   u32x4 xr[ITER], vr[ITER];
-  if (v) {
+  {
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, (int)head_bytes, kRawBufferWord3);
 #pragma unroll
-    for (int i = 0; i < ITER; ++i) {
-      if (((tid + i * NT) >> 3) < n) {
-        xr[i] = __builtin_nontemporal_load((const u32x4*)(x + off[i]));
-        vr[i] = __builtin_nontemporal_load((const u32x4*)(v + off[i]));
-      }
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < ITER; ++i) {
-      if (((tid + i * NT) >> 3) < n) xr[i] = __builtin_nontemporal_load((const u32x4*)(x + off[i]));
-    }
+    for (int i = 0; i < ITER; ++i) xr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off[i], 0, kBufferNonTemporal);
   }
+  auto request_v_rows = [&]() {
+    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void*)v, 0, (int)head_bytes, kRawBufferWord3);
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) vr[i] = __builtin_amdgcn_raw_buffer_load_b128(rv, (int)off[i], 0, kBufferNonTemporal);
+  };
 
   // ---- nothing to merge: copy ----------------------------------------------------------------
   if (k == n && (!TOPR || it.kd == n)) {
+    if (v) request_v_rows();
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
       const int e = tid + i * NT;
@@ -196,11 +205,11 @@ void match_merge_kernel(const MatchMergeArgs a) {
   }
 
   // ---- 1. rows to LDS, and their inverse norms ---------------------------------------------------
+  // (slots past the item's last row hold zeros and are written as well: the tile has MAXN rows)
 #pragma unroll
   for (int i = 0; i < ITER; ++i) {
     const int e = tid + i * NT;
-    const int row = e >> 3, c = e & 7;
-    if (row < n) *(u32x4*)(tile + row * kLdsRowBytes + c * 16) = xr[i];
+    *(u32x4*)(tile + (e >> 3) * kLdsRowBytes + (e & 7) * 16) = xr[i];
   }
   s_cl[tid] = -1;
   if (!s.preset) {
@@ -254,8 +263,7 @@ void match_merge_kernel(const MatchMergeArgs a) {
     // ---- 3. similarities and arg-max -----------------------------------------------------------
     // Wave w owns the tokens 64w .. 64w+63, i.e. the two 32-token tiles 2w and 2w+1.
     // The two tiles go through the dst tiles side by side: they share the dst operand and the dst
-    // norms, and their dependent chains of LDS reads overlap.  (The token operands are read again
-    // for every dst tile: registers are scarce, the V rows wait in them.)
+    // norms, and their dependent chains of LDS reads overlap.
     const int ndt = (kd + 31) >> 5;
     float my_sc = 1.0f;                // similarity of token `tid` to the dst it would join
     if (wave * 64 < n) {
@@ -269,7 +277,7 @@ void match_merge_kernel(const MatchMergeArgs a) {
       float best[2] = {-INFINITY, -INFINITY};
       int bm[2] = {0, 0};
       for (int dt = 0; dt < ndt; ++dt) {
-        asm volatile("" ::: "memory");   // keeps the reads of the token operands inside the loop
+        asm volatile("" ::: "memory");   // keeps the reads of the token operands inside the loop: registers
         const int m = dt * 32 + l32;
         const int drow = s_dpos[m < kd ? m : kd - 1];
         f32x16 acc[2];
@@ -410,6 +418,8 @@ void match_merge_kernel(const MatchMergeArgs a) {
     }
   }
 
+  if (v) request_v_rows();
+
   // ---- 4. stable counting sort of the tokens by cluster -----------------------------------------
   // Rank of a token among the tokens of its cluster inside its wave, and per-wave cluster sizes.
   // The set of lanes that hold the same cluster id is built bit by bit from wave ballots
@@ -462,72 +472,88 @@ void match_merge_kernel(const MatchMergeArgs a) {
 
   // ---- 5. aggregation: thread (cluster m, 16-byte chunk c) -----------------------------------------
   const PairSelectors sel = make_pair_selectors();
-  for (int pass = 0; pass < 2; ++pass) {
-    u32x4* __restrict__ out = pass == 0 ? xm : vm;
-    for (int mc = tid; mc < k * kRowChunks; mc += NT) {
-      const int m = mc >> 3, c = mc & 7;
-      const int beg = s_off[m], end = s_off[m + 1];
-      float acc[8];
+  // chunk c of the merged row of cluster m, mc = 8 * m + c, from the rows the tile holds (x: first)
+  auto merged_row = [&](const int mc, const bool first) -> u32x4 {
+    const int m = mc >> 3, c = mc & 7;
+    const int beg = s_off[m], end = s_off[m + 1];
+    float acc[8];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) acc[q] = 0.f;
-      // members in list order: the dst token, then its src tokens in ascending position
-      const unsigned char* col = tile + c * 16;
-      // kAggBatch members per round: their rows are requested together, and with them the list
-      // entries of the next round, so that a round costs one LDS round trip; a slot past the end
-      // adds a zero row
-      const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
-      int jj[kAggBatch];
+    for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+    // members in list order: the dst token, then its src tokens in ascending position
+    const unsigned char* col = tile + c * 16;
+    // kAggBatch members per round: their rows are requested together, and with them the list
+    // entries of the next round, so that a round costs one LDS round trip; a slot past the end
+    // adds a zero row
+    const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+    int jj[kAggBatch];
 #pragma unroll
-      for (int u = 0; u < kAggBatch; ++u) jj[u] = s_list[beg + u < end ? beg + u : end - 1];
-      for (int idx = beg; idx < end; idx += kAggBatch) {
-        bf16x8 w[kAggBatch];
+    for (int u = 0; u < kAggBatch; ++u) jj[u] = s_list[beg + u < end ? beg + u : end - 1];
+    for (int idx = beg; idx < end; idx += kAggBatch) {
+      bf16x8 w[kAggBatch];
 #pragma unroll
-        for (int u = 0; u < kAggBatch; ++u) w[u] = *(const bf16x8*)(col + jj[u] * kLdsRowBytes);
+      for (int u = 0; u < kAggBatch; ++u) w[u] = *(const bf16x8*)(col + jj[u] * kLdsRowBytes);
 #pragma unroll
-        for (int u = 0; u < kAggBatch; ++u) {
-          const int nx = idx + kAggBatch + u;
-          jj[u] = s_list[nx < end ? nx : end - 1];
-        }
-#pragma unroll
-        for (int u = 0; u < kAggBatch; ++u) add_row_chunk(acc, idx + u < end ? w[u] : zero8, sel);
+      for (int u = 0; u < kAggBatch; ++u) {
+        const int nx = idx + kAggBatch + u;
+        jj[u] = s_list[nx < end ? nx : end - 1];
       }
-      const float cnt = (float)(end - beg);
-      const float rcnt = 1.0f / cnt;
-      float mean[8];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) mean[q] = div_by_count(acc[q], cnt, rcnt);
-      const float f = pass == 0 ? s.xm_scale : 1.0f;   // 1 unless the keys carry the logit scale
-      u32x4 o;
+      for (int u = 0; u < kAggBatch; ++u) add_row_chunk(acc, idx + u < end ? w[u] : zero8, sel);
+    }
+    const float cnt = (float)(end - beg);
+    const float rcnt = 1.0f / cnt;
+    float mean[8];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(mean[2 * q] * f, mean[2 * q + 1] * f);
-      out[mc] = o;
-      if (s.eps && pass == 0) {
-        // Sec. 3.4 step 2: L2 distance of every constituent to the merged token (the fp32 mean);
-        // zero where nothing was merged.  The 8 lanes of a cluster hold 8 channels each.
-        float* __restrict__ eps = s.eps + h * N + it.start;
-        for (int i2 = beg; i2 < end; ++i2) {
-          const int j = s_list[i2];
-          const bf16x8 w = *(const bf16x8*)(col + j * kLdsRowBytes);
-          float d2 = 0.f;
+    for (int q = 0; q < 8; ++q) mean[q] = div_by_count(acc[q], cnt, rcnt);
+    const float f = first ? s.xm_scale : 1.0f;   // 1 unless the keys carry the logit scale
+    u32x4 o;
 #pragma unroll
-          for (int q = 0; q < 8; ++q) {
-            const float df = (float)w[q] - mean[q];
-            d2 = fmaf(df, df, d2);
-          }
-          d2 = sum_over_8_lanes(d2);
-          if (c == 0) eps[j] = end - beg >= 2 ? sqrtf(d2) : 0.f;
+    for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(mean[2 * q] * f, mean[2 * q + 1] * f);
+    if (s.eps && first) {
+      // Sec. 3.4 step 2: L2 distance of every constituent to the merged token (the fp32 mean);
+      // zero where nothing was merged.  The 8 lanes of a cluster hold 8 channels each.
+      float* __restrict__ eps = s.eps + h * N + it.start;
+      for (int i2 = beg; i2 < end; ++i2) {
+        const int j = s_list[i2];
+        const bf16x8 w = *(const bf16x8*)(col + j * kLdsRowBytes);
+        float d2 = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const float df = (float)w[q] - mean[q];
+          d2 = fmaf(df, df, d2);
         }
+        d2 = sum_over_8_lanes(d2);
+        if (c == 0) eps[j] = end - beg >= 2 ? sqrtf(d2) : 0.f;
       }
     }
-    if (pass == 1 || v == nullptr) break;
+    return o;
+  };
+  auto v_rows_to_lds = [&]() {
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
       const int e = tid + i * NT;
-      const int row = e >> 3, c = e & 7;
-      if (row < n) *(u32x4*)(tile + row * kLdsRowBytes + c * 16) = vr[i];
+      *(u32x4*)(tile + (e >> 3) * kLdsRowBytes + (e & 7) * 16) = vr[i];
     }
+  };
+  const int n_out = k * kRowChunks;
+  if (v && n_out <= NT) {
+    // One merged row chunk per thread (the usual case): it is stored only after the rows of v have
+    // gone to LDS - behind a store, the wait for those rows would wait for the store as well.
+    u32x4 o = {0, 0, 0, 0};
+    if (tid < n_out) o = merged_row(tid, true);
+    v_rows_to_lds();
+    if (tid < n_out) xm[tid] = o;
     __syncthreads();
+  } else {
+    for (int mc = tid; mc < n_out; mc += NT) xm[mc] = merged_row(mc, true);
+    if (v) {
+      v_rows_to_lds();
+      __syncthreads();
+    }
+  }
+  if (v) {
+    for (int mc = tid; mc < n_out; mc += NT) vm[mc] = merged_row(mc, false);
   }
 }
 
