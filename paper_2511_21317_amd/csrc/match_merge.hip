@@ -204,18 +204,32 @@ void match_merge_kernel(const MatchMergeArgs a) {
     return;
   }
 
-  // ---- 1. rows to LDS, and their inverse norms ---------------------------------------------------
+  // ---- 1. the table of the dst tokens, while the rows are on their way ------------------------------
+  const int kd = TOPR && !s.preset ? it.kd : k;   // dst tokens = clusters 0 .. kd-1
+  s_cl[tid] = -1;
+  __syncthreads();
+  for (int m = tid; m < kd; m += NT) {
+    const int p = dst_position(m, n, kd, it.n0);
+    s_dpos[m] = (uint16_t)p;
+    s_cl[p] = (int16_t)m;
+  }
+  // pad the last 32-wide dst tile with NaN: a NaN score never compares greater, so the arg-max
+  // below needs no bounds test
+  if (!s.preset)
+    for (int m = kd + tid; m < ((kd + 31) & ~31); m += NT) s_dinv[m] = __builtin_nanf("");
+  __syncthreads();
+
+  // ---- 2. rows to LDS, and their inverse norms ---------------------------------------------------
   // (slots past the item's last row hold zeros and are written as well: the tile has MAXN rows)
 #pragma unroll
   for (int i = 0; i < ITER; ++i) {
     const int e = tid + i * NT;
     *(u32x4*)(tile + (e >> 3) * kLdsRowBytes + (e & 7) * 16) = xr[i];
   }
-  s_cl[tid] = -1;
   if (!s.preset) {
-    // ---- 2. inverse norms, from the registers: the 8 lanes that hold the chunks of a row add their
-    // sums of squares; of the ITER rows a group of 8 lanes holds, lane c finishes the c-th (one
-    // square root and one division per thread)
+    // inverse norms, from the registers: the 8 lanes that hold the chunks of a row add their sums
+    // of squares; of the ITER rows a group of 8 lanes holds, lane c finishes the c-th (one square
+    // root and one division per thread) and, if the row is a dst token, files it under its cluster
     static_assert(ITER == kRowChunks, "one row per lane of a group");
     float mine = 0.f;
 #pragma unroll
@@ -230,7 +244,12 @@ void match_merge_kernel(const MatchMergeArgs a) {
       if ((tid & 7) == i) mine = ss;
     }
     const int row = (tid >> 3) + (NT >> 3) * (tid & 7);
-    if (row < n) s_invn[row] = 1.0f / fmaxf(sqrtf(mine), 1e-12f);
+    if (row < n) {
+      const float invn = 1.0f / fmaxf(sqrtf(mine), 1e-12f);
+      s_invn[row] = invn;
+      const int c = s_cl[row];
+      if (c >= 0) s_dinv[c] = invn;
+    }
   }
   __syncthreads();
 
@@ -239,27 +258,13 @@ void match_merge_kernel(const MatchMergeArgs a) {
 
   if (s.preset) {
     // Head-uniform variant: the clusters were computed once on the head-averaged tokens.
-    for (int m = tid; m < k; m += NT) s_dpos[m] = (uint16_t)dst_position(m, n, k, it.n0);
     if (tid < n) {
       const int32_t slot = s.preset[it.start + tid];
       my_cl = slot - it.moff;
       assign[tid] = slot;
       if (score) score[tid] = s.preset_score ? s.preset_score[it.start + tid] : 1.0f;
     }
-    __syncthreads();
   } else {
-    const int kd = TOPR ? it.kd : k;   // dst tokens = clusters 0 .. kd-1
-    for (int m = tid; m < kd; m += NT) {
-      const int p = dst_position(m, n, kd, it.n0);
-      s_dpos[m] = (uint16_t)p;
-      s_dinv[m] = s_invn[p];
-      s_cl[p] = (int16_t)m;
-    }
-    // pad the last 32-wide dst tile with NaN: a NaN score never compares greater, so the
-    // arg-max below needs no bounds test
-    for (int m = kd + tid; m < ((kd + 31) & ~31); m += NT) s_dinv[m] = __builtin_nanf("");
-    __syncthreads();
-
     // ---- 3. similarities and arg-max -----------------------------------------------------------
     // Wave w owns the tokens 64w .. 64w+63, i.e. the two 32-token tiles 2w and 2w+1.
     // The two tiles go through the dst tiles side by side: they share the dst operand and the dst
