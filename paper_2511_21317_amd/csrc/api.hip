@@ -84,6 +84,8 @@ int run_match_merge(const httm_plan_t* p, const int32_t* pi, const void* q, cons
   std::memset(&a, 0, sizeof(a));
   a.n_streams = 2;
   a.pi = pi;
+  a.tpf = g.n_special + g.Hp * g.Wp;
+  a.row_len = (g.flags & HTTM_FLAG_CHUNKED_BLOCKS) ? g.Hp * g.Wp : g.Wp;
   a.N = p->sizes.N;
   a.H = g.H;
   a.max_block = (int32_t)(p->sizes.max_block < kPrefixChunk ? kPrefixChunk : p->sizes.max_block);

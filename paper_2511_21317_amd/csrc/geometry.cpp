@@ -100,8 +100,8 @@ int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
   t.items_k.clear();
   for (int64_t p = 0; p < t.n_prefix; p += kPrefixChunk) {
     const int32_t n = (int32_t)((t.n_prefix - p) < kPrefixChunk ? (t.n_prefix - p) : kPrefixChunk);
-    t.items_q.push_back({(int32_t)p, n, n, (int32_t)p, 0, n, {0, 0}});
-    t.items_k.push_back({(int32_t)p, n, n, (int32_t)p, 0, n, {0, 0}});
+    t.items_q.push_back({(int32_t)p, n, n, (int32_t)p, 0, n, 0, 0});
+    t.items_k.push_back({(int32_t)p, n, n, (int32_t)p, 0, n, 0, 0});
   }
 
   int64_t mq = t.n_prefix, mk = t.n_prefix;
@@ -137,8 +137,22 @@ int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
         t.block_kk[bi] = kk;
         t.block_offq[bi] = (int32_t)mq;
         t.block_offk[bi] = (int32_t)mk;
-        t.items_q.push_back({(int32_t)pos, n, kq, (int32_t)mq, n0, kdq, {0, 0}});
-        t.items_k.push_back({(int32_t)pos, n, kk, (int32_t)mk, n0, kdk, {0, 0}});
+        const int32_t nx = x1 - x0, plane = (y1 - y0) * nx;
+        const int32_t src0 = f0 * tpf + g.n_special + y0 * row_len + x0;
+        int32_t dims = plane < 32768 ? (nx | (plane << 16)) : 0;
+        if (with_pi && dims) {
+          // the closed form is evaluated here the way the kernels evaluate it (fp32 quotients) and
+          // kept only if it reproduces the table
+          const float r_plane = 1.0f / (float)plane, r_nx = 1.0f / (float)nx;
+          for (int32_t r = 0; r < n && dims; ++r) {
+            const int32_t f = (int32_t)(((float)r + 0.5f) * r_plane);
+            const int32_t rem = r - f * plane;
+            const int32_t y = (int32_t)(((float)rem + 0.5f) * r_nx);
+            if (src0 + f * tpf + y * row_len + (rem - y * nx) != t.pi[pos + r]) dims = 0;
+          }
+        }
+        t.items_q.push_back({(int32_t)pos, n, kq, (int32_t)mq, n0, kdq, src0, dims});
+        t.items_k.push_back({(int32_t)pos, n, kk, (int32_t)mk, n0, kdk, src0, dims});
         mq += kq;
         mk += kk;
         pos += n;

@@ -21,7 +21,14 @@ struct WorkItem {
   int32_t moff;   // first merged slot
   int32_t n0;     // leading tokens that are always dst
   int32_t kd;     // clusters 0..kd-1 are the dst tokens; kd == k unless only the top-r src merge
-  int32_t pad[2];
+  // Closed form of the reorder inside the item, for kernels that read tokens in the caller's order
+  // (paper Sec. 3.3: a block is a run of frames x rows x columns of the patch grid, frame-major):
+  // token r of the item is the input token src0 + f * tpf + y * row_len + x with
+  // f = r / plane, y = (r % plane) / nx, x = r % nx, nx = dims & 0xFFFF, plane = dims >> 16
+  // (tpf = tokens per frame, row_len = slots per row of the patch grid).  dims == 0: no closed form
+  // (the special-token prefix), the reorder table pi is read instead.
+  int32_t src0;
+  int32_t dims;
 };
 
 struct HostTables {

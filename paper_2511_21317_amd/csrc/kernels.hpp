@@ -33,6 +33,8 @@ struct MatchMergeArgs {
   MatchMergeStream s[2];
   int32_t n_streams;
   const int32_t* pi;    // device; nullptr when x / v are already in reordered order
+  int32_t tpf;          // with pi: tokens per frame and slots per row of the patch grid, the strides of
+  int32_t row_len;      // the closed form of the reorder inside a work item (WorkItem.src0 / dims)
   int64_t N;
   int32_t H;
   int32_t max_block;

@@ -149,8 +149,8 @@ void match_merge_kernel(const MatchMergeArgs a) {
   float* __restrict__ score = s.score ? s.score + h * N + it.start : nullptr;
 
   // ---- the rows of x, all requested up front ---------------------------------------------------
-  // First the source rows of all of this thread's chunks (one index load each when the tokens are
-  // still in the caller's order), then all row loads back to back: the counter of outstanding loads
+  // First the source rows of all of this thread's chunks (when the tokens are still in the caller's
+  // order: from the closed form of the reorder, or one index load each), then all row loads back to back: the counter of outstanding loads
   // is kept in issue order, so a wait for an index placed between the row loads would make the rows
   // arrive one round trip after the other.  The rows are read with buffer loads - a descriptor of
   // the head's tensor in scalar registers plus a 32-bit byte offset per lane - because a slot past
@@ -160,7 +160,22 @@ void match_merge_kernel(const MatchMergeArgs a) {
   // arrive while the clusters are sorted and x is aggregated.
   const uint32_t head_bytes = (uint32_t)N * (uint32_t)kRowBytes;   // N < 2^25 is checked on the host
   uint32_t off[ITER];
-  if (a.pi) {
+  if (a.pi && it.dims) {
+    // the reorder in closed form (no index load in front of the row loads): row r of the item is
+    // frame r / plane, grid row (r % plane) / nx, column r % nx of the block; the quotients of these
+    // small integers are exact in fp32 with the half added (the true quotient of r + 1/2 is at
+    // least 1 / (2 * plane) away from every integer)
+    const int nx = it.dims & 0xFFFF, plane = it.dims >> 16;
+    const float r_plane = 1.0f / (float)plane, r_nx = 1.0f / (float)nx;
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      const int row = (tid + i * NT) >> 3;
+      const int f = (int)(((float)row + 0.5f) * r_plane);
+      const int rem = row - f * plane;
+      const int y = (int)(((float)rem + 0.5f) * r_nx);
+      off[i] = (uint32_t)(it.src0 + f * a.tpf + y * a.row_len + (rem - y * nx));
+    }
+  } else if (a.pi) {
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
       const int row = (tid + i * NT) >> 3;

@@ -543,7 +543,7 @@ hipError_t launch_global_match(const void* x, int64_t N, int H, int32_t kd, int3
   a.N = N;
   a.H = H;
   a.max_block = (int32_t)N;
-  a.single = {0, (int32_t)N, kd, 0, 0, kd, {0, 0}};
+  a.single = {0, (int32_t)N, kd, 0, 0, kd, 0, 0};
   a.s[0].x = x;
   a.s[0].assign = best;
   a.s[0].score = sim;
