@@ -133,6 +133,8 @@ int run_match_merge_filtered(const httm_plan_t* p, const void* q, const void* k,
   r.n_items = p->n_items;
   r.M = p->sizes.M_q;
   r.pi = p->d_pi;
+  r.tpf = p->geom.n_special + p->geom.Hp * p->geom.Wp;
+  r.row_len = (p->geom.flags & HTTM_FLAG_CHUNKED_BLOCKS) ? p->geom.Hp * p->geom.Wp : p->geom.Wp;
   r.N = p->sizes.N;
   r.H = p->geom.H;
   r.max_block = (int32_t)(p->sizes.max_block < kPrefixChunk ? kPrefixChunk : p->sizes.max_block);

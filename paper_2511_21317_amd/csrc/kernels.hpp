@@ -87,6 +87,7 @@ struct RefineArgs {
   int32_t n_items;
   int64_t M;
   const int32_t* pi;
+  int32_t tpf, row_len;   // as in MatchMergeArgs
   int64_t N;
   int32_t H;
   int32_t max_block;

@@ -106,6 +106,57 @@ __device__ __forceinline__ u32x4 scale_chunk(u32x4 w, float f) {
   return o;
 }
 
+// ---- requests for the token rows of a work item -------------------------------------------------
+// One thread stages ITER 16-byte chunks: chunk (tid & 7) of the rows (tid >> 3) + (NT / 8) * i.
+// First the byte offsets of all of them inside one head's tensor (when the tokens are still in the
+// caller's order: from the closed form of the reorder, or one index load each), then all row loads
+// back to back: the counter of outstanding loads is kept in issue order, so a wait for an index
+// placed between the row loads would make the rows arrive one round trip after the other.  The rows
+// are read with buffer loads - a descriptor of the head's tensor in scalar registers plus a 32-bit
+// byte offset per lane (N < 2^25 is checked on the host) - because a slot past the item's last row
+// can then be given the offset N * 128, which the descriptor's range check turns into zeros without
+// a memory access: the requests are straight-line code.
+template <int NT, int ITER>
+__device__ __forceinline__ void row_offsets(const int32_t* __restrict__ pi, int tpf, int row_len, const WorkItem& it,
+                                            int tid, uint32_t head_bytes, uint32_t (&off)[ITER]) {
+  const int n = it.n;
+  if (pi && it.dims) {
+    // the reorder in closed form: row r of the item is frame r / plane, grid row (r % plane) / nx,
+    // column r % nx of the block; the quotients of these small integers are exact in fp32 with the
+    // half added (the true quotient of r + 1/2 is at least 1 / (2 * plane) away from every integer)
+    const int nx = it.dims & 0xFFFF, plane = it.dims >> 16;
+    const float r_plane = 1.0f / (float)plane, r_nx = 1.0f / (float)nx;
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      const int row = (tid + i * NT) >> 3;
+      const int f = (int)(((float)row + 0.5f) * r_plane);
+      const int rem = row - f * plane;
+      const int y = (int)(((float)rem + 0.5f) * r_nx);
+      off[i] = (uint32_t)(it.src0 + f * tpf + y * row_len + (rem - y * nx));
+    }
+  } else if (pi) {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      const int row = (tid + i * NT) >> 3;
+      off[i] = row < n ? (uint32_t)pi[it.start + row] : 0u;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) off[i] = (uint32_t)(it.start + ((tid + i * NT) >> 3));
+  }
+#pragma unroll
+  for (int i = 0; i < ITER; ++i)
+    off[i] = ((tid + i * NT) >> 3) < n ? off[i] * kRowBytes + (tid & 7) * 16 : head_bytes;
+}
+
+template <int ITER>
+__device__ __forceinline__ void request_rows(const void* head_base, uint32_t head_bytes, const uint32_t (&off)[ITER],
+                                             u32x4 (&dst)[ITER]) {
+  const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)head_base, 0, (int)head_bytes, kRawBufferWord3);
+#pragma unroll
+  for (int i = 0; i < ITER; ++i) dst[i] = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off[i], 0, kBufferNonTemporal);
+}
+
 // TOPR: work items may have fewer dst tokens (WorkItem.kd) than clusters (k): the general rule of
 // Sec. 3.2, where only the n - k src tokens with the highest best-match similarity merge and the
 // other src tokens stay clusters of their own (a separate instantiation, so that the usual one
@@ -149,56 +200,14 @@ void match_merge_kernel(const MatchMergeArgs a) {
   float* __restrict__ score = s.score ? s.score + h * N + it.start : nullptr;
 
   // ---- the rows of x, all requested up front ---------------------------------------------------
-  // First the source rows of all of this thread's chunks (when the tokens are still in the caller's
-  // order: from the closed form of the reorder, or one index load each), then all row loads back to back: the counter of outstanding loads
-  // is kept in issue order, so a wait for an index placed between the row loads would make the rows
-  // arrive one round trip after the other.  The rows are read with buffer loads - a descriptor of
-  // the head's tensor in scalar registers plus a 32-bit byte offset per lane - because a slot past
-  // the item's last row can then be given the offset N * 128, which the descriptor's range check
-  // turns into zeros without a memory access: the requests are straight-line code.
   // The rows of v are requested after the matching (their registers are free until then) and
   // arrive while the clusters are sorted and x is aggregated.
-  const uint32_t head_bytes = (uint32_t)N * (uint32_t)kRowBytes;   // N < 2^25 is checked on the host
+  const uint32_t head_bytes = (uint32_t)N * (uint32_t)kRowBytes;
   uint32_t off[ITER];
-  if (a.pi && it.dims) {
-    // the reorder in closed form (no index load in front of the row loads): row r of the item is
-    // frame r / plane, grid row (r % plane) / nx, column r % nx of the block; the quotients of these
-    // small integers are exact in fp32 with the half added (the true quotient of r + 1/2 is at
-    // least 1 / (2 * plane) away from every integer)
-    const int nx = it.dims & 0xFFFF, plane = it.dims >> 16;
-    const float r_plane = 1.0f / (float)plane, r_nx = 1.0f / (float)nx;
-#pragma unroll
-    for (int i = 0; i < ITER; ++i) {
-      const int row = (tid + i * NT) >> 3;
-      const int f = (int)(((float)row + 0.5f) * r_plane);
-      const int rem = row - f * plane;
-      const int y = (int)(((float)rem + 0.5f) * r_nx);
-      off[i] = (uint32_t)(it.src0 + f * a.tpf + y * a.row_len + (rem - y * nx));
-    }
-  } else if (a.pi) {
-#pragma unroll
-    for (int i = 0; i < ITER; ++i) {
-      const int row = (tid + i * NT) >> 3;
-      off[i] = row < n ? (uint32_t)a.pi[it.start + row] : 0u;
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < ITER; ++i) off[i] = (uint32_t)(it.start + ((tid + i * NT) >> 3));
-  }
-#pragma unroll
-  for (int i = 0; i < ITER; ++i)
-    off[i] = ((tid + i * NT) >> 3) < n ? off[i] * kRowBytes + (tid & 7) * 16 : head_bytes;
+  row_offsets<NT, ITER>(a.pi, a.tpf, a.row_len, it, tid, head_bytes, off);
   u32x4 xr[ITER], vr[ITER];
-  {
-    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, (int)head_bytes, kRawBufferWord3);
-#pragma unroll
-    for (int i = 0; i < ITER; ++i) xr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off[i], 0, kBufferNonTemporal);
-  }
-  auto request_v_rows = [&]() {
-    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void*)v, 0, (int)head_bytes, kRawBufferWord3);
-#pragma unroll
-    for (int i = 0; i < ITER; ++i) vr[i] = __builtin_amdgcn_raw_buffer_load_b128(rv, (int)off[i], 0, kBufferNonTemporal);
-  };
+  request_rows<ITER>(x, head_bytes, off, xr);
+  auto request_v_rows = [&]() { request_rows<ITER>(v, head_bytes, off, vr); };
 
   // ---- nothing to merge: copy ----------------------------------------------------------------
   if (k == n && (!TOPR || it.kd == n)) {
@@ -612,24 +621,22 @@ void outlier_refine_kernel(const RefineArgs a) {
   // outliers are dense (`eager`: at least one per largest block on average), so that the row
   // latency does not queue behind the latency of the deviations; otherwise after the test.
   const char* __restrict__ x = (const char*)a.x + h * N * kRowBytes;
+  const uint32_t head_bytes = (uint32_t)N * (uint32_t)kRowBytes;
   u32x4 xr[ITER];
-#define HTTM_REFINE_ISSUE_ROW_LOADS()                                                             \
-  _Pragma("unroll") for (int i = 0; i < ITER; ++i) {                                              \
-    const int e = tid + i * NT;                                                                   \
-    const int row = e >> 3, c = e & 7;                                                            \
-    if (row < n) {                                                                                \
-      const uint32_t src = a.pi ? (uint32_t)a.pi[it.start + row] : (uint32_t)(it.start + row);    \
-      xr[i] = __builtin_nontemporal_load((const u32x4*)(x + src * kRowBytes + c * 16));           \
-    }                                                                                             \
+  uint32_t off[ITER];
+  if (a.eager) {
+    row_offsets<NT, ITER>(a.pi, a.tpf, a.row_len, it, tid, head_bytes, off);
+    request_rows<ITER>(x, head_bytes, off, xr);
   }
-  if (a.eager) HTTM_REFINE_ISSUE_ROW_LOADS()
   const float tau = a.b.state->tau;
   int cl = tid < n ? assign[tid] - it.moff : -1;   // cluster before the filter
   if (cl >= k) cl = -1;                            // (an entry that is not a slot of this item is left alone)
   const bool is_out = cl >= 0 && a.eps[h * N + it.start + tid] > tau;
   if (!__syncthreads_or(is_out)) return;
-  if (!a.eager) HTTM_REFINE_ISSUE_ROW_LOADS()
-#undef HTTM_REFINE_ISSUE_ROW_LOADS
+  if (!a.eager) {
+    row_offsets<NT, ITER>(a.pi, a.tpf, a.row_len, it, tid, head_bytes, off);
+    request_rows<ITER>(x, head_bytes, off, xr);
+  }
 
   // ---- rows to LDS ---------------------------------------------------------------------------------
   for (int m = tid; m < k; m += NT) {
