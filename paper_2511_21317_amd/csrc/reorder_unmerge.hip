@@ -25,20 +25,21 @@ __global__ __launch_bounds__(kThreads) void reorder_kernel(const u32x4* __restri
   const int r = threadIdx.x >> 3;
   const int64_t head_base = (int64_t)blockIdx.y * N * kRowChunks;
   const int64_t j0 = (int64_t)blockIdx.x * kRowsPerWg + r;
+  // All loads are unconditional (a slot past the last token reads token N-1 again and stores
+  // nothing): a load inside a branch is followed by a wait for everything outstanding, and the
+  // kUnroll rows of a thread would arrive one round trip after the other.
   int32_t idx[kUnroll];
   u32x4 val[kUnroll];
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const int64_t j = j0 + u * kRowsPerPass;
-    idx[u] = j < N ? pi[j] : 0;
+    idx[u] = pi[j < N ? j : N - 1];
   }
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const int64_t j = j0 + u * kRowsPerPass;
-    if (j < N) {
-      const int64_t row = DIR == 0 ? (int64_t)idx[u] : j;
-      val[u] = __builtin_nontemporal_load(&src[head_base + row * kRowChunks + c]);
-    }
+    const int64_t row = DIR == 0 ? (int64_t)idx[u] : (j < N ? j : N - 1);
+    val[u] = __builtin_nontemporal_load(&src[head_base + row * kRowChunks + c]);
   }
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
@@ -62,17 +63,17 @@ __global__ __launch_bounds__(kThreads) void unmerge_rows_kernel(const u32x4* __r
   const int64_t j0 = (int64_t)blockIdx.x * kRowsPerWg + r;
   int32_t idx[kUnroll];
   u32x4 val[kUnroll];
+  // (unconditional loads, as in reorder_kernel: one address per row, chosen before the load)
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const int64_t j = j0 + u * kRowsPerPass;
-    idx[u] = j < N ? assign[h * N + j] : 0;
+    idx[u] = assign[h * N + (j < N ? j : N - 1)];
   }
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
-    const int64_t j = j0 + u * kRowsPerPass;
-    if (j < N)
-      val[u] = idx[u] >= 0 ? o_m[(h * M_q + idx[u]) * kRowChunks + c]
-                           : o_out[(int64_t)(-1 - idx[u]) * kRowChunks + c];   // an outlier's own row
+    const u32x4* p = idx[u] >= 0 ? &o_m[(h * M_q + idx[u]) * kRowChunks + c]
+                                 : &o_out[(int64_t)(-1 - idx[u]) * kRowChunks + c];   // an outlier's own row
+    val[u] = *p;
   }
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
@@ -117,17 +118,16 @@ __global__ __launch_bounds__(kThreads) void unmerge_fused_kernel(const u32x4* __
   const int total = kTok * H;  // (token, head) rows of this tile, token-major
   for (int e0 = threadIdx.x >> 3; e0 < total; e0 += kRowsPerPass * kUnroll) {
     u32x4 val[kUnroll];
+    // (unconditional loads, as in reorder_kernel; a slot without a row reads row 0 of head 0)
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const int e = e0 + u * kRowsPerPass;
-      if (e < total) {
-        const int t = e / H, h = e % H;
-        if (j0 + t < N) {
-          const int32_t sl = s_assign[h * kTok + t];   // negative: row -1 - sl of the outlier outputs
-          val[u] = sl >= 0 ? o_m[((int64_t)h * M_q + sl) * kRowChunks + c]
-                           : o_out[(int64_t)(-1 - sl) * kRowChunks + c];
-        }
-      }
+      const int t = e / H, h = e % H;
+      const bool valid = e < total && j0 + t < N;
+      const int32_t sl = valid ? s_assign[h * kTok + t] : 0;   // negative: row -1 - sl of the outlier outputs
+      const u32x4* p = sl >= 0 ? &o_m[((int64_t)(valid ? h : 0) * M_q + sl) * kRowChunks + c]
+                               : &o_out[(int64_t)(-1 - sl) * kRowChunks + c];
+      val[u] = *p;
     }
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
