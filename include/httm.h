@@ -169,6 +169,17 @@ HTTM_API int httm_geom_sizes(const httm_geom_t* g, httm_sizes_t* out);
 HTTM_API int httm_geom_tables(const httm_geom_t* g, int32_t* pi, int32_t* block_start, int32_t* block_n,
                      int32_t* block_kq, int32_t* block_kk, int32_t* block_offq, int32_t* block_offk);
 
+/* The reorder inside every merging block in closed form, as the kernels that read tokens in the
+ * caller's order use it instead of pi (Sec. 3.3: a block is a run of frames x grid rows x columns,
+ * frame-major).  HOST arrays of n_blocks entries each, both required:
+ *   block_src0[b]   input position of the block's first token
+ *   block_dims[b]   n_x | (plane << 16): token r of the block is the input token
+ *                   block_src0[b] + (r / plane) * tpf + ((r % plane) / n_x) * row_len + r % n_x,
+ *                   tpf = n_special + Hp*Wp tokens per frame, row_len = Wp (Hp*Wp with
+ *                   HTTM_FLAG_CHUNKED_BLOCKS) slots per row of the patch grid;
+ *                   0 where the form does not reproduce pi (the kernels then read pi). */
+HTTM_API int httm_geom_block_forms(const httm_geom_t* g, int32_t* block_src0, int32_t* block_dims);
+
 /* ---- plan ---------------------------------------------------------------------------- */
 
 /* Build the index tables of *g on the current HIP device.  Allocates a few int32 per token of

@@ -60,6 +60,7 @@ def lib() -> C.CDLL:
     L.httm_geom_sizes.argtypes = [C.POINTER(Geom), C.POINTER(Sizes)]
     L.httm_workspace_layout.argtypes = [C.POINTER(Geom), C.POINTER(WorkspaceLayout)]
     L.httm_geom_tables.argtypes = [C.POINTER(Geom)] + [vp] * 7
+    L.httm_geom_block_forms.argtypes = [C.POINTER(Geom), vp, vp]
     L.httm_plan_create.argtypes = [C.POINTER(Geom), C.POINTER(vp)]
     L.httm_plan_destroy.argtypes = [vp]
     L.httm_plan_query.argtypes = [vp, C.POINTER(Sizes)]
@@ -75,7 +76,7 @@ def lib() -> C.CDLL:
     L.httm_unmerge_filtered.argtypes = [vp, vp, vp, i32p, vp, vp]
     L.httm_outlier_stats.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32), vp]
     L.httm_global_match.argtypes = [vp, C.c_int64, C.c_int, C.c_int, C.c_double, i32p, f32p, vp]
-    for name in ("httm_geom_sizes", "httm_workspace_layout", "httm_geom_tables", "httm_plan_create",
+    for name in ("httm_geom_sizes", "httm_workspace_layout", "httm_geom_tables", "httm_geom_block_forms", "httm_plan_create",
                  "httm_plan_destroy", "httm_plan_query", "httm_reorder", "httm_match_merge",
                  "httm_reorder_match_merge",
                  "httm_attention", "httm_attention_log2", "httm_unmerge", "httm_layer_forward",
@@ -134,6 +135,16 @@ def geom_tables(g: Geom) -> dict:
     _check(lib().httm_geom_tables(C.byref(g), ptr(out["pi"]), ptr(out["block_start"]),
                                   ptr(out["block_n"]), ptr(out["block_kq"]), ptr(out["block_kk"]),
                                   ptr(out["block_offq"]), ptr(out["block_offk"])), "httm_geom_tables")
+    return out
+
+
+def geom_block_forms(g: Geom) -> dict:
+    """The reorder inside every merging block in closed form (int32 NumPy arrays, no GPU needed)."""
+    s = geom_sizes(g)
+    out = {"block_src0": np.empty(s.n_blocks, np.int32), "block_dims": np.empty(s.n_blocks, np.int32)}
+    ptr = lambda a: a.ctypes.data_as(C.c_void_p)  # noqa: E731
+    _check(lib().httm_geom_block_forms(C.byref(g), ptr(out["block_src0"]), ptr(out["block_dims"])),
+           "httm_geom_block_forms")
     return out
 
 

@@ -210,6 +210,17 @@ int httm_geom_tables(const httm_geom_t* g, int32_t* pi, int32_t* block_start, in
   return HTTM_OK;
 }
 
+int httm_geom_block_forms(const httm_geom_t* g, int32_t* block_src0, int32_t* block_dims) {
+  if (!g || !block_src0 || !block_dims) return HTTM_E_INVALID_ARG;
+  HostTables t;
+  const int rc = build_tables(*g, true, &t);
+  if (rc != HTTM_OK) return rc;
+  const size_t nb = (size_t)t.n_blocks * sizeof(int32_t);
+  std::memcpy(block_src0, t.block_src0.data(), nb);
+  std::memcpy(block_dims, t.block_dims.data(), nb);
+  return HTTM_OK;
+}
+
 int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
   if (!g || !out) return HTTM_E_INVALID_ARG;
   *out = nullptr;

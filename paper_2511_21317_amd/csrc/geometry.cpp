@@ -86,7 +86,11 @@ int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
   t.block_kk.resize(t.n_blocks);
   t.block_offq.resize(t.n_blocks);
   t.block_offk.resize(t.n_blocks);
-  if (with_pi) t.pi.resize(t.N);
+  if (with_pi) {
+    t.pi.resize(t.N);
+    t.block_src0.resize(t.n_blocks);
+    t.block_dims.resize(t.n_blocks);
+  }
 
   // Special tokens first, frame-major.
   int64_t pos = 0;
@@ -150,6 +154,10 @@ int build_tables(const httm_geom_t& g, bool with_pi, HostTables* out) {
             const int32_t y = (int32_t)(((float)rem + 0.5f) * r_nx);
             if (src0 + f * tpf + y * row_len + (rem - y * nx) != t.pi[pos + r]) dims = 0;
           }
+        }
+        if (with_pi) {
+          t.block_src0[bi] = src0;
+          t.block_dims[bi] = dims;
         }
         t.items_q.push_back({(int32_t)pos, n, kq, (int32_t)mq, n0, kdq, src0, dims});
         t.items_k.push_back({(int32_t)pos, n, kk, (int32_t)mk, n0, kdk, src0, dims});

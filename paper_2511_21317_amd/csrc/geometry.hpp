@@ -38,6 +38,7 @@ struct HostTables {
   std::vector<int32_t> block_start;  // per real block
   std::vector<int32_t> block_n;
   std::vector<int32_t> block_kq, block_kk, block_offq, block_offk;
+  std::vector<int32_t> block_src0, block_dims;  // WorkItem.src0 / dims of every real block (with pi only)
   std::vector<WorkItem> items_q, items_k;  // prefix pseudo-blocks followed by the real blocks
 };
 

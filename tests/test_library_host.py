@@ -71,6 +71,31 @@ def test_host_tables_match_oracle(case, anchor):
     assert all(getattr(w, f) % 256 == 0 for f in ("q_m", "k_m", "v_m", "o_m", "assign_q", "assign_k"))
 
 
+@pytest.mark.parametrize("anchor", [False, True], ids=["plain", "anchored"])
+@pytest.mark.parametrize("case", GEOMS + CHUNKED_GEOMS + [(200, 37, 37, 8, 4, 0.9, 0.9), (7, 9, 5, 4, 3, 0.5, 0.5)])
+def test_closed_form_of_the_reorder_inside_a_block(case, anchor):
+    """Sec. 3.3: a block is frames x grid rows x columns, frame-major.  The kernels that read tokens in
+    the caller's order use that closed form instead of pi; here it is evaluated with integer
+    arithmetic for every token of every block and compared with the oracle's permutation, and every
+    block must have one (else the kernels would fall back to index loads)."""
+    S, Hp, Wp, b, T, rq, rk = case
+    chunked = case in CHUNKED_GEOMS
+    g = httm.make_geom(S, Hp, Wp, b, T, rq, rk, anchor_first_frame=anchor, chunked_blocks=chunked)
+    og = orc.Geometry(S, Hp, Wp, b, T, anchor=anchor, chunked=chunked)
+    pi, blocks = orc.temporal_reorder(og)
+    f = httm.geom_block_forms(g)
+    assert len(blocks) == len(f["block_dims"]) and (f["block_dims"] != 0).all()
+    tpf = og.n_special + Hp * Wp
+    row_len = Hp * Wp if chunked else Wp
+    for (start, n), src0, dims in zip(blocks, f["block_src0"].tolist(), f["block_dims"].tolist()):
+        nx, plane = dims & 0xFFFF, dims >> 16
+        r = np.arange(n)
+        want = src0 + (r // plane) * tpf + ((r % plane) // nx) * row_len + r % nx
+        assert np.array_equal(want, pi[start:start + n])
+    L = httm.lib()
+    assert L.httm_geom_block_forms(C.byref(g), None, None) == -1
+
+
 def test_merged_lengths_of_the_five_workloads():
     want = {1: 266, 2: 5516, 3: 6376, 4: 28650, 5: 28700}   # tests/golden/merged_counts.txt
     import synth
