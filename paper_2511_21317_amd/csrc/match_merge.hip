@@ -169,7 +169,8 @@ void match_merge_kernel(const MatchMergeArgs a) {
   static_assert(MAXN * kRowChunks % NT == 0, "tile must divide among the threads");
   static_assert(NT == MAXN, "one thread per token");
 
-  __shared__ __align__(16) unsigned char tile[MAXN * kLdsRowBytes];
+  // (row MAXN stays zero: the aggregation reads it for the slots of a round that have no member)
+  __shared__ __align__(16) unsigned char tile[(MAXN + 1) * kLdsRowBytes];
   // phase A (matching): inverse norms of all tokens / of the dst tokens
   // phase B (aggregation): member lists - the same storage, the phases are separated by barriers
   // (TOPR: the selection's 256-bin histogram and a few words, between the two phases)
@@ -231,6 +232,7 @@ void match_merge_kernel(const MatchMergeArgs a) {
   // ---- 1. the table of the dst tokens, while the rows are on their way ------------------------------
   const int kd = TOPR && !s.preset ? it.kd : k;   // dst tokens = clusters 0 .. kd-1
   s_cl[tid] = -1;
+  if (tid < kLdsRowBytes / 16) *(u32x4*)(tile + MAXN * kLdsRowBytes + tid * 16) = u32x4{0, 0, 0, 0};
   __syncthreads();
   for (int m = tid; m < kd; m += NT) {
     const int p = dst_position(m, n, kd, it.n0);
@@ -511,23 +513,28 @@ void match_merge_kernel(const MatchMergeArgs a) {
     // members in list order: the dst token, then its src tokens in ascending position
     const unsigned char* col = tile + c * 16;
     // kAggBatch members per round: their rows are requested together, and with them the list
-    // entries of the next round, so that a round costs one LDS round trip; a slot past the end
-    // adds a zero row
-    const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+    // entries of the next round, so that a round costs one LDS round trip.  A slot past the end of
+    // the cluster reads the tile's zero row - one select on the row number instead of four on the
+    // row's registers, and the list is read without a clamp (the entries behind a cluster's end are
+    // other clusters' members or, behind the last one, the words that follow the list in LDS:
+    // read, never used).  The kernel is bound by vector instruction issue; these loops are most of it.
     int jj[kAggBatch];
 #pragma unroll
-    for (int u = 0; u < kAggBatch; ++u) jj[u] = s_list[beg + u < end ? beg + u : end - 1];
+    for (int u = 0; u < kAggBatch; ++u) {
+      const int e = s_list[beg + u];
+      jj[u] = beg + u < end ? e : MAXN;
+    }
     for (int idx = beg; idx < end; idx += kAggBatch) {
       bf16x8 w[kAggBatch];
 #pragma unroll
       for (int u = 0; u < kAggBatch; ++u) w[u] = *(const bf16x8*)(col + jj[u] * kLdsRowBytes);
 #pragma unroll
       for (int u = 0; u < kAggBatch; ++u) {
-        const int nx = idx + kAggBatch + u;
-        jj[u] = s_list[nx < end ? nx : end - 1];
+        const int e = s_list[idx + kAggBatch + u];
+        jj[u] = idx + kAggBatch + u < end ? e : MAXN;
       }
 #pragma unroll
-      for (int u = 0; u < kAggBatch; ++u) add_row_chunk(acc, idx + u < end ? w[u] : zero8, sel);
+      for (int u = 0; u < kAggBatch; ++u) add_row_chunk(acc, w[u], sel);
     }
     const float cnt = (float)(end - beg);
     const float rcnt = 1.0f / cnt;
