@@ -179,8 +179,9 @@ def main():
             plan, qr, kr, vr, views["q_m"], views["k_m"], views["v_m"], views["assign_q"], views["assign_k"]), it)
         del kr, vr
     if LK:
+        # (with the workspace's scratch region, as httm_layer_forward runs it)
         t_attn = gpu_time_ms(lambda: httm.attention_log2(views["q_m"], views["k_m"], views["v_m"], views["o_m"],
-                                                         q_off, k_off), it)
+                                                         q_off, k_off, scratch=views["attn_split"]), it)
     else:
         t_attn = gpu_time_ms(lambda: httm.attention(views["q_m"], views["k_m"], views["v_m"], views["o_m"],
                                                     q_off, k_off, 0.125), it)

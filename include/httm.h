@@ -258,6 +258,18 @@ HTTM_API int httm_attention_log2(const void* q_m, const void* k_log2, const void
                                  const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
                                  void* stream);
 
+/* httm_attention_log2 with scratch memory (device, 16-byte aligned, scratch_bytes >=
+ * httm_attention_scratch_bytes(H); its contents before and after the call are meaningless).  With
+ * it, a long launch runs the partial last 256-row query tile of every head in pieces over the keys
+ * and adds the pieces up afterwards, so that the launch does not end on a few CUs running one more
+ * whole tile than the others; the results agree with httm_attention_log2 to fp32 rounding of the
+ * sums (the pieces are added in key order, run-to-run identical).  httm_layer_forward does the same
+ * with the attn_split region of its workspace. */
+HTTM_API int64_t httm_attention_scratch_bytes(int H);
+HTTM_API int httm_attention_log2_scratch(const void* q_m, const void* k_log2, const void* v_m, void* o_m,
+                                         const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
+                                         void* scratch, int64_t scratch_bytes, void* stream);
+
 /* ---- stage 4: unmerge (Sec. 3.2 Eq. 5-7) and inverse reorder (Sec. 3.3) ------------------ */
 
 /* o_m      : [H, M_q, d_head] bf16, attention output per merged query.
@@ -282,9 +294,10 @@ HTTM_API int httm_layer_forward(const httm_plan_t* plan, const void* q, const vo
                        void* out, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Byte offsets of the regions inside the workspace (host only).  eps_q, q_out and o_out have size
- * zero unless outlier filtering is on. */
+ * zero unless outlier filtering is on; attn_split (httm_attention_scratch_bytes(H) bytes) is the
+ * scratch region of stage 3. */
 typedef struct httm_workspace_layout {
-  int64_t q_m, k_m, v_m, o_m, assign_q, assign_k, eps_q, q_out, o_out, total;
+  int64_t q_m, k_m, v_m, o_m, assign_q, assign_k, eps_q, q_out, o_out, attn_split, total;
 } httm_workspace_layout_t;
 HTTM_API int httm_workspace_layout(const httm_geom_t* g, httm_workspace_layout_t* out);
 

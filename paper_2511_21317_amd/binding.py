@@ -37,7 +37,7 @@ class Sizes(C.Structure):
 
 class WorkspaceLayout(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("q_m", "k_m", "v_m", "o_m", "assign_q", "assign_k", "eps_q",
-                                         "q_out", "o_out", "total")]
+                                         "q_out", "o_out", "attn_split", "total")]
 
 
 _lib = None
@@ -69,6 +69,9 @@ def lib() -> C.CDLL:
     L.httm_reorder_match_merge.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, i32p, f32p, f32p, vp]
     L.httm_attention.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, C.c_float, vp]
     L.httm_attention_log2.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, vp]
+    L.httm_attention_log2_scratch.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, vp, C.c_int64, vp]
+    L.httm_attention_scratch_bytes.argtypes = [C.c_int]
+    L.httm_attention_scratch_bytes.restype = C.c_int64
     L.httm_unmerge.argtypes = [vp, vp, i32p, vp, C.c_int, vp]
     L.httm_layer_forward.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     L.httm_reorder_match_merge_filtered.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, i32p, f32p, vp, vp]
@@ -79,7 +82,7 @@ def lib() -> C.CDLL:
     for name in ("httm_geom_sizes", "httm_workspace_layout", "httm_geom_tables", "httm_geom_block_forms", "httm_plan_create",
                  "httm_plan_destroy", "httm_plan_query", "httm_reorder", "httm_match_merge",
                  "httm_reorder_match_merge",
-                 "httm_attention", "httm_attention_log2", "httm_unmerge", "httm_layer_forward",
+                 "httm_attention", "httm_attention_log2", "httm_attention_log2_scratch", "httm_unmerge", "httm_layer_forward",
                  "httm_reorder_match_merge_filtered", "httm_attention_outliers", "httm_unmerge_filtered",
                  "httm_outlier_stats", "httm_global_match"):
         getattr(L, name).restype = C.c_int
@@ -241,14 +244,24 @@ def attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, scale: float = 0.125):
     return o_m
 
 
-def attention_log2(q_m, k_log2, v_m, o_m, q_offsets, k_offsets):
-    """As attention(), for keys that carry the factor LOG2_KEY_SCALE (a plan with log2_keys)."""
+def attention_scratch_bytes(H: int) -> int:
+    return int(lib().httm_attention_scratch_bytes(int(H)))
+
+
+def attention_log2(q_m, k_log2, v_m, o_m, q_offsets, k_offsets, scratch=None):
+    """As attention(), for keys that carry the factor LOG2_KEY_SCALE (a plan with log2_keys).
+    scratch: a uint8 device tensor of at least attention_scratch_bytes(H) bytes, or None."""
     H = len(q_offsets) - 1
     qo = (C.c_int64 * (H + 1))(*[int(x) for x in q_offsets])
     ko = (C.c_int64 * (H + 1))(*[int(x) for x in k_offsets])
     bf = torch.bfloat16
-    _check(lib().httm_attention_log2(_dev(q_m, bf), _dev(k_log2, bf), _dev(v_m, bf), _dev(o_m, bf), qo, ko,
-                                     H, 64, _stream()), "httm_attention_log2")
+    if scratch is None:
+        _check(lib().httm_attention_log2(_dev(q_m, bf), _dev(k_log2, bf), _dev(v_m, bf), _dev(o_m, bf), qo, ko,
+                                         H, 64, _stream()), "httm_attention_log2")
+    else:
+        _check(lib().httm_attention_log2_scratch(_dev(q_m, bf), _dev(k_log2, bf), _dev(v_m, bf), _dev(o_m, bf),
+                                                 qo, ko, H, 64, _dev(scratch, torch.uint8),
+                                                 scratch.numel(), _stream()), "httm_attention_log2_scratch")
     return o_m
 
 
@@ -274,7 +287,7 @@ def layer_forward(plan: Plan, q, k, v, out, workspace):
 
 
 def workspace_views(plan: Plan, workspace: torch.Tensor) -> dict:
-    """Typed views of the six regions httm_layer_forward leaves in the workspace."""
+    """Typed views of the regions of the workspace of httm_layer_forward."""
     L, H, N = plan.layout, plan.H, plan.N
     def bf(off, rows):
         return workspace[off:off + H * rows * 128].view(torch.bfloat16).view(H, rows, 64)
@@ -287,6 +300,7 @@ def workspace_views(plan: Plan, workspace: torch.Tensor) -> dict:
         views["eps_q"] = workspace[L.eps_q:L.eps_q + H * N * 4].view(torch.float32).view(H, N)
         views["q_out"] = workspace[L.q_out:L.q_out + cap * 128].view(torch.bfloat16).view(cap, 64)
         views["o_out"] = workspace[L.o_out:L.o_out + cap * 128].view(torch.bfloat16).view(cap, 64)
+    views["attn_split"] = workspace[L.attn_split:L.attn_split + attention_scratch_bytes(H)]   # stage 3's scratch
     return views
 
 

@@ -354,10 +354,12 @@ int httm_attention(const void* q_m, const void* k_m, const void* v_m, void* o_m,
   return HTTM_OK;
 }
 
-int httm_attention_log2(const void* q_m, const void* k_log2, const void* v_m, void* o_m,
-                        const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
-                        void* stream) {
+int httm_attention_log2_scratch(const void* q_m, const void* k_log2, const void* v_m, void* o_m,
+                                const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
+                                void* scratch, int64_t scratch_bytes, void* stream) {
   if (!q_offsets || !k_offsets || H <= 0) return HTTM_E_INVALID_ARG;
+  if (scratch && (!aligned16(scratch) || scratch_bytes < attention_scratch_bytes(H < HTTM_MAX_HEADS ? H : HTTM_MAX_HEADS)))
+    return HTTM_E_INVALID_ARG;
   if (d_head != 64 || H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
   for (int h = 0; h < H; ++h)
     if (q_offsets[h + 1] < q_offsets[h] || k_offsets[h + 1] < k_offsets[h] ||
@@ -369,9 +371,18 @@ int httm_attention_log2(const void* q_m, const void* k_log2, const void* v_m, vo
   if (any_q && (!q_m || !o_m)) return HTTM_E_INVALID_ARG;
   if (any_q && any_k && (!k_log2 || !v_m)) return HTTM_E_INVALID_ARG;
   if (!aligned16(q_m) || !aligned16(k_log2) || !aligned16(v_m) || !aligned16(o_m)) return HTTM_E_INVALID_ARG;
-  HTTM_HIP(launch_attention(q_m, k_log2, v_m, o_m, q_offsets, k_offsets, H, 1.0f, true, (hipStream_t)stream));
+  HTTM_HIP(launch_attention(q_m, k_log2, v_m, o_m, q_offsets, k_offsets, H, 1.0f, true, (hipStream_t)stream,
+                            scratch, scratch_bytes));
   return HTTM_OK;
 }
+
+int httm_attention_log2(const void* q_m, const void* k_log2, const void* v_m, void* o_m,
+                        const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
+                        void* stream) {
+  return httm_attention_log2_scratch(q_m, k_log2, v_m, o_m, q_offsets, k_offsets, H, d_head, nullptr, 0, stream);
+}
+
+int64_t httm_attention_scratch_bytes(int H) { return H > 0 && H <= HTTM_MAX_HEADS ? attention_scratch_bytes(H) : 0; }
 
 int httm_unmerge(const httm_plan_t* p, const void* o_m, const int32_t* assign_q, void* out,
                  int fuse_inverse_reorder, void* stream) {
@@ -416,9 +427,11 @@ int httm_layer_forward(const httm_plan_t* p, const void* q, const void* k, const
   if (filtered) {
     // Alg. 1: the outlier queries attend on their own - same launch, workgroups appended to the grid
     HTTM_HIP(launch_attention_both(q_m, k_m, v_m, o_m, q_off, k_off, H, 0.125f, q_out, o_out, p->ob.offsets,
-                                   p->ob.tiles, p->ob.max_tiles, log2_keys(p), st));
+                                   p->ob.tiles, p->ob.max_tiles, log2_keys(p), st, ws + p->ws.attn_split,
+                                   attention_scratch_bytes(H)));
   } else {
-    HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_off, k_off, H, 0.125f, log2_keys(p), st));
+    HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_off, k_off, H, 0.125f, log2_keys(p), st, ws + p->ws.attn_split,
+                              attention_scratch_bytes(H)));
   }
   // Stage 4 with the inverse reorder fused.
   HTTM_HIP(launch_unmerge(o_m, assign_q, p->d_pi, out, H, p->sizes.N, p->sizes.M_q, 1, st,

@@ -98,7 +98,21 @@ struct AttnArgs {
   const bf16_t* q2;
   bf16_t* o2;
   int32_t dev_first_block;
+  // Fast kernel only: the partial last tiles of the heads split over the keys.  The first
+  // split_blocks workgroups (a multiple of 8) are pieces: block b is piece b % kSplitPieces of
+  // partial tile b / kSplitPieces, takes an equal share of its head's key tiles and writes
+  // unnormalised fp32 results, which attention_split_reduce_kernel adds up.  The other workgroups
+  // then number from split_blocks on and there is no partial tile among them (ragged_per_xcd = 0).
+  int32_t split_blocks;
+  float* split_o;   // [n_ragged * kSplitPieces * BQ][64] sums of weight * v
+  float* split_l;   // [n_ragged * kSplitPieces * BQ]     sums of weights
 };
+
+// Pieces per partial tile.  A launch ends when its last workgroup ends, and a CU runs whole tiles:
+// with 7 tiles per CU and 16 partial tiles on top, 16 CUs run an eighth tile while the others
+// idle (measured 2.80 against 2.55 ms without the partial tiles).  Cut into 16 pieces that run
+// first, the partial tiles cost every CU about a sixteenth of a tile instead.
+constexpr int kSplitPieces = kAttnSplitPieces;
 
 // V tile in LDS: 64 rows of 128 bytes, written by global->LDS loads like the K tile; the 16-byte
 // chunk c of row r sits at chunk position c ^ (2 * (r & 3)), so that the four rows a transposing read
@@ -447,13 +461,27 @@ void attention_kernel(const AttnArgs a) {
   // blockIdx order to free slots; the partial last tiles of the heads come first (they are
   // short, so they should not be what the grid ends on), then every XCD walks a contiguous
   // range of full tiles.
-  const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+  int block = (int)blockIdx.x;
+  int piece = -1, piece_tile = 0;               // a piece of a partial tile (fast kernel only)
+  if (!SHIFT && a.split_blocks) {
+    if (block < a.split_blocks) {
+      piece = block % kSplitPieces;
+      piece_tile = block / kSplitPieces;
+      if (piece_tile >= a.n_ragged) return;
+    } else {
+      block -= a.split_blocks;
+    }
+  }
+  const int xcd = block & 7, idx = block >> 3;
   int h = 0, q0;
   int64_t q_base_dev = 0;
   int mq_dev = 0;
-  const bool dev_tile = a.dev_tiles && (int)blockIdx.x >= a.dev_first_block;
-  if (dev_tile) {
-    const int t = (int)blockIdx.x - a.dev_first_block;
+  const bool dev_tile = piece < 0 && a.dev_tiles && block >= a.dev_first_block;
+  if (piece >= 0) {
+    h = a.ragged_head[piece_tile];
+    q0 = (a.tile_start[h + 1] - a.tile_start[h]) * BQ;
+  } else if (dev_tile) {
+    const int t = block - a.dev_first_block;
     if (t >= a.dev_tiles[0]) return;
     h = a.dev_tiles[1 + 2 * t];
     q0 = a.dev_tiles[2 + 2 * t];
@@ -470,15 +498,30 @@ void attention_kernel(const AttnArgs a) {
     while (tile >= a.tile_start[h + 1]) ++h;
     q0 = (tile - a.tile_start[h]) * BQ;
   }
-  const int64_t q_base = dev_tile ? q_base_dev : a.q_off[h], k_base = a.k_off[h];
+  const int64_t q_base = dev_tile ? q_base_dev : a.q_off[h];
+  int64_t k_base = a.k_off[h];
   const int Mq = dev_tile ? mq_dev : (int)(a.q_off[h + 1] - q_base);
   const bf16_t* __restrict__ q_rows = dev_tile ? a.q2 : a.q;
   bf16_t* __restrict__ o_rows = dev_tile ? a.o2 : a.o;
-  const int Mk = (int)(a.k_off[h + 1] - k_base);
+  int Mk = (int)(a.k_off[h + 1] - k_base);
   uint16_t* mark = (uint16_t*)(o_rows + (q_base + q0) * kDHead);
   if (SHIFT && a.marked_only && (Mk == 0 || *(volatile const uint16_t*)mark != kRedoMark)) return;
 
   const int tid = threadIdx.x, lane = tid & 63;
+  // a piece sees its share of the key tiles as the whole key sequence
+  const int64_t piece_row0 = ((int64_t)piece_tile * kSplitPieces + (piece < 0 ? 0 : piece)) * BQ;
+  if (piece >= 0) {
+    const int nt = (Mk + kKvTile - 1) / kKvTile, tpp = (nt + kSplitPieces - 1) / kSplitPieces;
+    const int t0 = piece * tpp, t1 = t0 + tpp < nt ? t0 + tpp : nt;
+    if (t0 >= t1) {   // no key tile left for this piece: it contributes zeros
+      for (int e = tid; e < (Mq - q0) * (kDHead / 4); e += NT)
+        ((f32x4*)(a.split_o + piece_row0 * kDHead))[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int e = tid; e < Mq - q0; e += NT) a.split_l[piece_row0 + e] = 0.f;
+      return;
+    }
+    k_base += (int64_t)t0 * kKvTile;
+    Mk = (t1 * kKvTile < Mk ? t1 * kKvTile : Mk) - t0 * kKvTile;
+  }
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS destinations stay scalar
   const int l32 = lane & 31, half = lane >> 5;
   const int wq0 = q0 + wave * 32 * QT;  // first query row of this wave
@@ -649,6 +692,27 @@ void attention_kernel(const AttnArgs a) {
       l_tot[qt] = l32 < 16 ? s0 : s1;
     }
   }
+  if (!SHIFT && piece >= 0) {
+    // a piece: unnormalised sums for attention_split_reduce_kernel (which also tests the row sums)
+    if (active) {
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) {
+        const int row = wq0 + qt * 32 + l32;
+        if (row < Mq) {
+          float* po = a.split_o + (piece_row0 + (row - q0)) * kDHead;
+#pragma unroll
+          for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+              *(f32x4*)(po + dt * 32 + 8 * g + 4 * half) =
+                  f32x4{w.o_acc[dt][qt][4 * g], w.o_acc[dt][qt][4 * g + 1], w.o_acc[dt][qt][4 * g + 2],
+                        w.o_acc[dt][qt][4 * g + 3]};
+          if (half == 0) a.split_l[piece_row0 + (row - q0)] = l_tot[qt];
+        }
+      }
+    }
+    return;
+  }
   if (!SHIFT) {
     // Rare: a row of this tile left the range in which unshifted weights are safe.  The whole
     // workgroup (its tiles are staged together) leaves the tile to the kernel with per-row shifts.
@@ -681,11 +745,67 @@ void attention_kernel(const AttnArgs a) {
   }
 }
 
+// The partial tiles after the fast kernel ran them in pieces: one workgroup per partial tile adds the
+// pieces in ascending key order, tests the row sums like the fast kernel does (a tile with a row
+// outside the window gets the mark and is redone by the kernel with per-row shifts), normalises and
+// stores.
+template <int BQ>
+__global__ __launch_bounds__(256) void attention_split_reduce_kernel(const AttnArgs a) {
+  __shared__ float s_inv[BQ];
+  const int i = blockIdx.x, tid = threadIdx.x;
+  const int h = a.ragged_head[i];
+  const int q0 = (a.tile_start[h + 1] - a.tile_start[h]) * BQ;
+  const int64_t q_base = a.q_off[h];
+  const int rows = (int)(a.q_off[h + 1] - q_base) - q0;
+  const int64_t base = (int64_t)i * kSplitPieces * BQ;
+  bool bad = false;
+  for (int r = tid; r < rows; r += 256) {
+    float l = 0.f;
+#pragma unroll
+    for (int p = 0; p < kSplitPieces; ++p) l += a.split_l[base + (int64_t)p * BQ + r];
+    bad = bad || !(l >= kFastSumMin && l <= kFastSumMax);
+    s_inv[r] = 1.0f / l;
+  }
+  uint16_t* mark = (uint16_t*)(a.o + (q_base + q0) * kDHead);
+  if (__syncthreads_or(bad)) {
+    if (tid == 0) *mark = kRedoMark;
+    return;
+  }
+  for (int e = tid; e < rows * kRowChunks; e += 256) {
+    const int r = e >> 3, c = e & 7;
+    float acc[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+#pragma unroll
+    for (int p = 0; p < kSplitPieces; ++p) {
+      const float* po = a.split_o + (base + (int64_t)p * BQ + r) * kDHead + c * 8;
+      const f32x4 lo = *(const f32x4*)po, hi = *(const f32x4*)(po + 4);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        acc[q] += lo[q];
+        acc[4 + q] += hi[q];
+      }
+    }
+    const float inv = s_inv[r];
+    u32x4 o;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(acc[2 * q] * inv, acc[2 * q + 1] * inv);
+    ((u32x4*)a.o)[(q_base + q0 + r) * kRowChunks + c] = o;
+  }
+}
+
+// 128-row tiles that run at once (three workgroups per CU): a problem with no more of them runs those
+constexpr int64_t kSmallTileRound = 768;
+
+// fp32 words one partial tile needs in the split (all pieces; sums of weight * v, then sums of weights)
+constexpr int64_t kSplitRowsPerTile = (int64_t)kSplitPieces * 256;
+
 // `extra_tiles` workgroups are appended for the device-side tile list (a.dev_tiles), if any.
+// `scratch` (fp32 words, or nullptr): room for the split of the partial tiles, see kSplitPieces.
 // a.marked_only != 0: the fast kernel, then the kernel with per-row shifts on the marked tiles.
 template <int QT, int NW>
 hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_off_host, int H,
-                      hipStream_t stream, int extra_tiles = 0) {
+                      hipStream_t stream, int extra_tiles = 0, float* scratch = nullptr, int64_t scratch_words = 0) {
   constexpr int BQ = 32 * QT * NW;
   int64_t full = 0;
   int ragged = 0;
@@ -709,9 +829,35 @@ hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_o
   a.ragged_per_xcd = (ragged + 7) / 8;
   if (full + ragged + extra_tiles == 0) return hipSuccess;
   a.dev_first_block = 8 * (a.full_per_xcd + a.ragged_per_xcd);
+  a.split_blocks = 0;
+  a.split_o = nullptr;
+  a.split_l = nullptr;
   const unsigned grid = (unsigned)a.dev_first_block + (unsigned)extra_tiles;
-  if (a.marked_only)
-    hipLaunchKernelGGL((attention_kernel<QT, NW, false>), dim3(grid), dim3(64 * NW), 0, stream, a);
+  if (a.marked_only) {
+    // The split pays when the launch is long (at least one full tile per CU) and every head has
+    // enough key tiles for all pieces; it needs the 256-row tiles and room for the partial sums.
+    int64_t min_mk = INT64_MAX;
+    for (int h = 0; h < H; ++h) min_mk = k_off_host[h + 1] - k_off_host[h] < min_mk ? k_off_host[h + 1] - k_off_host[h] : min_mk;
+    // (the same launches for which launch_attention takes the 256-row tiles at all)
+    int64_t tiles128 = 0;
+    for (int h = 0; h < H; ++h) tiles128 += (q_off_host[h + 1] - q_off_host[h] + 127) / 128;
+    const bool split = BQ == 256 && scratch && ragged > 0 && full >= 256 && tiles128 > kSmallTileRound &&
+                       min_mk >= 4 * kSplitPieces * kKvTile &&
+                       scratch_words >= (int64_t)ragged * kSplitRowsPerTile * (kDHead + 1);
+    if (split) {
+      AttnArgs f = a;
+      f.ragged_per_xcd = 0;
+      f.split_blocks = (ragged * kSplitPieces + 7) & ~7;
+      f.split_o = scratch;
+      f.split_l = scratch + (int64_t)ragged * kSplitRowsPerTile * kDHead;
+      f.dev_first_block = 8 * f.full_per_xcd;
+      const unsigned fgrid = (unsigned)f.split_blocks + (unsigned)f.dev_first_block + (unsigned)extra_tiles;
+      hipLaunchKernelGGL((attention_kernel<QT, NW, false>), dim3(fgrid), dim3(64 * NW), 0, stream, f);
+      hipLaunchKernelGGL((attention_split_reduce_kernel<BQ>), dim3((unsigned)ragged), dim3(256), 0, stream, f);
+    } else {
+      hipLaunchKernelGGL((attention_kernel<QT, NW, false>), dim3(grid), dim3(64 * NW), 0, stream, a);
+    }
+  }
   hipLaunchKernelGGL((attention_kernel<QT, NW, true>), dim3(grid), dim3(64 * NW), 0, stream, a);
   return hipGetLastError();
 }
@@ -748,7 +894,8 @@ hipError_t launch_attention_dev_tiles(const void* q, const void* k, const void* 
 hipError_t launch_attention_both(const void* q, const void* k, const void* v, void* o,
                                  const int64_t* q_off_host, const int64_t* k_off_host, int H, float scale,
                                  const void* q2, void* o2, const int32_t* q2_off_dev, const int32_t* tiles,
-                                 int max_tiles, bool log2_keys, hipStream_t stream) {
+                                 int max_tiles, bool log2_keys, hipStream_t stream, void* scratch,
+                                 int64_t scratch_bytes) {
   AttnArgs a;
   std::memset(&a, 0, sizeof(a));
   a.q = (const bf16_t*)q;
@@ -762,12 +909,13 @@ hipError_t launch_attention_both(const void* q, const void* k, const void* v, vo
   a.dev_tiles = max_tiles > 0 ? tiles : nullptr;
   a.q2 = (const bf16_t*)q2;
   a.o2 = (bf16_t*)o2;
-  return launch_cfg<2, 4>(a, q_off_host, k_off_host, H, stream, max_tiles > 0 ? max_tiles : 0);
+  return launch_cfg<2, 4>(a, q_off_host, k_off_host, H, stream, max_tiles > 0 ? max_tiles : 0, (float*)scratch,
+                          scratch_bytes / 4);
 }
 
 hipError_t launch_attention(const void* q, const void* k, const void* v, void* o,
                             const int64_t* q_off_host, const int64_t* k_off_host, int H,
-                            float scale, bool log2_keys, hipStream_t stream) {
+                            float scale, bool log2_keys, hipStream_t stream, void* scratch, int64_t scratch_bytes) {
   AttnArgs a;
   a.dev_q_off = nullptr;
   a.dev_tiles = nullptr;
@@ -787,8 +935,8 @@ hipError_t launch_attention(const void* q, const void* k, const void* v, void* o
   // against 0.144 ms at 16 x 5516 rows; with 800 small tiles, a second round, 0.19 against 0.17 ms).
   int64_t tiles128 = 0;
   for (int h = 0; h < H; ++h) tiles128 += (q_off_host[h + 1] - q_off_host[h] + 127) / 128;
-  if (tiles128 <= 768) return launch_cfg<1, 4>(a, q_off_host, k_off_host, H, stream);
-  return launch_cfg<2, 4>(a, q_off_host, k_off_host, H, stream);
+  if (tiles128 <= kSmallTileRound) return launch_cfg<1, 4>(a, q_off_host, k_off_host, H, stream);
+  return launch_cfg<2, 4>(a, q_off_host, k_off_host, H, stream, 0, (float*)scratch, scratch_bytes / 4);
 }
 
 }  // namespace httm

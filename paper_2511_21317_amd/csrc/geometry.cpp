@@ -185,6 +185,7 @@ int workspace_layout(const httm_geom_t& g, const HostTables& t, httm_workspace_l
   out->eps_q = off;    off = align_up(off + (cap ? (int64_t)g.H * t.N * 4 : 0), 256);
   out->q_out = off;    off = align_up(off + cap * row, 256);
   out->o_out = off;    off = align_up(off + cap * row, 256);
+  out->attn_split = off; off = align_up(off + attention_scratch_bytes(g.H), 256);
   out->total = off;
   return HTTM_OK;
 }

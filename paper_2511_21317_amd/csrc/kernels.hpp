@@ -110,9 +110,13 @@ constexpr int kAttnMaxHeads = HTTM_MAX_HEADS;
 // log2_keys: the keys carry the factor scale * log2(e) already (stage 2 with
 // MatchMergeStream.xm_scale), `scale` is ignored and the fast kernel runs first.
 constexpr float kLog2KeyScale = 0.125f * 1.4426950408889634f;   // log2(e) / sqrt(d_head)
+// `scratch` (device, 16-byte aligned, or nullptr): room for the fast kernel to run the partial last
+// tile of every head in pieces over the keys (attention_scratch_bytes(H) bytes cover any lengths);
+// without it, or when the launch is short, the partial tiles run whole.
 hipError_t launch_attention(const void* q, const void* k, const void* v, void* o,
                             const int64_t* q_off_host, const int64_t* k_off_host, int H,
-                            float scale, bool log2_keys, hipStream_t stream);
+                            float scale, bool log2_keys, hipStream_t stream, void* scratch = nullptr,
+                            int64_t scratch_bytes = 0);
 // Query rows and tiles are described by device memory (the outlier queries of Sec. 3.4, whose
 // number per head is only known on the device): q / o rows of head h are
 // [q_off_dev[h], q_off_dev[h+1]); tiles[0] tiles follow in `tiles` as (head, first row) pairs.
@@ -122,7 +126,8 @@ constexpr int kAttnDevTileRows = 256;
 hipError_t launch_attention_both(const void* q, const void* k, const void* v, void* o,
                                  const int64_t* q_off_host, const int64_t* k_off_host, int H, float scale,
                                  const void* q2, void* o2, const int32_t* q2_off_dev, const int32_t* tiles,
-                                 int max_tiles, bool log2_keys, hipStream_t stream);
+                                 int max_tiles, bool log2_keys, hipStream_t stream, void* scratch = nullptr,
+                                 int64_t scratch_bytes = 0);
 hipError_t launch_attention_dev_tiles(const void* q, const void* k, const void* v, void* o,
                                       const int32_t* q_off_dev, const int32_t* tiles, int max_tiles,
                                       const int64_t* k_off_host, int H, float scale, bool log2_keys,

@@ -1,0 +1,119 @@
+"""Stage 3 (Eq. 3-4) with scratch memory: a long launch runs the partial last query tile of every head
+in pieces over the keys and adds the pieces up.  Checked against the oracle's attention on the rows
+of the partial tiles, and against the same call without scratch on all rows."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_21317_amd as httm
+from oracle import httm_oracle as orc
+from gpu_util import require_gpu, f32, check_output
+
+pytestmark = pytest.mark.gpu
+
+
+def _log2_keys(k):
+    return (k.float() * float(np.float32(httm.LOG2_KEY_SCALE))).to(torch.bfloat16)
+
+
+def _case(mq, mk, seed, key_gain=None):
+    gen = torch.Generator().manual_seed(seed)
+    qo = [int(x) for x in np.concatenate([[0], np.cumsum(mq)])]
+    ko = [int(x) for x in np.concatenate([[0], np.cumsum(mk)])]
+    qm = torch.randn((qo[-1], 64), generator=gen).to(torch.bfloat16)
+    k = torch.randn((ko[-1], 64), generator=gen)
+    if key_gain is not None:
+        k = key_gain(k, ko)
+    vm = torch.randn((ko[-1], 64), generator=gen).to(torch.bfloat16)
+    return qm.cuda(), _log2_keys(k).cuda(), vm.cuda(), qo, ko
+
+
+def _run_both(qm, k2, vm, qo, ko):
+    H = len(qo) - 1
+    plain = torch.full_like(qm, float("nan"))
+    httm.attention_log2(qm, k2, vm, plain, qo, ko)
+    scratch = torch.full((httm.attention_scratch_bytes(H),), 0xFF, dtype=torch.uint8, device="cuda")   # NaN bit patterns
+    split = torch.full_like(qm, float("nan"))
+    httm.attention_log2(qm, k2, vm, split, qo, ko, scratch=scratch)
+    torch.cuda.synchronize()
+    _run_both.scratch_written = bool((scratch[:4096] != 0xFF).any())   # the pieces of the first partial tile
+    return f32(plain), f32(split)
+
+
+def _partial_rows(qo, h):
+    mq = qo[h + 1] - qo[h]
+    return qo[h] + (mq // 256) * 256, qo[h + 1]
+
+
+# The split is for launches of the 256-row kernel (more than 768 tiles of 128 rows) with at least 256
+# full tiles; ragged lengths, one head without a partial tile.
+CASES = [
+    ([12544 + 37] * 8, [8229] * 8),
+    ([12544 + 1, 12544 + 255, 12544 + 128, 12544, 12544 + 64, 12544 + 65, 12544 + 200, 12544 + 31],
+     [5000, 4100, 9000, 4096, 7777, 4500, 6001, 8192]),
+    ([25088 + 100] * 4, [12001] * 4),
+]
+
+
+@pytest.mark.parametrize("mq,mk", CASES)
+def test_partial_tiles_in_pieces_match_the_oracle_and_the_whole_tiles(mq, mk):
+    require_gpu()
+    print(f"[case] split attention mq={mq} mk={mk}", flush=True)
+    qm, k2, vm, qo, ko = _case(mq, mk, 4000 + sum(mq) % 997)
+    plain, split = _run_both(qm, k2, vm, qo, ko)
+    assert np.isfinite(split).all()
+    assert _run_both.scratch_written, "the launch did not take the split"
+    for h in range(len(mq)):
+        r0, r1 = _partial_rows(qo, h)
+        # rows of full tiles: the same workgroups ran them
+        assert np.array_equal(split[qo[h]:r0], plain[qo[h]:r0]), f"head {h}: full tiles differ"
+        if r1 == r0:
+            continue
+        kk = f32(k2[ko[h]:ko[h + 1]]) / np.float32(httm.LOG2_KEY_SCALE)
+        want = orc.attention(f32(qm[r0:r1]), kk, f32(vm[ko[h]:ko[h + 1]]))
+        check_output(split[r0:r1], want, f"split, head {h}")
+        check_output(plain[r0:r1], want, f"whole, head {h}")
+        # the two differ by the fp32 rounding of the partial sums only: one bf16 step, or - where the
+        # weighted values cancel to almost nothing - the fp32 noise of sums of terms of size one
+        d = np.abs(split[r0:r1] - plain[r0:r1])
+        assert (d <= 2.0 ** -7 * np.abs(plain[r0:r1]) + 1e-5).all(), f"head {h}: {d.max()}"
+
+
+def test_a_partial_tile_that_leaves_the_unshifted_range_is_redone_with_shifts():
+    """Keys of one piece of one head give weights far above 2^64: the sum of the pieces fails the
+    window test, the tile gets the mark and the kernel with per-row shifts redoes it (whole)."""
+    require_gpu()
+    mq, mk = [12544 + 37] * 8, [8229] * 8
+
+    def gain(k, ko):
+        k = k.clone()
+        k[ko[3] + 6000:ko[3] + 6100] *= 60.0     # head 3, inside one piece
+        k[ko[5]:ko[5 + 1]] *= 0.0                # head 5: all weights 1 (row sum = number of keys)
+        return k
+
+    qm, k2, vm, qo, ko = _case(mq, mk, 4242, gain)
+    plain, split = _run_both(qm, k2, vm, qo, ko)
+    assert np.isfinite(split).all()
+    for h in (3, 5, 0):
+        r0, r1 = _partial_rows(qo, h)
+        kk = f32(k2[ko[h]:ko[h + 1]]) / np.float32(httm.LOG2_KEY_SCALE)
+        want = orc.attention(f32(qm[r0:r1]), kk, f32(vm[ko[h]:ko[h + 1]]))
+        check_output(split[r0:r1], want, f"split, head {h}")
+    r0, r1 = _partial_rows(qo, 3)
+    assert np.array_equal(split[r0:r1], plain[r0:r1])     # both came from the kernel with shifts
+
+
+def test_short_launches_and_missing_room_run_the_partial_tiles_whole():
+    require_gpu()
+    qm, k2, vm, qo, ko = _case([300, 700, 129], [500, 640, 90], 4343)
+    plain, split = _run_both(qm, k2, vm, qo, ko)
+    assert np.array_equal(plain, split) and not _run_both.scratch_written
+    L = httm.lib()
+    import ctypes as C
+    qo_c = (C.c_int64 * 4)(*qo)
+    ko_c = (C.c_int64 * 4)(*ko)
+    small = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    rc = L.httm_attention_log2_scratch(C.c_void_p(qm.data_ptr()), C.c_void_p(k2.data_ptr()), C.c_void_p(vm.data_ptr()),
+                                       C.c_void_p(qm.data_ptr()), qo_c, ko_c, 3, 64, C.c_void_p(small.data_ptr()),
+                                       1024, None)
+    assert rc == -1      # scratch given but smaller than httm_attention_scratch_bytes(H)
