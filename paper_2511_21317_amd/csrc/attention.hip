@@ -794,6 +794,17 @@ __global__ __launch_bounds__(256) void attention_split_reduce_kernel(const AttnA
   }
 }
 
+// compute units of the current device (asked once per device)
+int64_t compute_units() {
+  static int cached[64] = {0};
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev]) return cached[dev];
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+  cached[dev] = n;
+  return n;
+}
+
 // 128-row tiles that run at once (three workgroups per CU): a problem with no more of them runs those
 constexpr int64_t kSmallTileRound = 768;
 
@@ -841,7 +852,12 @@ hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_o
     // (the same launches for which launch_attention takes the 256-row tiles at all)
     int64_t tiles128 = 0;
     for (int h = 0; h < H; ++h) tiles128 += (q_off_host[h + 1] - q_off_host[h] + 127) / 128;
-    const bool split = BQ == 256 && scratch && ragged > 0 && full >= 256 && tiles128 > kSmallTileRound &&
+    // and only where the partial tiles are what gives some CUs one more whole tile than the full tiles
+    // alone would (a CU runs its tiles two at a time, but one alone nearly twice as fast: the launch
+    // time follows the largest number of tiles a CU gets)
+    const int64_t cus = compute_units();
+    const bool one_more = (full + ragged + cus - 1) / cus > (full + cus - 1) / cus;
+    const bool split = BQ == 256 && scratch && ragged > 0 && full >= cus && one_more && tiles128 > kSmallTileRound &&
                        min_mk >= 4 * kSplitPieces * kKvTile &&
                        scratch_words >= (int64_t)ragged * kSplitRowsPerTile * (kDHead + 1);
     if (split) {

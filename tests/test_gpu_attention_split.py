@@ -45,13 +45,14 @@ def _partial_rows(qo, h):
     return qo[h] + (mq // 256) * 256, qo[h + 1]
 
 
-# The split is for launches of the 256-row kernel (more than 768 tiles of 128 rows) with at least 256
-# full tiles; ragged lengths, one head without a partial tile.
+# The split is taken by launches of the 256-row kernel (more than 768 tiles of 128 rows) in which the
+# partial tiles give some of the 256 CUs one more tile than the full tiles alone: here 512 full
+# tiles (two per CU) plus the partial ones.  Ragged lengths, one head without a partial tile.
 CASES = [
-    ([12544 + 37] * 8, [8229] * 8),
-    ([12544 + 1, 12544 + 255, 12544 + 128, 12544, 12544 + 64, 12544 + 65, 12544 + 200, 12544 + 31],
+    ([16384 + 37] * 8, [8229] * 8),
+    ([16384 + 1, 16384 + 255, 16384 + 128, 16384, 16384 + 64, 16384 + 65, 16384 + 200, 16384 + 31],
      [5000, 4100, 9000, 4096, 7777, 4500, 6001, 8192]),
-    ([25088 + 100] * 4, [12001] * 4),
+    ([32768 + 100] * 4, [12001] * 4),
 ]
 
 
@@ -83,7 +84,7 @@ def test_a_partial_tile_that_leaves_the_unshifted_range_is_redone_with_shifts():
     """Keys of one piece of one head give weights far above 2^64: the sum of the pieces fails the
     window test, the tile gets the mark and the kernel with per-row shifts redoes it (whole)."""
     require_gpu()
-    mq, mk = [12544 + 37] * 8, [8229] * 8
+    mq, mk = [16384 + 37] * 8, [8229] * 8
 
     def gain(k, ko):
         k = k.clone()
@@ -105,6 +106,10 @@ def test_a_partial_tile_that_leaves_the_unshifted_range_is_redone_with_shifts():
 
 def test_short_launches_and_missing_room_run_the_partial_tiles_whole():
     require_gpu()
+    # 392 full tiles + 8 partial ones: the partial tiles fit into the second tile of every CU
+    qm, k2, vm, qo, ko = _case([12544 + 37] * 8, [4100] * 8, 4344)
+    plain, split = _run_both(qm, k2, vm, qo, ko)
+    assert np.array_equal(plain, split) and not _run_both.scratch_written
     qm, k2, vm, qo, ko = _case([300, 700, 129], [500, 640, 90], 4343)
     plain, split = _run_both(qm, k2, vm, qo, ko)
     assert np.array_equal(plain, split) and not _run_both.scratch_written
