@@ -3,25 +3,28 @@
 // merged tokens (Sec. 3.2, mean of the constituents; Alg. 1 "BlockAggregate").
 //
 // One workgroup handles one (work item, head, stream); stream 0 is Q, stream 1 is K with V riding
-// on K's matches (Eq. 2 and the sentence after it).  The kernel is bound by HBM bandwidth: it
-// reads every token row once and writes the merged rows and one int32 per token.  All global
-// loads of the workgroup are issued before anything else happens so that each wave has up to
-// 16 independent 16-byte loads per lane in flight.
+// on K's matches (Eq. 2 and the sentence after it).  The kernel reads every token row once and
+// writes the merged rows and one int32 per token; what bounds it is the issue of vector
+// instructions inside a chain of dependent steps (four workgroups per CU), not the memory system.
 //
 // Inside a workgroup:
-//   1. the block's rows go to LDS (144-byte padded rows);
-//   2. one thread per token computes 1/||x|| in fp32;
-//   3. similarities are raw dot products from v_mfma_f32_32x32x16_bf16 (products of two bf16 are
+//   0. all rows of x are requested at once (straight-line buffer loads, see row_offsets); while
+//      they are on their way the table of the dst tokens is built;
+//   1. the rows go to LDS (144-byte padded rows), and 1/||x|| in fp32 comes from the registers
+//      that staged them (the 8 lanes of a row add their partial sums of squares);
+//   2. similarities are raw dot products from v_mfma_f32_32x32x16_bf16 (products of two bf16 are
 //      exact in fp32, accumulation is fp32), computed transposed - D * X^T - so that a lane holds
 //      one token's scores against 16 of 32 dst tokens; scaling by 1/||d|| and the arg-max run in
 //      registers, the two half-waves are combined with one cross-lane exchange.  Lowest cluster
 //      id wins exact ties;
+//   3. for the K stream the rows of v are requested now (their staging registers were free for the
+//      matching) and arrive during 4;
 //   4. the tokens are ordered by (cluster, position) with a stable counting sort built from wave
 //      ballots (no atomics, so the order is fixed and results are run-to-run identical); one
 //      thread per (cluster, 16-byte chunk) then adds the dst and its src tokens in ascending
 //      position in fp32, divides by the member count and rounds once to bf16;
-//   5. for the K stream the V rows, held in registers since the start, replace the K rows in LDS
-//      and step 4 runs again with the same clusters.
+//   5. the rows of v replace the rows of x in LDS and the aggregation of 4 runs again with the
+//      same clusters.
 // Work items with k == n (special-token prefix, or merge ratio 0) skip 1-5 and copy rows.
 #include "dev_common.hpp"
 #include "kernels.hpp"
