@@ -58,6 +58,12 @@
 // stays well inside the fp32 range; every workgroup checks its final row sums against
 // [2^-64, 2^64] and, if a row is outside (or inf / NaN), writes a mark instead of its tile.  The
 // SHIFT kernel is launched right behind on the same grid and redoes exactly the marked tiles.
+//
+// End of a launch.  A CU runs its 256-row tiles two at a time, but one alone nearly twice as fast,
+// so the launch time follows the largest number of whole tiles a CU gets.  When the partial last
+// tiles of the heads are what gives some CUs one more tile than the others, and the caller has given
+// scratch memory, the fast kernel runs those tiles in kSplitPieces pieces over the keys, dispatched
+// first, and attention_split_reduce_kernel adds the pieces up (see kSplitPieces and launch_cfg()).
 #include <cstring>
 #include <type_traits>
 
