@@ -259,12 +259,15 @@ HTTM_API int httm_attention_log2(const void* q_m, const void* k_log2, const void
                                  void* stream);
 
 /* httm_attention_log2 with scratch memory (device, 16-byte aligned, scratch_bytes >=
- * httm_attention_scratch_bytes(H); its contents before and after the call are meaningless).  With
- * it, a long launch runs the partial last 256-row query tile of every head in pieces over the keys
- * and adds the pieces up afterwards, so that the launch does not end on a few CUs running one more
- * whole tile than the others; the results agree with httm_attention_log2 to fp32 rounding of the
- * sums (the pieces are added in key order, run-to-run identical).  httm_layer_forward does the same
- * with the attn_split region of its workspace. */
+ * httm_attention_scratch_bytes(H); its contents before and after the call are meaningless).  A
+ * launch ends when its last workgroup ends, and a compute unit runs whole 256-row query tiles; with
+ * scratch, a long launch whose number of tiles lies a little (at most 64) above a multiple of the
+ * number of compute units runs the tiles in excess - the partial last tiles of the heads first,
+ * then full tiles from the end - in pieces over the keys and adds the pieces up afterwards, so
+ * that it does not end on a few compute units running one more whole tile than the others.  The
+ * results agree with httm_attention_log2 to fp32 rounding of the sums (the pieces are added in key
+ * order, run-to-run identical).  httm_layer_forward does the same with the attn_split region of
+ * its workspace. */
 HTTM_API int64_t httm_attention_scratch_bytes(int H);
 HTTM_API int httm_attention_log2_scratch(const void* q_m, const void* k_log2, const void* v_m, void* o_m,
                                          const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,

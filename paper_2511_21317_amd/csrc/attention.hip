@@ -104,20 +104,26 @@ struct AttnArgs {
   const bf16_t* q2;
   bf16_t* o2;
   int32_t dev_first_block;
-  // Fast kernel only: the partial last tiles of the heads split over the keys.  The first
+  // Fast kernel only: the tiles in excess (see kSplitPieces) split over the keys.  The first
   // split_blocks workgroups (a multiple of 8) are pieces: block b is piece b % kSplitPieces of
-  // partial tile b / kSplitPieces, takes an equal share of its head's key tiles and writes
-  // unnormalised fp32 results, which attention_split_reduce_kernel adds up.  The other workgroups
-  // then number from split_blocks on and there is no partial tile among them (ragged_per_xcd = 0).
+  // split tile b / kSplitPieces = (split_head[i], first row split_q0[i]), takes an equal share of its
+  // head's key tiles and writes unnormalised fp32 results, which attention_split_reduce_kernel adds
+  // up.  The other workgroups then number from split_blocks on; among them there is no partial tile
+  // (ragged_per_xcd = 0) and n_full does not count the full tiles that are split.
   int32_t split_blocks;
-  float* split_o;   // [n_ragged * kSplitPieces * BQ][64] sums of weight * v
-  float* split_l;   // [n_ragged * kSplitPieces * BQ]     sums of weights
+  int32_t n_split;
+  int32_t split_head[kAttnSplitTiles];
+  int32_t split_q0[kAttnSplitTiles];
+  float* split_o;   // [n_split * kSplitPieces * BQ][64] sums of weight * v
+  float* split_l;   // [n_split * kSplitPieces * BQ]     sums of weights
 };
 
-// Pieces per partial tile.  A launch ends when its last workgroup ends, and a CU runs whole tiles:
-// with 7 tiles per CU and 16 partial tiles on top, 16 CUs run an eighth tile while the others
-// idle (measured 2.80 against 2.55 ms without the partial tiles).  Cut into 16 pieces that run
-// first, the partial tiles cost every CU about a sixteenth of a tile instead.
+// Pieces per split tile.  A launch ends when its last workgroup ends, and a CU runs whole tiles:
+// with 7 tiles per CU and 16 tiles on top (the partial last tile of every head, say), 16 CUs run
+// an eighth tile while the others idle (measured 2.80 against 2.55 ms without those tiles).  The
+// tiles in excess of a multiple of the CU count - the partial tiles first, then the last full
+// ones, at most kAttnSplitTiles - are therefore cut into 16 pieces over the keys that run first and
+// cost every CU about a sixteenth of a tile each.
 constexpr int kSplitPieces = kAttnSplitPieces;
 
 // V tile in LDS: 64 rows of 128 bytes, written by global->LDS loads like the K tile; the 16-byte
@@ -473,7 +479,7 @@ void attention_kernel(const AttnArgs a) {
     if (block < a.split_blocks) {
       piece = block % kSplitPieces;
       piece_tile = block / kSplitPieces;
-      if (piece_tile >= a.n_ragged) return;
+      if (piece_tile >= a.n_split) return;
     } else {
       block -= a.split_blocks;
     }
@@ -484,8 +490,8 @@ void attention_kernel(const AttnArgs a) {
   int mq_dev = 0;
   const bool dev_tile = piece < 0 && a.dev_tiles && block >= a.dev_first_block;
   if (piece >= 0) {
-    h = a.ragged_head[piece_tile];
-    q0 = (a.tile_start[h + 1] - a.tile_start[h]) * BQ;
+    h = a.split_head[piece_tile];
+    q0 = a.split_q0[piece_tile];
   } else if (dev_tile) {
     const int t = block - a.dev_first_block;
     if (t >= a.dev_tiles[0]) return;
@@ -520,9 +526,10 @@ void attention_kernel(const AttnArgs a) {
     const int nt = (Mk + kKvTile - 1) / kKvTile, tpp = (nt + kSplitPieces - 1) / kSplitPieces;
     const int t0 = piece * tpp, t1 = t0 + tpp < nt ? t0 + tpp : nt;
     if (t0 >= t1) {   // no key tile left for this piece: it contributes zeros
-      for (int e = tid; e < (Mq - q0) * (kDHead / 4); e += NT)
+      const int rows = Mq - q0 < BQ ? Mq - q0 : BQ;
+      for (int e = tid; e < rows * (kDHead / 4); e += NT)
         ((f32x4*)(a.split_o + piece_row0 * kDHead))[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-      for (int e = tid; e < Mq - q0; e += NT) a.split_l[piece_row0 + e] = 0.f;
+      for (int e = tid; e < rows; e += NT) a.split_l[piece_row0 + e] = 0.f;
       return;
     }
     k_base += (int64_t)t0 * kKvTile;
@@ -751,7 +758,7 @@ void attention_kernel(const AttnArgs a) {
   }
 }
 
-// The partial tiles after the fast kernel ran them in pieces: one workgroup per partial tile adds the
+// The split tiles after the fast kernel ran them in pieces: one workgroup per split tile adds the
 // pieces in ascending key order, tests the row sums like the fast kernel does (a tile with a row
 // outside the window gets the mark and is redone by the kernel with per-row shifts), normalises and
 // stores.
@@ -759,10 +766,11 @@ template <int BQ>
 __global__ __launch_bounds__(256) void attention_split_reduce_kernel(const AttnArgs a) {
   __shared__ float s_inv[BQ];
   const int i = blockIdx.x, tid = threadIdx.x;
-  const int h = a.ragged_head[i];
-  const int q0 = (a.tile_start[h + 1] - a.tile_start[h]) * BQ;
+  const int h = a.split_head[i];
+  const int q0 = a.split_q0[i];
   const int64_t q_base = a.q_off[h];
-  const int rows = (int)(a.q_off[h + 1] - q_base) - q0;
+  const int left = (int)(a.q_off[h + 1] - q_base) - q0;
+  const int rows = left < BQ ? left : BQ;
   const int64_t base = (int64_t)i * kSplitPieces * BQ;
   bool bad = false;
   for (int r = tid; r < rows; r += 256) {
@@ -847,6 +855,7 @@ hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_o
   if (full + ragged + extra_tiles == 0) return hipSuccess;
   a.dev_first_block = 8 * (a.full_per_xcd + a.ragged_per_xcd);
   a.split_blocks = 0;
+  a.n_split = 0;
   a.split_o = nullptr;
   a.split_l = nullptr;
   const unsigned grid = (unsigned)a.dev_first_block + (unsigned)extra_tiles;
@@ -858,24 +867,46 @@ hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_o
     // (the same launches for which launch_attention takes the 256-row tiles at all)
     int64_t tiles128 = 0;
     for (int h = 0; h < H; ++h) tiles128 += (q_off_host[h + 1] - q_off_host[h] + 127) / 128;
-    // and only where the partial tiles are what gives some CUs one more whole tile than the full tiles
-    // alone would (a CU runs its tiles two at a time, but one alone nearly twice as fast: the launch
-    // time follows the largest number of tiles a CU gets)
+    // The tiles in excess: a CU runs its tiles two at a time, but one alone nearly twice as fast, so
+    // the launch time follows the largest number of whole tiles a CU gets - ceil(tiles / CUs).  The
+    // `excess` tiles beyond a multiple of the CU count are split if they are few (splitting e of them
+    // saves (1 - e / CUs) of a tile's time).
     const int64_t cus = compute_units();
-    const bool one_more = (full + ragged + cus - 1) / cus > (full + cus - 1) / cus;
-    const bool split = BQ == 256 && scratch && ragged > 0 && full >= cus && one_more && tiles128 > kSmallTileRound &&
-                       min_mk >= 4 * kSplitPieces * kKvTile &&
-                       scratch_words >= (int64_t)ragged * kSplitRowsPerTile * (kDHead + 1);
+    const int64_t excess = (full + ragged) % cus;
+    const int64_t room = scratch ? scratch_words / (kSplitRowsPerTile * (kDHead + 1)) : 0;
+    const bool split = BQ == 256 && excess > 0 && excess <= kAttnSplitTiles && excess <= room && full >= cus &&
+                       tiles128 > kSmallTileRound && min_mk >= 4 * kSplitPieces * kKvTile;
     if (split) {
       AttnArgs f = a;
-      f.ragged_per_xcd = 0;
-      f.split_blocks = (ragged * kSplitPieces + 7) & ~7;
+      // the partial tiles first (as many as the excess allows), then full tiles from the end
+      int ns = 0;
+      for (int i = 0; i < ragged && ns < excess; ++i) {
+        const int h = a.ragged_head[i];
+        f.split_head[ns] = h;
+        f.split_q0[ns++] = (a.tile_start[h + 1] - a.tile_start[h]) * BQ;
+      }
+      const int keep_ragged = ragged - ns;           // partial tiles that stay whole
+      int64_t nf = full;
+      for (int h = H - 1; ns < excess && nf > 0;) {
+        while (a.tile_start[h] >= nf) --h;           // the head of full tile nf - 1
+        f.split_head[ns] = h;
+        f.split_q0[ns++] = (int32_t)(nf - 1 - a.tile_start[h]) * BQ;
+        --nf;
+      }
+      f.n_split = ns;
+      f.n_full = (int32_t)nf;
+      f.full_per_xcd = (int32_t)((nf + 7) / 8);
+      // partial tiles beyond the excess keep their place in front of the full tiles
+      f.n_ragged = keep_ragged;
+      f.ragged_per_xcd = (keep_ragged + 7) / 8;
+      for (int i = 0; i < keep_ragged; ++i) f.ragged_head[i] = a.ragged_head[ragged - keep_ragged + i];
+      f.split_blocks = (ns * kSplitPieces + 7) & ~7;
       f.split_o = scratch;
-      f.split_l = scratch + (int64_t)ragged * kSplitRowsPerTile * kDHead;
-      f.dev_first_block = 8 * f.full_per_xcd;
+      f.split_l = scratch + (int64_t)ns * kSplitRowsPerTile * kDHead;
+      f.dev_first_block = 8 * (f.full_per_xcd + f.ragged_per_xcd);
       const unsigned fgrid = (unsigned)f.split_blocks + (unsigned)f.dev_first_block + (unsigned)extra_tiles;
       hipLaunchKernelGGL((attention_kernel<QT, NW, false>), dim3(fgrid), dim3(64 * NW), 0, stream, f);
-      hipLaunchKernelGGL((attention_split_reduce_kernel<BQ>), dim3((unsigned)ragged), dim3(256), 0, stream, f);
+      hipLaunchKernelGGL((attention_split_reduce_kernel<BQ>), dim3((unsigned)ns), dim3(256), 0, stream, f);
     } else {
       hipLaunchKernelGGL((attention_kernel<QT, NW, false>), dim3(grid), dim3(64 * NW), 0, stream, a);
     }

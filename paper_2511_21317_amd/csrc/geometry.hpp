@@ -31,11 +31,13 @@ struct WorkItem {
   int32_t dims;
 };
 
-// Stage 3 runs the partial last query tile of every head in kAttnSplitPieces pieces over the keys when
-// it is given room for their fp32 partial results: per head and piece 256 rows of 64 sums of
-// weight * v and one sum of weights.
+// Stage 3 runs the query tiles in excess of a multiple of the CU count - at most kAttnSplitTiles, the
+// partial last tiles of the heads first - in kAttnSplitPieces pieces over the keys when it is given
+// room for their fp32 partial results: per tile and piece 256 rows of 64 sums of weight * v and
+// one sum of weights.
 constexpr int kAttnSplitPieces = 16;
-inline int64_t attention_scratch_bytes(int H) { return (int64_t)H * kAttnSplitPieces * 256 * (64 + 1) * 4; }
+constexpr int kAttnSplitTiles = 64;
+inline int64_t attention_scratch_bytes(int) { return (int64_t)kAttnSplitTiles * kAttnSplitPieces * 256 * (64 + 1) * 4; }
 
 struct HostTables {
   int64_t N = 0, n_prefix = 0, n_blocks = 0, max_block = 0;
