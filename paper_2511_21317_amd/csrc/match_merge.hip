@@ -38,8 +38,11 @@ namespace {
 constexpr int kRawBufferWord3 = 0x00020000;
 constexpr int kBufferNonTemporal = 2;
 
-// members of a cluster whose LDS reads the aggregation keeps in flight together (2, 6 and 8 measured slower)
-constexpr int kAggBatch = 4;
+// members of a cluster whose rows the aggregation requests together.  Every lane of a wave runs as
+// many rounds as the largest cluster among its 8 needs, so a round of 4 wastes more vector issue
+// slots than it saves LDS round trips now that a round is one round trip (measured at cfg 5, fused
+// launch: 1 -> 0.409, 2 -> 0.391, 3 -> 0.409, 4 -> 0.405, 6 -> 0.47, 8 -> 0.56 ms)
+constexpr int kAggBatch = 2;
 
 // Inclusive prefix sum over the 64 lanes of a wave with data-parallel primitives only (no LDS round
 // trips): shifts by 1, 2, 4 and 8 inside each row of 16 lanes (a lane without a source adds 0), then
