@@ -191,7 +191,9 @@ void match_merge_kernel(const MatchMergeArgs a) {
   uint16_t* s_off = s_list + MAXN;                    // [MAXN+1]  first list entry of every cluster
   uint8_t* s_wcnt = (uint8_t*)(s_off + MAXN + 4);     // [NW][MAXN] members of cluster m inside wave w (<= 64)
 
-  const MatchMergeStream& s = a.s[blockIdx.z];
+  // (the last stream first: it is the one with v, whose workgroups live longest - the launch should
+  // not end on them)
+  const MatchMergeStream& s = a.s[a.n_streams - 1 - blockIdx.z];
   if ((int)blockIdx.x >= s.n_items) return;
   const WorkItem it = s.items[blockIdx.x];
   const int64_t h = blockIdx.y;
