@@ -96,6 +96,32 @@ def test_closed_form_of_the_reorder_inside_a_block(case, anchor):
     assert L.httm_geom_block_forms(C.byref(g), None, None) == -1
 
 
+def test_closed_form_of_the_reorder_on_random_geometries():
+    """60 seeded draws of frames, grid, block shape / kind, special-token count and anchoring: the
+    closed form reproduces the library's own pi, which test_host_tables_match_oracle pins to the oracle."""
+    rng = np.random.default_rng(20251121)
+    for _ in range(60):
+        chunked = bool(rng.integers(0, 2))
+        S, Hp, Wp = int(rng.integers(1, 12)), int(rng.integers(1, 40)), int(rng.integers(1, 40))
+        b = int(rng.integers(1, 300)) if chunked else int(rng.integers(1, 12))
+        T = int(rng.integers(1, 7))
+        ns = int(rng.choice([0, 1, 5]))
+        g = httm.make_geom(S, Hp, Wp, b, T, 0.5, n_special=ns, chunked_blocks=chunked,
+                           anchor_first_frame=bool(rng.integers(0, 2)))
+        sz = httm.Sizes()
+        if httm.lib().httm_geom_sizes(C.byref(g), C.byref(sz)) != 0:
+            continue                                   # (a block larger than the library takes)
+        t, f = httm.geom_tables(g), httm.geom_block_forms(g)
+        tpf, row_len = ns + Hp * Wp, (Hp * Wp if chunked else Wp)
+        assert (f["block_dims"] != 0).all(), (S, Hp, Wp, b, T, ns, chunked)
+        for start, n, src0, dims in zip(t["block_start"].tolist(), t["block_n"].tolist(),
+                                        f["block_src0"].tolist(), f["block_dims"].tolist()):
+            nx, plane = dims & 0xFFFF, dims >> 16
+            r = np.arange(n)
+            want = src0 + (r // plane) * tpf + ((r % plane) // nx) * row_len + r % nx
+            assert np.array_equal(want, t["pi"][start:start + n]), (S, Hp, Wp, b, T, ns, chunked)
+
+
 def test_merged_lengths_of_the_five_workloads():
     want = {1: 266, 2: 5516, 3: 6376, 4: 28650, 5: 28700}   # tests/golden/merged_counts.txt
     import synth
