@@ -117,6 +117,10 @@ def test_short_launches_and_missing_room_run_the_partial_tiles_whole():
     qm, k2, vm, qo, ko = _case([12544 + 37] * 8, [4100] * 8, 4344)
     plain, split = _run_both(qm, k2, vm, qo, ko)
     assert np.array_equal(plain, split) and not _run_both.scratch_written
+    # a head with fewer than 4096 keys (too few key tiles for 16 pieces): no split either
+    qm, k2, vm, qo, ko = _case([16384 + 37] * 8, [8229] * 7 + [3000], 4345)
+    plain, split = _run_both(qm, k2, vm, qo, ko)
+    assert np.array_equal(plain, split) and not _run_both.scratch_written
     qm, k2, vm, qo, ko = _case([300, 700, 129], [500, 640, 90], 4343)
     plain, split = _run_both(qm, k2, vm, qo, ko)
     assert np.array_equal(plain, split) and not _run_both.scratch_written
