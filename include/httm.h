@@ -267,11 +267,17 @@ HTTM_API int httm_attention_log2(const void* q_m, const void* k_log2, const void
  * that it does not end on a few compute units running one more whole tile than the others.  The
  * results agree with httm_attention_log2 to fp32 rounding of the sums (the pieces are added in key
  * order, run-to-run identical).  httm_layer_forward does the same with the attn_split region of
- * its workspace. */
+ * its workspace.
+ * httm_attention_scratch is httm_attention with the same scratch and the same rule; there every
+ * piece keeps the shift its sums are relative to, and the pieces of a row are brought to the
+ * largest of their shifts before they are added. */
 HTTM_API int64_t httm_attention_scratch_bytes(int H);
 HTTM_API int httm_attention_log2_scratch(const void* q_m, const void* k_log2, const void* v_m, void* o_m,
                                          const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
                                          void* scratch, int64_t scratch_bytes, void* stream);
+HTTM_API int httm_attention_scratch(const void* q_m, const void* k_m, const void* v_m, void* o_m,
+                                    const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
+                                    float scale, void* scratch, int64_t scratch_bytes, void* stream);
 
 /* ---- stage 4: unmerge (Sec. 3.2 Eq. 5-7) and inverse reorder (Sec. 3.3) ------------------ */
 

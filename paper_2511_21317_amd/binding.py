@@ -68,6 +68,7 @@ def lib() -> C.CDLL:
     L.httm_match_merge.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, i32p, f32p, f32p, vp]
     L.httm_reorder_match_merge.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, i32p, f32p, f32p, vp]
     L.httm_attention.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, C.c_float, vp]
+    L.httm_attention_scratch.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, C.c_float, vp, C.c_int64, vp]
     L.httm_attention_log2.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, vp]
     L.httm_attention_log2_scratch.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, vp, C.c_int64, vp]
     L.httm_attention_scratch_bytes.argtypes = [C.c_int]
@@ -82,7 +83,7 @@ def lib() -> C.CDLL:
     for name in ("httm_geom_sizes", "httm_workspace_layout", "httm_geom_tables", "httm_geom_block_forms", "httm_plan_create",
                  "httm_plan_destroy", "httm_plan_query", "httm_reorder", "httm_match_merge",
                  "httm_reorder_match_merge",
-                 "httm_attention", "httm_attention_log2", "httm_attention_log2_scratch", "httm_unmerge", "httm_layer_forward",
+                 "httm_attention", "httm_attention_scratch", "httm_attention_log2", "httm_attention_log2_scratch", "httm_unmerge", "httm_layer_forward",
                  "httm_reorder_match_merge_filtered", "httm_attention_outliers", "httm_unmerge_filtered",
                  "httm_outlier_stats", "httm_global_match"):
         getattr(L, name).restype = C.c_int
@@ -233,14 +234,20 @@ def reorder_match_merge(plan: Plan, q, k, v, q_m, k_m, v_m, assign_q, assign_k, 
         _dev(score_k, f32, (H, N)) if score_k is not None else None, _stream()), "httm_reorder_match_merge")
 
 
-def attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, scale: float = 0.125):
-    """q_m/o_m: [sum M_q, 64] (or [H, M, 64]) bf16; offsets: sequences of H+1 row indices (host)."""
+def attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, scale: float = 0.125, scratch=None):
+    """q_m/o_m: [sum M_q, 64] (or [H, M, 64]) bf16; offsets: sequences of H+1 row indices (host).
+    scratch: a uint8 device tensor of at least attention_scratch_bytes(H) bytes, or None."""
     H = len(q_offsets) - 1
     qo = (C.c_int64 * (H + 1))(*[int(x) for x in q_offsets])
     ko = (C.c_int64 * (H + 1))(*[int(x) for x in k_offsets])
     bf = torch.bfloat16
-    _check(lib().httm_attention(_dev(q_m, bf), _dev(k_m, bf), _dev(v_m, bf), _dev(o_m, bf), qo, ko,
-                                H, 64, float(scale), _stream()), "httm_attention")
+    if scratch is None:
+        _check(lib().httm_attention(_dev(q_m, bf), _dev(k_m, bf), _dev(v_m, bf), _dev(o_m, bf), qo, ko,
+                                    H, 64, float(scale), _stream()), "httm_attention")
+    else:
+        _check(lib().httm_attention_scratch(_dev(q_m, bf), _dev(k_m, bf), _dev(v_m, bf), _dev(o_m, bf), qo, ko,
+                                            H, 64, float(scale), _dev(scratch, torch.uint8), scratch.numel(),
+                                            _stream()), "httm_attention_scratch")
     return o_m
 
 

@@ -335,10 +335,12 @@ int httm_global_match(const void* x, int64_t N, int H, int d_head, double dst_fr
   return HTTM_OK;
 }
 
-int httm_attention(const void* q_m, const void* k_m, const void* v_m, void* o_m,
-                   const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
-                   float scale, void* stream) {
+int httm_attention_scratch(const void* q_m, const void* k_m, const void* v_m, void* o_m,
+                           const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
+                           float scale, void* scratch, int64_t scratch_bytes, void* stream) {
   if (!q_offsets || !k_offsets || H <= 0 || !(scale > 0.0f)) return HTTM_E_INVALID_ARG;
+  if (scratch && (!aligned16(scratch) || scratch_bytes < attention_scratch_bytes(H < HTTM_MAX_HEADS ? H : HTTM_MAX_HEADS)))
+    return HTTM_E_INVALID_ARG;
   if (d_head != 64 || H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
   for (int h = 0; h < H; ++h)
     if (q_offsets[h + 1] < q_offsets[h] || k_offsets[h + 1] < k_offsets[h] ||
@@ -350,8 +352,15 @@ int httm_attention(const void* q_m, const void* k_m, const void* v_m, void* o_m,
   if (any_q && (!q_m || !o_m)) return HTTM_E_INVALID_ARG;
   if (any_q && any_k && (!k_m || !v_m)) return HTTM_E_INVALID_ARG;
   if (!aligned16(q_m) || !aligned16(k_m) || !aligned16(v_m) || !aligned16(o_m)) return HTTM_E_INVALID_ARG;
-  HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, H, scale, false, (hipStream_t)stream));
+  HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, H, scale, false, (hipStream_t)stream,
+                            scratch, scratch_bytes));
   return HTTM_OK;
+}
+
+int httm_attention(const void* q_m, const void* k_m, const void* v_m, void* o_m,
+                   const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
+                   float scale, void* stream) {
+  return httm_attention_scratch(q_m, k_m, v_m, o_m, q_offsets, k_offsets, H, d_head, scale, nullptr, 0, stream);
 }
 
 int httm_attention_log2_scratch(const void* q_m, const void* k_log2, const void* v_m, void* o_m,

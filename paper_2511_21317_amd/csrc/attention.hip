@@ -104,7 +104,8 @@ struct AttnArgs {
   const bf16_t* q2;
   bf16_t* o2;
   int32_t dev_first_block;
-  // Fast kernel only: the tiles in excess (see kSplitPieces) split over the keys.  The first
+  // The tiles in excess (see kSplitPieces) split over the keys (not in a launch that only redoes
+  // marked tiles).  The first
   // split_blocks workgroups (a multiple of 8) are pieces: block b is piece b % kSplitPieces of
   // split tile b / kSplitPieces = (split_head[i], first row split_q0[i]), takes an equal share of its
   // head's key tiles and writes unnormalised fp32 results, which attention_split_reduce_kernel adds
@@ -116,6 +117,7 @@ struct AttnArgs {
   int32_t split_q0[kAttnSplitTiles];
   float* split_o;   // [n_split * kSplitPieces * BQ][64] sums of weight * v
   float* split_l;   // [n_split * kSplitPieces * BQ]     sums of weights
+  float* split_m;   // [n_split * kSplitPieces * BQ]     the rows' shifts (kernel with per-row shifts only)
 };
 
 // Pieces per split tile.  A launch ends when its last workgroup ends, and a CU runs whole tiles:
@@ -474,8 +476,8 @@ void attention_kernel(const AttnArgs a) {
   // short, so they should not be what the grid ends on), then every XCD walks a contiguous
   // range of full tiles.
   int block = (int)blockIdx.x;
-  int piece = -1, piece_tile = 0;               // a piece of a partial tile (fast kernel only)
-  if (!SHIFT && a.split_blocks) {
+  int piece = -1, piece_tile = 0;               // a piece of a split tile
+  if (a.split_blocks) {
     if (block < a.split_blocks) {
       piece = block % kSplitPieces;
       piece_tile = block / kSplitPieces;
@@ -529,7 +531,10 @@ void attention_kernel(const AttnArgs a) {
       const int rows = Mq - q0 < BQ ? Mq - q0 : BQ;
       for (int e = tid; e < rows * (kDHead / 4); e += NT)
         ((f32x4*)(a.split_o + piece_row0 * kDHead))[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-      for (int e = tid; e < rows; e += NT) a.split_l[piece_row0 + e] = 0.f;
+      for (int e = tid; e < rows; e += NT) {
+        a.split_l[piece_row0 + e] = 0.f;
+        if (SHIFT) a.split_m[piece_row0 + e] = -1e30f;
+      }
       return;
     }
     k_base += (int64_t)t0 * kKvTile;
@@ -705,8 +710,8 @@ void attention_kernel(const AttnArgs a) {
       l_tot[qt] = l32 < 16 ? s0 : s1;
     }
   }
-  if (!SHIFT && piece >= 0) {
-    // a piece: unnormalised sums for attention_split_reduce_kernel (which also tests the row sums)
+  if (piece >= 0) {
+    // a piece: unnormalised sums (and the shifts they are relative to) for attention_split_reduce_kernel
     if (active) {
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt) {
@@ -720,7 +725,10 @@ void attention_kernel(const AttnArgs a) {
               *(f32x4*)(po + dt * 32 + 8 * g + 4 * half) =
                   f32x4{w.o_acc[dt][qt][4 * g], w.o_acc[dt][qt][4 * g + 1], w.o_acc[dt][qt][4 * g + 2],
                         w.o_acc[dt][qt][4 * g + 3]};
-          if (half == 0) a.split_l[piece_row0 + (row - q0)] = l_tot[qt];
+          if (half == 0) {
+            a.split_l[piece_row0 + (row - q0)] = l_tot[qt];
+            if (SHIFT) a.split_m[piece_row0 + (row - q0)] = w.mc[qt];
+          }
         }
       }
     }
@@ -758,13 +766,15 @@ void attention_kernel(const AttnArgs a) {
   }
 }
 
-// The split tiles after the fast kernel ran them in pieces: one workgroup per split tile adds the
-// pieces in ascending key order, tests the row sums like the fast kernel does (a tile with a row
-// outside the window gets the mark and is redone by the kernel with per-row shifts), normalises and
-// stores.
-template <int BQ>
+// The split tiles after a kernel ran them in pieces: one workgroup per split tile adds the pieces in
+// ascending key order and stores the normalised rows.  After the fast kernel it tests the row sums
+// like that kernel does (a tile with a row outside the window gets the mark and is redone by the
+// kernel with per-row shifts); after the kernel with per-row shifts every piece is first brought to
+// the largest of the pieces' shifts of its row.
+template <int BQ, bool SHIFT>
 __global__ __launch_bounds__(256) void attention_split_reduce_kernel(const AttnArgs a) {
   __shared__ float s_inv[BQ];
+  __shared__ float s_w[SHIFT ? kSplitPieces * BQ : 1];   // factor of piece p for row r: [p][r]
   const int i = blockIdx.x, tid = threadIdx.x;
   const int h = a.split_head[i];
   const int q0 = a.split_q0[i];
@@ -775,9 +785,21 @@ __global__ __launch_bounds__(256) void attention_split_reduce_kernel(const AttnA
   bool bad = false;
   for (int r = tid; r < rows; r += 256) {
     float l = 0.f;
+    if (SHIFT) {
+      float m = -1e30f;
 #pragma unroll
-    for (int p = 0; p < kSplitPieces; ++p) l += a.split_l[base + (int64_t)p * BQ + r];
-    bad = bad || !(l >= kFastSumMin && l <= kFastSumMax);
+      for (int p = 0; p < kSplitPieces; ++p) m = fmaxf(m, a.split_m[base + (int64_t)p * BQ + r]);
+#pragma unroll
+      for (int p = 0; p < kSplitPieces; ++p) {
+        const float wgt = __builtin_amdgcn_exp2f(a.split_m[base + (int64_t)p * BQ + r] - m);
+        s_w[p * BQ + r] = wgt;
+        l = fmaf(a.split_l[base + (int64_t)p * BQ + r], wgt, l);
+      }
+    } else {
+#pragma unroll
+      for (int p = 0; p < kSplitPieces; ++p) l += a.split_l[base + (int64_t)p * BQ + r];
+      bad = bad || !(l >= kFastSumMin && l <= kFastSumMax);
+    }
     s_inv[r] = 1.0f / l;
   }
   uint16_t* mark = (uint16_t*)(a.o + (q_base + q0) * kDHead);
@@ -794,10 +816,11 @@ __global__ __launch_bounds__(256) void attention_split_reduce_kernel(const AttnA
     for (int p = 0; p < kSplitPieces; ++p) {
       const float* po = a.split_o + (base + (int64_t)p * BQ + r) * kDHead + c * 8;
       const f32x4 lo = *(const f32x4*)po, hi = *(const f32x4*)(po + 4);
+      const float wgt = SHIFT ? s_w[p * BQ + r] : 1.0f;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        acc[q] += lo[q];
-        acc[4 + q] += hi[q];
+        acc[q] = SHIFT ? fmaf(lo[q], wgt, acc[q]) : acc[q] + lo[q];
+        acc[4 + q] = SHIFT ? fmaf(hi[q], wgt, acc[4 + q]) : acc[4 + q] + hi[q];
       }
     }
     const float inv = s_inv[r];
@@ -824,6 +847,7 @@ constexpr int64_t kSmallTileRound = 768;
 
 // fp32 words one partial tile needs in the split (all pieces; sums of weight * v, then sums of weights)
 constexpr int64_t kSplitRowsPerTile = (int64_t)kSplitPieces * 256;
+constexpr int64_t kSplitWordsPerRow = kDHead + 2;   // 64 sums of weight * v, the sum of weights, the shift
 
 // `extra_tiles` workgroups are appended for the device-side tile list (a.dev_tiles), if any.
 // `scratch` (fp32 words, or nullptr): room for the split of the partial tiles, see kSplitPieces.
@@ -858,60 +882,67 @@ hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_o
   a.n_split = 0;
   a.split_o = nullptr;
   a.split_l = nullptr;
+  a.split_m = nullptr;
   const unsigned grid = (unsigned)a.dev_first_block + (unsigned)extra_tiles;
-  if (a.marked_only) {
-    // The split pays when the launch is long (at least one full tile per CU) and every head has
-    // enough key tiles for all pieces; it needs the 256-row tiles and room for the partial sums.
-    int64_t min_mk = INT64_MAX;
-    for (int h = 0; h < H; ++h) min_mk = k_off_host[h + 1] - k_off_host[h] < min_mk ? k_off_host[h + 1] - k_off_host[h] : min_mk;
-    // (the same launches for which launch_attention takes the 256-row tiles at all)
-    int64_t tiles128 = 0;
-    for (int h = 0; h < H; ++h) tiles128 += (q_off_host[h + 1] - q_off_host[h] + 127) / 128;
-    // The tiles in excess: a CU runs its tiles two at a time, but one alone nearly twice as fast, so
-    // the launch time follows the largest number of whole tiles a CU gets - ceil(tiles / CUs).  The
-    // `excess` tiles beyond a multiple of the CU count are split if they are few (splitting e of them
-    // saves (1 - e / CUs) of a tile's time).
-    const int64_t cus = compute_units();
-    const int64_t excess = (full + ragged) % cus;
-    const int64_t room = scratch ? scratch_words / (kSplitRowsPerTile * (kDHead + 1)) : 0;
-    const bool split = BQ == 256 && excess > 0 && excess <= kAttnSplitTiles && excess <= room && full >= cus &&
-                       tiles128 > kSmallTileRound && min_mk >= 4 * kSplitPieces * kKvTile;
-    if (split) {
-      AttnArgs f = a;
-      // the partial tiles first (as many as the excess allows), then full tiles from the end
-      int ns = 0;
-      for (int i = 0; i < ragged && ns < excess; ++i) {
-        const int h = a.ragged_head[i];
-        f.split_head[ns] = h;
-        f.split_q0[ns++] = (a.tile_start[h + 1] - a.tile_start[h]) * BQ;
-      }
-      const int keep_ragged = ragged - ns;           // partial tiles that stay whole
-      int64_t nf = full;
-      for (int h = H - 1; ns < excess && nf > 0;) {
-        while (a.tile_start[h] >= nf) --h;           // the head of full tile nf - 1
-        f.split_head[ns] = h;
-        f.split_q0[ns++] = (int32_t)(nf - 1 - a.tile_start[h]) * BQ;
-        --nf;
-      }
-      f.n_split = ns;
-      f.n_full = (int32_t)nf;
-      f.full_per_xcd = (int32_t)((nf + 7) / 8);
-      // partial tiles beyond the excess keep their place in front of the full tiles
-      f.n_ragged = keep_ragged;
-      f.ragged_per_xcd = (keep_ragged + 7) / 8;
-      for (int i = 0; i < keep_ragged; ++i) f.ragged_head[i] = a.ragged_head[ragged - keep_ragged + i];
-      f.split_blocks = (ns * kSplitPieces + 7) & ~7;
-      f.split_o = scratch;
-      f.split_l = scratch + (int64_t)ns * kSplitRowsPerTile * kDHead;
-      f.dev_first_block = 8 * (f.full_per_xcd + f.ragged_per_xcd);
-      const unsigned fgrid = (unsigned)f.split_blocks + (unsigned)f.dev_first_block + (unsigned)extra_tiles;
-      hipLaunchKernelGGL((attention_kernel<QT, NW, false>), dim3(fgrid), dim3(64 * NW), 0, stream, f);
-      hipLaunchKernelGGL((attention_split_reduce_kernel<BQ>), dim3((unsigned)ns), dim3(256), 0, stream, f);
-    } else {
-      hipLaunchKernelGGL((attention_kernel<QT, NW, false>), dim3(grid), dim3(64 * NW), 0, stream, a);
+  // The split pays when the launch is long (at least one full tile per CU) and every head has
+  // enough key tiles for all pieces; it needs the 256-row tiles and room for the partial sums.
+  int64_t min_mk = INT64_MAX;
+  for (int h = 0; h < H; ++h) min_mk = k_off_host[h + 1] - k_off_host[h] < min_mk ? k_off_host[h + 1] - k_off_host[h] : min_mk;
+  // (the same launches for which launch_attention takes the 256-row tiles at all)
+  int64_t tiles128 = 0;
+  for (int h = 0; h < H; ++h) tiles128 += (q_off_host[h + 1] - q_off_host[h] + 127) / 128;
+  // The tiles in excess: a CU runs its tiles two at a time, but one alone nearly twice as fast, so
+  // the launch time follows the largest number of whole tiles a CU gets - ceil(tiles / CUs).  The
+  // `excess` tiles beyond a multiple of the CU count are split if they are few (splitting e of them
+  // saves (1 - e / CUs) of a tile's time).
+  const int64_t cus = compute_units();
+  const int64_t excess = (full + ragged) % cus;
+  const int64_t room = scratch ? scratch_words / (kSplitRowsPerTile * kSplitWordsPerRow) : 0;
+  const bool split = BQ == 256 && excess > 0 && excess <= kAttnSplitTiles && excess <= room && full >= cus &&
+                     tiles128 > kSmallTileRound && min_mk >= 4 * kSplitPieces * kKvTile;
+  AttnArgs f = a;   // the first launch when the tiles in excess are split
+  unsigned fgrid = grid;
+  if (split) {
+    // the partial tiles first (as many as the excess allows), then full tiles from the end
+    int ns = 0;
+    for (int i = 0; i < ragged && ns < excess; ++i) {
+      const int h = a.ragged_head[i];
+      f.split_head[ns] = h;
+      f.split_q0[ns++] = (a.tile_start[h + 1] - a.tile_start[h]) * BQ;
     }
+    const int keep_ragged = ragged - ns;           // partial tiles that stay whole
+    int64_t nf = full;
+    for (int h = H - 1; ns < excess && nf > 0;) {
+      while (a.tile_start[h] >= nf) --h;           // the head of full tile nf - 1
+      f.split_head[ns] = h;
+      f.split_q0[ns++] = (int32_t)(nf - 1 - a.tile_start[h]) * BQ;
+      --nf;
+    }
+    f.n_split = ns;
+    f.n_full = (int32_t)nf;
+    f.full_per_xcd = (int32_t)((nf + 7) / 8);
+    // partial tiles beyond the excess keep their place in front of the full tiles
+    f.n_ragged = keep_ragged;
+    f.ragged_per_xcd = (keep_ragged + 7) / 8;
+    for (int i = 0; i < keep_ragged; ++i) f.ragged_head[i] = a.ragged_head[ragged - keep_ragged + i];
+    f.split_blocks = (ns * kSplitPieces + 7) & ~7;
+    f.split_o = scratch;
+    f.split_l = scratch + (int64_t)ns * kSplitRowsPerTile * kDHead;
+    f.split_m = f.split_l + (int64_t)ns * kSplitRowsPerTile;
+    f.dev_first_block = 8 * (f.full_per_xcd + f.ragged_per_xcd);
+    fgrid = (unsigned)f.split_blocks + (unsigned)f.dev_first_block + (unsigned)extra_tiles;
   }
-  hipLaunchKernelGGL((attention_kernel<QT, NW, true>), dim3(grid), dim3(64 * NW), 0, stream, a);
+  if (a.marked_only) {
+    // the fast kernel (and the sum of its pieces), then the kernel with per-row shifts on the marked tiles
+    hipLaunchKernelGGL((attention_kernel<QT, NW, false>), dim3(fgrid), dim3(64 * NW), 0, stream, f);
+    if (split)
+      hipLaunchKernelGGL((attention_split_reduce_kernel<BQ, false>), dim3((unsigned)f.n_split), dim3(256), 0, stream, f);
+    hipLaunchKernelGGL((attention_kernel<QT, NW, true>), dim3(grid), dim3(64 * NW), 0, stream, a);
+  } else {
+    hipLaunchKernelGGL((attention_kernel<QT, NW, true>), dim3(fgrid), dim3(64 * NW), 0, stream, f);
+    if (split)
+      hipLaunchKernelGGL((attention_split_reduce_kernel<BQ, true>), dim3((unsigned)f.n_split), dim3(256), 0, stream, f);
+  }
   return hipGetLastError();
 }
 

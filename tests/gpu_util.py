@@ -62,13 +62,13 @@ def merged_attention(plan: httm.Plan, q_m, k_m, v_m, o_m):
     H = plan.H
     qo = [h * plan.M_q for h in range(H + 1)]
     ko = [h * plan.M_k for h in range(H + 1)]
+    # with scratch memory, as httm_layer_forward runs stage 3 (long launches then take the tiles
+    # in excess in pieces: the same code path gives the same bits)
+    scratch = torch.empty(httm.attention_scratch_bytes(H), dtype=torch.uint8, device=q_m.device)
     if plan.log2_keys:
-        # with scratch memory, as httm_layer_forward runs stage 3 (long launches then take the
-        # partial last tile of every head in pieces: the same code path gives the same bits)
-        scratch = torch.empty(httm.attention_scratch_bytes(H), dtype=torch.uint8, device=q_m.device)
         httm.attention_log2(q_m, k_m, v_m, o_m, qo, ko, scratch=scratch)
     else:
-        httm.attention(q_m, k_m, v_m, o_m, qo, ko, 0.125)
+        httm.attention(q_m, k_m, v_m, o_m, qo, ko, 0.125, scratch=scratch)
 
 
 def check_assign(gpu_assign: np.ndarray, ref_assign: np.ndarray, ref_gap: np.ndarray, what=""):

@@ -133,3 +133,70 @@ def test_short_launches_and_missing_room_run_the_partial_tiles_whole():
                                        C.c_void_p(qm.data_ptr()), qo_c, ko_c, 3, 64, C.c_void_p(small.data_ptr()),
                                        1024, None)
     assert rc == -1      # scratch given but smaller than httm_attention_scratch_bytes(H)
+
+
+# ---- the same split in httm_attention (keys without the logit scale; every row has its shift) ----
+
+def _plain_case(mq, mk, seed, key_gain=None):
+    gen = torch.Generator().manual_seed(seed)
+    qo = [int(x) for x in np.concatenate([[0], np.cumsum(mq)])]
+    ko = [int(x) for x in np.concatenate([[0], np.cumsum(mk)])]
+    qm = torch.randn((qo[-1], 64), generator=gen).to(torch.bfloat16)
+    k = torch.randn((ko[-1], 64), generator=gen)
+    if key_gain is not None:
+        k = key_gain(k, ko)
+    vm = torch.randn((ko[-1], 64), generator=gen).to(torch.bfloat16)
+    return qm.cuda(), k.to(torch.bfloat16).cuda(), vm.cuda(), qo, ko
+
+
+def _run_both_plain(qm, km, vm, qo, ko):
+    H = len(qo) - 1
+    plain = torch.full_like(qm, float("nan"))
+    httm.attention(qm, km, vm, plain, qo, ko, 0.125)
+    scratch = torch.full((httm.attention_scratch_bytes(H),), 0xFF, dtype=torch.uint8, device="cuda")
+    split = torch.full_like(qm, float("nan"))
+    httm.attention(qm, km, vm, split, qo, ko, 0.125, scratch=scratch)
+    torch.cuda.synchronize()
+    return f32(plain), f32(split), bool((scratch[:4096] != 0xFF).any())
+
+
+def _gain_one_piece(k, ko):
+    k = k.clone()
+    k[ko[3] + 6000:ko[3] + 6100] *= 30.0     # head 3: one piece's shift far above the others'
+    k[ko[5]:ko[5 + 1]] *= 0.0                # head 5: all weights equal
+    return k
+
+
+@pytest.mark.parametrize("mq,mk,gain", [(CASES[1][0], CASES[1][1], None), (CASES[3][0], CASES[3][1], None),
+                                        (CASES[0][0], CASES[0][1], _gain_one_piece)])
+def test_pieces_with_per_row_shifts_match_the_oracle_and_the_whole_tiles(mq, mk, gain):
+    require_gpu()
+    print(f"[case] split attention, plain keys mq={mq} mk={mk} gain={gain is not None}", flush=True)
+    qm, km, vm, qo, ko = _plain_case(mq, mk, 4600 + sum(mq) % 997, gain)
+    plain, split, written = _run_both_plain(qm, km, vm, qo, ko)
+    assert np.isfinite(split).all()
+    assert written, "the launch did not take the split"
+    # the pieces round their weights to bf16 relative to their own shifts: a few 2^-9 steps of terms
+    # that average out, and one bf16 step of the result
+    d = np.abs(split - plain)
+    assert (d <= 2.0 ** -6 * np.abs(plain) + 2e-4).all(), f"{d.max()}"
+    n_full = sum(m // 256 for m in mq)
+    n_part = sum(1 for m in mq if m % 256)
+    n_split_full = max(0, (n_full + n_part) % 256 - n_part)
+    for h in range(len(mq)):
+        r0, r1 = _partial_rows(qo, h)
+        if h == len(mq) - 1:
+            r0 -= 256 * n_split_full
+        assert np.array_equal(split[qo[h]:r0], plain[qo[h]:r0]), f"head {h}: whole tiles differ"
+        if r1 == r0:
+            continue
+        want = orc.attention(f32(qm[r0:r1]), f32(km[ko[h]:ko[h + 1]]), f32(vm[ko[h]:ko[h + 1]]))
+        check_output(split[r0:r1], want, f"split, head {h}")
+        check_output(plain[r0:r1], want, f"whole, head {h}")
+
+
+def test_plain_keys_short_launch_takes_no_split():
+    require_gpu()
+    qm, km, vm, qo, ko = _plain_case([300, 700, 129], [500, 640, 90], 4343)
+    plain, split, written = _run_both_plain(qm, km, vm, qo, ko)
+    assert np.array_equal(plain, split) and not written
