@@ -105,12 +105,11 @@ struct AttnArgs {
   bf16_t* o2;
   int32_t dev_first_block;
   // The tiles in excess (see kSplitPieces) split over the keys (not in a launch that only redoes
-  // marked tiles).  The first
-  // split_blocks workgroups (a multiple of 8) are pieces: block b is piece b % kSplitPieces of
-  // split tile b / kSplitPieces = (split_head[i], first row split_q0[i]), takes an equal share of its
-  // head's key tiles and writes unnormalised fp32 results, which attention_split_reduce_kernel adds
-  // up.  The other workgroups then number from split_blocks on; among them there is no partial tile
-  // (ragged_per_xcd = 0) and n_full does not count the full tiles that are split.
+  // marked tiles).  The first split_blocks workgroups (a multiple of 8) are pieces: block b is piece
+  // b % kSplitPieces of split tile b / kSplitPieces = (split_head[i], first row split_q0[i]), takes
+  // an equal share of its head's key tiles and writes unnormalised fp32 results, which
+  // attention_split_reduce_kernel adds up.  The other workgroups then number from split_blocks on;
+  // n_ragged / ragged_head and n_full count only the tiles that stay whole.
   int32_t split_blocks;
   int32_t n_split;
   int32_t split_head[kAttnSplitTiles];

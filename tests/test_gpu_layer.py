@@ -71,7 +71,9 @@ def _sampled_head_check(w, q, k, v, out, views, heads, n_rows, tag, rho_q, rho_k
         if ok_k:     # no tie mismatch in this head: merged rows are one bf16 rounding from the fp32 mean
             assert (np.abs(f32(views["k_m"][h]) - km * kscale) <= 2.0 ** -8 * np.abs(km * kscale) + 1e-30).all()
             assert (np.abs(f32(views["v_m"][h]) - vm) <= 2.0 ** -8 * np.abs(vm) + 1e-30).all()
-        rows = np.sort(rng.choice(qm.shape[0], size=min(n_rows, qm.shape[0]), replace=False))
+        rows = rng.choice(qm.shape[0], size=min(n_rows, qm.shape[0]), replace=False)
+        # always with the head's last query tile of 256 rows (partial, and run in pieces at cfg 5)
+        rows = np.unique(np.concatenate([rows, np.arange((qm.shape[0] - 1) // 256 * 256, qm.shape[0])]))
         om_rows = orc.attention(qm, km, vm, rows=rows)
         check_output(f32(views["o_m"][h][torch.from_numpy(rows).cuda()]), om_rows, f"{tag} o_m head {h}")
         # unmerge + inverse reorder of the sampled rows: every input token whose merged query was sampled
@@ -84,15 +86,16 @@ def _sampled_head_check(w, q, k, v, out, views, heads, n_rows, tag, rho_q, rho_k
         print(f"{tag} head {h}: {sel.size} output rows checked, max_abs {err:.4g}, rel_l2 {rel:.4g}", flush=True)
 
 
-@pytest.mark.parametrize("idx", [4, 5])
-def test_layer_forward_full_size_sampled(idx):
+@pytest.mark.parametrize("idx,log2_keys", [(4, True), (5, True), (5, False)])
+def test_layer_forward_full_size_sampled(idx, log2_keys):
     require_gpu()
     w = synth.workload(idx)
     q, k, v = _inputs(w)
-    plan = plan_for(w)
+    plan = plan_for(w, log2_keys=log2_keys)
     out, views = run_layer(plan, q, k, v)
     assert plan.M_q == {4: 28650, 5: 28700}[idx]
-    _sampled_head_check(w, q, k, v, out, views, heads=[0, 11], n_rows=1024, tag=f"cfg{idx}",
+    _sampled_head_check(w, q, k, v, out, views, heads=[0, 11] if log2_keys else [7], n_rows=1024,
+                        tag=f"cfg{idx}{'' if log2_keys else ' plain keys'}",
                         rho_q=w.rho, rho_kv=w.rho, kscale=key_scale(plan))
     # properties that hold at any size: constituents of one merged query share identical output rows
     h = 5
