@@ -844,12 +844,12 @@ int64_t compute_units() {
 // 128-row tiles that run at once (three workgroups per CU): a problem with no more of them runs those
 constexpr int64_t kSmallTileRound = 768;
 
-// fp32 words one partial tile needs in the split (all pieces; sums of weight * v, then sums of weights)
+// rows of partial results one split tile needs (all pieces), and the fp32 words of such a row
 constexpr int64_t kSplitRowsPerTile = (int64_t)kSplitPieces * 256;
 constexpr int64_t kSplitWordsPerRow = kDHead + 2;   // 64 sums of weight * v, the sum of weights, the shift
 
 // `extra_tiles` workgroups are appended for the device-side tile list (a.dev_tiles), if any.
-// `scratch` (fp32 words, or nullptr): room for the split of the partial tiles, see kSplitPieces.
+// `scratch` (fp32 words, or nullptr): room for the split of the tiles in excess, see kSplitPieces.
 // a.marked_only != 0: the fast kernel, then the kernel with per-row shifts on the marked tiles.
 template <int QT, int NW>
 hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_off_host, int H,

@@ -309,3 +309,36 @@ def test_filtered_layer_full_size_sampled(paper_blocks):
     got_m = f32(out[torch.from_numpy(pi[sel]).cuda(), h * 64:(h + 1) * 64])
     check_output(got_m, want[row_of[aq[sel]]], "cfg5 filtered merged output rows")
     plan.close()
+
+
+def test_filtered_layer_full_size_plain_keys_stage3():
+    """The filtered layer at workload 5 on a plan with plain keys: both attentions run in one launch of
+    the kernel with per-row shifts, the tiles in excess in pieces.  Stage 2 does not depend on the key
+    scale (covered above), so this checks stage 3 on the layer's own merged tensors: sampled rows and
+    the last query tile of two heads, and sampled outlier rows, against the oracle's attention."""
+    require_gpu()
+    w, frac = synth.workload(5), 0.1
+    print(f"[case] filtered layer, plain keys {w.name} frac={frac}", flush=True)
+    q, k, v = synth.make_qkv(w, device="cuda")
+    plan = plan_for(w, outlier_frac=frac, log2_keys=False)
+    out = torch.empty((plan.N, plan.H * 64), dtype=torch.bfloat16, device="cuda")
+    ws = httm.alloc_workspace(plan)
+    httm.layer_forward(plan, q, k, v, out, ws)
+    _, counts = httm.outlier_stats(plan)
+    views = httm.workspace_views(plan, ws)
+    off = np.concatenate([[0], np.cumsum(counts)])
+    rng = np.random.default_rng(77)
+    for h in (3, 15):
+        qm, km, vm = (f32(views[n][h]) for n in ("q_m", "k_m", "v_m"))
+        # (a merged query whose constituents all left keeps a row of zeros - NaN-free - and any output)
+        rows = np.unique(np.concatenate([rng.choice(plan.M_q, size=256, replace=False),
+                                         np.arange((plan.M_q - 1) // 256 * 256, plan.M_q)]))
+        want = orc.attention(qm, km, vm, rows=rows)
+        check_output(f32(views["o_m"][h][torch.from_numpy(rows).cuda()]), want, f"plain keys o_m head {h}")
+        pos = off[h] + np.sort(rng.choice(counts[h], size=256, replace=False))
+        sel = torch.from_numpy(pos).cuda()
+        want_o = orc.attention(f32(views["q_out"][sel]), km, vm)
+        check_output(f32(views["o_out"][sel]), want_o, f"plain keys o_out head {h}")
+        print(f"[step] head {h} checked", flush=True)
+    assert torch.isfinite(out.float()).all()
+    plan.close()
