@@ -57,4 +57,9 @@ __device__ __forceinline__ int dst_position_any(int m, int n, int k, int n0) {
   return m < n0 ? m : n0 + (int)(((int64_t)(m - n0) * (int64_t)(n - n0)) / (int64_t)(k - n0));
 }
 
+// last word of a raw buffer descriptor on gfx9-family targets (32-bit data format, no swizzle, no
+// stride), and the cache-policy bit of a buffer load that marks it non-temporal
+constexpr int kRawBufferWord3 = 0x00020000;
+constexpr int kBufferNonTemporal = 2;
+
 }  // namespace httm

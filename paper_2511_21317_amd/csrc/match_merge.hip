@@ -33,11 +33,6 @@ namespace httm {
 
 namespace {
 
-// last word of a raw buffer descriptor on gfx9-family targets (32-bit data format, no swizzle, no
-// stride), and the cache-policy bit of a buffer load that marks it non-temporal
-constexpr int kRawBufferWord3 = 0x00020000;
-constexpr int kBufferNonTemporal = 2;
-
 // members of a cluster whose rows the aggregation requests together.  Every lane of a wave runs as
 // many rounds as the largest cluster among its 8 needs, so a round of 4 wastes more vector issue
 // slots than it saves LDS round trips now that a round is one round trip (measured at cfg 5, fused

@@ -16,6 +16,8 @@
 //                         position, the same from run to run); the member LISTS fit in LDS even
 //                         though the rows do not, and one thread per (cluster, 16-byte chunk) gathers
 //                         its members' rows from global memory, adds them in fp32 and rounds once.
+#include <type_traits>
+
 #include "dev_common.hpp"
 #include "kernels.hpp"
 
@@ -441,7 +443,40 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
     for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(mean[2 * q] * f, mean[2 * q + 1] * f);
     return o;
   };
-  const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+  // The rows come through buffer loads: the four offsets of a batch first (a missing member gets the
+  // offset one past the head's rows, for which the load returns zeros), then the loads in a straight
+  // line.  A load inside a branch, or one whose address is computed between the loads, makes the
+  // compiler wait for all earlier loads before its first use, which would run the batch one row at
+  // a time; so the loop exists twice, with and without V, instead of testing v inside.
+  const uint32_t head_bytes = (uint32_t)N * kRowBytes;
+  const __amdgpu_buffer_rsrc_t x_rows = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, (int)head_bytes, kRawBufferWord3);
+  const __amdgpu_buffer_rsrc_t v_rows =
+      __builtin_amdgcn_make_buffer_rsrc((void*)(v ? v : x), 0, (int)head_bytes, kRawBufferWord3);
+  auto sum_members = [&](auto with_v, int beg, int end, int c, float (&acc)[8], float (&accv)[8]) {
+    constexpr bool kWithV = decltype(with_v)::value;
+    for (int idx = beg; idx < end; idx += 4) {
+      uint32_t off[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int token = s_list[idx + u < end ? idx + u : beg];
+        const uint32_t o = (uint32_t)s_src[token] * kRowBytes + c * 16;
+        off[u] = idx + u < end ? o : head_bytes;
+      }
+      u32x4 w[4], wv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) w[u] = __builtin_amdgcn_raw_buffer_load_b128(x_rows, (int)off[u], 0, 0);
+      if constexpr (kWithV) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) wv[u] = __builtin_amdgcn_raw_buffer_load_b128(v_rows, (int)off[u], 0, 0);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) add_chunk(acc, __builtin_bit_cast(bf16x8, w[u]));
+      if constexpr (kWithV) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) add_chunk(accv, __builtin_bit_cast(bf16x8, wv[u]));
+      }
+    }
+  };
   for (int mc = tid; mc < k * kRowChunks; mc += kBaThreads) {
     const int m = mc >> 3, c = mc & 7;
     if (REFINE && !s_aff[m]) continue;
@@ -449,24 +484,10 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
     float acc[8], accv[8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) acc[q] = accv[q] = 0.f;
-    for (int idx = beg; idx < end; idx += 4) {
-      bf16x8 w[4], wv[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        w[u] = zero8;
-        wv[u] = zero8;
-        if (idx + u < end) {
-          const uint32_t off = (uint32_t)s_src[s_list[idx + u]] * kRowBytes + c * 16;
-          w[u] = *(const bf16x8*)(x + off);
-          if (v) wv[u] = *(const bf16x8*)(v + off);
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        add_chunk(acc, w[u]);
-        if (v) add_chunk(accv, wv[u]);
-      }
-    }
+    if (v)
+      sum_members(std::true_type{}, beg, end, c, acc, accv);
+    else
+      sum_members(std::false_type{}, beg, end, c, acc, accv);
     if (REFINE && end == beg) {   // every constituent has left: a zero row nobody reads
       xm[mc] = u32x4{0, 0, 0, 0};
       continue;
@@ -478,17 +499,31 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
     if (!REFINE && s.eps) {
       // Sec. 3.4 step 2: L2 distance of every constituent to the fp32 mean; zero if nothing was merged
       float* __restrict__ eps = s.eps + h * N + it.start;
-      for (int i2 = beg; i2 < end; ++i2) {
-        const int j = s_list[i2];
-        const bf16x8 w = *(const bf16x8*)(x + (uint32_t)s_src[j] * kRowBytes + c * 16);
-        float d2 = 0.f;
+      // (the members' rows again, four at a time like the sums above)
+      for (int i2 = beg; i2 < end; i2 += 4) {
+        int j[4];
+        uint32_t off[4];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          const float df = (float)w[q] - mean[q];
-          d2 = fmaf(df, df, d2);
+        for (int u = 0; u < 4; ++u) {
+          j[u] = s_list[i2 + u < end ? i2 + u : beg];
+          const uint32_t o = (uint32_t)s_src[j[u]] * kRowBytes + c * 16;
+          off[u] = i2 + u < end ? o : head_bytes;
         }
-        d2 = sum8(d2);
-        if (c == 0) eps[j] = end - beg >= 2 ? sqrtf(d2) : 0.f;
+        u32x4 w4[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) w4[u] = __builtin_amdgcn_raw_buffer_load_b128(x_rows, (int)off[u], 0, 0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const bf16x8 w = __builtin_bit_cast(bf16x8, w4[u]);
+          float d2 = 0.f;
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const float df = (float)w[q] - mean[q];
+            d2 = fmaf(df, df, d2);
+          }
+          d2 = sum8(d2);
+          if (c == 0 && i2 + u < end) eps[j[u]] = end - beg >= 2 ? sqrtf(d2) : 0.f;
+        }
       }
     }
   }
