@@ -76,13 +76,14 @@ enum {
                                      N >= 2^25 tokens per head */
   HTTM_E_WORKSPACE_TOO_SMALL = -3,
   HTTM_E_HIP = -4,                /* a HIP runtime call failed; see httm_last_hip_error() */
-  HTTM_E_NO_DEVICE = -5           /* no usable GPU */
+  HTTM_E_NO_DEVICE = -5,          /* no usable GPU */
+  HTTM_E_OUT_OF_MEMORY = -6       /* host memory ran out while the index tables were built */
 };
 
 enum {
   HTTM_VARIANT_HEADWISE = 0,      /* the paper's method: every head matches on its own tokens (Sec. 3.2) */
   HTTM_VARIANT_UNIFORM = 1,       /* comparison: one matching for all heads, computed on the head-averaged
-                                     tokens (the "shared merge topology" the paper argues against, Sec. 3.2) */
+                                     tokens (the single topology for every head that Sec. 3.2 argues against) */
   HTTM_VARIANT_NONE = 2           /* no merging (rho ignored): plain multi-head attention, Eq. 3-4 with M = N */
 };
 
@@ -229,7 +230,7 @@ HTTM_API int httm_reorder_match_merge(const httm_plan_t* plan, const void* q, co
  * are dst; Eq. 1 and the best-match rule over all N x kd pairs (about dst_frac * (1 - dst_frac) * N^2 *
  * d_head multiply-adds per head - the "0.19 N^2 d_head" of Sec. 3.3 at 25 %).  Matching only: it is
  * here to be timed against the block-local stage 2.
- * x        : [H, N, d_head] bf16, any token order.  N * kd pairs; N < 2^25, grid limit N <= 16 M.
+ * x        : [H, N, d_head] bf16, any token order.  N * kd pairs; N < 2^24 (else HTTM_E_UNSUPPORTED).
  * best_dst : [H, N] int32 out; index 0..kd-1 of the most similar dst (lowest index on exact ties);
  *            a dst token gets its own index.
  * sim      : [H, N] float out or NULL; that cosine similarity (1.0 for dst tokens). */
@@ -286,11 +287,14 @@ HTTM_API int httm_attention_scratch(const void* q_m, const void* k_m, const void
  * fuse_inverse_reorder != 0:  out is [N, H*d_head] in INPUT token order, heads concatenated on
  *     channels:  out[pi[j]][h*d_head + c] = o_m[h][assign_q[h][j]][c].
  * fuse_inverse_reorder == 0:  out is [H, N, d_head] in REORDERED order:
- *     out[h][j] = o_m[h][assign_q[h][j]]   (follow with httm_reorder(..., 1, ...)). */
+ *     out[h][j] = o_m[h][assign_q[h][j]]   (follow with httm_reorder(..., 1, ...)).
+ * A plan with outlier_frac > 0 is refused (HTTM_E_INVALID_ARG): the assignment its stage 2 writes
+ * refers to rows of o_out as well, which only httm_unmerge_filtered takes. */
 HTTM_API int httm_unmerge(const httm_plan_t* plan, const void* o_m, const int32_t* assign_q, void* out,
                  int fuse_inverse_reorder, void* stream);
 
-/* ---- the whole layer (Alg. 1 without projections and outlier filter) --------------------- */
+/* ---- the whole layer (Alg. 1 between the two projections; with the outlier filter of Sec. 3.4
+ *      when the plan's outlier_frac > 0) ---------------------------------------------------- */
 
 /* q, k, v : [H, N, d_head] bf16 in INPUT token order.  out : [N, H*d_head] bf16.
  * workspace: at least httm_sizes_t.workspace_bytes bytes, 256-byte aligned.  After the call it

@@ -33,8 +33,8 @@ Readings taken where the paper is silent (all listed in the design notes):
     slot) order, in front of all blocks in the reordered sequence;
   * inside a block tokens are ordered (frame, row, column);
   * a block of n tokens keeps k = max(1, n - floor(rho*n + 1e-9)) clusters
-    (Alg. 1 is parameterised by a cluster number per block; Sec. 4.1 fixes
-    "merge ratio rho leaves (1 - rho) of the tokens");
+    (Alg. 1 is parameterised by a cluster number per block; in Sec. 4.1 a merge
+    ratio rho means that the share 1 - rho of the tokens remains);
   * the dst tokens of a block are those at positions floor(m*n/k), m = 0..k-1;
     every other token is src and merges into its most similar dst (lowest m on
     exact ties);
@@ -180,7 +180,7 @@ def inverse_reorder(xr: np.ndarray, pi: np.ndarray) -> np.ndarray:
 
 def dst_count(n: int, rho: float, n0: int = 0, dst_frac: float = 0.0) -> int:
     """Number of dst tokens of a block.  Alg. 1's rule (dst_frac = 0): as many as the block keeps.
-    General rule (Sec. 3.2, "partitioned into src and dst"; the 25 % / 75 % example of Sec. 3.3):
+    General rule (the src / dst partition of Sec. 3.2; the 25 % / 75 % example of Sec. 3.3):
     floor(dst_frac * n), at least one, at least the n0 anchored tokens."""
     if dst_frac <= 0.0:
         return cluster_count(n, rho, n0)
@@ -250,7 +250,7 @@ def match_block(xb: np.ndarray, k: int, n0: int = 0, kd: int = None):
             gap[spos] = score[spos] - rest.max(axis=1)
         r = n - k
         if r < spos.size:
-            # "merge the top-r src tokens with the highest similarity scores" (Sec. 3.2)
+            # Sec. 3.2: only the r src tokens whose best similarity is highest merge
             order = np.lexsort((spos, -score[spos]))              # score descending, then position
             merged = np.zeros(spos.size, dtype=bool)
             merged[order[:r]] = True

@@ -11,7 +11,7 @@ import numpy as np
 import torch
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("HTTM_LIB_PATH") or os.path.join(PKG_DIR, "libhttm.so")  # override: experiments only
+LIB_PATH = os.path.join(PKG_DIR, "libhttm.so")   # the library built in-tree; nothing else is ever loaded
 
 VARIANT_HEADWISE, VARIANT_UNIFORM, VARIANT_NONE = 0, 1, 2
 VARIANTS = {"headwise": VARIANT_HEADWISE, "uniform": VARIANT_UNIFORM, "none": VARIANT_NONE}

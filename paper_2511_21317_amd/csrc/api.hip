@@ -47,6 +47,17 @@ int hip_fail(hipError_t e) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// build_tables() fills std::vectors; nothing may throw across the C boundary.
+int build_tables_nothrow(const httm_geom_t& g, bool with_pi, HostTables* t) {
+  try {
+    return build_tables(g, with_pi, t);
+  } catch (const std::bad_alloc&) {
+    return HTTM_E_OUT_OF_MEMORY;
+  } catch (...) {
+    return HTTM_E_INVALID_ARG;
+  }
+}
+
 void fill_sizes(const httm_geom_t& g, const HostTables& t, httm_sizes_t* s,
                 httm_workspace_layout_t* ws) {
   s->N = t.N;
@@ -170,6 +181,7 @@ const char* httm_strerror(int code) {
     case HTTM_E_WORKSPACE_TOO_SMALL: return "workspace too small";
     case HTTM_E_HIP: return "HIP runtime error (see httm_last_hip_error)";
     case HTTM_E_NO_DEVICE: return "no usable GPU";
+    case HTTM_E_OUT_OF_MEMORY: return "out of host memory while building the index tables";
     default: return "unknown error code";
   }
 }
@@ -179,7 +191,7 @@ int httm_last_hip_error(void) { return g_last_hip_error; }
 int httm_geom_sizes(const httm_geom_t* g, httm_sizes_t* out) {
   if (!g || !out) return HTTM_E_INVALID_ARG;
   HostTables t;
-  const int rc = build_tables(*g, false, &t);
+  const int rc = build_tables_nothrow(*g, false, &t);
   if (rc != HTTM_OK) return rc;
   fill_sizes(*g, t, out, nullptr);
   return HTTM_OK;
@@ -188,7 +200,7 @@ int httm_geom_sizes(const httm_geom_t* g, httm_sizes_t* out) {
 int httm_workspace_layout(const httm_geom_t* g, httm_workspace_layout_t* out) {
   if (!g || !out) return HTTM_E_INVALID_ARG;
   HostTables t;
-  const int rc = build_tables(*g, false, &t);
+  const int rc = build_tables_nothrow(*g, false, &t);
   if (rc != HTTM_OK) return rc;
   return workspace_layout(*g, t, out);
 }
@@ -197,7 +209,7 @@ int httm_geom_tables(const httm_geom_t* g, int32_t* pi, int32_t* block_start, in
                      int32_t* block_kq, int32_t* block_kk, int32_t* block_offq, int32_t* block_offk) {
   if (!g) return HTTM_E_INVALID_ARG;
   HostTables t;
-  const int rc = build_tables(*g, pi != nullptr, &t);
+  const int rc = build_tables_nothrow(*g, pi != nullptr, &t);
   if (rc != HTTM_OK) return rc;
   const size_t nb = (size_t)t.n_blocks * sizeof(int32_t);
   if (pi) std::memcpy(pi, t.pi.data(), (size_t)t.N * sizeof(int32_t));
@@ -213,7 +225,7 @@ int httm_geom_tables(const httm_geom_t* g, int32_t* pi, int32_t* block_start, in
 int httm_geom_block_forms(const httm_geom_t* g, int32_t* block_src0, int32_t* block_dims) {
   if (!g || !block_src0 || !block_dims) return HTTM_E_INVALID_ARG;
   HostTables t;
-  const int rc = build_tables(*g, true, &t);
+  const int rc = build_tables_nothrow(*g, true, &t);
   if (rc != HTTM_OK) return rc;
   const size_t nb = (size_t)t.n_blocks * sizeof(int32_t);
   std::memcpy(block_src0, t.block_src0.data(), nb);
@@ -225,12 +237,12 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
   if (!g || !out) return HTTM_E_INVALID_ARG;
   *out = nullptr;
   HostTables t;
-  int rc = build_tables(*g, true, &t);
+  int rc = build_tables_nothrow(*g, true, &t);
   if (rc != HTTM_OK) return rc;
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || ndev == 0) return HTTM_E_NO_DEVICE;
   httm_plan_t* p = new (std::nothrow) httm_plan_t();
-  if (!p) return HTTM_E_INVALID_ARG;
+  if (!p) return HTTM_E_OUT_OF_MEMORY;
   p->geom = *g;
   fill_sizes(*g, t, &p->sizes, &p->ws);
   p->n_items = (int32_t)t.items_q.size();
@@ -269,6 +281,12 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
       b.item_base = b.offsets + g->H + 1;
       b.tiles = b.item_base + (size_t)g->H * p->n_items;
     }
+  }
+  // "Synchronous": the copies and the memset above are complete before a kernel on any stream
+  // (blocking or not) can read the tables.
+  if (rc == HTTM_OK) {
+    e = hipDeviceSynchronize();
+    if (e != hipSuccess) rc = hip_fail(e);
   }
   if (rc != HTTM_OK) {
     httm_plan_destroy(p);
@@ -335,12 +353,18 @@ int httm_global_match(const void* x, int64_t N, int H, int d_head, double dst_fr
   return HTTM_OK;
 }
 
-int httm_attention_scratch(const void* q_m, const void* k_m, const void* v_m, void* o_m,
-                           const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
-                           float scale, void* scratch, int64_t scratch_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// Stage 3 behind its six entry points: argument checks, then the launch.  `scratch` may be nullptr
+// (every tile runs whole) or any 16-byte aligned room; the launch uses it only if its partial
+// results fit.
+int run_attention(const void* q_m, const void* k_m, const void* v_m, void* o_m, const int64_t* q_offsets,
+                  const int64_t* k_offsets, int H, int d_head, float scale, bool log2_keys_in, void* scratch,
+                  int64_t scratch_bytes, void* stream) {
   if (!q_offsets || !k_offsets || H <= 0 || !(scale > 0.0f)) return HTTM_E_INVALID_ARG;
-  if (scratch && (!aligned16(scratch) || scratch_bytes < attention_scratch_bytes(H < HTTM_MAX_HEADS ? H : HTTM_MAX_HEADS)))
-    return HTTM_E_INVALID_ARG;
+  if (scratch && (!aligned16(scratch) || scratch_bytes < 0)) return HTTM_E_INVALID_ARG;
   if (d_head != 64 || H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
   for (int h = 0; h < H; ++h)
     if (q_offsets[h + 1] < q_offsets[h] || k_offsets[h + 1] < k_offsets[h] ||
@@ -352,43 +376,39 @@ int httm_attention_scratch(const void* q_m, const void* k_m, const void* v_m, vo
   if (any_q && (!q_m || !o_m)) return HTTM_E_INVALID_ARG;
   if (any_q && any_k && (!k_m || !v_m)) return HTTM_E_INVALID_ARG;
   if (!aligned16(q_m) || !aligned16(k_m) || !aligned16(v_m) || !aligned16(o_m)) return HTTM_E_INVALID_ARG;
-  HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, H, scale, false, (hipStream_t)stream,
-                            scratch, scratch_bytes));
+  HTTM_HIP(launch_attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, H, log2_keys_in ? 1.0f : scale, log2_keys_in,
+                            (hipStream_t)stream, scratch, scratch ? scratch_bytes : 0));
   return HTTM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int httm_attention_scratch(const void* q_m, const void* k_m, const void* v_m, void* o_m,
+                           const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
+                           float scale, void* scratch, int64_t scratch_bytes, void* stream) {
+  if (scratch && H > 0 && H <= HTTM_MAX_HEADS && scratch_bytes < attention_scratch_bytes(H)) return HTTM_E_INVALID_ARG;
+  return run_attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, H, d_head, scale, false, scratch, scratch_bytes, stream);
 }
 
 int httm_attention(const void* q_m, const void* k_m, const void* v_m, void* o_m,
                    const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
                    float scale, void* stream) {
-  return httm_attention_scratch(q_m, k_m, v_m, o_m, q_offsets, k_offsets, H, d_head, scale, nullptr, 0, stream);
+  return run_attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, H, d_head, scale, false, nullptr, 0, stream);
 }
 
 int httm_attention_log2_scratch(const void* q_m, const void* k_log2, const void* v_m, void* o_m,
                                 const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
                                 void* scratch, int64_t scratch_bytes, void* stream) {
-  if (!q_offsets || !k_offsets || H <= 0) return HTTM_E_INVALID_ARG;
-  if (scratch && (!aligned16(scratch) || scratch_bytes < attention_scratch_bytes(H < HTTM_MAX_HEADS ? H : HTTM_MAX_HEADS)))
-    return HTTM_E_INVALID_ARG;
-  if (d_head != 64 || H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
-  for (int h = 0; h < H; ++h)
-    if (q_offsets[h + 1] < q_offsets[h] || k_offsets[h + 1] < k_offsets[h] ||
-        q_offsets[h + 1] - q_offsets[h] >= ((int64_t)1 << 24) ||
-        k_offsets[h + 1] - k_offsets[h] >= ((int64_t)1 << 24))
-      return HTTM_E_INVALID_ARG;
-  if (q_offsets[0] < 0 || k_offsets[0] < 0) return HTTM_E_INVALID_ARG;
-  const bool any_q = q_offsets[H] > q_offsets[0], any_k = k_offsets[H] > k_offsets[0];
-  if (any_q && (!q_m || !o_m)) return HTTM_E_INVALID_ARG;
-  if (any_q && any_k && (!k_log2 || !v_m)) return HTTM_E_INVALID_ARG;
-  if (!aligned16(q_m) || !aligned16(k_log2) || !aligned16(v_m) || !aligned16(o_m)) return HTTM_E_INVALID_ARG;
-  HTTM_HIP(launch_attention(q_m, k_log2, v_m, o_m, q_offsets, k_offsets, H, 1.0f, true, (hipStream_t)stream,
-                            scratch, scratch_bytes));
-  return HTTM_OK;
+  if (scratch && H > 0 && H <= HTTM_MAX_HEADS && scratch_bytes < attention_scratch_bytes(H)) return HTTM_E_INVALID_ARG;
+  return run_attention(q_m, k_log2, v_m, o_m, q_offsets, k_offsets, H, d_head, 1.0f, true, scratch, scratch_bytes, stream);
 }
 
 int httm_attention_log2(const void* q_m, const void* k_log2, const void* v_m, void* o_m,
                         const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
                         void* stream) {
-  return httm_attention_log2_scratch(q_m, k_log2, v_m, o_m, q_offsets, k_offsets, H, d_head, nullptr, 0, stream);
+  return run_attention(q_m, k_log2, v_m, o_m, q_offsets, k_offsets, H, d_head, 1.0f, true, nullptr, 0, stream);
 }
 
 int64_t httm_attention_scratch_bytes(int H) { return H > 0 && H <= HTTM_MAX_HEADS ? attention_scratch_bytes(H) : 0; }
@@ -396,6 +416,9 @@ int64_t httm_attention_scratch_bytes(int H) { return H > 0 && H <= HTTM_MAX_HEAD
 int httm_unmerge(const httm_plan_t* p, const void* o_m, const int32_t* assign_q, void* out,
                  int fuse_inverse_reorder, void* stream) {
   if (!p || !o_m || !assign_q || !out || o_m == out) return HTTM_E_INVALID_ARG;
+  // The assignment a plan with the outlier filter writes holds negative entries (rows of o_out),
+  // which this call has no tensor for: such plans go through httm_unmerge_filtered.
+  if (p->outlier_cap > 0) return HTTM_E_INVALID_ARG;
   if (!aligned16(o_m) || !aligned16(out) || !aligned16(assign_q)) return HTTM_E_INVALID_ARG;
   HTTM_HIP(launch_unmerge(o_m, assign_q, p->d_pi, out, p->geom.H, p->sizes.N, p->sizes.M_q,
                           fuse_inverse_reorder ? 1 : 0, (hipStream_t)stream));

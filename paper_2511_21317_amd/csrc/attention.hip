@@ -848,6 +848,29 @@ constexpr int64_t kSmallTileRound = 768;
 constexpr int64_t kSplitRowsPerTile = (int64_t)kSplitPieces * 256;
 constexpr int64_t kSplitWordsPerRow = kDHead + 2;   // 64 sums of weight * v, the sum of weights, the shift
 
+// Number of 256-row query tiles a launch runs in pieces over the keys when it has room for their
+// partial results (0: every tile runs whole).  A CU runs its tiles two at a time, but one alone
+// nearly twice as fast, so the launch time follows the largest number of whole tiles a CU gets -
+// ceil(tiles / CUs).  The tiles in excess of a multiple of the CU count are split if they are few
+// (splitting e of them saves (1 - e / CUs) of a tile's time), the launch is long (at least one full
+// tile per CU, and not one round of 128-row tiles) and every head has enough key tiles for all
+// pieces.
+int64_t tiles_to_split(const int64_t* q_off_host, const int64_t* k_off_host, int H) {
+  int64_t full = 0, ragged = 0, tiles128 = 0, min_mk = INT64_MAX;
+  for (int h = 0; h < H; ++h) {
+    const int64_t mq = q_off_host[h + 1] - q_off_host[h], mk = k_off_host[h + 1] - k_off_host[h];
+    full += mq / 256;
+    ragged += (mq % 256) != 0;
+    tiles128 += (mq + 127) / 128;
+    min_mk = mk < min_mk ? mk : min_mk;
+  }
+  const int64_t cus = compute_units();
+  const int64_t excess = (full + ragged) % cus;
+  const bool split = excess > 0 && excess <= kAttnSplitTiles && full >= cus && tiles128 > kSmallTileRound &&
+                     min_mk >= 4 * kSplitPieces * kKvTile;
+  return split ? excess : 0;
+}
+
 // `extra_tiles` workgroups are appended for the device-side tile list (a.dev_tiles), if any.
 // `scratch` (fp32 words, or nullptr): room for the split of the tiles in excess, see kSplitPieces.
 // a.marked_only != 0: the fast kernel, then the kernel with per-row shifts on the marked tiles.
@@ -883,22 +906,9 @@ hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_o
   a.split_l = nullptr;
   a.split_m = nullptr;
   const unsigned grid = (unsigned)a.dev_first_block + (unsigned)extra_tiles;
-  // The split pays when the launch is long (at least one full tile per CU) and every head has
-  // enough key tiles for all pieces; it needs the 256-row tiles and room for the partial sums.
-  int64_t min_mk = INT64_MAX;
-  for (int h = 0; h < H; ++h) min_mk = k_off_host[h + 1] - k_off_host[h] < min_mk ? k_off_host[h + 1] - k_off_host[h] : min_mk;
-  // (the same launches for which launch_attention takes the 256-row tiles at all)
-  int64_t tiles128 = 0;
-  for (int h = 0; h < H; ++h) tiles128 += (q_off_host[h + 1] - q_off_host[h] + 127) / 128;
-  // The tiles in excess: a CU runs its tiles two at a time, but one alone nearly twice as fast, so
-  // the launch time follows the largest number of whole tiles a CU gets - ceil(tiles / CUs).  The
-  // `excess` tiles beyond a multiple of the CU count are split if they are few (splitting e of them
-  // saves (1 - e / CUs) of a tile's time).
-  const int64_t cus = compute_units();
-  const int64_t excess = (full + ragged) % cus;
   const int64_t room = scratch ? scratch_words / (kSplitRowsPerTile * kSplitWordsPerRow) : 0;
-  const bool split = BQ == 256 && excess > 0 && excess <= kAttnSplitTiles && excess <= room && full >= cus &&
-                     tiles128 > kSmallTileRound && min_mk >= 4 * kSplitPieces * kKvTile;
+  const int64_t excess = BQ == 256 ? tiles_to_split(q_off_host, k_off_host, H) : 0;
+  const bool split = excess > 0 && excess <= room;
   AttnArgs f = a;   // the first launch when the tiles in excess are split
   unsigned fgrid = grid;
   if (split) {

@@ -33,8 +33,8 @@ int check_geom(const httm_geom_t& g) {
 }
 
 int32_t clusters_kept(int32_t n, double rho, int32_t n0, double dst_frac, int32_t* kd_out) {
-  // Sec. 3.2: r tokens are merged away, M = N - r remain; Sec. 4.1 fixes "ratio rho leaves
-  // (1 - rho)".  Applied per block with the count rounded down; at least one cluster survives,
+  // Sec. 3.2: r tokens are merged away, M = N - r remain; in Sec. 4.1 a ratio rho leaves the share
+  // 1 - rho.  Applied per block with the count rounded down; at least one cluster survives,
   // and every anchored token (App. C.2) is one.
   const int32_t r = (int32_t)std::floor(rho * (double)n + 1e-9);
   int32_t k, kd;
@@ -56,7 +56,7 @@ int32_t clusters_kept(int32_t n, double rho, int32_t n0, double dst_frac, int32_
 }
 
 int64_t outlier_budget(const httm_geom_t& g, int64_t N) {
-  // Sec. 3.4 step 3: "the top d % of tokens ... across all heads", rounded down
+  // Sec. 3.4 step 3: the share d of the tokens of all heads together, rounded down
   if (g.variant == HTTM_VARIANT_NONE || !(g.outlier_frac > 0.0)) return 0;
   return (int64_t)std::floor(g.outlier_frac * (double)g.H * (double)N + 1e-9);
 }

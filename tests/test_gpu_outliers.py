@@ -221,8 +221,9 @@ def test_filtered_layer_full_size_sampled(paper_blocks):
     query tokens filtered out again), in the launch configuration the benchmark times - once with
     the benchmark's 8 x 8 x 4 blocks, once with the paper's own runs of 128 tokens x 30 frames and
     70 % of the keys / values merged.  The threshold needs the deviations of all heads, so the oracle
-    matches and aggregates the queries of every head; merged tokens, attention rows and outputs are
-    then checked for one head on samples."""
+    matches and aggregates the queries of every head: indices, deviations and outlier decisions are
+    compared for all of them; recomputed merged tokens, attention rows and outputs for one head on
+    samples."""
     require_gpu()
     w, frac, h = synth.workload(5), 0.1, 3
     rho_kv = w.rho
@@ -239,12 +240,14 @@ def test_filtered_layer_full_size_sampled(paper_blocks):
     views = httm.workspace_views(plan, ws)
     g = oracle_geom(w)
     pi, blocks = orc.temporal_reorder(g)
-    eps_all, keep = [], {}
+    eps_all, aq_all, gap_all, keep = [], [], [], {}
     for hh in range(w.H):
         qr = orc.reorder(f32(q[hh]), pi)
         aq, _, gap = orc.blockwise_tome(qr, g, blocks, w.rho)
         qm0 = orc.block_aggregate(qr, aq, g, blocks, w.rho)
         eps_all.append(orc.deviations(qr, aq, qm0))
+        aq_all.append(aq)
+        gap_all.append(gap)
         if hh == h:
             keep = dict(qr=qr, aq=aq, gap=gap, qm0=qm0)
         print(f"[step] oracle deviations head {hh}", flush=True)
@@ -253,6 +256,36 @@ def test_filtered_layer_full_size_sampled(paper_blocks):
     assert sum(counts) <= plan.outlier_cap and sum(counts) >= plan.outlier_cap - 16
     n_ref = [int((e > tau).sum()) for e in eps_all]
     assert max(abs(a - b) for a, b in zip(counts, n_ref)) <= 32          # per-head split of the shared budget
+    # ---- every head: the clusters before the filter, the deviations and the outlier decisions.
+    # The GPU's clusters before the filter (an outlier's entry no longer shows the cluster it left) come
+    # from the same stage 2 on a plan without the filter.
+    plan0 = plan_for(w, rho_kv=rho_kv)
+    v0 = httm.workspace_views(plan0, httm.alloc_workspace(plan0))
+    httm.reorder_match_merge(plan0, q, k, v, v0["q_m"], v0["k_m"], v0["v_m"], v0["assign_q"], v0["assign_k"])
+    torch.cuda.synchronize()
+    a_pre_all = v0["assign_q"].cpu().numpy()
+    plan0.close()
+    del v0
+    a_gpu_all = views["assign_q"].cpu().numpy()
+    e_gpu_all = views["eps_q"].cpu().numpy()
+    n_flip = n_moved = 0
+    for hh in range(w.H):
+        m_ref, m_gpu_h = eps_all[hh] > tau, a_gpu_all[hh] < 0
+        assert np.array_equal(a_pre_all[hh][~m_gpu_h], a_gpu_all[hh][~m_gpu_h])
+        n_moved += check_assign(a_pre_all[hh], aq_all[hh], gap_all[hh], f"{w.name} filtered assign_q head {hh}")
+        touched_h = np.zeros(plan.M_q, dtype=bool)
+        moved = np.flatnonzero(a_pre_all[hh] != aq_all[hh])
+        touched_h[a_pre_all[hh][moved]] = True
+        touched_h[aq_all[hh][moved]] = True
+        clean = ~touched_h[aq_all[hh]]
+        assert np.abs(e_gpu_all[hh] - eps_all[hh])[clean].max() <= 2e-5 * float(eps_all[hh].max()), f"eps head {hh}"
+        flip_h = np.flatnonzero(m_gpu_h != m_ref)
+        near = np.abs(eps_all[hh][flip_h] - tau) <= NEAR_TAU * tau
+        assert (near | ~clean[flip_h] | (gap_all[hh][flip_h] < 1e-3)).all(), f"head {hh}: a decision flipped away from tau"
+        n_flip += flip_h.size
+    print(f"{w.name} d={frac}: all {w.H} heads - {n_moved} of {w.H * w.N} indices differ (gap < 1e-3), "
+          f"{n_flip} outlier decisions differ (near tau or in a cluster a tie changed)", flush=True)
+    assert n_flip <= 1e-3 * w.H * w.N
     # ---- head h in detail
     qr, aq, gap = keep["qr"], keep["aq"], keep["gap"]
     mask = eps_all[h] > tau
@@ -267,15 +300,7 @@ def test_filtered_layer_full_size_sampled(paper_blocks):
     ak, _, _ = orc.blockwise_tome(kr, g, blocks, rho_kv)
     km = orc.block_aggregate(kr, ak, g, blocks, rho_kv)
     vm = orc.block_aggregate(vr, ak, g, blocks, rho_kv)
-    # the GPU's clusters before the filter (an outlier's entry no longer shows the cluster it left):
-    # the same stage 2 on a plan without the filter
-    plan0 = plan_for(w, rho_kv=rho_kv)
-    v0 = httm.workspace_views(plan0, httm.alloc_workspace(plan0))
-    httm.reorder_match_merge(plan0, q, k, v, v0["q_m"], v0["k_m"], v0["v_m"], v0["assign_q"], v0["assign_k"])
-    torch.cuda.synchronize()
-    a_pre = v0["assign_q"][h].cpu().numpy()
-    plan0.close()
-    del v0
+    a_pre = a_pre_all[h]
     assert np.array_equal(a_pre[~m_gpu], a_gpu[~m_gpu])
     touched = np.zeros(qm.shape[0], dtype=bool)          # clusters a tie or a flipped decision changed
     moved = np.flatnonzero(a_pre != aq)
@@ -341,4 +366,22 @@ def test_filtered_layer_full_size_plain_keys_stage3():
         check_output(f32(views["o_out"][sel]), want_o, f"plain keys o_out head {h}")
         print(f"[step] head {h} checked", flush=True)
     assert torch.isfinite(out.float()).all()
+    plan.close()
+
+
+def test_plain_unmerge_refuses_a_plan_with_the_filter():
+    """httm_unmerge has no tensor for the rows that negative assign_q entries refer to: on a plan
+    with outlier_frac > 0 it returns an error before anything is launched."""
+    require_gpu()
+    w = synth.workload(1)
+    plan = plan_for(w, outlier_frac=0.05)
+    o_m = torch.zeros((plan.H, plan.M_q, 64), dtype=torch.bfloat16, device="cuda")
+    aq = torch.zeros((plan.H, plan.N), dtype=torch.int32, device="cuda")
+    for fused in (True, False):
+        out = torch.full((plan.N, plan.H * 64) if fused else (plan.H, plan.N, 64), float("nan"),
+                         dtype=torch.bfloat16, device="cuda")
+        with pytest.raises(httm.HttmError, match="invalid argument"):
+            httm.unmerge(plan, o_m, aq, out, fuse_inverse_reorder=fused)
+        torch.cuda.synchronize()
+        assert torch.isnan(out.float()).all()
     plan.close()

@@ -167,35 +167,6 @@ def test_paper_scale_blocks_with_separate_ratios():
     plan.close()
 
 
-def test_exact_ties_and_zero_vectors_follow_the_lowest_cluster_rule():
-    """Duplicated dst tokens (exact similarity ties) and all-zero tokens, on the GPU and in the oracle."""
-    require_gpu()
-    w = Workload("ties", 21, 4, 8, 8, 4, 2, 0.75, 1, H=2)
-    q, k, v = _inputs(w)
-    g = oracle_geom(w)
-    pi, blocks = orc.temporal_reorder(g)
-    qn = f32(q).copy()
-    # in every block: make dst 1 an exact copy of dst 0, and zero one src token
-    for (start, n) in blocks:
-        kk = orc.cluster_count(n, w.rho)
-        d = orc.dst_positions(n, kk)
-        qn[:, pi[start + d[1]]] = qn[:, pi[start + d[0]]]
-        qn[:, pi[start + d[0] + 1]] = 0.0
-    q = torch.from_numpy(qn).to(torch.bfloat16).cuda()
-    plan = plan_for(w)
-    got = run_stages(plan, q, k, v)
-    ref = _oracle_stages(w, q, k, v)
-    for h in range(w.H):
-        ga = got["assign_q"][h].cpu().numpy()
-        assert np.array_equal(ga, ref["assign_q"][h])          # ties resolved identically: exact
-        ks, offs, _ = orc.merged_layout(g, blocks, w.rho)
-        for (start, n), off in zip(blocks, offs):
-            # cluster 1 duplicates cluster 0, so it never wins: its only member is its own dst token
-            assert int((ga[start:start + n] == off + 1).sum()) == 1
-    check_output(f32(got["out"]), ref["O"], "ties", relative_to_magnitude=True)
-    plan.close()
-
-
 RAGGED = [
     ([1, 63, 64, 65, 129, 300], [7, 64, 1, 200, 513, 65]),
     ([128, 0, 5, 257], [64, 33, 0, 1000]),            # a head without queries, a head without keys
