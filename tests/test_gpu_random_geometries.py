@@ -10,8 +10,8 @@ import synth
 from oracle import httm_oracle as orc
 from synth.vggt_tokens import Workload
 
-from gpu_util import (TIE_FRACTION, TIE_GAP, check_output, excuse_tie_tokens, f32, oracle_geom, plain_keys, plan_for,
-                      require_gpu, run_layer, run_stages)
+from gpu_util import (TIE_FRACTION, TIE_GAP, check_output, f32, oracle_continued_from, oracle_geom, output_bar,
+                      plain_keys, plan_for, require_gpu, run_layer, run_stages)
 
 pytestmark = pytest.mark.gpu
 
@@ -84,17 +84,19 @@ def test_layer_on_a_random_geometry(seed):
         want_r = orc.unmerge_by_cluster(got["o_m"][h].cpu().view(torch.int16).numpy(), aq[h].astype(np.int64))
         assert np.array_equal(got["out"].cpu().view(torch.int16).numpy()[:, h * 64:(h + 1) * 64],
                               orc.inverse_reorder(want_r, pi))
-    # end to end against the all-fp32 oracle.  The bar of the five workloads (2e-2) assumes thousands of
-    # keys per row; with a few hundred the roundings of the merged tokens (2^-9 each on q, k, v) are not
-    # averaged over keys, so small cases are read against three times that.
+    # end to end against the all-fp32 oracle, downstream of the GPU's own (checked) cluster decisions
+    # where an allowed tie went the other way.  The bar is the spec bar, or twice what bf16 storage
+    # of the intermediates costs on this very case (gpu_util.output_bar: with a few hundred keys per row
+    # and un-normalised values that alone passes 2e-2; tests/test_tolerance_model.py pins the model).
     out_f = f32(got["out"])
     assert np.isfinite(out_f).all()
-    if all(np.array_equal(ak[h], ref["assign_k"][h]) for h in range(w.H)):
-        want = excuse_tie_tokens(out_f, ref["O"], aq.astype(np.int64), ref)
-        diff = np.abs(out_f - want) / np.maximum(1.0, np.abs(want))
-        rel = float(np.linalg.norm(out_f - want) / max(np.linalg.norm(want), 1e-30))
-        bar = 2e-2 if plan.M_k >= 1024 else 6e-2
-        assert diff.max() < bar and rel < 1e-2, f"{w.name} layer output: max_abs={diff.max():.4g} rel_l2={rel:.4g}"
+    want = oracle_continued_from(ref, f32(q), f32(k), f32(v), g, w.rho, rho_kv, aq, ak)
+    bar_abs, bar_rel, e_abs, e_rel = output_bar(ref, got["key_scale"])
+    err = float(np.abs(out_f - want).max())
+    rel = float(np.linalg.norm(out_f - want) / max(np.linalg.norm(want), 1e-30))
+    print(f"{w.name}: max_abs {err:.4g} (bf16 storage alone {e_abs:.4g}, bar {bar_abs:.4g}), "
+          f"rel_l2 {rel:.4g} (storage {e_rel:.4g}, bar {bar_rel:.4g})", flush=True)
+    assert err < bar_abs and rel < bar_rel, f"{w.name} layer output: max_abs={err:.4g} rel_l2={rel:.4g}"
     out, _ = run_layer(plan, q, k, v)
     assert torch.equal(out, got["out"])                  # the layer call = the four stages, bit for bit
     plan.close()
