@@ -280,6 +280,22 @@ HTTM_API int httm_attention_scratch(const void* q_m, const void* k_m, const void
                                     const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
                                     float scale, void* scratch, int64_t scratch_bytes, void* stream);
 
+/* httm_attention_log2_scratch for callers that cannot allocate device memory and have no buffer to
+ * pass: code that runs under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The scratch is an array of HTTM_STATIC_SCRATCH_BYTES inside the library's device code
+ * (every GPU the library has run on holds its copy until the process ends); the call allocates and
+ * frees nothing.  Arguments, layout and results as httm_attention_log2_scratch (bit-identical to
+ * it).  A launch whose partial results need more than the array holds is refused with
+ * HTTM_E_WORKSPACE_TOO_SMALL and nothing is launched: use httm_attention_log2_scratch with a buffer
+ * of the caller, or httm_attention_log2, which needs none.  All calls on one GPU share the array:
+ * two of them that overlap in time (two streams) race - serialise them.  Its contents between
+ * calls are meaningless; every call writes what it later reads.  The first call on a device looks up
+ * the array's address (not capturable: make one call before capturing). */
+#define HTTM_STATIC_SCRATCH_BYTES (32ll << 20)
+HTTM_API int httm_attention_log2_static(const void* q_m, const void* k_log2, const void* v_m, void* o_m,
+                                        const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
+                                        void* stream);
+
 /* ---- stage 4: unmerge (Sec. 3.2 Eq. 5-7) and inverse reorder (Sec. 3.3) ------------------ */
 
 /* o_m      : [H, M_q, d_head] bf16, attention output per merged query.

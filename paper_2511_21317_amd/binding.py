@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
     L.httm_attention_scratch.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, C.c_float, vp, C.c_int64, vp]
     L.httm_attention_log2.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, vp]
     L.httm_attention_log2_scratch.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, vp, C.c_int64, vp]
+    L.httm_attention_log2_static.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, vp]
     L.httm_attention_scratch_bytes.argtypes = [C.c_int]
     L.httm_attention_scratch_bytes.restype = C.c_int64
     L.httm_unmerge.argtypes = [vp, vp, i32p, vp, C.c_int, vp]
@@ -83,7 +84,7 @@ def lib() -> C.CDLL:
     for name in ("httm_geom_sizes", "httm_workspace_layout", "httm_geom_tables", "httm_geom_block_forms", "httm_plan_create",
                  "httm_plan_destroy", "httm_plan_query", "httm_reorder", "httm_match_merge",
                  "httm_reorder_match_merge",
-                 "httm_attention", "httm_attention_scratch", "httm_attention_log2", "httm_attention_log2_scratch", "httm_unmerge", "httm_layer_forward",
+                 "httm_attention", "httm_attention_scratch", "httm_attention_log2", "httm_attention_log2_scratch", "httm_attention_log2_static", "httm_unmerge", "httm_layer_forward",
                  "httm_reorder_match_merge_filtered", "httm_attention_outliers", "httm_unmerge_filtered",
                  "httm_outlier_stats", "httm_global_match"):
         getattr(L, name).restype = C.c_int
@@ -269,6 +270,18 @@ def attention_log2(q_m, k_log2, v_m, o_m, q_offsets, k_offsets, scratch=None):
         _check(lib().httm_attention_log2_scratch(_dev(q_m, bf), _dev(k_log2, bf), _dev(v_m, bf), _dev(o_m, bf),
                                                  qo, ko, H, 64, _dev(scratch, torch.uint8),
                                                  scratch.numel(), _stream()), "httm_attention_log2_scratch")
+    return o_m
+
+
+def attention_log2_static(q_m, k_log2, v_m, o_m, q_offsets, k_offsets):
+    """attention_log2() with the library's own static scratch (httm_attention_log2_static): no
+    allocation anywhere in the call."""
+    H = len(q_offsets) - 1
+    qo = (C.c_int64 * (H + 1))(*[int(x) for x in q_offsets])
+    ko = (C.c_int64 * (H + 1))(*[int(x) for x in k_offsets])
+    bf = torch.bfloat16
+    _check(lib().httm_attention_log2_static(_dev(q_m, bf), _dev(k_log2, bf), _dev(v_m, bf), _dev(o_m, bf), qo, ko,
+                                            H, 64, _stream()), "httm_attention_log2_static")
     return o_m
 
 

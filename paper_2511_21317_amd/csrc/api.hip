@@ -411,6 +411,21 @@ int httm_attention_log2(const void* q_m, const void* k_log2, const void* v_m, vo
   return run_attention(q_m, k_log2, v_m, o_m, q_offsets, k_offsets, H, d_head, 1.0f, true, nullptr, 0, stream);
 }
 
+int httm_attention_log2_static(const void* q_m, const void* k_log2, const void* v_m, void* o_m,
+                               const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
+                               void* stream) {
+  if (!q_offsets || !k_offsets || H <= 0) return HTTM_E_INVALID_ARG;
+  if (d_head != 64 || H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
+  for (int h = 0; h < H; ++h)
+    if (q_offsets[h + 1] < q_offsets[h] || k_offsets[h + 1] < k_offsets[h]) return HTTM_E_INVALID_ARG;
+  // the partial results of this launch must fit the library's array; nothing is launched otherwise
+  if (attention_scratch_need(q_offsets, k_offsets, H) > kAttnStaticScratchBytes) return HTTM_E_WORKSPACE_TOO_SMALL;
+  void* lib_scratch = nullptr;
+  HTTM_HIP(attention_static_scratch(&lib_scratch));
+  return run_attention(q_m, k_log2, v_m, o_m, q_offsets, k_offsets, H, d_head, 1.0f, true, lib_scratch,
+                       kAttnStaticScratchBytes, stream);
+}
+
 int64_t httm_attention_scratch_bytes(int H) { return H > 0 && H <= HTTM_MAX_HEADS ? attention_scratch_bytes(H) : 0; }
 
 int httm_unmerge(const httm_plan_t* p, const void* o_m, const int32_t* assign_q, void* out,

@@ -65,6 +65,7 @@
 // scratch memory, the fast kernel runs those tiles in kSplitPieces pieces over the keys, dispatched
 // first, and attention_split_reduce_kernel adds the pieces up (see kSplitPieces and launch_cfg()).
 #include <cstring>
+#include <mutex>
 #include <type_traits>
 
 #include "dev_common.hpp"
@@ -1030,6 +1031,37 @@ hipError_t launch_attention(const void* q, const void* k, const void* v, void* o
   for (int h = 0; h < H; ++h) tiles128 += (q_off_host[h + 1] - q_off_host[h] + 127) / 128;
   if (tiles128 <= kSmallTileRound) return launch_cfg<1, 4>(a, q_off_host, k_off_host, H, stream);
   return launch_cfg<2, 4>(a, q_off_host, k_off_host, H, stream, 0, (float*)scratch, scratch_bytes / 4);
+}
+
+// ---- scratch that belongs to the library -------------------------------------------------------
+// For callers that cannot allocate device memory (code under HIP graph capture, serving loops, test
+// harnesses that forbid it): the room for the partial results of the tiles that run in pieces, as a
+// device array of fixed size.  Every GPU the library runs on holds its own copy at its own address
+// until the process ends; the array's name is only a host-side handle, the address comes from
+// hipGetSymbolAddress, once per device, and only that pointer is ever handed to a kernel.
+static __device__ __align__(256) unsigned char g_static_scratch[kAttnStaticScratchBytes];
+
+int64_t attention_scratch_need(const int64_t* q_off_host, const int64_t* k_off_host, int H) {
+  return tiles_to_split(q_off_host, k_off_host, H) * kSplitRowsPerTile * kSplitWordsPerRow * 4;
+}
+
+hipError_t attention_static_scratch(void** ptr) {
+  static std::mutex mu;
+  static void* per_device[64] = {nullptr};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!per_device[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    per_device[dev] = p;
+  }
+  *ptr = per_device[dev];
+  return hipSuccess;
 }
 
 }  // namespace httm

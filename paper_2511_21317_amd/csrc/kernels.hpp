@@ -117,6 +117,12 @@ hipError_t launch_attention(const void* q, const void* k, const void* v, void* o
                             const int64_t* q_off_host, const int64_t* k_off_host, int H,
                             float scale, bool log2_keys, hipStream_t stream, void* scratch = nullptr,
                             int64_t scratch_bytes = 0);
+// Bytes of scratch launch_attention would use for these head lengths if it had them (0: every tile
+// runs whole), and the library's own scratch for callers that cannot allocate: a static device
+// array of kAttnStaticScratchBytes, whose address on the current device *ptr receives.
+constexpr int64_t kAttnStaticScratchBytes = 32ll << 20;
+int64_t attention_scratch_need(const int64_t* q_off_host, const int64_t* k_off_host, int H);
+hipError_t attention_static_scratch(void** ptr);
 // Query rows and tiles are described by device memory (the outlier queries of Sec. 3.4, whose
 // number per head is only known on the device): q / o rows of head h are
 // [q_off_dev[h], q_off_dev[h+1]); tiles[0] tiles follow in `tiles` as (head, first row) pairs.
