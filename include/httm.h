@@ -261,14 +261,15 @@ HTTM_API int httm_attention_log2(const void* q_m, const void* k_log2, const void
 
 /* httm_attention_log2 with scratch memory (device, 16-byte aligned, scratch_bytes >=
  * httm_attention_scratch_bytes(H); its contents before and after the call are meaningless).  A
- * launch ends when its last workgroup ends, and a compute unit runs whole 256-row query tiles; with
- * scratch, a long launch whose number of tiles lies a little (at most 64) above a multiple of the
- * number of compute units runs the tiles in excess - the partial last tiles of the heads first,
- * then full tiles from the end - in pieces over the keys and adds the pieces up afterwards, so
- * that it does not end on a few compute units running one more whole tile than the others.  The
- * results agree with httm_attention_log2 to fp32 rounding of the sums (the pieces are added in key
- * order, run-to-run identical).  httm_layer_forward does the same with the attn_split region of
- * its workspace.
+ * launch ends when its last workgroup ends, and a compute unit runs whole 256-row query tiles: T
+ * tiles on C compute units take ceil(T / C) tile times.  With scratch, the T mod C tiles in excess
+ * of a multiple of C - the partial last tiles of the heads first, then full tiles from the end - are
+ * not run whole: their work is cut into equal shares over the keys, one or two per compute unit,
+ * that run behind the whole tiles, and a second kernel adds the pieces of every tile up (in key
+ * order: run-to-run identical), so that any tile count fills the chip.  Launches too short for the
+ * split to pay (it costs about 15 us) run as without scratch.  The results agree with
+ * httm_attention_log2 to fp32 rounding of the sums.  httm_layer_forward does the same with the
+ * attn_split region of its workspace.
  * httm_attention_scratch is httm_attention with the same scratch and the same rule; there every
  * piece keeps the shift its sums are relative to, and the pieces of a row are brought to the
  * largest of their shifts before they are added. */
@@ -279,6 +280,21 @@ HTTM_API int httm_attention_log2_scratch(const void* q_m, const void* k_log2, co
 HTTM_API int httm_attention_scratch(const void* q_m, const void* k_m, const void* v_m, void* o_m,
                                     const int64_t* q_offsets, const int64_t* k_offsets, int H, int d_head,
                                     float scale, void* scratch, int64_t scratch_bytes, void* stream);
+
+/* Host only (no GPU needed): how stage 3 with scratch cuts a launch with these head lengths on a
+ * device of `compute_units` compute units - the very functions the kernels evaluate; for tests and
+ * diagnostics.  HOST arrays:
+ *   summary[8]  : tiles that run in pieces (0: none), shares, key tiles (of 64 keys) per share,
+ *                 most tiles a share touches, slots of scratch (256 rows x 66 fp32 each), key tiles of
+ *                 all split tiles together, full tiles that stay whole, partial tiles that are split
+ *   segments    : or NULL; 5 int32 per slot (one workgroup each, at most max_segments): head, first
+ *                 query row, key tiles [t0, t1) of the head's sequence (t0 >= t1: the slot is unused,
+ *                 its workgroup has nothing to do), slot
+ *   tiles       : or NULL; 4 int32 per split tile (at most max_tiles): head, first query row, first
+ *                 and last share that left a piece of it (their slots are share + tile index) */
+HTTM_API int httm_attention_split_plan(const int64_t* q_offsets, const int64_t* k_offsets, int H, int compute_units,
+                                       int32_t* summary, int32_t* segments, int64_t max_segments,
+                                       int32_t* tiles, int64_t max_tiles);
 
 /* httm_attention_log2_scratch for callers that cannot allocate device memory and have no buffer to
  * pass: code that runs under HIP graph capture, tight serving loops, harnesses that forbid

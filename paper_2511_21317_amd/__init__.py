@@ -5,5 +5,5 @@ from .binding import (  # noqa: F401
     workspace_layout, reorder, match_merge, reorder_match_merge, attention, unmerge, layer_forward,
     workspace_views, alloc_workspace, lib, LIB_PATH, VARIANTS,
     reorder_match_merge_filtered, attention_outliers, unmerge_filtered, outlier_stats, global_match,
-    attention_log2, attention_log2_static, attention_scratch_bytes, FLAG_LOG2_KEYS, LOG2_KEY_SCALE,
+    attention_log2, attention_log2_static, attention_scratch_bytes, attention_split_plan, FLAG_LOG2_KEYS, LOG2_KEY_SCALE,
 )

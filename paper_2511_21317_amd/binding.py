@@ -72,6 +72,7 @@ def lib() -> C.CDLL:
     L.httm_attention_log2.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, vp]
     L.httm_attention_log2_scratch.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, vp, C.c_int64, vp]
     L.httm_attention_log2_static.argtypes = [vp, vp, vp, vp, i64p, i64p, C.c_int, C.c_int, vp]
+    L.httm_attention_split_plan.argtypes = [i64p, i64p, C.c_int, C.c_int, vp, vp, C.c_int64, vp, C.c_int64]
     L.httm_attention_scratch_bytes.argtypes = [C.c_int]
     L.httm_attention_scratch_bytes.restype = C.c_int64
     L.httm_unmerge.argtypes = [vp, vp, i32p, vp, C.c_int, vp]
@@ -84,7 +85,7 @@ def lib() -> C.CDLL:
     for name in ("httm_geom_sizes", "httm_workspace_layout", "httm_geom_tables", "httm_geom_block_forms", "httm_plan_create",
                  "httm_plan_destroy", "httm_plan_query", "httm_reorder", "httm_match_merge",
                  "httm_reorder_match_merge",
-                 "httm_attention", "httm_attention_scratch", "httm_attention_log2", "httm_attention_log2_scratch", "httm_attention_log2_static", "httm_unmerge", "httm_layer_forward",
+                 "httm_attention", "httm_attention_scratch", "httm_attention_log2", "httm_attention_log2_scratch", "httm_attention_log2_static", "httm_attention_split_plan", "httm_unmerge", "httm_layer_forward",
                  "httm_reorder_match_merge_filtered", "httm_attention_outliers", "httm_unmerge_filtered",
                  "httm_outlier_stats", "httm_global_match"):
         getattr(L, name).restype = C.c_int
@@ -250,6 +251,25 @@ def attention(q_m, k_m, v_m, o_m, q_offsets, k_offsets, scale: float = 0.125, sc
                                             H, 64, float(scale), _dev(scratch, torch.uint8), scratch.numel(),
                                             _stream()), "httm_attention_scratch")
     return o_m
+
+
+def attention_split_plan(q_offsets, k_offsets, compute_units: int = 256) -> dict:
+    """How stage 3 with scratch cuts a launch with these head lengths (host only, no GPU needed)."""
+    H = len(q_offsets) - 1
+    qo = (C.c_int64 * (H + 1))(*[int(x) for x in q_offsets])
+    ko = (C.c_int64 * (H + 1))(*[int(x) for x in k_offsets])
+    summary = np.zeros(8, np.int32)
+    ptr = lambda a: a.ctypes.data_as(C.c_void_p)  # noqa: E731
+    _check(lib().httm_attention_split_plan(qo, ko, H, int(compute_units), ptr(summary), None, 0, None, 0),
+           "httm_attention_split_plan")
+    names = ("n_tiles", "shares", "share_units", "span", "slots", "units", "kept_full", "split_ragged")
+    out = {n: int(v) for n, v in zip(names, summary)}
+    seg = np.zeros((out["slots"], 5), np.int32)
+    tiles = np.zeros((out["n_tiles"], 4), np.int32)
+    _check(lib().httm_attention_split_plan(qo, ko, H, int(compute_units), ptr(summary), ptr(seg), seg.shape[0],
+                                           ptr(tiles), tiles.shape[0]), "httm_attention_split_plan")
+    out["segments"], out["tiles"] = seg, tiles
+    return out
 
 
 def attention_scratch_bytes(H: int) -> int:

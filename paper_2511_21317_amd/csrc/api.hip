@@ -6,6 +6,7 @@
 #include <new>
 
 #include "../../include/httm.h"
+#include "attention_split.hpp"
 #include "geometry.hpp"
 #include "kernels.hpp"
 
@@ -424,6 +425,54 @@ int httm_attention_log2_static(const void* q_m, const void* k_log2, const void* 
   HTTM_HIP(attention_static_scratch(&lib_scratch));
   return run_attention(q_m, k_log2, v_m, o_m, q_offsets, k_offsets, H, d_head, 1.0f, true, lib_scratch,
                        kAttnStaticScratchBytes, stream);
+}
+
+int httm_attention_split_plan(const int64_t* q_offsets, const int64_t* k_offsets, int H, int compute_units,
+                              int32_t* summary, int32_t* segments, int64_t max_segments, int32_t* tiles,
+                              int64_t max_tiles) {
+  if (!q_offsets || !k_offsets || !summary || H <= 0 || compute_units <= 0) return HTTM_E_INVALID_ARG;
+  if (H > HTTM_MAX_HEADS) return HTTM_E_UNSUPPORTED;
+  for (int h = 0; h < H; ++h)
+    if (q_offsets[h + 1] < q_offsets[h] || k_offsets[h + 1] < k_offsets[h]) return HTTM_E_INVALID_ARG;
+  SplitPlan sp;
+  int64_t kept_full = 0;
+  int split_ragged = 0;
+  plan_attention_split(q_offsets, k_offsets, H, compute_units, &sp, &kept_full, &split_ragged);
+  const int64_t n_slots = split_slots(sp);
+  summary[0] = sp.n_tiles;
+  summary[1] = sp.shares;
+  summary[2] = sp.share_units;
+  summary[3] = sp.span;
+  summary[4] = (int32_t)n_slots;
+  summary[5] = sp.units;
+  summary[6] = (int32_t)kept_full;
+  summary[7] = split_ragged;
+  if (segments) {
+    if (max_segments < n_slots) return HTTM_E_WORKSPACE_TOO_SMALL;
+    for (int64_t b = 0; b < n_slots; ++b) {
+      const int32_t unused[5] = {0, 0, 0, 0, (int32_t)b};
+      std::memcpy(segments + 5 * b, unused, sizeof(unused));
+    }
+    for (int s = 0; s < sp.shares; ++s) {       // as a workgroup walks its share
+      int first = 0, count = 0;
+      split_share_tiles(sp, s, &first, &count);
+      for (int e = first; e < first + count; ++e) {
+        const SplitSegment g = split_segment(sp, s, e);
+        const int32_t row[5] = {g.head, g.q0, g.t0, g.t1, g.slot};
+        if (g.slot < 0 || g.slot >= n_slots) return HTTM_E_INVALID_ARG;
+        std::memcpy(segments + 5 * (int64_t)g.slot, row, sizeof(row));
+      }
+    }
+  }
+  if (tiles) {
+    if (max_tiles < sp.n_tiles) return HTTM_E_WORKSPACE_TOO_SMALL;
+    for (int e = 0; e < sp.n_tiles; ++e) {
+      const SplitTile t = split_tile(sp, e);
+      const int32_t row[4] = {t.head, t.q0, t.first_share, t.last_share};
+      std::memcpy(tiles + 4 * e, row, sizeof(row));
+    }
+  }
+  return HTTM_OK;
 }
 
 int64_t httm_attention_scratch_bytes(int H) { return H > 0 && H <= HTTM_MAX_HEADS ? attention_scratch_bytes(H) : 0; }

@@ -60,14 +60,15 @@
 // SHIFT kernel is launched right behind on the same grid and redoes exactly the marked tiles.
 //
 // End of a launch.  A CU runs its 256-row tiles two at a time, but one alone nearly twice as fast,
-// so the launch time follows the largest number of whole tiles a CU gets.  When the partial last
-// tiles of the heads are what gives some CUs one more tile than the others, and the caller has given
-// scratch memory, the fast kernel runs those tiles in kSplitPieces pieces over the keys, dispatched
-// first, and attention_split_reduce_kernel adds the pieces up (see kSplitPieces and launch_cfg()).
+// so the launch time follows the largest number of whole tiles a CU gets.  When the caller has given
+// scratch memory, the tiles in excess of a multiple of the CU count are not run whole: their work
+// is cut into equal shares over the keys, one or two per CU, that are dispatched behind the whole
+// tiles, and attention_split_reduce_kernel adds the pieces of every tile up (attention_split.hpp).
 #include <cstring>
 #include <mutex>
 #include <type_traits>
 
+#include "attention_split.hpp"
 #include "dev_common.hpp"
 #include "kernels.hpp"
 
@@ -99,34 +100,26 @@ struct AttnArgs {
   // When set, a second set of query tiles is described by device memory: rows of head h are
   // [dev_q_off[h], dev_q_off[h+1]) and workgroup t takes tile (head, first row) =
   // (dev_tiles[1+2t], dev_tiles[2+2t]) for t < dev_tiles[0].
-  // Workgroups from dev_first_block on take these tiles; their queries and outputs are q2 / o2.
+  // The workgroups behind the whole tiles and the segments take these tiles; their queries and outputs
+  // are q2 / o2.
   const int32_t* dev_q_off;
   const int32_t* dev_tiles;
   const bf16_t* q2;
   bf16_t* o2;
-  int32_t dev_first_block;
-  // The tiles in excess (see kSplitPieces) split over the keys (not in a launch that only redoes
-  // marked tiles).  The first split_blocks workgroups (a multiple of 8) are pieces: block b is piece
-  // b % kSplitPieces of split tile b / kSplitPieces = (split_head[i], first row split_q0[i]), takes
-  // an equal share of its head's key tiles and writes unnormalised fp32 results, which
-  // attention_split_reduce_kernel adds up.  The other workgroups then number from split_blocks on;
-  // n_ragged / ragged_head and n_full count only the tiles that stay whole.
-  int32_t split_blocks;
-  int32_t n_split;
-  int32_t split_head[kAttnSplitTiles];
-  int32_t split_q0[kAttnSplitTiles];
-  float* split_o;   // [n_split * kSplitPieces * BQ][64] sums of weight * v
-  float* split_l;   // [n_split * kSplitPieces * BQ]     sums of weights
-  float* split_m;   // [n_split * kSplitPieces * BQ]     the rows' shifts (kernel with per-row shifts only)
+  // Every XCD (workgroup b goes to XCD b % 8) walks a sequence of full_per_xcd + ragged_per_xcd whole
+  // tiles and then split_per_xcd shares of the tiles that run in segments over the keys
+  // (attention_split.hpp; none in a launch that only redoes marked tiles).  A segment writes
+  // un-normalised fp32 results into its slot of the scratch memory and attention_split_reduce_kernel
+  // adds them up.  The workgroups behind main_blocks = 8 * (sequence length) take the device-side tile
+  // list.  n_ragged / ragged_head and n_full count only the tiles that stay whole.
+  int32_t split_per_xcd;
+  int32_t main_blocks;
+  float* split_o;   // [slots * 256][64] sums of weight * v
+  float* split_l;   // [slots * 256]     sums of weights
+  float* split_m;   // [slots * 256]     the rows' shifts (kernel with per-row shifts only)
+  SplitPlan sp;
 };
-
-// Pieces per split tile.  A launch ends when its last workgroup ends, and a CU runs whole tiles:
-// with 7 tiles per CU and 16 tiles on top (the partial last tile of every head, say), 16 CUs run
-// an eighth tile while the others idle (measured 2.80 against 2.55 ms without those tiles).  The
-// tiles in excess of a multiple of the CU count - the partial tiles first, then the last full
-// ones, at most kAttnSplitTiles - are therefore cut into 16 pieces over the keys that run first and
-// cost every CU about a sixteenth of a tile each.
-constexpr int kSplitPieces = kAttnSplitPieces;
+static_assert(sizeof(AttnArgs) <= 4096, "kernel arguments are limited to 4 KB");
 
 // V tile in LDS: 64 rows of 128 bytes, written by global->LDS loads like the K tile; the 16-byte
 // chunk c of row r sits at chunk position c ^ (2 * (r & 3)), so that the four rows a transposing read
@@ -456,62 +449,19 @@ constexpr uint16_t kRedoMark = 0x7FA5;
 constexpr float kFastSumMin = 5.421010862427522e-20f;    // 2^-64
 constexpr float kFastSumMax = 1.8446744073709552e19f;    // 2^64
 
-// SHIFT = false: the fast kernel (keys carry the logit scale; weights exp2(s)).  SHIFT = true: per-row
-// shifts and the overflow guard; with a.marked_only it is launched right after the fast kernel on
-// the same grid and a workgroup leaves at once unless the fast kernel marked its tile.
+// One query tile (or one segment of it) of a workgroup: see attention_kernel.
+//   h, q0          : head and first query row of the tile
+//   dev_tile       : the tile comes from the device-side list (rows q_base_dev .. + mq_dev of q2 / o2)
+//   seg.slot >= 0  : only the key tiles [seg.t0, seg.t1) of the head, results into scratch slot seg.slot
 template <int QT, int NW, bool SHIFT>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, QT == 1 ? 3 : 2)))
-void attention_kernel(const AttnArgs a) {
+__device__ __forceinline__ void attention_tile(const AttnArgs& a, bf16_t (*s_k)[kKvTile * kDHead],
+                                               bf16_t (*s_v)[kKvTile * kDHead], const int h, const int q0,
+                                               const bool dev_tile, const int64_t q_base_dev, const int mq_dev,
+                                               const SplitSegment seg) {
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * QT * NW;
-  constexpr int LD_ITER = kKvTile * kRowChunks / NT;       // 16-byte K chunks per thread per tile
-  static_assert(LD_ITER >= 2 && LD_ITER % 2 == 0, "tile staging needs an even chunk count");
-  constexpr int kTileElems = kKvTile * kDHead;
   constexpr int LDK = 8 / NW;                              // 1 KB global->LDS loads per wave per tile
-  __shared__ __align__(16) bf16_t s_k[2][kTileElems];    // [kv][d], 128-byte rows, chunk-swizzled
-  __shared__ __align__(16) bf16_t s_v[2][kTileElems];    // [kv][d], 128-byte rows, chunk-swizzled
-
-  // blockIdx -> (head, first query row).  Workgroups go round-robin to the 8 XCDs, and in
-  // blockIdx order to free slots; the partial last tiles of the heads come first (they are
-  // short, so they should not be what the grid ends on), then every XCD walks a contiguous
-  // range of full tiles.
-  int block = (int)blockIdx.x;
-  int piece = -1, piece_tile = 0;               // a piece of a split tile
-  if (a.split_blocks) {
-    if (block < a.split_blocks) {
-      piece = block % kSplitPieces;
-      piece_tile = block / kSplitPieces;
-      if (piece_tile >= a.n_split) return;
-    } else {
-      block -= a.split_blocks;
-    }
-  }
-  const int xcd = block & 7, idx = block >> 3;
-  int h = 0, q0;
-  int64_t q_base_dev = 0;
-  int mq_dev = 0;
-  const bool dev_tile = piece < 0 && a.dev_tiles && block >= a.dev_first_block;
-  if (piece >= 0) {
-    h = a.split_head[piece_tile];
-    q0 = a.split_q0[piece_tile];
-  } else if (dev_tile) {
-    const int t = block - a.dev_first_block;
-    if (t >= a.dev_tiles[0]) return;
-    h = a.dev_tiles[1 + 2 * t];
-    q0 = a.dev_tiles[2 + 2 * t];
-    q_base_dev = a.dev_q_off[h];
-    mq_dev = a.dev_q_off[h + 1] - a.dev_q_off[h];
-  } else if (idx < a.ragged_per_xcd) {
-    const int i = idx * 8 + xcd;
-    if (i >= a.n_ragged) return;
-    h = a.ragged_head[i];
-    q0 = (a.tile_start[h + 1] - a.tile_start[h]) * BQ;
-  } else {
-    const int tile = xcd * a.full_per_xcd + (idx - a.ragged_per_xcd);
-    if (idx - a.ragged_per_xcd >= a.full_per_xcd || tile >= a.n_full) return;
-    while (tile >= a.tile_start[h + 1]) ++h;
-    q0 = (tile - a.tile_start[h]) * BQ;
-  }
+  const bool piece = seg.slot >= 0;
   const int64_t q_base = dev_tile ? q_base_dev : a.q_off[h];
   int64_t k_base = a.k_off[h];
   const int Mq = dev_tile ? mq_dev : (int)(a.q_off[h + 1] - q_base);
@@ -521,24 +471,16 @@ void attention_kernel(const AttnArgs a) {
   uint16_t* mark = (uint16_t*)(o_rows + (q_base + q0) * kDHead);
   if (SHIFT && a.marked_only && (Mk == 0 || *(volatile const uint16_t*)mark != kRedoMark)) return;
 
-  const int tid = threadIdx.x, lane = tid & 63;
-  // a piece sees its share of the key tiles as the whole key sequence
-  const int64_t piece_row0 = ((int64_t)piece_tile * kSplitPieces + (piece < 0 ? 0 : piece)) * BQ;
-  if (piece >= 0) {
-    const int nt = (Mk + kKvTile - 1) / kKvTile, tpp = (nt + kSplitPieces - 1) / kSplitPieces;
-    const int t0 = piece * tpp, t1 = t0 + tpp < nt ? t0 + tpp : nt;
-    if (t0 >= t1) {   // no key tile left for this piece: it contributes zeros
-      const int rows = Mq - q0 < BQ ? Mq - q0 : BQ;
-      for (int e = tid; e < rows * (kDHead / 4); e += NT)
-        ((f32x4*)(a.split_o + piece_row0 * kDHead))[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-      for (int e = tid; e < rows; e += NT) {
-        a.split_l[piece_row0 + e] = 0.f;
-        if (SHIFT) a.split_m[piece_row0 + e] = -1e30f;
-      }
-      return;
-    }
-    k_base += (int64_t)t0 * kKvTile;
-    Mk = (t1 * kKvTile < Mk ? t1 * kKvTile : Mk) - t0 * kKvTile;
+  // (the empty asm keeps per-lane values that derive from the thread index from being computed once
+  // in front of the loop over a share's segments and held in registers across the whole tile)
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
+  // a segment sees its key tiles as the whole key sequence
+  const int64_t piece_row0 = (int64_t)(piece ? seg.slot : 0) * BQ;
+  if (piece) {
+    k_base += (int64_t)seg.t0 * kKvTile;
+    Mk = (seg.t1 * kKvTile < Mk ? seg.t1 * kKvTile : Mk) - seg.t0 * kKvTile;
   }
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS destinations stay scalar
   const int l32 = lane & 31, half = lane >> 5;
@@ -710,19 +652,22 @@ void attention_kernel(const AttnArgs a) {
       l_tot[qt] = l32 < 16 ? s0 : s1;
     }
   }
-  if (piece >= 0) {
-    // a piece: unnormalised sums (and the shifts they are relative to) for attention_split_reduce_kernel
+  if (piece) {
+    // a segment: unnormalised sums (and the shifts they are relative to) for attention_split_reduce_kernel
     if (active) {
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt) {
         const int row = wq0 + qt * 32 + l32;
         if (row < Mq) {
-          float* po = a.split_o + (piece_row0 + (row - q0)) * kDHead;
+          // slot layout [16 channel groups of 4][BQ rows][4]: group (dt * 4 + g) * 2 + half holds the
+          // channels dt * 32 + 8 * g + 4 * half .. + 3, so that the 32 lanes of a half write 512
+          // contiguous bytes and the kernel that adds the segments up reads whole lines
+          float* po = a.split_o + piece_row0 * kDHead + (row - q0) * 4;
 #pragma unroll
           for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
             for (int g = 0; g < 4; ++g)
-              *(f32x4*)(po + dt * 32 + 8 * g + 4 * half) =
+              *(f32x4*)(po + ((dt * 4 + g) * 2 + half) * (BQ * 4)) =
                   f32x4{w.o_acc[dt][qt][4 * g], w.o_acc[dt][qt][4 * g + 1], w.o_acc[dt][qt][4 * g + 2],
                         w.o_acc[dt][qt][4 * g + 3]};
           if (half == 0) {
@@ -766,68 +711,156 @@ void attention_kernel(const AttnArgs a) {
   }
 }
 
-// The split tiles after a kernel ran them in pieces: one workgroup per split tile adds the pieces in
-// ascending key order and stores the normalised rows.  After the fast kernel it tests the row sums
-// like that kernel does (a tile with a row outside the window gets the mark and is redone by the
-// kernel with per-row shifts); after the kernel with per-row shifts every piece is first brought to
-// the largest of the pieces' shifts of its row.
+// SHIFT = false: the fast kernel (keys carry the logit scale; weights exp2(s)).  SHIFT = true: per-row
+// shifts and the overflow guard; with a.marked_only it is launched right after the fast kernel on
+// the same grid and a workgroup leaves at once unless the fast kernel marked its tile.
+template <int QT, int NW, bool SHIFT>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, QT == 1 ? 3 : 2)))
+void attention_kernel(const AttnArgs a) {
+  constexpr int NT = 64 * NW;
+  constexpr int BQ = 32 * QT * NW;
+  constexpr int LD_ITER = kKvTile * kRowChunks / NT;       // 16-byte K chunks per thread per tile
+  static_assert(LD_ITER >= 2 && LD_ITER % 2 == 0, "tile staging needs an even chunk count");
+  constexpr int kTileElems = kKvTile * kDHead;
+  __shared__ __align__(16) bf16_t s_k[2][kTileElems];    // [kv][d], 128-byte rows, chunk-swizzled
+  __shared__ __align__(16) bf16_t s_v[2][kTileElems];    // [kv][d], 128-byte rows, chunk-swizzled
+
+  // blockIdx -> work.  Workgroups go round-robin to the 8 XCDs, and in blockIdx order to free
+  // slots.  Every XCD walks its whole tiles first - the partial last tiles of the heads (they are
+  // short, so they should not be what the grid ends on), then a contiguous range of full tiles -
+  // and then its shares of the tiles that run in segments; the device-side tile list comes last.
+  const int block = (int)blockIdx.x;
+  const int xcd = block & 7;
+  int h = 0, q0 = 0, mq_dev = 0;
+  int64_t q_base_dev = 0;
+  int share = -1, first = 0, count = 1;           // share >= 0: `count` segments, in the tiles first, first + 1, ...
+  const bool dev_tile = block >= a.main_blocks;
+  const int pos = block >> 3, whole_per_xcd = a.full_per_xcd + a.ragged_per_xcd;
+  if (dev_tile) {
+    if (!a.dev_tiles) return;
+    const int t = block - a.main_blocks;
+    if (t >= a.dev_tiles[0]) return;
+    h = a.dev_tiles[1 + 2 * t];
+    q0 = a.dev_tiles[2 + 2 * t];
+    q_base_dev = a.dev_q_off[h];
+    mq_dev = a.dev_q_off[h + 1] - a.dev_q_off[h];
+  } else if (pos >= whole_per_xcd) {
+    const int item = pos - whole_per_xcd;
+    share = xcd * a.split_per_xcd + item;
+    if (item >= a.split_per_xcd || share >= a.sp.shares) return;
+    split_share_tiles(a.sp, share, &first, &count);
+  } else if (pos < a.ragged_per_xcd) {
+    const int i = pos * 8 + xcd;
+    if (i >= a.n_ragged) return;
+    h = a.ragged_head[i];
+    q0 = (a.tile_start[h + 1] - a.tile_start[h]) * BQ;
+  } else {
+    const int tile = xcd * a.full_per_xcd + (pos - a.ragged_per_xcd);
+    if (tile >= a.n_full) return;
+    while (tile >= a.tile_start[h + 1]) ++h;
+    q0 = (tile - a.tile_start[h]) * BQ;
+  }
+  // a whole tile; or a share of the tiles that run in segments: its segments one after the other
+  for (int i = 0; i < count; ++i) {
+    SplitSegment seg = {0, 0, 0, 0, -1};
+    if (share >= 0) {
+      seg = split_segment(a.sp, share, first + i);
+      h = seg.head;
+      q0 = seg.q0;
+      if (i) __syncthreads();                       // the tile buffers in LDS are free again
+    }
+    attention_tile<QT, NW, SHIFT>(a, s_k, s_v, h, q0, dev_tile, q_base_dev, mq_dev, seg);
+  }
+}
+
+// The split tiles after a kernel ran them in segments: four workgroups per split tile (64 rows each)
+// add its segments in ascending key order (run-to-run identical) and store the normalised rows.
+// After the fast kernel every workgroup tests the row sums of the whole tile like that kernel does (a
+// tile with a row outside the window gets the mark and is redone by the kernel with per-row
+// shifts); after the kernel with per-row shifts every segment is first brought to the largest of
+// the segments' shifts of its row.
+constexpr int kReduceRows = 64;
 template <int BQ, bool SHIFT>
 __global__ __launch_bounds__(256) void attention_split_reduce_kernel(const AttnArgs a) {
+  static_assert(BQ == 256, "one thread per row of the tile in the first phase");
   __shared__ float s_inv[BQ];
-  __shared__ float s_w[SHIFT ? kSplitPieces * BQ : 1];   // factor of piece p for row r: [p][r]
-  const int i = blockIdx.x, tid = threadIdx.x;
-  const int h = a.split_head[i];
-  const int q0 = a.split_q0[i];
-  const int64_t q_base = a.q_off[h];
-  const int left = (int)(a.q_off[h + 1] - q_base) - q0;
+  __shared__ float s_max[SHIFT ? BQ : 1];      // the row's largest shift
+  __shared__ __align__(16) uint32_t s_out[kReduceRows * 32];   // the normalised bf16 rows, for whole-line stores
+  const int e = blockIdx.x >> 2, part = blockIdx.x & 3, tid = threadIdx.x;
+  const SplitTile t = split_tile(a.sp, e);
+  const int64_t q_base = a.q_off[t.head];
+  const int left = (int)(a.q_off[t.head + 1] - q_base) - t.q0;
   const int rows = left < BQ ? left : BQ;
-  const int64_t base = (int64_t)i * kSplitPieces * BQ;
+  const int np = t.last_share - t.first_share + 1;
+  // consecutive shares of one tile have consecutive slots
+  const int64_t row0 = (int64_t)split_slot(t.first_share, e) * BQ;     // segment p: rows from row0 + p * BQ
+  // ---- the row sums of the whole tile (every workgroup of the tile, so that all four decide alike)
   bool bad = false;
-  for (int r = tid; r < rows; r += 256) {
+  if (tid < rows) {
     float l = 0.f;
     if (SHIFT) {
       float m = -1e30f;
-#pragma unroll
-      for (int p = 0; p < kSplitPieces; ++p) m = fmaxf(m, a.split_m[base + (int64_t)p * BQ + r]);
-#pragma unroll
-      for (int p = 0; p < kSplitPieces; ++p) {
-        const float wgt = __builtin_amdgcn_exp2f(a.split_m[base + (int64_t)p * BQ + r] - m);
-        s_w[p * BQ + r] = wgt;
-        l = fmaf(a.split_l[base + (int64_t)p * BQ + r], wgt, l);
+#pragma unroll 4
+      for (int p = 0; p < np; ++p) m = fmaxf(m, a.split_m[row0 + (int64_t)p * BQ + tid]);
+#pragma unroll 4
+      for (int p = 0; p < np; ++p) {
+        const float wgt = __builtin_amdgcn_exp2f(a.split_m[row0 + (int64_t)p * BQ + tid] - m);
+        l = fmaf(a.split_l[row0 + (int64_t)p * BQ + tid], wgt, l);
       }
+      s_max[tid] = m;
     } else {
-#pragma unroll
-      for (int p = 0; p < kSplitPieces; ++p) l += a.split_l[base + (int64_t)p * BQ + r];
-      bad = bad || !(l >= kFastSumMin && l <= kFastSumMax);
+#pragma unroll 4
+      for (int p = 0; p < np; ++p) l += a.split_l[row0 + (int64_t)p * BQ + tid];
+      bad = !(l >= kFastSumMin && l <= kFastSumMax);
     }
-    s_inv[r] = 1.0f / l;
+    s_inv[tid] = 1.0f / l;
   }
-  uint16_t* mark = (uint16_t*)(a.o + (q_base + q0) * kDHead);
   if (__syncthreads_or(bad)) {
-    if (tid == 0) *mark = kRedoMark;
+    if (tid == 0 && part == 0) *(uint16_t*)(a.o + (q_base + t.q0) * kDHead) = kRedoMark;
     return;
   }
-  for (int e = tid; e < rows * kRowChunks; e += 256) {
-    const int r = e >> 3, c = e & 7;
-    float acc[8];
+  // ---- rows part * 64 .. + 63: thread -> row r = tid % 64 and the 16-byte output chunks c, c + 4
+  const int r = part * kReduceRows + (tid & 63), c0 = tid >> 6;
+  if (part * kReduceRows >= rows) return;
+  const int rr = r < rows ? r : rows - 1;          // a row past the end reads a valid row and stores nothing
+  float acc[2][8];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int p = 0; p < kSplitPieces; ++p) {
-      const float* po = a.split_o + (base + (int64_t)p * BQ + r) * kDHead + c * 8;
-      const f32x4 lo = *(const f32x4*)po, hi = *(const f32x4*)(po + 4);
-      const float wgt = SHIFT ? s_w[p * BQ + r] : 1.0f;
+    for (int q = 0; q < 8; ++q) acc[i][q] = 0.f;
+  const float m_row = SHIFT ? s_max[rr] : 0.f;
+#pragma unroll 4
+  for (int p = 0; p < np; ++p) {
+    const float* ps = a.split_o + (row0 + (int64_t)p * BQ) * kDHead + rr * 4;
+    f32x4 v[2][2];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        acc[q] = SHIFT ? fmaf(lo[q], wgt, acc[q]) : acc[q] + lo[q];
-        acc[4 + q] = SHIFT ? fmaf(hi[q], wgt, acc[4 + q]) : acc[4 + q] + hi[q];
-      }
-    }
-    const float inv = s_inv[r];
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) v[i][hf] = *(const f32x4*)(ps + ((c0 + 4 * i) * 2 + hf) * (BQ * 4));
+    const float wgt = SHIFT ? __builtin_amdgcn_exp2f(a.split_m[row0 + (int64_t)p * BQ + rr] - m_row) : 1.0f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          acc[i][4 * hf + q] = SHIFT ? fmaf(v[i][hf][q], wgt, acc[i][4 * hf + q]) : acc[i][4 * hf + q] + v[i][hf][q];
+  }
+  const float inv = s_inv[rr];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
     u32x4 o;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(acc[2 * q] * inv, acc[2 * q + 1] * inv);
-    ((u32x4*)a.o)[(q_base + q0 + r) * kRowChunks + c] = o;
+    for (int q = 0; q < 4; ++q) o[q] = pack_bf16x2(acc[i][2 * q] * inv, acc[i][2 * q + 1] * inv);
+    *(u32x4*)&s_out[(tid & 63) * 32 + (c0 + 4 * i) * 4] = o;
+  }
+  __syncthreads();
+  // whole 128-byte rows: 8 threads per row
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int lr = (tid >> 3) + 32 * i, ch = tid & 7;
+    if (part * kReduceRows + lr < rows)
+      ((u32x4*)a.o)[(q_base + t.q0 + part * kReduceRows + lr) * kRowChunks + ch] = *(const u32x4*)&s_out[lr * 32 + ch * 4];
   }
 }
 
@@ -845,35 +878,8 @@ int64_t compute_units() {
 // 128-row tiles that run at once (three workgroups per CU): a problem with no more of them runs those
 constexpr int64_t kSmallTileRound = 768;
 
-// rows of partial results one split tile needs (all pieces), and the fp32 words of such a row
-constexpr int64_t kSplitRowsPerTile = (int64_t)kSplitPieces * 256;
-constexpr int64_t kSplitWordsPerRow = kDHead + 2;   // 64 sums of weight * v, the sum of weights, the shift
-
-// Number of 256-row query tiles a launch runs in pieces over the keys when it has room for their
-// partial results (0: every tile runs whole).  A CU runs its tiles two at a time, but one alone
-// nearly twice as fast, so the launch time follows the largest number of whole tiles a CU gets -
-// ceil(tiles / CUs).  The tiles in excess of a multiple of the CU count are split if they are few
-// (splitting e of them saves (1 - e / CUs) of a tile's time), the launch is long (at least one full
-// tile per CU, and not one round of 128-row tiles) and every head has enough key tiles for all
-// pieces.
-int64_t tiles_to_split(const int64_t* q_off_host, const int64_t* k_off_host, int H) {
-  int64_t full = 0, ragged = 0, tiles128 = 0, min_mk = INT64_MAX;
-  for (int h = 0; h < H; ++h) {
-    const int64_t mq = q_off_host[h + 1] - q_off_host[h], mk = k_off_host[h + 1] - k_off_host[h];
-    full += mq / 256;
-    ragged += (mq % 256) != 0;
-    tiles128 += (mq + 127) / 128;
-    min_mk = mk < min_mk ? mk : min_mk;
-  }
-  const int64_t cus = compute_units();
-  const int64_t excess = (full + ragged) % cus;
-  const bool split = excess > 0 && excess <= kAttnSplitTiles && full >= cus && tiles128 > kSmallTileRound &&
-                     min_mk >= 4 * kSplitPieces * kKvTile;
-  return split ? excess : 0;
-}
-
 // `extra_tiles` workgroups are appended for the device-side tile list (a.dev_tiles), if any.
-// `scratch` (fp32 words, or nullptr): room for the split of the tiles in excess, see kSplitPieces.
+// `scratch` (fp32 words, or nullptr): room for the tiles that run in segments (attention_split.hpp).
 // a.marked_only != 0: the fast kernel, then the kernel with per-row shifts on the marked tiles.
 template <int QT, int NW>
 hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_off_host, int H,
@@ -900,63 +906,65 @@ hipError_t launch_cfg(AttnArgs& a, const int64_t* q_off_host, const int64_t* k_o
   a.full_per_xcd = (int32_t)((full + 7) / 8);
   a.ragged_per_xcd = (ragged + 7) / 8;
   if (full + ragged + extra_tiles == 0) return hipSuccess;
-  a.dev_first_block = 8 * (a.full_per_xcd + a.ragged_per_xcd);
-  a.split_blocks = 0;
-  a.n_split = 0;
+  a.main_blocks = 8 * (a.full_per_xcd + a.ragged_per_xcd);
+  a.split_per_xcd = 0;
   a.split_o = nullptr;
   a.split_l = nullptr;
   a.split_m = nullptr;
-  const unsigned grid = (unsigned)a.dev_first_block + (unsigned)extra_tiles;
-  const int64_t room = scratch ? scratch_words / (kSplitRowsPerTile * kSplitWordsPerRow) : 0;
-  const int64_t excess = BQ == 256 ? tiles_to_split(q_off_host, k_off_host, H) : 0;
-  const bool split = excess > 0 && excess <= room;
-  AttnArgs f = a;   // the first launch when the tiles in excess are split
+  a.sp.n_tiles = 0;
+  a.sp.slots = 0;
+  const unsigned grid = (unsigned)a.main_blocks + (unsigned)extra_tiles;
+  AttnArgs f = a;   // the first launch when tiles are split
   unsigned fgrid = grid;
-  if (split) {
-    // the partial tiles first (as many as the excess allows), then full tiles from the end
-    int ns = 0;
-    for (int i = 0; i < ragged && ns < excess; ++i) {
-      const int h = a.ragged_head[i];
-      f.split_head[ns] = h;
-      f.split_q0[ns++] = (a.tile_start[h + 1] - a.tile_start[h]) * BQ;
+  bool split = false;
+  if (BQ == kAttnTileRows && scratch) {
+    int64_t kept_full = full;
+    int split_ragged = 0;
+    plan_attention_split(q_off_host, k_off_host, H, compute_units(), &f.sp, &kept_full, &split_ragged);
+    const int64_t slots = split_slots(f.sp);
+    split = f.sp.n_tiles > 0 && slots * kAttnSlotWords <= scratch_words;
+    if (split) {
+      // the first partial tiles (in head order) and the last full tiles run in segments; the others
+      // keep their order: partial tiles in front of the full tiles
+      f.n_full = (int32_t)kept_full;
+      f.full_per_xcd = (int32_t)((kept_full + 7) / 8);
+      f.n_ragged = ragged - split_ragged;
+      f.ragged_per_xcd = (f.n_ragged + 7) / 8;
+      for (int i = 0; i < f.n_ragged; ++i) f.ragged_head[i] = a.ragged_head[split_ragged + i];
+      f.split_per_xcd = (f.sp.shares + 7) / 8;
+      f.main_blocks = 8 * (f.full_per_xcd + f.ragged_per_xcd + f.split_per_xcd);
+      f.split_o = scratch;
+      f.split_l = scratch + slots * kAttnTileRows * kDHead;
+      f.split_m = f.split_l + slots * kAttnTileRows;
+      fgrid = (unsigned)f.main_blocks + (unsigned)extra_tiles;
+    } else {
+      f.sp.n_tiles = 0;
+      f.sp.slots = 0;
     }
-    const int keep_ragged = ragged - ns;           // partial tiles that stay whole
-    int64_t nf = full;
-    for (int h = H - 1; ns < excess && nf > 0;) {
-      while (a.tile_start[h] >= nf) --h;           // the head of full tile nf - 1
-      f.split_head[ns] = h;
-      f.split_q0[ns++] = (int32_t)(nf - 1 - a.tile_start[h]) * BQ;
-      --nf;
-    }
-    f.n_split = ns;
-    f.n_full = (int32_t)nf;
-    f.full_per_xcd = (int32_t)((nf + 7) / 8);
-    // partial tiles beyond the excess keep their place in front of the full tiles
-    f.n_ragged = keep_ragged;
-    f.ragged_per_xcd = (keep_ragged + 7) / 8;
-    for (int i = 0; i < keep_ragged; ++i) f.ragged_head[i] = a.ragged_head[ragged - keep_ragged + i];
-    f.split_blocks = (ns * kSplitPieces + 7) & ~7;
-    f.split_o = scratch;
-    f.split_l = scratch + (int64_t)ns * kSplitRowsPerTile * kDHead;
-    f.split_m = f.split_l + (int64_t)ns * kSplitRowsPerTile;
-    f.dev_first_block = 8 * (f.full_per_xcd + f.ragged_per_xcd);
-    fgrid = (unsigned)f.split_blocks + (unsigned)f.dev_first_block + (unsigned)extra_tiles;
   }
   if (a.marked_only) {
-    // the fast kernel (and the sum of its pieces), then the kernel with per-row shifts on the marked tiles
+    // the fast kernel (and the sum of its segments), then the kernel with per-row shifts on the marked tiles
     hipLaunchKernelGGL((attention_kernel<QT, NW, false>), dim3(fgrid), dim3(64 * NW), 0, stream, f);
     if (split)
-      hipLaunchKernelGGL((attention_split_reduce_kernel<BQ, false>), dim3((unsigned)f.n_split), dim3(256), 0, stream, f);
+      hipLaunchKernelGGL((attention_split_reduce_kernel<kAttnTileRows, false>), dim3(4u * (unsigned)f.sp.n_tiles), dim3(256), 0, stream, f);
     hipLaunchKernelGGL((attention_kernel<QT, NW, true>), dim3(grid), dim3(64 * NW), 0, stream, a);
   } else {
     hipLaunchKernelGGL((attention_kernel<QT, NW, true>), dim3(fgrid), dim3(64 * NW), 0, stream, f);
     if (split)
-      hipLaunchKernelGGL((attention_split_reduce_kernel<BQ, true>), dim3((unsigned)f.n_split), dim3(256), 0, stream, f);
+      hipLaunchKernelGGL((attention_split_reduce_kernel<kAttnTileRows, true>), dim3(4u * (unsigned)f.sp.n_tiles), dim3(256), 0, stream, f);
   }
   return hipGetLastError();
 }
 
 }  // namespace
+
+int64_t attention_scratch_need(const int64_t* q_off_host, const int64_t* k_off_host, int H) {
+  SplitPlan sp;
+  int64_t kept_full = 0;
+  int split_ragged = 0;
+  plan_attention_split(q_off_host, k_off_host, H, compute_units(), &sp, &kept_full, &split_ragged);
+  return split_slots(sp) * kAttnSlotWords * 4;
+}
 
 hipError_t launch_attention_dev_tiles(const void* q, const void* k, const void* v, void* o,
                                       const int32_t* q_off_dev, const int32_t* tiles, int max_tiles,
@@ -978,7 +986,7 @@ hipError_t launch_attention_dev_tiles(const void* q, const void* k, const void* 
   a.dev_tiles = tiles;
   a.q2 = a.q;
   a.o2 = a.o;
-  a.dev_first_block = 0;
+  a.main_blocks = 0;        // no whole tiles, no segments: every workgroup takes the device-side list
   if (a.marked_only)
     hipLaunchKernelGGL((attention_kernel<2, 4, false>), dim3((unsigned)max_tiles), dim3(256), 0, stream, a);
   hipLaunchKernelGGL((attention_kernel<2, 4, true>), dim3((unsigned)max_tiles), dim3(256), 0, stream, a);
@@ -1011,11 +1019,7 @@ hipError_t launch_attention(const void* q, const void* k, const void* v, void* o
                             const int64_t* q_off_host, const int64_t* k_off_host, int H,
                             float scale, bool log2_keys, hipStream_t stream, void* scratch, int64_t scratch_bytes) {
   AttnArgs a;
-  a.dev_q_off = nullptr;
-  a.dev_tiles = nullptr;
-  a.q2 = nullptr;
-  a.o2 = nullptr;
-  a.dev_first_block = 0;
+  std::memset(&a, 0, sizeof(a));
   a.q = (const bf16_t*)q;
   a.k = (const bf16_t*)k;
   a.v = (const bf16_t*)v;
@@ -1023,13 +1027,19 @@ hipError_t launch_attention(const void* q, const void* k, const void* v, void* o
   a.scale_log2 = log2_keys ? 1.0f : scale * 1.4426950408889634f;
   a.marked_only = log2_keys ? 1 : 0;
   a.H = H;
-  // Tiles of 256 query rows (two workgroups per CU) are the efficient shape.  A short problem that
-  // fits into one round of 128-row tiles (three workgroups per CU, 768 at a time) runs those
-  // instead: they fill the chip where the big tiles leave a third of it idle (measured: 0.132
-  // against 0.144 ms at 16 x 5516 rows; with 800 small tiles, a second round, 0.19 against 0.17 ms).
+  // Tiles of 256 query rows (two workgroups per CU) are the efficient shape, and with scratch memory
+  // the tiles in excess of a multiple of the CU count run in segments, so that any tile count fills
+  // the chip.  Without that split, a short problem that fits into one round of 128-row tiles (three
+  // workgroups per CU, 768 at a time) runs those instead: they fill the chip where the big tiles
+  // leave a third of it idle (measured: 0.132 against 0.144 ms at 16 x 5516 rows; with 800 small
+  // tiles, a second round, 0.19 against 0.17 ms).
   int64_t tiles128 = 0;
   for (int h = 0; h < H; ++h) tiles128 += (q_off_host[h + 1] - q_off_host[h] + 127) / 128;
-  if (tiles128 <= kSmallTileRound) return launch_cfg<1, 4>(a, q_off_host, k_off_host, H, stream);
+  if (tiles128 <= kSmallTileRound) {
+    const bool splits = scratch && attention_scratch_need(q_off_host, k_off_host, H) > 0 &&
+                        attention_scratch_need(q_off_host, k_off_host, H) <= scratch_bytes;
+    if (!splits) return launch_cfg<1, 4>(a, q_off_host, k_off_host, H, stream);
+  }
   return launch_cfg<2, 4>(a, q_off_host, k_off_host, H, stream, 0, (float*)scratch, scratch_bytes / 4);
 }
 
@@ -1040,10 +1050,6 @@ hipError_t launch_attention(const void* q, const void* k, const void* v, void* o
 // until the process ends; the array's name is only a host-side handle, the address comes from
 // hipGetSymbolAddress, once per device, and only that pointer is ever handed to a kernel.
 static __device__ __align__(256) unsigned char g_static_scratch[kAttnStaticScratchBytes];
-
-int64_t attention_scratch_need(const int64_t* q_off_host, const int64_t* k_off_host, int H) {
-  return tiles_to_split(q_off_host, k_off_host, H) * kSplitRowsPerTile * kSplitWordsPerRow * 4;
-}
 
 hipError_t attention_static_scratch(void** ptr) {
   static std::mutex mu;

@@ -31,13 +31,9 @@ struct WorkItem {
   int32_t dims;
 };
 
-// Stage 3 runs the query tiles in excess of a multiple of the CU count - at most kAttnSplitTiles, the
-// partial last tiles of the heads first - in kAttnSplitPieces pieces over the keys when it is given
-// room for their fp32 partial results: per tile and piece 256 rows of 64 sums of weight * v and
-// one sum of weights, and (kernel with per-row shifts) the shift the sums are relative to.
-constexpr int kAttnSplitPieces = 16;
-constexpr int kAttnSplitTiles = 64;
-inline int64_t attention_scratch_bytes(int) { return (int64_t)kAttnSplitTiles * kAttnSplitPieces * 256 * (64 + 2) * 4; }
+// Scratch of stage 3 that covers any launch (attention_split.hpp: kAttnScratchBytes; a slot of
+// 256 rows x 66 fp32 for each of the at most 512 + 255 - 1 segments).
+inline int64_t attention_scratch_bytes(int) { return (int64_t)(512 + 255) * 256 * (64 + 2) * 4; }
 
 struct HostTables {
   int64_t N = 0, n_prefix = 0, n_blocks = 0, max_block = 0;

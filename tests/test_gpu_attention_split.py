@@ -1,6 +1,7 @@
-"""Stage 3 (Eq. 3-4) with scratch memory: a long launch runs the partial last query tile of every head
-in pieces over the keys and adds the pieces up.  Checked against the oracle's attention on the rows
-of the partial tiles, and against the same call without scratch on all rows."""
+"""Stage 3 (Eq. 3-4) with scratch memory: the query tiles in excess of a multiple of the CU count run
+in segments over the keys that are added up afterwards, so that any tile count fills the chip.
+Checked against the oracle's attention on the rows of the tiles that ran in segments, and against
+the same call without scratch on all rows."""
 import numpy as np
 import pytest
 import torch
@@ -45,10 +46,9 @@ def _partial_rows(qo, h):
     return qo[h] + (mq // 256) * 256, qo[h + 1]
 
 
-# The split is taken by launches of the 256-row kernel (more than 768 tiles of 128 rows) whose number
-# of tiles lies at most 64 above a multiple of the 256 CUs: those tiles in excess - the partial tiles
-# first, then full tiles from the end - run in pieces.  Here 512 or 520 full tiles plus the partial
-# ones; ragged lengths, one head without a partial tile; the last case splits 8 full tiles as well.
+# The tiles in excess of a multiple of the 256 CUs - the partial tiles first, then full tiles from the
+# end - run in segments.  Here 512 or 520 full tiles plus the partial ones; ragged lengths, one head
+# without a partial tile; the last case splits 8 full tiles as well.
 CASES = [
     ([16384 + 37] * 8, [8229] * 8),
     ([16384 + 1, 16384 + 255, 16384 + 128, 16384, 16384 + 64, 16384 + 65, 16384 + 200, 16384 + 31],
@@ -111,14 +111,79 @@ def test_a_partial_tile_that_leaves_the_unshifted_range_is_redone_with_shifts():
     assert np.array_equal(split[r0:r1], plain[r0:r1])     # both came from the kernel with shifts
 
 
-def test_short_launches_and_missing_room_run_the_partial_tiles_whole():
+def _split_rows(mq, mk):
+    """Per head: the query rows of the tiles the library runs in segments (from its own host-side plan)."""
+    qo = [int(x) for x in np.concatenate([[0], np.cumsum(mq)])]
+    ko = [int(x) for x in np.concatenate([[0], np.cumsum(mk)])]
+    plan = httm.attention_split_plan(qo, ko, torch.cuda.get_device_properties(0).multi_processor_count)
+    rows = {h: [] for h in range(len(mq))}
+    for head, q0, _, _ in plan["tiles"]:
+        rows[int(head)].append(np.arange(int(q0), min(int(q0) + 256, mq[int(head)])))
+    return {h: (np.concatenate(r) if r else np.zeros(0, dtype=np.int64)) for h, r in rows.items()}, plan
+
+
+# 300 to 700 tiles on 256 CUs, heads of 5 to 9 thousand keys: every count leaves some CUs a tile short
+# without the split.  (tiles, heads): the rows per head are tiles / heads * 256 plus a ragged bit.
+TILE_COUNTS = [(300, 4), (352, 16), (400, 16), (400, 8), (530, 8), (640, 5), (700, 7)]
+
+
+@pytest.mark.parametrize("tiles,H", TILE_COUNTS)
+@pytest.mark.parametrize("log2", [True, False], ids=["log2_keys", "plain_keys"])
+def test_any_tile_count_runs_its_excess_in_segments(tiles, H, log2):
     require_gpu()
-    # 392 full tiles + 8 partial ones: the partial tiles fit into the second tile of every CU
-    qm, k2, vm, qo, ko = _case([12544 + 37] * 8, [4100] * 8, 4344)
+    rng = np.random.default_rng(5000 + tiles)
+    per = tiles // H
+    # heads with a partial last tile (one row to 255) and, for the remainder, one more full tile
+    mq = [256 * (per - 1) + int(rng.integers(1, 256)) for _ in range(H)]
+    for h in range(tiles - per * H):
+        mq[h] += 256
+    mk = [int(rng.integers(5000, 9000)) for _ in range(H)]
+    assert sum(-(-m // 256) for m in mq) == tiles
+    print(f"[case] {tiles} tiles in {H} heads, log2={log2}: mq={mq} mk={mk}", flush=True)
+    rows, plan = _split_rows(mq, mk)
+    assert plan["n_tiles"] == tiles % 256 and plan["slots"] > 0
+    if log2:
+        qm, km, vm, qo, ko = _case(mq, mk, 5100 + tiles)
+        plain, split = _run_both(qm, km, vm, qo, ko)
+        written = _run_both.scratch_written
+        kscale = np.float32(httm.LOG2_KEY_SCALE)
+    else:
+        qm, km, vm, qo, ko = _plain_case(mq, mk, 5100 + tiles)
+        plain, split, written = _run_both_plain(qm, km, vm, qo, ko)
+        kscale = np.float32(1.0)
+    assert written and np.isfinite(split).all()
+    # the run without scratch uses 128-row tiles when the launch fits one round of those: then only
+    # the oracle is the reference; else the tiles that stay whole ran in the same workgroups
+    same_kernel = sum(-(-m // 128) for m in mq) > 768
+    for h in range(H):
+        kk = f32(km[ko[h]:ko[h + 1]]) / kscale
+        vv = f32(vm[ko[h]:ko[h + 1]])
+        r = rows[h]
+        if r.size:
+            want = orc.attention(f32(qm[qo[h]:qo[h + 1]]), kk, vv, rows=r)
+            check_output(split[qo[h]:qo[h + 1]][r], want, f"{tiles} tiles, segments, head {h}")
+        whole = np.setdiff1d(np.arange(mq[h]), r)
+        if same_kernel:
+            assert np.array_equal(split[qo[h]:qo[h + 1]][whole], plain[qo[h]:qo[h + 1]][whole]), f"head {h}: whole tiles differ"
+        if whole.size == 0:          # every tile of this head ran in segments
+            continue
+        sample = whole[:: max(1, whole.size // 300)]
+        want = orc.attention(f32(qm[qo[h]:qo[h + 1]]), kk, vv, rows=sample)
+        check_output(split[qo[h]:qo[h + 1]][sample], want, f"{tiles} tiles, whole tiles, head {h}")
+    # the two runs (other tile shapes, other key ranges per piece, other shifts for the bf16 weights)
+    # agree to a few bf16 steps of the result and the rounding noise of the weights
+    d = np.abs(split - plain)
+    assert (d <= 2.0 ** -5 * np.abs(plain) + 1e-3).all(), f"{d.max()}"
+
+
+def test_launches_where_the_split_cannot_pay_and_missing_room_run_every_tile_whole():
+    require_gpu()
+    # a head with fewer than 512 keys: no split
+    qm, k2, vm, qo, ko = _case([16384 + 37] * 8, [8229] * 7 + [300], 4345)
     plain, split = _run_both(qm, k2, vm, qo, ko)
     assert np.array_equal(plain, split) and not _run_both.scratch_written
-    # a head with fewer than 4096 keys (too few key tiles for 16 pieces): no split either
-    qm, k2, vm, qo, ko = _case([16384 + 37] * 8, [8229] * 7 + [3000], 4345)
+    # a multiple of the CU count: nothing in excess
+    qm, k2, vm, qo, ko = _case([16384] * 8, [4100] * 8, 4346)
     plain, split = _run_both(qm, k2, vm, qo, ko)
     assert np.array_equal(plain, split) and not _run_both.scratch_written
     qm, k2, vm, qo, ko = _case([300, 700, 129], [500, 640, 90], 4343)
@@ -178,8 +243,11 @@ def test_pieces_with_per_row_shifts_match_the_oracle_and_the_whole_tiles(mq, mk,
     assert written, "the launch did not take the split"
     # the pieces round their weights to bf16 relative to their own shifts: a few 2^-9 steps of terms
     # that average out, and one bf16 step of the result
+    # (with the amplified keys a row is dominated by a few keys with values of size one: the 2^-9
+    # rounding of their weights, relative to other shifts in the two runs, shows in full where the
+    # weighted values cancel)
     d = np.abs(split - plain)
-    assert (d <= 2.0 ** -6 * np.abs(plain) + 2e-4).all(), f"{d.max()}"
+    assert (d <= 2.0 ** -6 * np.abs(plain) + (5e-3 if gain is not None else 2e-4)).all(), f"{d.max()}"
     n_full = sum(m // 256 for m in mq)
     n_part = sum(1 for m in mq if m % 256)
     n_split_full = max(0, (n_full + n_part) % 256 - n_part)

@@ -164,8 +164,9 @@ def test_outlier_budget_and_workspace_regions():
     assert w0.eps_q == w0.q_out == w0.o_out == w0.attn_split
     assert w1.q_out - w1.eps_q >= 16 * 10992 * 4 and w1.o_out - w1.q_out >= 3517 * 128
     assert w1.attn_split - w1.o_out >= 3517 * 128 and w1.total == s1.workspace_bytes
-    # stage 3's scratch region: up to 64 tiles in 16 pieces of 256 rows x (64 + 1) fp32
-    assert httm.attention_scratch_bytes(16) == 64 * 16 * 256 * 66 * 4
+    # stage 3's scratch region: a slot of 256 rows x (64 + 2) fp32 for each of the at most 512 shares +
+    # 255 tiles in excess - 1 segments of a launch
+    assert httm.attention_scratch_bytes(16) == (512 + 255) * 256 * 66 * 4
     for w in (w0, w1):
         assert w.total - w.attn_split >= httm.attention_scratch_bytes(16) and w.attn_split % 256 == 0
     assert httm.geom_sizes(httm.make_geom(8, 37, 37, 4, 2, 0.5, variant="none", outlier_frac=0.1)).outlier_cap == 0

@@ -31,8 +31,8 @@ def _check_against_oracle(qm, k2, vm, qo, ko, got, h, r0, r1, what):
 
 def test_static_scratch_entry_point_matches_the_one_with_caller_scratch():
     require_gpu()
-    # 8 x (64 full tiles + a partial one) = 520 tiles on 256 CUs: the 8 partial tiles run in pieces;
-    # then 3 x (171 full + a partial one) = 516: fewer pieces, which leaves stale rows of the first
+    # 8 x (64 full tiles + a partial one) = 520 tiles on 256 CUs: the 8 partial tiles run in segments;
+    # then 3 x (171 full + a partial one) = 516: fewer segments, which leaves stale rows of the first
     # call in the static array; then a short launch that uses no scratch at all
     cases = [([16384 + 37, 16384 + 200, 16384 + 1, 16384 + 255, 16384 + 128, 16384 + 64, 16384 + 65, 16384 + 31],
               [4200, 4100, 5000, 4096, 7777, 4500, 6001, 8192], 7001),
@@ -59,8 +59,11 @@ def test_static_scratch_entry_point_matches_the_one_with_caller_scratch():
 
 def test_static_scratch_entry_point_refuses_what_does_not_fit():
     require_gpu()
-    # 552 full tiles on 256 CUs: 40 tiles in excess would run in pieces, 43 MB of partial results
-    mq, mk = [552 * 256], [4200]
+    # 456 full tiles on 256 CUs against 20 000 keys: the 200 tiles in excess would run as 512 shares,
+    # 711 slots = 48 MB of partial results, more than the 32 MiB array holds
+    mq, mk = [456 * 256], [20000]
+    plan = httm.attention_split_plan([0, mq[0]], [0, mk[0]])
+    assert plan["slots"] * 256 * 66 * 4 > 32 << 20
     qm, k2, vm, qo, ko = _case(mq, mk, 7004)
     out = torch.full_like(qm, float("nan"))
     with pytest.raises(httm.HttmError, match="workspace"):
