@@ -106,8 +106,7 @@ enum {
 
 #define HTTM_MAX_OUTLIER_FRAC 0.5
 #define HTTM_MAX_BLOCK 4096       /* largest merging block (n_s*n_t tokens) the kernels accept; blocks of more
-                                     than 512 tokens (the paper's 128 x 30 = 3840, Sec. 4.1) take a two-kernel path
-                                     and are not available with HTTM_VARIANT_UNIFORM */
+                                     than 512 tokens (the paper's 128 x 30 = 3840, Sec. 4.1) take a two-kernel path */
 #define HTTM_MAX_HEADS 64
 
 /* Problem description.  Plain data, filled by the caller. */
@@ -133,8 +132,7 @@ typedef struct httm_geom {
                          of a block are dst (at least one), and only the r = min(floor(rho * n), number of
                          src) src tokens with the highest best-match similarity merge (ties: lower
                          position first); the other src stay clusters of their own, placed behind the
-                         block's dst clusters in ascending position.  Blocks of at most 512 tokens,
-                         HTTM_VARIANT_HEADWISE only. */
+                         block's dst clusters in ascending position.  Any block size, both variants. */
 } httm_geom_t;
 
 /* Sizes derived from a geometry. */
@@ -184,10 +182,11 @@ HTTM_API int httm_geom_block_forms(const httm_geom_t* g, int32_t* block_src0, in
 /* ---- plan ---------------------------------------------------------------------------- */
 
 /* Build the index tables of *g on the current HIP device.  Allocates a few int32 per token of
- * device memory (and, for HTTM_VARIANT_UNIFORM, 2*N*d_head floats for the head-averaged tokens).
- * Synchronous.  The plan may be used by any number of later calls but not by two calls
- * running concurrently when variant == HTTM_VARIANT_UNIFORM (they share the averaged-token
- * buffer). */
+ * device memory (for HTTM_VARIANT_UNIFORM also 2*N*d_head floats for the head-averaged tokens; for
+ * dst_frac > 0 on blocks of more than 512 tokens 2*H*N floats for the similarities the selection
+ * reads when the caller passes no score arrays).  Synchronous.  The plan may be used by any number of
+ * later calls, but two calls that use these buffers (or those of the outlier filter) must not run
+ * concurrently: they share them. */
 HTTM_API int httm_plan_create(const httm_geom_t* g, httm_plan_t** out);
 HTTM_API int httm_plan_destroy(httm_plan_t* plan);
 HTTM_API int httm_plan_query(const httm_plan_t* plan, httm_sizes_t* out);

@@ -26,6 +26,9 @@ struct httm_plan {
   float* d_mean = nullptr;    // [2][N][64] fp32: head-averaged Q then K
   int32_t* d_slot = nullptr;  // [2][N] shared cluster slot of every reordered token
   float* d_uscore = nullptr;  // [2][N]
+  // general rule (dst_frac > 0) on blocks of more than 512 tokens: the similarities the selection of
+  // the merging src tokens needs, when the caller asks for none
+  float* d_score = nullptr;   // [2][H][N]
   // outlier filtering only
   int64_t outlier_cap = 0;
   OutlierBuffers ob = {};
@@ -103,6 +106,10 @@ int run_match_merge(const httm_plan_t* p, const int32_t* pi, const void* q, cons
   a.max_block = (int32_t)(p->sizes.max_block < kPrefixChunk ? kPrefixChunk : p->sizes.max_block);
   a.max_k = p->max_k;
   a.top_r = p->geom.dst_frac > 0.0 && p->geom.variant != HTTM_VARIANT_NONE;
+  if (p->d_score) {
+    if (!score_q) score_q = p->d_score;
+    if (!score_k) score_k = p->d_score + (int64_t)g.H * p->sizes.N;
+  }
   a.s[0] = {q, nullptr, q_m, nullptr, assign_q, score_q, p->d_items_q, p->n_items, p->sizes.M_q,
             nullptr, nullptr, eps_q, 1.0f};
   a.s[1] = {k, v, k_m, v_m, assign_k, score_k, p->d_items_k, p->n_items, p->sizes.M_k, nullptr,
@@ -118,6 +125,13 @@ int run_match_merge(const httm_plan_t* p, const int32_t* pi, const void* q, cons
                                 p->d_uscore + t * N, st));
       a.s[t].preset = p->d_slot + t * N;
       a.s[t].preset_score = p->d_uscore + t * N;
+    }
+    if (a.top_r) {
+      // general rule of Sec. 3.2 on the shared topology: which src tokens merge
+      TopRArgs tr = {};
+      tr.n_streams = 2;
+      for (int t = 0; t < 2; ++t) tr.s[t] = {p->d_slot + t * N, p->d_uscore + t * N, items[t], p->n_items, N};
+      HTTM_HIP(launch_top_r_select(tr, 1, st));
     }
   }
   HTTM_HIP(launch_match_merge(a, st));
@@ -263,6 +277,10 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_uscore, (size_t)2 * t.N * sizeof(float));
     if (e != hipSuccess) rc = hip_fail(e);
   }
+  if (rc == HTTM_OK && g->dst_frac > 0.0 && g->variant == HTTM_VARIANT_HEADWISE && t.max_block > kSmallBlockMax) {
+    e = hipMalloc((void**)&p->d_score, (size_t)2 * g->H * t.N * sizeof(float));
+    if (e != hipSuccess) rc = hip_fail(e);
+  }
   p->outlier_cap = p->sizes.outlier_cap;
   if (rc == HTTM_OK && p->outlier_cap > 0) {
     OutlierBuffers& b = p->ob;
@@ -299,7 +317,7 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
 
 int httm_plan_destroy(httm_plan_t* p) {
   if (!p) return HTTM_OK;
-  void* ptrs[] = {p->d_pi, p->d_items_q, p->d_items_k, p->d_mean, p->d_slot, p->d_uscore, p->ob.state};
+  void* ptrs[] = {p->d_pi, p->d_items_q, p->d_items_k, p->d_mean, p->d_slot, p->d_uscore, p->d_score, p->ob.state};
   for (void* q : ptrs)
     if (q) (void)hipFree(q);
   delete p;

@@ -57,6 +57,16 @@ __device__ __forceinline__ int dst_position_any(int m, int n, int k, int n0) {
   return m < n0 ? m : n0 + (int)(((int64_t)(m - n0) * (int64_t)(n - n0)) / (int64_t)(k - n0));
 }
 
+// Cluster whose dst token sits at block position p, or -1 if p is a src position (inverse of
+// dst_position_any; k = number of dst tokens).
+__device__ __forceinline__ int cluster_at(int p, int n, int k, int n0) {
+  if (p < n0) return p;
+  if (k == n0) return -1;
+  // 64-bit: (p - n0) * (k - n0) passes 2^31 for sequences of more than ~46 000 tokens
+  const int m = n0 + (int)(((int64_t)(p - n0) * (int64_t)(k - n0) + (n - n0) - 1) / (int64_t)(n - n0));
+  return (m < k && dst_position_any(m, n, k, n0) == p) ? m : -1;
+}
+
 // last word of a raw buffer descriptor on gfx9-family targets (32-bit data format, no swizzle, no
 // stride), and the cache-policy bit of a buffer load that marks it non-temporal
 constexpr int kRawBufferWord3 = 0x00020000;

@@ -25,10 +25,6 @@ int check_geom(const httm_geom_t& g) {
   const int64_t P = (int64_t)g.Hp * g.Wp;
   const int64_t ns = (g.flags & HTTM_FLAG_CHUNKED_BLOCKS) ? (g.b < P ? g.b : P) : bh * bw;
   if (ns * bt > HTTM_MAX_BLOCK) return HTTM_E_UNSUPPORTED;
-  if (ns * bt > 512 && g.variant == HTTM_VARIANT_UNIFORM) return HTTM_E_UNSUPPORTED;
-  if (g.dst_frac > 0.0 && g.variant != HTTM_VARIANT_NONE &&
-      (ns * bt > 512 || g.variant == HTTM_VARIANT_UNIFORM))
-    return HTTM_E_UNSUPPORTED;
   return HTTM_OK;
 }
 

@@ -46,6 +46,23 @@ hipError_t launch_match_merge(const MatchMergeArgs& a, hipStream_t stream);
 // The same for blocks of more than kSmallBlockMax tokens (two kernels; no preset mode).
 constexpr int kSmallBlockMax = 512;
 hipError_t launch_match_merge_big(const MatchMergeArgs& a, hipStream_t stream);
+// General rule of Sec. 3.2 (a fixed share of dst tokens, WorkItem.kd < k): after a matching kernel has
+// written, for every token, the slot of its most similar dst token (a dst token: its own slot) and
+// that similarity, this kernel decides per work item which r = n - k src tokens merge - those with
+// the highest similarity, ties by lower position - and gives every other src token a cluster of
+// its own behind the dst clusters, in ascending position.  assign is rewritten in place.
+struct TopRStream {
+  int32_t* assign;        // [heads][head_stride]
+  const float* score;     // [heads][head_stride]
+  const WorkItem* items;
+  int32_t n_items;
+  int64_t head_stride;
+};
+struct TopRArgs {
+  TopRStream s[2];
+  int32_t n_streams;
+};
+hipError_t launch_top_r_select(const TopRArgs& a, int heads, hipStream_t stream);
 // Un-blocked matching (the cost the merging blocks remove, paper Sec. 3.3): the whole sequence of a
 // head is one block of N tokens with kd strided dst tokens.  best[h][j] = index 0..kd-1 of the dst
 // most similar to token j (a dst token: its own index), sim[h][j] = that cosine similarity.

@@ -233,7 +233,7 @@ void match_merge_kernel(const MatchMergeArgs a) {
   }
 
   // ---- 1. the table of the dst tokens, while the rows are on their way ------------------------------
-  const int kd = TOPR && !s.preset ? it.kd : k;   // dst tokens = clusters 0 .. kd-1
+  const int kd = TOPR ? it.kd : k;   // dst tokens = clusters 0 .. kd-1
   s_cl[tid] = -1;
   if (tid < kLdsRowBytes / 16) *(u32x4*)(tile + MAXN * kLdsRowBytes + tid * 16) = u32x4{0, 0, 0, 0};
   __syncthreads();
@@ -292,7 +292,10 @@ void match_merge_kernel(const MatchMergeArgs a) {
       my_cl = slot - it.moff;
       assign[tid] = slot;
       if (score) score[tid] = s.preset_score ? s.preset_score[it.start + tid] : 1.0f;
+      // (general rule: a src token that did not merge is the only member of a cluster behind the dst ones)
+      if (TOPR && my_cl >= kd) s_dpos[my_cl] = (uint16_t)tid;
     }
+    if (TOPR) __syncthreads();
   } else {
     // ---- 3. similarities and arg-max -----------------------------------------------------------
     // Wave w owns the tokens 64w .. 64w+63, i.e. the two 32-token tiles 2w and 2w+1.
@@ -786,69 +789,81 @@ __global__ __launch_bounds__(256) void head_mean_kernel(const u32x4* __restrict_
 }
 
 constexpr int kF32Stride = 68;  // floats per LDS row (272 B: 16-byte aligned, odd granule count)
+constexpr int kF32Tile = 64;    // dst tokens per LDS tile
 
-// Block-wise matching of fp32 tokens (one head's worth): one thread per token, fp32 FMA dots.
+// Block-wise matching of fp32 tokens (the head-averaged tokens of the head-uniform variant, one
+// "head's" worth): one workgroup per (work item, 256 of its tokens), one thread per token with the
+// token in registers; the item's dst tokens pass through LDS in tiles of 64 and every thread takes
+// its fp32 FMA dot products with them in ascending cluster order (first maximum wins).  Any block
+// size; writes the slot of the most similar dst token (a dst token: its own slot) and the similarity.
 __global__ __launch_bounds__(256) void match_f32_kernel(const float* __restrict__ xbar,
                                                         const int32_t* __restrict__ pi,
                                                         const WorkItem* __restrict__ items,
-                                                        int32_t max_block,
                                                         int32_t* __restrict__ slot,
                                                         float* __restrict__ score) {
-  extern __shared__ __align__(16) float lds_f[];
-  float* tile = lds_f;                                   // [max_block][kF32Stride]
-  float* s_invn = tile + (size_t)max_block * kF32Stride;  // [max_block]
-  int32_t* s_dpos = (int32_t*)(s_invn + max_block);      // [max_block]
-  int32_t* s_cl = s_dpos + max_block;                    // [max_block]
+  __shared__ __align__(16) float s_d[kF32Tile * kF32Stride];
+  __shared__ float s_dinv[kF32Tile];
   const WorkItem it = items[blockIdx.x];
-  const int n = it.n, k = it.k, tid = threadIdx.x;
-  if (k == n) {
-    for (int t = tid; t < n; t += 256) {
+  const int n = it.n, kd = it.kd, n0 = it.n0, tid = threadIdx.x;
+  if ((int)blockIdx.y * 256 >= n) return;
+  const int t = blockIdx.y * 256 + tid;
+  if (kd == n) {
+    if (t < n) {
       slot[it.start + t] = it.moff + t;
       score[it.start + t] = 1.0f;
     }
     return;
   }
-  for (int e = tid; e < n * 16; e += 256) {
-    const int row = e >> 4, c = e & 15;
-    const int64_t src = pi ? (int64_t)pi[it.start + row] : (int64_t)(it.start + row);
-    *(f32x4*)(tile + row * kF32Stride + c * 4) = *(const f32x4*)(xbar + src * kDHead + c * 4);
+  const int tc = t < n ? t : n - 1;
+  const int64_t src = pi ? (int64_t)pi[it.start + tc] : (int64_t)(it.start + tc);
+  float xr[kDHead];
+#pragma unroll
+  for (int c = 0; c < kDHead / 4; ++c) {
+    const f32x4 w = *(const f32x4*)(xbar + src * kDHead + c * 4);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) xr[c * 4 + q] = w[q];
   }
-  for (int t = tid; t < n; t += 256) s_cl[t] = -1;
-  __syncthreads();
-  for (int t = tid; t < n; t += 256) {
-    float ss = 0.f;
-    for (int c = 0; c < kDHead; ++c) ss = fmaf(tile[t * kF32Stride + c], tile[t * kF32Stride + c], ss);
-    s_invn[t] = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
+  float ss = 0.f;
+#pragma unroll
+  for (int q = 0; q < kDHead; ++q) ss = fmaf(xr[q], xr[q], ss);
+  const float invn = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
+  float best = -INFINITY;
+  int bm = 0;
+  for (int m0 = 0; m0 < kd; m0 += kF32Tile) {
+#pragma unroll
+    for (int i = 0; i < kF32Tile * 16 / 256; ++i) {
+      const int e = tid + i * 256, row = e >> 4, c = e & 15;
+      const int m = m0 + row < kd ? m0 + row : kd - 1;
+      const int p = dst_position(m, n, kd, n0);
+      const int64_t sd = pi ? (int64_t)pi[it.start + p] : (int64_t)(it.start + p);
+      *(f32x4*)(s_d + row * kF32Stride + c * 4) = *(const f32x4*)(xbar + sd * kDHead + c * 4);
+    }
+    __syncthreads();
+    if (tid < kF32Tile) {
+      float ds = 0.f;
+      for (int q = 0; q < kDHead; ++q) ds = fmaf(s_d[tid * kF32Stride + q], s_d[tid * kF32Stride + q], ds);
+      s_dinv[tid] = 1.0f / fmaxf(sqrtf(ds), 1e-12f);
+    }
+    __syncthreads();
+    const int lim = kd - m0 < kF32Tile ? kd - m0 : kF32Tile;
+    for (int mm = 0; mm < lim; ++mm) {
+      float dot = 0.f;
+#pragma unroll
+      for (int q = 0; q < kDHead; ++q) dot = fmaf(xr[q], s_d[mm * kF32Stride + q], dot);
+      const float sim = dot * s_dinv[mm];
+      if (sim > best) {
+        best = sim;
+        bm = m0 + mm;
+      }
+    }
+    __syncthreads();
   }
-  __syncthreads();
-  for (int m = tid; m < k; m += 256) {
-    const int p = dst_position(m, n, k, it.n0);
-    s_dpos[m] = p;
-    s_cl[p] = m;
-  }
-  __syncthreads();
-  for (int t = tid; t < n; t += 256) {
-    int c = s_cl[t];
+  if (t < n) {
+    int c = cluster_at(t, n, kd, n0);
     float sc = 1.0f;
     if (c < 0) {
-      float xr[kDHead];
-#pragma unroll
-      for (int q = 0; q < kDHead; ++q) xr[q] = tile[t * kF32Stride + q];
-      float best = -INFINITY;
-      int bm = 0;
-      for (int m = 0; m < k; ++m) {
-        const int dp = s_dpos[m];
-        float dot = 0.f;
-#pragma unroll
-        for (int q = 0; q < kDHead; ++q) dot = fmaf(xr[q], tile[dp * kF32Stride + q], dot);
-        const float sim = dot * s_invn[dp];
-        if (sim > best) {
-          best = sim;
-          bm = m;
-        }
-      }
       c = bm;
-      sc = best * s_invn[t];
+      sc = best * invn;
     }
     slot[it.start + t] = it.moff + c;
     score[it.start + t] = sc;
@@ -905,15 +920,9 @@ hipError_t launch_match_f32(const float* xbar, const int32_t* pi, const WorkItem
                             int32_t n_items, int32_t max_block, int32_t* slot, float* score,
                             hipStream_t stream) {
   if (n_items == 0) return hipSuccess;
-  int mb = max_block < kPrefixChunk ? kPrefixChunk : max_block;
-  const size_t lds = (size_t)mb * (kF32Stride * 4 + 12);
-  if (lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)match_f32_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-  }
-  hipLaunchKernelGGL(match_f32_kernel, dim3((unsigned)n_items), dim3(256), lds, stream, xbar, pi,
-                     items, mb, slot, score);
+  const int mb = max_block < kPrefixChunk ? kPrefixChunk : max_block;
+  hipLaunchKernelGGL(match_f32_kernel, dim3((unsigned)n_items, (unsigned)((mb + 255) / 256)), dim3(256), 0, stream,
+                     xbar, pi, items, slot, score);
   return hipGetLastError();
 }
 

@@ -53,16 +53,6 @@ __device__ __forceinline__ float chunk_sumsq(const bf16x8 w, float ss) {
   return ss;
 }
 
-// Cluster whose dst token sits at block position p, or -1 if p is a src position
-// (inverse of dst_position).
-__device__ __forceinline__ int cluster_at(int p, int n, int k, int n0) {
-  if (p < n0) return p;
-  if (k == n0) return -1;
-  // 64-bit: (p - n0) * (k - n0) passes 2^31 for sequences of more than ~46 000 tokens
-  const int m = n0 + (int)(((int64_t)(p - n0) * (int64_t)(k - n0) + (n - n0) - 1) / (int64_t)(n - n0));
-  return (m < k && dst_position_any(m, n, k, n0) == p) ? m : -1;
-}
-
 constexpr int kBmWaves = 4;
 constexpr int kBmThreads = 64 * kBmWaves;
 constexpr int kBmTokens = 64 * kBmWaves;   // tokens per workgroup (two 32-token tiles per wave)
@@ -79,7 +69,9 @@ void big_match_kernel(const MatchMergeArgs a) {
   const MatchMergeStream& s = a.s[sidx];
   if ((int)blockIdx.x >= s.n_items) return;
   const WorkItem it = s.items ? s.items[blockIdx.x] : a.single;
-  const int n = it.n, k = it.k, n0 = it.n0;
+  // k: the dst tokens of the item (all its clusters under Alg. 1's rule; with a fixed dst share the
+  // clusters behind them are the src tokens that stay unmerged, numbered by the selection kernel)
+  const int n = it.n, k = it.kd, n0 = it.n0;
   const int t0 = blockIdx.y * kBmTokens;
   if (t0 >= n) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -230,6 +222,120 @@ void big_match_kernel(const MatchMergeArgs a) {
   }
 }
 
+// ---- top-r selection -----------------------------------------------------------------------------
+// One workgroup of 1024 threads per (work item, head, stream), up to four tokens per thread (token t =
+// round * 1024 + thread, so ascending position is (round, wave, lane) order).  The r-th largest
+// similarity of the item's src tokens comes from a radix select on an order-preserving image of the
+// floats (4 passes of 8 bits, LDS histogram, integer counts only); similarities that tie with it are
+// taken in ascending position.
+constexpr int kSelThreads = 1024;
+constexpr int kSelRounds = HTTM_MAX_BLOCK / kSelThreads;
+
+__global__ __launch_bounds__(kSelThreads) void top_r_select_kernel(const TopRArgs a) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t sel[2];
+  __shared__ int s_part[kSelThreads / 64];
+  const TopRStream& s = a.s[blockIdx.z];
+  if ((int)blockIdx.x >= s.n_items) return;
+  const WorkItem it = s.items[blockIdx.x];
+  const int n = it.n, k = it.k, kd = it.kd, n0 = it.n0;
+  if (kd >= k) return;                 // every src token merges: the matching kernel's entries stand
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int32_t* __restrict__ assign = s.assign + (int64_t)blockIdx.y * s.head_stride + it.start;
+  const float* __restrict__ score = s.score + (int64_t)blockIdx.y * s.head_stride + it.start;
+  const int r = n - k, n_src = n - kd;   // src tokens that merge, src tokens there are (r < n_src here)
+  bool is_src[kSelRounds];
+  uint32_t key[kSelRounds];
+#pragma unroll
+  for (int i = 0; i < kSelRounds; ++i) {
+    const int t = i * kSelThreads + tid;
+    is_src[i] = t < n && cluster_at(t, n, kd, n0) < 0;
+    key[i] = 0;
+    if (is_src[i]) {
+      const uint32_t u = __float_as_uint(score[t]);
+      key[i] = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    }
+  }
+  // ascending-position rank of the flagged tokens: exclusive count over (round, wave, lane)
+  auto rank_in_order = [&](const bool (&flag)[kSelRounds], int (&rank)[kSelRounds]) {
+    int base = 0;
+#pragma unroll
+    for (int i = 0; i < kSelRounds; ++i) {
+      const unsigned long long b = __ballot(flag[i]);
+      if (lane == 0) s_part[wave] = __popcll(b);
+      __syncthreads();
+      int before = 0, total = 0;
+      for (int w = 0; w < kSelThreads / 64; ++w) {
+        before += w < wave ? s_part[w] : 0;
+        total += s_part[w];
+      }
+      rank[i] = base + before + __builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, 0u));
+      base += total;
+      __syncthreads();
+    }
+  };
+  bool merged[kSelRounds];
+#pragma unroll
+  for (int i = 0; i < kSelRounds; ++i) merged[i] = false;
+  if (r > 0) {
+    uint32_t prefix = 0, rank = (uint32_t)(r - 1);   // descending rank of the last key taken
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+      const int shift = 24 - 8 * pass;
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < kSelRounds; ++i)
+        if (is_src[i] && (pass == 0 || (key[i] >> (shift + 8)) == prefix)) atomicAdd(&hist[(key[i] >> shift) & 255u], 1u);
+      __syncthreads();
+      if (wave == 0) {
+        uint32_t hb[4], mine = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          hb[i] = hist[lane * 4 + i];
+          mine += hb[i];
+        }
+        uint32_t incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+          const uint32_t up = (uint32_t)__shfl_up((int)incl, d);
+          if (lane >= d) incl += up;
+        }
+        uint32_t above = (uint32_t)__shfl((int)incl, 63) - incl;   // keys in the bins of higher lanes
+#pragma unroll
+        for (int i = 3; i >= 0; --i) {
+          if (rank >= above && rank < above + hb[i]) {
+            sel[0] = (prefix << 8) | (uint32_t)(lane * 4 + i);
+            sel[1] = rank - above;
+          }
+          above += hb[i];
+        }
+      }
+      __syncthreads();
+      prefix = sel[0];
+      rank = sel[1];
+      __syncthreads();
+    }
+    // `prefix` is the key of the last src taken; rank + 1 of the keys equal to it are taken
+    bool eq[kSelRounds];
+    int er[kSelRounds];
+#pragma unroll
+    for (int i = 0; i < kSelRounds; ++i) eq[i] = is_src[i] && key[i] == prefix;
+    rank_in_order(eq, er);
+#pragma unroll
+    for (int i = 0; i < kSelRounds; ++i) merged[i] = is_src[i] && (key[i] > prefix || (eq[i] && er[i] <= (int)rank));
+  }
+  bool stay[kSelRounds];
+  int idx[kSelRounds];
+#pragma unroll
+  for (int i = 0; i < kSelRounds; ++i) stay[i] = is_src[i] && !merged[i];
+  rank_in_order(stay, idx);
+#pragma unroll
+  for (int i = 0; i < kSelRounds; ++i)
+    if (stay[i]) assign[i * kSelThreads + tid] = it.moff + kd + idx[i];
+  (void)n_src;
+}
+
 // ---- aggregation ---------------------------------------------------------------------------------
 
 constexpr int kBaWaves = 16;
@@ -268,8 +374,11 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
   const MatchMergeStream& s = a.s[REFINE ? 0 : blockIdx.z];
   if ((int)blockIdx.x >= s.n_items) return;
   const WorkItem it = s.items[blockIdx.x];
-  const int n = it.n, k = it.k;
+  const int n = it.n, k = it.k, kd = it.kd;
   if (REFINE && k == n) return;   // nothing was merged here: no deviation, no outlier
+  // position of the dst token of cluster m; the clusters kd .. k-1 are single src tokens that did not
+  // merge (general rule of Sec. 3.2): they have no dst token, their only member comes first anyway
+  auto dst_of = [&](int m) { return m < kd ? dst_position(m, n, kd, it.n0) : -1; };
   const int64_t h = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t N = a.N, M = s.M;
@@ -292,6 +401,15 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
       any = any || out;
     }
     if (!__syncthreads_or(any)) return;
+  } else if (s.preset) {
+    // head-uniform variant: the clusters were computed once on the head-averaged tokens
+    float* __restrict__ score = s.score ? s.score + h * N + it.start : nullptr;
+    for (int t = tid; t < n; t += kBaThreads) {
+      const int32_t slot = s.preset[it.start + t];
+      assign[t] = slot;
+      if (score) score[t] = s.preset_score ? s.preset_score[it.start + t] : 1.0f;
+      s_cl[t] = (int16_t)(slot - it.moff);
+    }
   } else {
     for (int t = tid; t < n; t += kBaThreads) s_cl[t] = (int16_t)(assign[t] - it.moff);
   }
@@ -309,7 +427,7 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
     if (REFINE && cl <= -2) {
       const int left = -2 - cl;
       s_aff[left] = 1;
-      if (dst_position(left, n, k, it.n0) == t) s_dout[left] = 1;
+      if (dst_of(left) == t) s_dout[left] = 1;
     }
   }
   __syncthreads();
@@ -395,7 +513,7 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
       // ascending position, re-ordered so that the dst token comes first (the order of the sums
       // in match_merge.hip); plain ascending if the dst token has left
       const int first = s_off[my_cl];
-      const int dp = dst_position(my_cl, n, k, it.n0);
+      const int dp = dst_of(my_cl);
       const int fin = (REFINE && s_dout[my_cl]) ? pos - first
                                                 : (t == dp ? 0 : (t < dp ? pos - first + 1 : pos - first));
       s_list[first + fin] = (uint16_t)t;
@@ -547,6 +665,15 @@ hipError_t allow_big_lds() {
 
 }  // namespace
 
+hipError_t launch_top_r_select(const TopRArgs& a, int heads, hipStream_t stream) {
+  int n_items = 0;
+  for (int i = 0; i < a.n_streams; ++i) n_items = a.s[i].n_items > n_items ? a.s[i].n_items : n_items;
+  if (n_items == 0 || heads == 0) return hipSuccess;
+  hipLaunchKernelGGL(top_r_select_kernel, dim3((unsigned)n_items, (unsigned)heads, (unsigned)a.n_streams),
+                     dim3(kSelThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_match_merge_big(const MatchMergeArgs& a, hipStream_t stream) {
   int n_items = 0, preset = 0;
   for (int i = 0; i < a.n_streams; ++i) {
@@ -554,13 +681,26 @@ hipError_t launch_match_merge_big(const MatchMergeArgs& a, hipStream_t stream) {
     preset |= a.s[i].preset != nullptr;
   }
   if (n_items == 0 || a.H == 0) return hipSuccess;
-  if (preset) return hipErrorNotSupported;
   const int nmax = a.max_block;
   const int kmax = a.max_k > 0 ? a.max_k : a.max_block;
-  dim3 mgrid((unsigned)n_items, (unsigned)((nmax + kBmTokens - 1) / kBmTokens), (unsigned)(a.H * a.n_streams));
-  hipLaunchKernelGGL(big_match_kernel, mgrid, dim3(kBmThreads), 0, stream, a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  hipError_t e;
+  if (!preset) {
+    dim3 mgrid((unsigned)n_items, (unsigned)((nmax + kBmTokens - 1) / kBmTokens), (unsigned)(a.H * a.n_streams));
+    hipLaunchKernelGGL(big_match_kernel, mgrid, dim3(kBmThreads), 0, stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (a.top_r) {
+      // general rule of Sec. 3.2: which src tokens merge, and the clusters of those that do not
+      TopRArgs t = {};
+      t.n_streams = a.n_streams;
+      for (int i = 0; i < a.n_streams; ++i) {
+        if (!a.s[i].score) return hipErrorInvalidValue;     // the selection needs every token's similarity
+        t.s[i] = {a.s[i].assign, a.s[i].score, a.s[i].items, a.s[i].n_items, a.N};
+      }
+      e = launch_top_r_select(t, a.H, stream);
+      if (e != hipSuccess) return e;
+    }
+  }
   e = allow_big_lds<false>();
   if (e != hipSuccess) return e;
   dim3 agrid((unsigned)n_items, (unsigned)a.H, (unsigned)a.n_streams);

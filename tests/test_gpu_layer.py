@@ -12,6 +12,7 @@ import torch
 
 import paper_2511_21317_amd as httm
 import synth
+import synth.vggt_tokens
 from oracle import httm_oracle as orc
 
 from gpu_util import (check_assign, check_output, f32, key_scale, oracle_geom, plan_for, require_gpu, round_bf16,
@@ -189,6 +190,36 @@ def test_head_uniform_variant(idx):
     check_assign(ak[0], ref["assign_k"][0], ref["gap_k"][0], "uniform assign_k")
     check_output(f32(out), ref["O"], f"cfg{idx} uniform output")
     staged = run_stages(plan, q, k, v, with_scores=False)
+    assert torch.equal(staged["out"], out)
+    plan.close()
+
+
+@pytest.mark.parametrize("w,rho_kv", [
+    (synth.vggt_tokens.Workload("uniform_big_b16T8", 71, 8, 16, 20, 16, 8, 0.75, 1, H=3), 0.5),                    # 2048 + 512
+    (synth.vggt_tokens.Workload("uniform_paper_blocks", 72, 30, 16, 16, 128, 30, 0.9, 1, H=3, chunked=True), 0.7),  # 3840
+], ids=lambda c: getattr(c, "name", str(c)))
+def test_head_uniform_variant_on_blocks_of_more_than_512_tokens(w, rho_kv):
+    """One topology for all heads (Sec. 3.2's counter-example) on the two-kernel path: the shared
+    matching runs on the head-averaged fp32 tokens with the dst tokens tiled through LDS."""
+    require_gpu()
+    q, k, v = _inputs(w)
+    plan = plan_for(w, variant="uniform", rho_kv=rho_kv)
+    out, views = run_layer(plan, q, k, v)
+    ref = orc.layer_forward(f32(q), f32(k), f32(v), oracle_geom(w), w.rho, rho_kv, variant="uniform")
+    aq, ak = views["assign_q"].cpu().numpy(), views["assign_k"].cpu().numpy()
+    for h in range(w.H):
+        assert np.array_equal(aq[h], aq[0]) and np.array_equal(ak[h], ak[0])
+    nq = check_assign(aq[0], ref["assign_q"][0], ref["gap_q"][0], f"{w.name} assign_q")
+    nk = check_assign(ak[0], ref["assign_k"][0], ref["gap_k"][0], f"{w.name} assign_k")
+    from gpu_util import oracle_continued_from, output_bar
+    want = oracle_continued_from(ref, f32(q), f32(k), f32(v), oracle_geom(w), w.rho, rho_kv, aq, ak)
+    bar_abs, bar_rel, _, _ = output_bar(ref, key_scale(plan))
+    got = f32(out)
+    err = float(np.abs(got - want).max())
+    rel = float(np.linalg.norm(got - want) / np.linalg.norm(want))
+    print(f"{w.name}: {nq} + {nk} shared indices differ, max_abs {err:.4g} (bar {bar_abs:.4g}), rel_l2 {rel:.4g}", flush=True)
+    assert err < bar_abs and rel < bar_rel
+    staged = run_stages(plan, q, k, v, with_scores=True)
     assert torch.equal(staged["out"], out)
     plan.close()
 

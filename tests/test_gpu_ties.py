@@ -122,6 +122,7 @@ def test_exact_ties_and_zero_vectors_follow_the_lowest_cluster_rule(w, rho_kv):
 TOPR_CASES = [
     Workload("topr_ties_block256", 45, 4, 16, 16, 8, 4, 0.5, 1, H=2, dst_frac=0.25),     # kd = 64, r = 128 of 192 src
     Workload("topr_ties_block512", 46, 8, 16, 16, 8, 8, 0.5, 1, H=2, dst_frac=0.25),     # kd = 128, r = 256 of 384 src
+    Workload("topr_ties_block3840", 47, 30, 16, 16, 128, 30, 0.5, 1, H=2, chunked=True, dst_frac=0.25),   # kd = 960, r = 1920 of 2880
 ]
 
 

@@ -43,6 +43,21 @@ def _random_case(seed):
 
 CASES += [_random_case(s) for s in range(8)]
 
+# blocks of more than 512 tokens (the two-kernel path with the selection kernel between the two), the
+# paper's own block shape among them, and the head-uniform variant under the general rule
+BIG_CASES = [
+    (Workload("topr_big_b16T8", 51, 8, 16, 20, 16, 8, 0.5, 1, H=2, dst_frac=0.25), "headwise"),        # 2048 + 512
+    (Workload("topr_paper_blocks_ns128_nt30", 52, 30, 16, 16, 128, 30, 0.5, 1, H=2, chunked=True, dst_frac=0.25),
+     "headwise"),                                                                                          # 3840: 960 dst, 1920 of 2880 src merge
+    (Workload("topr_paper_blocks_ratio_capped", 53, 30, 16, 12, 128, 30, 0.9, 1, H=2, chunked=True, dst_frac=0.25),
+     "headwise"),                                                                                          # every src merges
+    (Workload("topr_big_anchored_nothing_merges", 54, 12, 10, 13, 100, 12, 0.0, 1, H=2, chunked=True, anchor=True,
+              dst_frac=0.1), "headwise"),
+    (Workload("topr_uniform_block256", 55, 4, 16, 16, 8, 4, 0.5, 1, H=3, dst_frac=0.25), "uniform"),
+    (Workload("topr_uniform_small_blocks", 56, 4, 9, 11, 4, 3, 0.6, 1, H=2, dst_frac=0.25), "uniform"),
+    (Workload("topr_uniform_paper_blocks", 57, 30, 16, 16, 128, 30, 0.6, 1, H=3, chunked=True, dst_frac=0.25), "uniform"),
+]
+
 
 def _rep_from_gpu(assign, pi, g, blocks, rho):
     """Owner token of every slot, from the GPU's own assignment: the dst token of a dst cluster, the
@@ -67,15 +82,15 @@ def _rep_from_gpu(assign, pi, g, blocks, rho):
     return rep
 
 
-@pytest.mark.parametrize("w", CASES, ids=lambda w: w.name)
-def test_top_r_rule_matches_the_oracle(w):
+@pytest.mark.parametrize("w,variant", [(w, "headwise") for w in CASES] + BIG_CASES, ids=lambda c: getattr(c, "name", c))
+def test_top_r_rule_matches_the_oracle(w, variant):
     require_gpu()
-    print(f"[case] {w.name} N={w.N} H={w.H} dst_frac={w.dst_frac}", flush=True)
+    print(f"[case] {w.name} N={w.N} H={w.H} dst_frac={w.dst_frac} {variant}", flush=True)
     q, k, v = synth.make_qkv(w, device="cuda")
-    plan = plan_for(w)
+    plan = plan_for(w, variant=variant)
     g = oracle_geom(w)
     got = run_stages(plan, q, k, v)
-    ref = orc.layer_forward(f32(q), f32(k), f32(v), g, w.rho, w.rho)
+    ref = orc.layer_forward(f32(q), f32(k), f32(v), g, w.rho, w.rho, variant=variant)
     pi, blocks = ref["pi"], ref["blocks"]
     assert plan.M_q == ref["q_m"][0].shape[0] and plan.M_k == ref["k_m"][0].shape[0]
     inv = np.empty_like(pi)
@@ -113,13 +128,19 @@ def test_top_r_rule_matches_the_oracle(w):
     httm.layer_forward(plan, q, k, v, out, httm.alloc_workspace(plan))
     torch.cuda.synchronize()
     assert torch.equal(out, got["out"])
+    if variant == "uniform":
+        aq = got["assign_q"].cpu().numpy()
+        assert all(np.array_equal(aq[h], aq[0]) for h in range(w.H))
     plan.close()
 
 
-def test_top_r_with_outlier_filter_runs_and_matches():
+@pytest.mark.parametrize("w", [
+    Workload("topr_filtered", 37, 4, 16, 16, 4, 4, 0.6, 1, H=2, dst_frac=0.25),
+    Workload("topr_filtered_paper_blocks", 58, 30, 16, 16, 128, 30, 0.6, 1, H=2, chunked=True, dst_frac=0.25),
+], ids=lambda w: w.name)
+def test_top_r_with_outlier_filter_runs_and_matches(w):
     """The general rule and the adaptive outlier filter together (Sec. 3.2 + Sec. 3.4)."""
     require_gpu()
-    w = Workload("topr_filtered", 37, 4, 16, 16, 4, 4, 0.6, 1, H=2, dst_frac=0.25)
     q, k, v = synth.make_qkv(w, device="cuda")
     plan = plan_for(w, outlier_frac=0.05)
     out = torch.empty((plan.N, plan.H * 64), dtype=torch.bfloat16, device="cuda")

@@ -147,8 +147,10 @@ def test_host_tables_with_a_fixed_dst_share(case):
     assert t["block_kq"].tolist() == kq and t["block_offq"].tolist() == oq and s.M_q == Mq
     assert t["block_kk"].tolist() == kk and t["block_offk"].tolist() == ok and s.M_k == Mk
     L, sz = httm.lib(), httm.Sizes()
-    bad = httm.make_geom(8, 32, 32, 16, 4, 0.5, dst_frac=0.25)           # 1024-token blocks: not with this rule
-    assert L.httm_geom_sizes(C.byref(bad), C.byref(sz)) == -2
+    big = httm.make_geom(8, 32, 32, 16, 4, 0.5, dst_frac=0.25)           # 1024-token blocks, and head-uniform
+    assert L.httm_geom_sizes(C.byref(big), C.byref(sz)) == 0
+    big = httm.make_geom(8, 32, 32, 16, 4, 0.5, dst_frac=0.25, variant="uniform")
+    assert L.httm_geom_sizes(C.byref(big), C.byref(sz)) == 0
     bad = httm.make_geom(8, 16, 16, 4, 2, 0.5, dst_frac=1.5)
     assert L.httm_geom_sizes(C.byref(bad), C.byref(sz)) == -1
     assert L.httm_global_match(None, 10, 1, 64, 0.25, None, None, None) == -1
@@ -192,8 +194,8 @@ def test_argument_errors_are_reported_not_crashed():
     assert L.httm_geom_sizes(C.byref(big), C.byref(s)) == 0
     bad = httm.make_geom(32, 32, 32, 16, 32, 0.5)          # 8192-token block
     assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -2
-    bad = httm.make_geom(8, 32, 32, 16, 4, 0.5, variant="uniform")   # no head-uniform matching of big blocks
-    assert L.httm_geom_sizes(C.byref(bad), C.byref(s)) == -2
+    ok = httm.make_geom(8, 32, 32, 16, 4, 0.5, variant="uniform")    # head-uniform matching of big blocks: fine
+    assert L.httm_geom_sizes(C.byref(ok), C.byref(s)) == 0
     ok = httm.make_geom(8, 32, 32, 16, 4, 0.5, outlier_frac=0.1)     # outlier filtering of big blocks: fine
     assert L.httm_geom_sizes(C.byref(ok), C.byref(s)) == 0
     bad = httm.make_geom(2, 16, 16, 4, 2, 1.5)
