@@ -188,6 +188,9 @@ HTTM_API int httm_geom_block_forms(const httm_geom_t* g, int32_t* block_src0, in
  * later calls, but two calls that use these buffers (or those of the outlier filter) must not run
  * concurrently: they share them. */
 HTTM_API int httm_plan_create(const httm_geom_t* g, httm_plan_t** out);
+/* A second plan of the same geometry with device buffers of its own (on the current device), for a
+ * second stream: calls on the two plans may overlap freely.  Costs what httm_plan_create costs. */
+HTTM_API int httm_plan_clone(const httm_plan_t* plan, httm_plan_t** out);
 HTTM_API int httm_plan_destroy(httm_plan_t* plan);
 HTTM_API int httm_plan_query(const httm_plan_t* plan, httm_sizes_t* out);
 

@@ -62,6 +62,7 @@ def lib() -> C.CDLL:
     L.httm_geom_tables.argtypes = [C.POINTER(Geom)] + [vp] * 7
     L.httm_geom_block_forms.argtypes = [C.POINTER(Geom), vp, vp]
     L.httm_plan_create.argtypes = [C.POINTER(Geom), C.POINTER(vp)]
+    L.httm_plan_clone.argtypes = [vp, C.POINTER(vp)]
     L.httm_plan_destroy.argtypes = [vp]
     L.httm_plan_query.argtypes = [vp, C.POINTER(Sizes)]
     L.httm_reorder.argtypes = [vp, vp, vp, C.c_int, vp]
@@ -82,7 +83,7 @@ def lib() -> C.CDLL:
     L.httm_unmerge_filtered.argtypes = [vp, vp, vp, i32p, vp, vp]
     L.httm_outlier_stats.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32), vp]
     L.httm_global_match.argtypes = [vp, C.c_int64, C.c_int, C.c_int, C.c_double, i32p, f32p, vp]
-    for name in ("httm_geom_sizes", "httm_workspace_layout", "httm_geom_tables", "httm_geom_block_forms", "httm_plan_create",
+    for name in ("httm_geom_sizes", "httm_workspace_layout", "httm_geom_tables", "httm_geom_block_forms", "httm_plan_create", "httm_plan_clone",
                  "httm_plan_destroy", "httm_plan_query", "httm_reorder", "httm_match_merge",
                  "httm_reorder_match_merge",
                  "httm_attention", "httm_attention_scratch", "httm_attention_log2", "httm_attention_log2_scratch", "httm_attention_log2_static", "httm_attention_split_plan", "httm_unmerge", "httm_layer_forward",
@@ -173,13 +174,20 @@ def _dev(t: torch.Tensor, dtype, shape=None) -> C.c_void_p:
 class Plan:
     """Owns an httm_plan_t (device index tables of one geometry)."""
 
-    def __init__(self, g: Geom):
+    def __init__(self, g: Geom, _clone_of=None):
         self.geom = g
         self._h = C.c_void_p()
-        _check(lib().httm_plan_create(C.byref(g), C.byref(self._h)), "httm_plan_create")
+        if _clone_of is None:
+            _check(lib().httm_plan_create(C.byref(g), C.byref(self._h)), "httm_plan_create")
+        else:
+            _check(lib().httm_plan_clone(_clone_of._h, C.byref(self._h)), "httm_plan_clone")
         self.sizes = Sizes()
         _check(lib().httm_plan_query(self._h, C.byref(self.sizes)), "httm_plan_query")
         self.layout = workspace_layout(g)
+
+    def clone(self) -> "Plan":
+        """A second plan of the same geometry with buffers of its own (for a second stream)."""
+        return Plan(self.geom, _clone_of=self)
 
     def close(self):
         if self._h:

@@ -315,6 +315,11 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
   return HTTM_OK;
 }
 
+int httm_plan_clone(const httm_plan_t* p, httm_plan_t** out) {
+  if (!p || !out) return HTTM_E_INVALID_ARG;
+  return httm_plan_create(&p->geom, out);
+}
+
 int httm_plan_destroy(httm_plan_t* p) {
   if (!p) return HTTM_OK;
   void* ptrs[] = {p->d_pi, p->d_items_q, p->d_items_k, p->d_mean, p->d_slot, p->d_uscore, p->d_score, p->ob.state};

@@ -41,6 +41,8 @@ struct MatchMergeArgs {
   int32_t max_k;        // most clusters any work item of any stream keeps
   int32_t top_r;        // some work item merges only its top-r src tokens (WorkItem.kd < k)
   WorkItem single;      // used instead of s[].items when those are nullptr (one work item, n_items = 1)
+  int32_t chunks;       // big_match_kernel: chunks of 256 tokens per work item, and the item count the
+  int32_t n_items_max;  // grid is laid out for (set by its launchers)
 };
 hipError_t launch_match_merge(const MatchMergeArgs& a, hipStream_t stream);
 // The same for blocks of more than kSmallBlockMax tokens (two kernels; no preset mode).

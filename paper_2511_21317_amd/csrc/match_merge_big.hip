@@ -63,16 +63,24 @@ void big_match_kernel(const MatchMergeArgs a) {
   __shared__ __align__(16) unsigned char s_d[2][kBmDstTile * kLdsRowBytes];
   __shared__ __align__(16) float s_dinv[2][kBmDstTile];
 
+  // blockIdx -> (work item, head, stream) group and its chunk of 256 tokens.  All chunks of a group
+  // stream the same dst tokens, and workgroups go round-robin to the 8 XCDs (each with its own L2),
+  // so the chunks of a group are made consecutive workgroups of ONE XCD: XCD x walks the groups
+  // x, x + 8, ... and inside a group its a.chunks chunks.
+  const int xcd = blockIdx.x & 7, pos = blockIdx.x >> 3;
+  const int group = (pos / a.chunks) * 8 + xcd, chunk = pos % a.chunks;
   const int n_heads = a.H;
-  const int sidx = blockIdx.z / n_heads;
-  const int64_t h = blockIdx.z % n_heads;
+  const int item = group % a.n_items_max, hs = group / a.n_items_max;
+  if (hs >= n_heads * a.n_streams) return;
+  const int sidx = hs / n_heads;
+  const int64_t h = hs % n_heads;
   const MatchMergeStream& s = a.s[sidx];
-  if ((int)blockIdx.x >= s.n_items) return;
-  const WorkItem it = s.items ? s.items[blockIdx.x] : a.single;
+  if (item >= s.n_items) return;
+  const WorkItem it = s.items ? s.items[item] : a.single;
   // k: the dst tokens of the item (all its clusters under Alg. 1's rule; with a fixed dst share the
   // clusters behind them are the src tokens that stay unmerged, numbered by the selection kernel)
   const int n = it.n, k = it.kd, n0 = it.n0;
-  const int t0 = blockIdx.y * kBmTokens;
+  const int t0 = chunk * kBmTokens;
   if (t0 >= n) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
@@ -685,8 +693,12 @@ hipError_t launch_match_merge_big(const MatchMergeArgs& a, hipStream_t stream) {
   const int kmax = a.max_k > 0 ? a.max_k : a.max_block;
   hipError_t e;
   if (!preset) {
-    dim3 mgrid((unsigned)n_items, (unsigned)((nmax + kBmTokens - 1) / kBmTokens), (unsigned)(a.H * a.n_streams));
-    hipLaunchKernelGGL(big_match_kernel, mgrid, dim3(kBmThreads), 0, stream, a);
+    MatchMergeArgs m = a;
+    m.chunks = (nmax + kBmTokens - 1) / kBmTokens;
+    m.n_items_max = n_items;
+    const int64_t groups = (int64_t)n_items * a.H * a.n_streams;
+    const unsigned mgrid = (unsigned)(8 * ((groups + 7) / 8) * m.chunks);
+    hipLaunchKernelGGL(big_match_kernel, dim3(mgrid), dim3(kBmThreads), 0, stream, m);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (a.top_r) {
@@ -724,8 +736,11 @@ hipError_t launch_global_match(const void* x, int64_t N, int H, int32_t kd, int3
   a.s[0].score = sim;
   a.s[0].items = nullptr;
   a.s[0].n_items = 1;
-  dim3 grid(1u, (unsigned)((N + kBmTokens - 1) / kBmTokens), (unsigned)H);
-  hipLaunchKernelGGL(big_match_kernel, grid, dim3(kBmThreads), 0, stream, a);
+  a.chunks = (int32_t)((N + kBmTokens - 1) / kBmTokens);
+  a.n_items_max = 1;
+  // (one group per head: the groups of 8 consecutive heads run side by side on the 8 XCDs)
+  const unsigned grid = (unsigned)(8 * ((H + 7) / 8) * a.chunks);
+  hipLaunchKernelGGL(big_match_kernel, dim3(grid), dim3(kBmThreads), 0, stream, a);
   return hipGetLastError();
 }
 

@@ -385,3 +385,37 @@ def test_plain_unmerge_refuses_a_plan_with_the_filter():
         torch.cuda.synchronize()
         assert torch.isnan(out.float()).all()
     plan.close()
+
+
+def test_a_cloned_plan_serves_a_second_stream():
+    """A plan with the outlier filter keeps the threshold and the outlier row offsets in device memory of
+    its own, so two streams take two plans: httm_plan_clone.  Both layers, launched side by side on two
+    streams with different inputs, give the bits of the same calls made one after the other."""
+    require_gpu()
+    w = synth.workload(2)
+    q, k, v = synth.make_qkv(w, device="cuda")
+    q2, k2, v2 = (t.flip(0).contiguous() for t in (q, k, v))       # the heads in reverse order
+    plan = plan_for(w, outlier_frac=0.05)
+    twin = plan.clone()
+    assert (twin.N, twin.M_q, twin.outlier_cap) == (plan.N, plan.M_q, plan.outlier_cap)
+
+    def fresh():
+        return (torch.empty((plan.N, plan.H * 64), dtype=torch.bfloat16, device="cuda"), httm.alloc_workspace(plan))
+    (ref1, ws_a), (ref2, ws_b) = fresh(), fresh()
+    httm.layer_forward(plan, q, k, v, ref1, ws_a)
+    httm.layer_forward(plan, q2, k2, v2, ref2, ws_b)
+    torch.cuda.synchronize()
+    (out1, ws1), (out2, ws2) = fresh(), fresh()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for s in (s1, s2):
+        s.wait_stream(torch.cuda.current_stream())
+    for _ in range(3):
+        with torch.cuda.stream(s1):
+            httm.layer_forward(plan, q, k, v, out1, ws1)
+        with torch.cuda.stream(s2):
+            httm.layer_forward(twin, q2, k2, v2, out2, ws2)
+    torch.cuda.synchronize()
+    assert torch.equal(out1, ref1) and torch.equal(out2, ref2)
+    assert not torch.equal(out1, out2)
+    twin.close()
+    plan.close()
