@@ -84,10 +84,9 @@ def pmc_traffic_bytes(kernel: str, workload_index: int):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload
     (FETCH_SIZE + WRITE_SIZE, already scaled by the copy-kernel calibration), and the file, or None."""
     import glob
-    for path in glob.glob(os.path.join(ROOT, "profiles", f"hbm_traffic_pmc_cfg{workload_index}_*.txt")):
+    for path in glob.glob(os.path.join(ROOT, "profiles", f"hbm_traffic_pmc_cfg{workload_index}_S*_N*.txt")):
         for line in open(path):
-            t = line.split()
-            if t and t[0] == kernel and "|" in t:
+            if line.startswith(kernel) and "|" in line:
                 cols = [c.split() for c in line.split("|")]
                 return (float(cols[1][0]) + float(cols[1][1])) * 1e6, os.path.relpath(path, ROOT)
     return None, None
@@ -252,7 +251,7 @@ def main():
     clocks["after_headline"] = shader_clock_mhz()
 
     a = headline["stages"]["attention"]
-    traffic, traffic_file = pmc_traffic_bytes("attention_kernel", w.index)
+    traffic, traffic_file = pmc_traffic_bytes("attention_kernel<2, 4, false>" if LK else "attention_kernel<2, 4, true>", w.index)
     roofline = {"kernel": "attention_kernel", "bound": "mfma", "achieved": a["TFLOP/s"],
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": a["TFLOP/s"] / PEAK_BF16_TFLOPS,
                 "traffic": None if special else traffic,
