@@ -67,6 +67,54 @@ __device__ __forceinline__ int cluster_at(int p, int n, int k, int n0) {
   return (m < k && dst_position_any(m, n, k, n0) == p) ? m : -1;
 }
 
+// The same two maps for a merging block (at most 4096 tokens: every product below stays under 2^25
+// and every quotient under 2^13) without an integer division per call.  The quotient comes from a
+// float reciprocal (relative error below 2^-21, so it is off by at most one) and is put right with
+// the exact integer remainder.
+__device__ __forceinline__ int div_block(int num, int den, float rcp_den) {
+  int q = (int)((float)num * rcp_den);
+  const int r = num - q * den;
+  q = r < 0 ? q - 1 : q;
+  q = r >= den ? q + 1 : q;
+  return q;
+}
+struct BlockMap {
+  int n, k, n0;
+  float rcp_k, rcp_n;   // 1 / (k - n0) and 1 / (n - n0); unused (and infinite) where those are 0
+  __device__ __forceinline__ BlockMap(int n_, int k_, int n0_)
+      : n(n_), k(k_), n0(n0_), rcp_k(__builtin_amdgcn_rcpf((float)(k_ - n0_))),
+        rcp_n(__builtin_amdgcn_rcpf((float)(n_ - n0_))) {}
+  __device__ __forceinline__ int dst_position(int m) const {
+    const int p = n0 + div_block((m - n0) * (n - n0), k - n0, rcp_k);
+    return m < n0 || k == n0 ? m : p;
+  }
+  // dst tokens at positions below p (0 <= p <= n): floor(j * A / B) < x  <=>  j < ceil(x * B / A)
+  __device__ __forceinline__ int dst_before(int p) const {
+    const int m = n0 + div_block((p - n0) * (k - n0) + (n - n0) - 1, n - n0, rcp_n);
+    return p <= n0 ? p : (k == n0 ? n0 : m);
+  }
+  __device__ __forceinline__ int cluster_at(int p) const {
+    if (p < n0) return p;
+    if (k == n0) return -1;
+    const int m = dst_before(p);
+    return (m < k && dst_position(m) == p) ? m : -1;
+  }
+  // Position of the s-th src token (0 <= s < n - k, ascending position): the smallest p with s + 1
+  // src tokens at positions <= p.  The count grows by at most one per position, so that p is a src
+  // position; 12 halvings cover 4096 positions.
+  __device__ __forceinline__ int src_position(int s) const {
+    int lo = 0, hi = n - 1;
+#pragma unroll 1
+    for (int i = 0; i < 12; ++i) {
+      const int mid = (lo + hi) >> 1;
+      const bool enough = mid + 1 - dst_before(mid + 1) >= s + 1;
+      hi = enough ? mid : hi;
+      lo = enough ? lo : mid + 1;
+    }
+    return lo;
+  }
+};
+
 // last word of a raw buffer descriptor on gfx9-family targets (32-bit data format, no swizzle, no
 // stride), and the cache-policy bit of a buffer load that marks it non-temporal
 constexpr int kRawBufferWord3 = 0x00020000;

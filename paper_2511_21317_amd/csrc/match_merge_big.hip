@@ -58,10 +58,19 @@ constexpr int kBmThreads = 64 * kBmWaves;
 constexpr int kBmTokens = 64 * kBmWaves;   // tokens per workgroup (two 32-token tiles per wave)
 constexpr int kBmDstTile = 64;
 
+// WIDE: the work item may be a whole sequence (un-blocked matching): positions are computed with
+// 64-bit products and integer divisions where they are needed, and a workgroup takes 256 consecutive
+// positions, dst tokens included.  Merging blocks (at most HTTM_MAX_BLOCK tokens) are handled with
+// less index arithmetic, which would otherwise cost more than the arithmetic on the scores: the
+// division-free maps of BlockMap, the source rows of all dst tokens of the block looked up once into
+// LDS, and workgroups that take 256 consecutive SRC tokens (a dst token has no match to look for, so
+// a block with 30 % dst tokens has 30 % fewer scores).
+template <bool WIDE>
 __global__ __launch_bounds__(kBmThreads) __attribute__((amdgpu_waves_per_eu(2, 4)))
 void big_match_kernel(const MatchMergeArgs a) {
   __shared__ __align__(16) unsigned char s_d[2][kBmDstTile * kLdsRowBytes];
   __shared__ __align__(16) float s_dinv[2][kBmDstTile];
+  __shared__ uint32_t s_rows[WIDE ? 1 : HTTM_MAX_BLOCK];   // source row of the dst token of every cluster
 
   // blockIdx -> (work item, head, stream) group and its chunk of 256 tokens.  All chunks of a group
   // stream the same dst tokens, and workgroups go round-robin to the 8 XCDs (each with its own L2),
@@ -82,6 +91,7 @@ void big_match_kernel(const MatchMergeArgs a) {
   const int n = it.n, k = it.kd, n0 = it.n0;
   const int t0 = chunk * kBmTokens;
   if (t0 >= n) return;
+  const BlockMap bm(n, k, n0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
   const int64_t N = a.N;
@@ -98,15 +108,34 @@ void big_match_kernel(const MatchMergeArgs a) {
     }
     return;
   }
+  // tokens this workgroup matches: positions [t0, t0 + 256) (WIDE) or the src tokens of those ranks
+  const int n_tok = WIDE ? n : n - k;
+  if constexpr (!WIDE) {
+    // the entries of the dst tokens themselves: chunk c writes those of the clusters [256 c, 256 c + 256)
+    const int m = t0 + tid;
+    if (m < k) {
+      const int p = bm.dst_position(m);
+      assign[p] = it.moff + m;
+      if (score) score[p] = 1.0f;
+    }
+    if (t0 >= n_tok) return;
+    for (int m2 = tid; m2 < k; m2 += kBmThreads) {
+      const int p = bm.dst_position(m2);
+      s_rows[m2] = pi ? (uint32_t)pi[it.start + p] : (uint32_t)(it.start + p);
+    }
+  }
 
   // ---- this wave's 64 tokens as B operands: lane -> token column, 8 channels per k-step ---------
   bf16x8 bx[2][4];
   float invn[2], bias[2];
+  int tpos[2];
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
     const int tok = t0 + wave * 64 + qt * 32 + l32;
-    const int tokc = tok < n ? tok : n - 1;
-    const uint32_t src = pi ? (uint32_t)pi[it.start + tokc] : (uint32_t)(it.start + tokc);
+    const int tokc = tok < n_tok ? tok : n_tok - 1;
+    if constexpr (WIDE) tpos[qt] = tokc;
+    else tpos[qt] = bm.src_position(tokc);
+    const uint32_t src = pi ? (uint32_t)pi[it.start + tpos[qt]] : (uint32_t)(it.start + tpos[qt]);
     float ss = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -118,6 +147,7 @@ void big_match_kernel(const MatchMergeArgs a) {
     invn[qt] = 1.0f / fmaxf(nrm, 1e-12f);
     bias[qt] = nrm * 1.001f;   // score + bias >= 0 for every dst: |<x, d>| / ||d|| <= ||x||
   }
+  if constexpr (!WIDE) __syncthreads();   // s_rows complete
 
   // ---- dst tiles: thread (row r0 / r0 + 32, chunk c) moves two 16-byte pieces per tile -----------
   const int r0 = tid >> 3, c16 = (tid & 7) * 16;
@@ -125,8 +155,12 @@ void big_match_kernel(const MatchMergeArgs a) {
   u32x4 dreg[2];
   auto dst_src_row = [&](int m) -> uint32_t {   // source row of the dst token of cluster m (clamped)
     const int mc = m < k ? m : k - 1;
-    const int p = dst_position_any(mc, n, k, n0);
-    return pi ? (uint32_t)pi[it.start + p] : (uint32_t)(it.start + p);
+    if constexpr (WIDE) {
+      const int p = dst_position_any(mc, n, k, n0);
+      return pi ? (uint32_t)pi[it.start + p] : (uint32_t)(it.start + p);
+    } else {
+      return s_rows[mc];
+    }
   };
   uint32_t srow[2];
 #pragma unroll
@@ -154,7 +188,7 @@ void big_match_kernel(const MatchMergeArgs a) {
       *(u32x4*)(&s_d[buf][r * kLdsRowBytes + c16]) = dreg[i];
       const float ss = sum8(chunk_sumsq(__builtin_bit_cast(bf16x8, dreg[i]), 0.f));
       if ((tid & 7) == 0)
-        s_dinv[buf][r] = j * kBmDstTile + r < k ? 1.0f / fmaxf(sqrtf(ss), 1e-12f) : __builtin_nanf("");
+        s_dinv[buf][r] = j * kBmDstTile + r < k ? __builtin_amdgcn_rsqf(fmaxf(ss, 1e-24f)) : __builtin_nanf("");
     }
     // tile j+1 on its way while tile j is used; the source rows of tile j+2 behind it
     if (j + 1 < n_tiles) {
@@ -217,15 +251,16 @@ void big_match_kernel(const MatchMergeArgs a) {
       bmq = om;
     }
     const int tok = t0 + wave * 64 + qt * 32 + l32;
-    if (half == 0 && tok < n) {
-      int c = cluster_at(tok, n, k, n0);
+    if (half == 0 && tok < n_tok) {
+      int c = -1;
+      if constexpr (WIDE) c = cluster_at(tok, n, k, n0);   // (a src token by construction otherwise)
       float sc = 1.0f;
       if (c < 0) {
         c = bmq;
         sc = (bestq - bias[qt]) * invn[qt];
       }
-      assign[tok] = it.moff + c;
-      if (score) score[tok] = sc;
+      assign[tpos[qt]] = it.moff + c;
+      if (score) score[tpos[qt]] = sc;
     }
   }
 }
@@ -698,7 +733,7 @@ hipError_t launch_match_merge_big(const MatchMergeArgs& a, hipStream_t stream) {
     m.n_items_max = n_items;
     const int64_t groups = (int64_t)n_items * a.H * a.n_streams;
     const unsigned mgrid = (unsigned)(8 * ((groups + 7) / 8) * m.chunks);
-    hipLaunchKernelGGL(big_match_kernel, dim3(mgrid), dim3(kBmThreads), 0, stream, m);
+    hipLaunchKernelGGL(big_match_kernel<false>, dim3(mgrid), dim3(kBmThreads), 0, stream, m);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (a.top_r) {
@@ -740,7 +775,7 @@ hipError_t launch_global_match(const void* x, int64_t N, int H, int32_t kd, int3
   a.n_items_max = 1;
   // (one group per head: the groups of 8 consecutive heads run side by side on the 8 XCDs)
   const unsigned grid = (unsigned)(8 * ((H + 7) / 8) * a.chunks);
-  hipLaunchKernelGGL(big_match_kernel, dim3(grid), dim3(kBmThreads), 0, stream, a);
+  hipLaunchKernelGGL(big_match_kernel<true>, dim3(grid), dim3(kBmThreads), 0, stream, a);
   return hipGetLastError();
 }
 
