@@ -18,7 +18,7 @@ roofline: for the dominant kernel of the headline workload (the MFMA attention):
           4*H*M_q*M_k*64 per launch over its launch time, measured with events on the launch stream.
 extras  : the same inputs without merging (r = 0), with the head-uniform variant, with first-frame
           anchoring, with the outlier filter and in the paper's own block configuration.
-clock   : the shader clock rocm-smi reports before, between and after the timed regions (unpinned).
+clock   : the shader clock the driver (or rocm-smi) reports before, between and after the timed regions (unpinned).
 cpu_baseline: the CPU oracle timed on a bounded sample (a few heads) of the headline workload.
 """
 from __future__ import annotations
@@ -70,7 +70,20 @@ def gpu_time_ms(fn, iters, warmup=1):
 
 
 def shader_clock_mhz():
-    """Current shader clock of GPU 0 as rocm-smi reports it (None if the tool is not usable)."""
+    """Current shader clock of GPU 0 in MHz (None if it cannot be read): the starred level of the
+    driver's pp_dpm_sclk file, else what rocm-smi reports.  Under a profiler that is preloaded into
+    every child process no other program is started, so there only the file is tried."""
+    import glob
+    for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+        try:
+            for line in open(path):
+                m = re.match(r"\s*\d+:\s*(\d+)\s*Mhz\s*\*", line, re.IGNORECASE)
+                if m:
+                    return int(m.group(1))
+        except OSError:
+            pass
+    if "rocprof" in os.environ.get("LD_PRELOAD", "") or any(k.startswith("ROCPROF") for k in os.environ):
+        return None
     try:
         r = subprocess.run(["rocm-smi", "-d", "0", "--showclocks"], stdout=subprocess.PIPE, stderr=subprocess.DEVNULL,
                            text=True, timeout=20)
@@ -226,7 +239,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     httm.lib()   # fails loudly if libhttm.so is missing
-    clocks = {"tool": "rocm-smi -d 0 --showclocks (sclk, MHz; clocks are not pinned)", "before": shader_clock_mhz()}
+    clocks = {"tool": "pp_dpm_sclk of the driver, else rocm-smi -d 0 --showclocks (sclk, MHz; clocks are not pinned)", "before": shader_clock_mhz()}
     LK = not args.plain_keys
     special = args.paper_blocks or args.outlier_frac > 0.0
 

@@ -11,11 +11,12 @@
 //                         It is the score half of a flash-attention kernel with an arg-max in place
 //                         of the softmax.
 //   big_aggregate_kernel  one workgroup of 1024 threads per (work item, head, stream).  Cluster sizes
-//                         with integer LDS atomics, a prefix sum, then a stable counting sort in rounds
-//                         of 1024 tokens (wave ballots, no atomics: the member order is ascending
-//                         position, the same from run to run); the member LISTS fit in LDS even
-//                         though the rows do not, and one thread per (cluster, 16-byte chunk) gathers
-//                         its members' rows from global memory, adds them in fp32 and rounds once.
+//                         with integer LDS atomics, a prefix sum, the members of every cluster placed
+//                         with a second integer atomic and then put into ascending position by
+//                         counting (the lists, and so the sums, are the same from run to run); the
+//                         member LISTS fit in LDS even though the rows do not, and one thread per
+//                         (cluster, 16-byte chunk) gathers its members' rows from global memory, adds
+//                         them in fp32 and rounds once.
 #include <type_traits>
 
 #include "dev_common.hpp"
@@ -392,10 +393,12 @@ struct RefineExtra {
   void* q_out;                // [budget, 64] bf16
 };
 
-// Dynamic LDS: s_src[nmax] int32 | s_off[kmax + 1] int32 | s_cur[kmax] int32 | s_list[nmax] u16 |
-//              s_cl[nmax] int16 | s_wcnt[kBaWaves][kmax] u8 | s_aff[kmax] u8 | s_dout[kmax] u8
+// Dynamic LDS: s_src[nmax] int32 | s_off[kmax + 1] int32 | s_cur[kmax] int32 | s_any[nmax] u16 |
+//              s_cl[nmax] int16 | s_list[nmax] u16 | s_aff[kmax] u8 | s_dout[kmax] u8
 //
-// REFINE = false: first aggregation of stream blockIdx.z (X and, for the K stream, V).
+// REFINE = false: first aggregation of one stream (X and, for the K stream, V); the workgroups of the
+//                 last stream, which carries V and takes twice as long, are dispatched first, so the
+//                 launch ends on the short ones.
 // REFINE = true : the un-merging of the outliers for the query stream a.s[0] (see
 //                 outlier_refine_kernel in match_merge.hip for the rules): tokens whose deviation lies
 //                 above tau get a row of q_out and a negative assign entry, and only the clusters that
@@ -407,21 +410,22 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
   int32_t* s_src = (int32_t*)lds;
   int32_t* s_off = s_src + nmax;
   int32_t* s_cur = s_off + kmax + 1;
-  uint16_t* s_list = (uint16_t*)(s_cur + kmax);
-  int16_t* s_cl = (int16_t*)(s_list + nmax + (nmax & 1));
-  uint8_t* s_wcnt = (uint8_t*)(s_cl + nmax + (nmax & 1));
-  uint8_t* s_aff = s_wcnt + (size_t)kBaWaves * kmax;
+  uint16_t* s_any = (uint16_t*)(s_cur + kmax);                 // members of every cluster, in any order
+  int16_t* s_cl = (int16_t*)(s_any + nmax + (nmax & 1));
+  uint16_t* s_list = (uint16_t*)(s_cl + nmax + (nmax & 1));    // the same in the order of the sums
+  uint8_t* s_aff = (uint8_t*)(s_list + nmax + (nmax & 1));
   uint8_t* s_dout = s_aff + kmax;
   __shared__ int s_part[kBaWaves];
 
-  const MatchMergeStream& s = a.s[REFINE ? 0 : blockIdx.z];
+  const MatchMergeStream& s = a.s[REFINE ? 0 : gridDim.z - 1 - blockIdx.z];
   if ((int)blockIdx.x >= s.n_items) return;
   const WorkItem it = s.items[blockIdx.x];
   const int n = it.n, k = it.k, kd = it.kd;
   if (REFINE && k == n) return;   // nothing was merged here: no deviation, no outlier
   // position of the dst token of cluster m; the clusters kd .. k-1 are single src tokens that did not
   // merge (general rule of Sec. 3.2): they have no dst token, their only member comes first anyway
-  auto dst_of = [&](int m) { return m < kd ? dst_position(m, n, kd, it.n0) : -1; };
+  const BlockMap bm(n, kd, it.n0);
+  auto dst_of = [&](int m) { return m < kd ? bm.dst_position(m) : -1; };
   const int64_t h = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t N = a.N, M = s.M;
@@ -461,7 +465,6 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
     s_aff[m] = 0;
     s_dout[m] = 0;
   }
-  for (int e = tid; e < kBaWaves * k; e += kBaThreads) s_wcnt[(e / k) * kmax + e % k] = 0;
   __syncthreads();
   for (int t = tid; t < n; t += kBaThreads) {
     s_src[t] = a.pi ? a.pi[it.start + t] : it.start + t;
@@ -531,52 +534,28 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
   for (int m = tid; m < k; m += kBaThreads) s_cur[m] = s_off[m];
   __syncthreads();
 
-  // ---- stable counting sort in rounds of kBaThreads tokens ------------------------------------------------
-  for (int base = 0; base < n; base += kBaThreads) {
-    const int t = base + tid;
-    int my_cl = t < n ? s_cl[t] : -1;
-    if (my_cl < 0) my_cl = -1;
-    int my_rank = 0;
-    {
-      unsigned long long same = __ballot(my_cl >= 0);
-      for (int bit = 0; (1 << bit) < k; ++bit) {
-        const bool set = (my_cl >> bit) & 1;
-        const unsigned long long b = __ballot(set);
-        same &= set ? b : ~b;
-      }
-      if (my_cl >= 0) {
-        my_rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(same >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)same, 0u));
-        if (my_rank == 0) s_wcnt[wave * kmax + my_cl] = (uint8_t)__popcll(same);
-      }
-    }
-    __syncthreads();
-    if (my_cl >= 0) {
-      int pos = s_cur[my_cl] + my_rank;
-      for (int w = 0; w < wave; ++w) pos += s_wcnt[w * kmax + my_cl];
-      // ascending position, re-ordered so that the dst token comes first (the order of the sums
-      // in match_merge.hip); plain ascending if the dst token has left
-      const int first = s_off[my_cl];
-      const int dp = dst_of(my_cl);
-      const int fin = (REFINE && s_dout[my_cl]) ? pos - first
-                                                : (t == dp ? 0 : (t < dp ? pos - first + 1 : pos - first));
-      s_list[first + fin] = (uint16_t)t;
-    }
-    __syncthreads();
-    // advance the cursors of the clusters touched in this round and clear the per-wave counts
-    if (my_cl >= 0 && my_rank == 0) {
-      // the first wave (lowest index) that saw the cluster does the update for all waves
-      bool first = true;
-      for (int w = 0; w < wave; ++w) first = first && s_wcnt[w * kmax + my_cl] == 0;
-      if (first) {
-        int tot = 0;
-        for (int w = wave; w < kBaWaves; ++w) tot += s_wcnt[w * kmax + my_cl];
-        s_cur[my_cl] += tot;
-      }
-    }
-    __syncthreads();
-    if (my_cl >= 0 && my_rank == 0) s_wcnt[wave * kmax + my_cl] = 0;
-    __syncthreads();
+  // ---- member lists -------------------------------------------------------------------------------------------
+  // Every token takes a slot of its cluster's range with an integer LDS atomic (any order), then finds
+  // its place in the order of the sums by counting the members that precede it: ascending position,
+  // re-ordered so that the dst token comes first (the order of match_merge.hip); plain ascending if
+  // the dst token has left.  The result does not depend on the order of the atomics, so it is the
+  // same from run to run; the work per token is the size of its cluster.
+  for (int t = tid; t < n; t += kBaThreads) {
+    const int cl = s_cl[t];
+    if (cl >= 0) s_any[atomicAdd(&s_cur[cl], 1)] = (uint16_t)t;
   }
+  __syncthreads();
+  for (int t = tid; t < n; t += kBaThreads) {
+    const int cl = s_cl[t];
+    if (cl < 0) continue;
+    const int first = s_off[cl], len = s_off[cl + 1] - first;
+    int rank = 0;
+    for (int j = 0; j < len; ++j) rank += (int)s_any[first + j] < t;
+    const int dp = (REFINE && s_dout[cl]) ? -1 : dst_of(cl);
+    const int fin = t == dp ? 0 : (t < dp ? rank + 1 : rank);
+    s_list[first + fin] = (uint16_t)t;
+  }
+  __syncthreads();
 
   // ---- aggregation: thread (cluster m, 16-byte chunk c) gathers its members' rows ---------------------------
   // Four members at a time, all loads of a batch (X and V) issued before the first add; a batch that
@@ -692,8 +671,7 @@ __global__ __launch_bounds__(kBaThreads) void big_aggregate_kernel(const MatchMe
 
 size_t big_aggregate_lds(int nmax, int kmax) {
   const size_t n2 = (size_t)nmax + (nmax & 1);
-  return (size_t)nmax * 4 + ((size_t)kmax + 1) * 4 + (size_t)kmax * 4 + n2 * 2 + n2 * 2 +
-         (size_t)kBaWaves * kmax + 2 * (size_t)kmax;
+  return (size_t)nmax * 4 + ((size_t)kmax + 1) * 4 + (size_t)kmax * 4 + 3 * n2 * 2 + 2 * (size_t)kmax;
 }
 
 template <bool REFINE>
