@@ -285,8 +285,8 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
   if (rc == HTTM_OK && p->outlier_cap > 0) {
     OutlierBuffers& b = p->ob;
     b.max_tiles = (int32_t)(p->outlier_cap / kAttnDevTileRows + g->H);
-    const size_t words = sizeof(SelectState) / 4 + 2048 + (size_t)g->H * 2 + 1 +
-                         (size_t)g->H * p->n_items + 1 + 2 * (size_t)b.max_tiles;
+    const size_t words = sizeof(SelectState) / 4 + 3 * 2048 + (size_t)g->H * 2 + 1 +
+                         2 * (size_t)g->H * p->n_items + 1 + 2 * (size_t)b.max_tiles;
     uint32_t* base = nullptr;
     e = hipMalloc((void**)&base, words * 4);
     if (e == hipSuccess) e = hipMemset(base, 0, words * 4);
@@ -295,9 +295,10 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
     } else {
       b.state = (SelectState*)base;
       b.hist = base + sizeof(SelectState) / 4;
-      b.counts = (int32_t*)(b.hist + 2048);
+      b.counts = (int32_t*)(b.hist + 3 * 2048);
       b.offsets = b.counts + g->H;
-      b.item_base = b.offsets + g->H + 1;
+      b.item_cnt = b.offsets + g->H + 1;
+      b.item_base = b.item_cnt + (size_t)g->H * p->n_items;
       b.tiles = b.item_base + (size_t)g->H * p->n_items;
     }
   }

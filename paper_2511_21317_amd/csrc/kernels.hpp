@@ -74,16 +74,20 @@ hipError_t launch_global_match(const void* x, int64_t N, int H, int32_t kd, int3
 // ---- adaptive outlier filtering of the merged queries (paper Sec. 3.4, Alg. 2) ---------------
 // State of the device-side selection of the threshold tau.
 struct SelectState {
-  uint32_t prefix;   // leading bits of tau's bit pattern decided so far
-  uint32_t rank;     // descending rank of tau among the values that share the prefix
+  uint32_t prefix1;  // the first 11 bits of tau's bit pattern
+  uint32_t rank1;    // descending rank of tau among the values that share them
   float tau;         // the threshold: a deviation strictly above it marks an outlier
   uint32_t pad;
+  uint32_t prefix2;  // the first 22 bits, and the rank among the values that share those
+  uint32_t rank2;
+  uint32_t pad2[2];
 };
 struct OutlierBuffers {      // all device memory, owned by the plan
   SelectState* state;
-  uint32_t* hist;            // [2048], zero between calls
+  uint32_t* hist;            // [3][2048] one histogram per pass of the select, zero between calls
   int32_t* counts;           // [H] outliers per head
   int32_t* offsets;          // [H + 1] first outlier row of every head in q_out / o_out
+  int32_t* item_cnt;         // [H][n_items] outliers of a work item
   int32_t* item_base;        // [H][n_items] first outlier row of a work item, relative to its head
   int32_t* tiles;            // [1 + 2 * max_tiles]: n, then (head, first row) per attention tile
   int32_t max_tiles;

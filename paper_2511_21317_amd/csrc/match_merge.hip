@@ -555,17 +555,38 @@ void match_merge_kernel(const MatchMergeArgs a) {
       // Sec. 3.4 step 2: L2 distance of every constituent to the merged token (the fp32 mean);
       // zero where nothing was merged.  The 8 lanes of a cluster hold 8 channels each.
       float* __restrict__ eps = s.eps + h * N + it.start;
-      for (int i2 = beg; i2 < end; ++i2) {
-        const int j = s_list[i2];
-        const bf16x8 w = *(const bf16x8*)(col + j * kLdsRowBytes);
-        float d2 = 0.f;
+      // (the members again, kAggBatch per round with the next list entries on their way, like the sums)
+      const bool merged = end - beg >= 2;
+      int ej[kAggBatch];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          const float df = (float)w[q] - mean[q];
-          d2 = fmaf(df, df, d2);
+      for (int u = 0; u < kAggBatch; ++u) {
+        const int e = s_list[beg + u];
+        ej[u] = beg + u < end ? e : MAXN;
+      }
+      for (int i2 = beg; i2 < end; i2 += kAggBatch) {
+        bf16x8 w[kAggBatch];
+        int cur[kAggBatch];
+#pragma unroll
+        for (int u = 0; u < kAggBatch; ++u) {
+          cur[u] = ej[u];
+          w[u] = *(const bf16x8*)(col + ej[u] * kLdsRowBytes);
         }
-        d2 = sum_over_8_lanes(d2);
-        if (c == 0) eps[j] = end - beg >= 2 ? sqrtf(d2) : 0.f;
+#pragma unroll
+        for (int u = 0; u < kAggBatch; ++u) {
+          const int e = s_list[i2 + kAggBatch + u];
+          ej[u] = i2 + kAggBatch + u < end ? e : MAXN;
+        }
+#pragma unroll
+        for (int u = 0; u < kAggBatch; ++u) {
+          float d2 = 0.f;
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const float df = (float)w[u][q] - mean[q];
+            d2 = fmaf(df, df, d2);
+          }
+          d2 = sum_over_8_lanes(d2);
+          if (c == 0 && cur[u] != MAXN) eps[cur[u]] = merged ? __builtin_amdgcn_sqrtf(d2) : 0.f;
+        }
       }
     }
     return o;

@@ -5,12 +5,14 @@
 // threshold - the largest deviation outside the budget of the `budget` largest ones - is found by
 // a three-pass radix select on the bit pattern (11 + 11 + 10 bits): a pass histograms the digit
 // of every value that matches the digits fixed so far (LDS atomics, then one global atomic per
-// non-empty bin) and a one-workgroup kernel walks the histogram from the top to the wanted
-// rank.  Integer counts only, so the result does not depend on the order of the atomics.
-// Then one pass counts the values above the threshold per (work item, head), a prefix sum per
-// head gives every work item the first outlier row it owns (no atomics: the rows of q_out are
-// the same from run to run), and one wave turns the head totals into row offsets and into the
-// tile list of the second attention.
+// non-empty bin).  Walking a histogram from the top to the wanted rank is the prologue of the NEXT
+// kernel - every workgroup does it for itself, from the finished histogram of the launch before -
+// so the select costs three launches, not six.  Integer counts only: the result does not depend
+// on the order of the atomics.  Then one pass counts the values above the threshold per (work
+// item, head), and one kernel with a workgroup per head gives every work item the first outlier
+// row it owns (a prefix sum, no atomics: the rows of q_out are the same from run to run), turns
+// the head totals into row offsets and into the tile list of the second attention, and clears
+// the histograms for the next call.
 #include "dev_common.hpp"
 #include "kernels.hpp"
 
@@ -20,6 +22,79 @@ namespace {
 
 constexpr int kBins = 2048;
 constexpr int kSelThreads = 256;
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t v) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t up = __shfl_up(v, d);
+    if (lane >= d) v += up;
+  }
+  return v;
+}
+
+// All kSelThreads threads of a workgroup: the bin of `hist` (kBins counts, bin = digit) that holds the
+// value of descending rank `rank` (0 = the largest), and the rank inside that bin.
+__device__ __forceinline__ void pick_digit(const uint32_t* __restrict__ hist, uint32_t rank, uint32_t* digit,
+                                           uint32_t* rank_in_bin) {
+  constexpr int PER = kBins / kSelThreads;
+  __shared__ uint32_t s_wave[kSelThreads / 64];
+  __shared__ uint32_t s_res[2];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  uint32_t h[PER], mine = 0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    h[i] = hist[t * PER + i];
+    mine += h[i];
+  }
+  const uint32_t incl = wave_inclusive_scan_u32(mine);
+  const uint32_t wave_total = __shfl(incl, 63);
+  if (lane == 63) s_wave[wave] = incl;
+  if (t == 0) s_res[0] = s_res[1] = 0;
+  __syncthreads();
+  uint32_t above = wave_total - incl;   // values in the bins of the threads above this one
+  for (int w = wave + 1; w < kSelThreads / 64; ++w) above += s_wave[w];
+#pragma unroll
+  for (int i = PER - 1; i >= 0; --i) {
+    if (rank >= above && rank < above + h[i]) {
+      s_res[0] = (uint32_t)(t * PER + i);
+      s_res[1] = rank - above;
+    }
+    above += h[i];
+  }
+  __syncthreads();
+  *digit = s_res[0];
+  *rank_in_bin = s_res[1];
+}
+
+// The digits decided before pass PASS and the rank among the values that share them, from the
+// histogram of the pass before (pass 0: nothing decided, the rank is the budget).  Workgroup 0
+// leaves them in the state, where the next launch starts from.
+template <int PASS>
+__device__ __forceinline__ void select_prologue(const uint32_t* __restrict__ hist, SelectState* __restrict__ st,
+                                                uint32_t budget, bool writer, uint32_t* prefix, uint32_t* rank) {
+  if (PASS == 0) {
+    *prefix = 0;
+    *rank = budget;
+    return;
+  }
+  uint32_t digit;
+  if (PASS == 1) {
+    pick_digit(hist, budget, &digit, rank);
+    *prefix = digit;
+    if (writer && threadIdx.x == 0) {
+      st->prefix1 = *prefix;
+      st->rank1 = *rank;
+    }
+  } else {
+    pick_digit(hist + kBins, st->rank1, &digit, rank);
+    *prefix = (st->prefix1 << 11) | digit;
+    if (writer && threadIdx.x == 0) {
+      st->prefix2 = *prefix;
+      st->rank2 = *rank;
+    }
+  }
+}
 
 template <int PASS>
 __device__ __forceinline__ bool digit_of(uint32_t key, uint32_t prefix, uint32_t* digit) {
@@ -37,13 +112,13 @@ __device__ __forceinline__ bool digit_of(uint32_t key, uint32_t prefix, uint32_t
 
 template <int PASS>
 __global__ __launch_bounds__(kSelThreads) void select_hist_kernel(const uint32_t* __restrict__ keys,
-                                                                  int64_t total,
-                                                                  const SelectState* __restrict__ st,
-                                                                  uint32_t* __restrict__ hist) {
+                                                                  int64_t total, SelectState* __restrict__ st,
+                                                                  uint32_t* __restrict__ hist, uint32_t budget) {
   __shared__ uint32_t s_hist[kBins];
   for (int b = threadIdx.x; b < kBins; b += kSelThreads) s_hist[b] = 0;
+  uint32_t prefix, rank;
+  select_prologue<PASS>(hist, st, budget, blockIdx.x == 0, &prefix, &rank);
   __syncthreads();
-  const uint32_t prefix = PASS == 0 ? 0u : st->prefix;
   // 16-byte loads; `keys` is 16-byte aligned and the tail is handled by the last threads
   const int64_t n4 = total >> 2;
   const int64_t stride = (int64_t)gridDim.x * kSelThreads;
@@ -62,114 +137,115 @@ __global__ __launch_bounds__(kSelThreads) void select_hist_kernel(const uint32_t
     }
   }
   __syncthreads();
+  uint32_t* __restrict__ out = hist + PASS * kBins;
   for (int b = threadIdx.x; b < kBins; b += kSelThreads) {
     const uint32_t c = s_hist[b];
-    if (c) atomicAdd(&hist[b], c);
+    if (c) atomicAdd(&out[b], c);
   }
 }
 
-// One workgroup.  Finds the bin that holds the value of descending rank st->rank (0 = largest),
-// extends the prefix by that digit, and leaves the histogram zeroed for the next pass / call.
-template <int PASS>
-__global__ __launch_bounds__(kSelThreads) void select_pick_kernel(uint32_t* __restrict__ hist,
-                                                                  SelectState* __restrict__ st,
-                                                                  uint32_t budget) {
-  constexpr int PER = kBins / kSelThreads;
-  __shared__ uint32_t s_part[kSelThreads];
-  const int t = threadIdx.x;
-  uint32_t h[PER], mine = 0;
+// item_cnt[h][i] = number of deviations above tau among the tokens of work item i of head h.  The
+// prologue takes the last digit of tau from the third histogram.  One wave per (item, head) at a
+// time, kCountItems items per workgroup.
+constexpr int kCountItems = 32;
+__global__ __launch_bounds__(kSelThreads) void outlier_count_kernel(const float* __restrict__ eps, int64_t N,
+                                                                    const WorkItem* __restrict__ items, int n_items,
+                                                                    SelectState* __restrict__ st,
+                                                                    const uint32_t* __restrict__ hist,
+                                                                    int32_t* __restrict__ item_cnt) {
+  uint32_t digit, rank_in_bin;
+  pick_digit(hist + 2 * kBins, st->rank2, &digit, &rank_in_bin);
+  const float tau = __uint_as_float((st->prefix2 << 10) | digit);
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) st->tau = tau;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = wave; i < kCountItems; i += kSelThreads / 64) {
+    const int item = blockIdx.x * kCountItems + i;
+    if (item >= n_items) break;
+    const WorkItem it = items[item];
+    const float* e = eps + (int64_t)blockIdx.y * N + it.start;
+    int c = 0;
+    for (int t = lane; t < it.n; t += 64) c += e[t] > tau ? 1 : 0;
 #pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    h[i] = hist[t * PER + i];
-    hist[t * PER + i] = 0;
-    mine += h[i];
+    for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d);
+    if (lane == 0) item_cnt[(int64_t)blockIdx.y * n_items + item] = c;
   }
-  s_part[t] = mine;
-  __syncthreads();
-  uint32_t above = 0;   // values in the bins of the threads above this one
-  for (int u = t + 1; u < kSelThreads; ++u) above += s_part[u];
-  const uint32_t rank = PASS == 0 ? budget : st->rank;
-  const uint32_t prefix = PASS == 0 ? 0u : st->prefix;
-  __syncthreads();      // everybody has read the old state
-#pragma unroll
-  for (int i = PER - 1; i >= 0; --i) {
-    if (rank >= above && rank < above + h[i]) {
-      const uint32_t digit = (uint32_t)(t * PER + i);
-      const uint32_t np = PASS == 0 ? digit : (prefix << (PASS == 1 ? 11 : 10)) | digit;
-      st->prefix = np;
-      st->rank = rank - above;
-      if (PASS == 2) st->tau = __uint_as_float(np);
+}
+
+// One workgroup per head h:
+//  - item_base[h][i] = exclusive prefix sum of item_cnt[h][.], so that every work item knows the first
+//    outlier row it owns (relative to its head);
+//  - the totals of ALL heads (every workgroup adds them up for itself, so no workgroup waits for
+//    another), from which workgroup 0 writes the first outlier row of every head and the (head,
+//    first row) list of the second attention's query tiles;
+//  - its share of the three histograms cleared for the next call.
+__global__ __launch_bounds__(kSelThreads) void outlier_offsets_kernel(const int32_t* __restrict__ item_cnt,
+                                                                      int32_t* __restrict__ item_base, int n_items,
+                                                                      int H, uint32_t* __restrict__ hist,
+                                                                      int32_t* __restrict__ counts,
+                                                                      int32_t* __restrict__ offsets,
+                                                                      int32_t* __restrict__ tiles, int tile_rows,
+                                                                      int max_tiles) {
+  __shared__ int s_part[kSelThreads];
+  __shared__ int s_total[HTTM_MAX_HEADS];
+  const int t = threadIdx.x, h = blockIdx.x;
+  for (int b = h * kSelThreads + t; b < 3 * kBins; b += H * kSelThreads) hist[b] = 0;
+  // totals of all heads: thread t adds a slice of head t % H
+  {
+    const int slices = kSelThreads / H, g = t % H, sl = t / H;   // H <= 64: at least 4 slices
+    int sum = 0;
+    if (sl < slices) {
+      const int per = (n_items + slices - 1) / slices;
+      const int i0 = sl * per, i1 = i0 + per < n_items ? i0 + per : n_items;
+      const int32_t* c = item_cnt + (int64_t)g * n_items;
+      for (int i = i0; i < i1; ++i) sum += c[i];
     }
-    above += h[i];
+    s_part[t] = sum;
+    __syncthreads();
+    if (t < H) {
+      int tot = 0;
+      for (int u = 0; u < slices; ++u) tot += s_part[u * H + t];
+      s_total[t] = tot;
+    }
+    __syncthreads();
   }
-}
-
-// item_cnt[h][i] = number of deviations above tau among the tokens of work item i of head h.
-// One wave per (item, head).
-__global__ __launch_bounds__(256) void outlier_count_kernel(const float* __restrict__ eps, int64_t N,
-                                                            const WorkItem* __restrict__ items, int n_items,
-                                                            const SelectState* __restrict__ st,
-                                                            int32_t* __restrict__ item_cnt) {
-  const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (item >= n_items) return;
-  const int lane = threadIdx.x & 63;
-  const float tau = st->tau;
-  const WorkItem it = items[item];
-  const float* e = eps + (int64_t)blockIdx.y * N + it.start;
-  int c = 0;
-  for (int t = lane; t < it.n; t += 64) c += e[t] > tau ? 1 : 0;
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d);
-  if (lane == 0) item_cnt[(int64_t)blockIdx.y * n_items + item] = c;
-}
-
-// One workgroup per head: exclusive prefix sum of the head's item counts, in place, so that every
-// work item knows the first outlier row it owns (relative to its head); counts[h] = the head's total.
-__global__ __launch_bounds__(256) void outlier_scan_kernel(int32_t* __restrict__ item_cnt, int n_items,
-                                                           int32_t* __restrict__ counts) {
-  __shared__ int s_part[256];
-  int32_t* c = item_cnt + (int64_t)blockIdx.x * n_items;
-  const int t = threadIdx.x;
-  const int per = (n_items + 255) / 256;
-  const int i0 = t * per, i1 = i0 + per < n_items ? i0 + per : n_items;
-  int sum = 0;
-  for (int i = i0; i < i1; ++i) sum += c[i];
-  s_part[t] = sum;
-  __syncthreads();
-  int base = 0;
-  for (int u = 0; u < t; ++u) base += s_part[u];
-  for (int i = i0; i < i1; ++i) {
-    const int v = c[i];
-    c[i] = base;
-    base += v;
+  // prefix sum over this head's work items
+  {
+    const int32_t* c = item_cnt + (int64_t)h * n_items;
+    int32_t* o = item_base + (int64_t)h * n_items;
+    const int per = (n_items + kSelThreads - 1) / kSelThreads;
+    const int i0 = t * per, i1 = i0 + per < n_items ? i0 + per : n_items;
+    int sum = 0;
+    for (int i = i0; i < i1; ++i) sum += c[i];
+    const int incl = (int)wave_inclusive_scan_u32((uint32_t)sum);
+    if ((t & 63) == 63) s_part[t >> 6] = incl;
+    __syncthreads();
+    int base = incl - sum;
+    for (int w = 0; w < (t >> 6); ++w) base += s_part[w];
+    for (int i = i0; i < i1; ++i) {
+      o[i] = base;
+      base += c[i];
+    }
   }
-  if (t == 255) counts[blockIdx.x] = base;
-}
-
-// One wave: first outlier row of every head, and the (head, first row) list of the second
-// attention's query tiles.  Lane h looks after head h (H <= 64).
-__global__ __launch_bounds__(64) void outlier_offsets_kernel(const int32_t* __restrict__ counts,
-                                                             int32_t* __restrict__ offsets,
-                                                             int32_t* __restrict__ tiles, int H,
-                                                             int tile_rows, int max_tiles) {
-  const int h = threadIdx.x;
+  if (h != 0 || t >= 64) return;
+  // one wave: lane g looks after head g
   int32_t off = 0, first_tile = 0, mine = 0;
   for (int g = 0; g < H; ++g) {
-    const int32_t c = counts[g];
-    if (g < h) {
+    const int32_t c = s_total[g];
+    if (g < t) {
       off += c;
       first_tile += (c + tile_rows - 1) / tile_rows;
     }
-    if (g == h) mine = c;
+    if (g == t) mine = c;
   }
-  if (h < H) {
-    offsets[h] = off;
+  if (t < H) {
+    counts[t] = mine;
+    offsets[t] = off;
     int nt = first_tile;
     for (int32_t r = 0; r < mine && nt < max_tiles; r += tile_rows, ++nt) {
-      tiles[1 + 2 * nt] = h;
+      tiles[1 + 2 * nt] = t;
       tiles[2 + 2 * nt] = r;
     }
-    if (h == H - 1) {
+    if (t == H - 1) {
       offsets[H] = off + mine;
       tiles[0] = nt < max_tiles ? nt : max_tiles;
     }
@@ -188,18 +264,14 @@ hipError_t launch_outlier_select(const float* eps, int H, int64_t N, int64_t bud
   // a handful of bins in the first pass, so the number of workgroups is what serialises there.
   int64_t want = (total / 4 + kSelThreads - 1) / kSelThreads;
   const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 256 ? 256 : want));
-  hipLaunchKernelGGL(select_hist_kernel<0>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist);
-  hipLaunchKernelGGL(select_pick_kernel<0>, dim3(1), dim3(kSelThreads), 0, stream, b.hist, b.state, (uint32_t)budget);
-  hipLaunchKernelGGL(select_hist_kernel<1>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist);
-  hipLaunchKernelGGL(select_pick_kernel<1>, dim3(1), dim3(kSelThreads), 0, stream, b.hist, b.state, (uint32_t)budget);
-  hipLaunchKernelGGL(select_hist_kernel<2>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist);
-  hipLaunchKernelGGL(select_pick_kernel<2>, dim3(1), dim3(kSelThreads), 0, stream, b.hist, b.state, (uint32_t)budget);
-  hipLaunchKernelGGL(outlier_count_kernel, dim3((unsigned)((n_items + 3) / 4), (unsigned)H), dim3(256), 0,
-                     stream, eps, N, items, n_items, b.state, b.item_base);
-  hipLaunchKernelGGL(outlier_scan_kernel, dim3((unsigned)H), dim3(256), 0, stream, b.item_base, n_items,
-                     b.counts);
-  hipLaunchKernelGGL(outlier_offsets_kernel, dim3(1), dim3(64), 0, stream, b.counts, b.offsets, b.tiles, H,
-                     tile_rows, b.max_tiles);
+  const uint32_t bud = (uint32_t)budget;
+  hipLaunchKernelGGL(select_hist_kernel<0>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist, bud);
+  hipLaunchKernelGGL(select_hist_kernel<1>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist, bud);
+  hipLaunchKernelGGL(select_hist_kernel<2>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist, bud);
+  hipLaunchKernelGGL(outlier_count_kernel, dim3((unsigned)((n_items + kCountItems - 1) / kCountItems), (unsigned)H),
+                     dim3(kSelThreads), 0, stream, eps, N, items, n_items, b.state, b.hist, b.item_cnt);
+  hipLaunchKernelGGL(outlier_offsets_kernel, dim3((unsigned)H), dim3(kSelThreads), 0, stream, b.item_cnt, b.item_base,
+                     n_items, H, b.hist, b.counts, b.offsets, b.tiles, tile_rows, b.max_tiles);
   return hipGetLastError();
 }
 
