@@ -286,7 +286,8 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
     OutlierBuffers& b = p->ob;
     b.max_tiles = (int32_t)(p->outlier_cap / kAttnDevTileRows + g->H);
     const size_t words = sizeof(SelectState) / 4 + 3 * 2048 + (size_t)g->H * 2 + 1 +
-                         2 * (size_t)g->H * p->n_items + 1 + 2 * (size_t)b.max_tiles;
+                         2 * (size_t)g->H * p->n_items + (size_t)g->H * (p->n_items / kOutlierCountItems + 1) + 1 +
+                         2 * (size_t)b.max_tiles;
     uint32_t* base = nullptr;
     e = hipMalloc((void**)&base, words * 4);
     if (e == hipSuccess) e = hipMemset(base, 0, words * 4);
@@ -299,7 +300,8 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
       b.offsets = b.counts + g->H;
       b.item_cnt = b.offsets + g->H + 1;
       b.item_base = b.item_cnt + (size_t)g->H * p->n_items;
-      b.tiles = b.item_base + (size_t)g->H * p->n_items;
+      b.wg_cnt = b.item_base + (size_t)g->H * p->n_items;
+      b.tiles = b.wg_cnt + (size_t)g->H * (p->n_items / kOutlierCountItems + 1);
     }
   }
   // "Synchronous": the copies and the memset above are complete before a kernel on any stream

@@ -82,12 +82,14 @@ struct SelectState {
   uint32_t rank2;
   uint32_t pad2[2];
 };
+constexpr int kOutlierCountItems = 16;   // work items per workgroup of the kernel that counts the outliers
 struct OutlierBuffers {      // all device memory, owned by the plan
   SelectState* state;
   uint32_t* hist;            // [3][2048] one histogram per pass of the select, zero between calls
   int32_t* counts;           // [H] outliers per head
   int32_t* offsets;          // [H + 1] first outlier row of every head in q_out / o_out
   int32_t* item_cnt;         // [H][n_items] outliers of a work item
+  int32_t* wg_cnt;           // [H][ceil(n_items / kOutlierCountItems)] the same summed per workgroup of the count kernel
   int32_t* item_base;        // [H][n_items] first outlier row of a work item, relative to its head
   int32_t* tiles;            // [1 + 2 * max_tiles]: n, then (head, first row) per attention tile
   int32_t max_tiles;

@@ -122,12 +122,20 @@ __global__ __launch_bounds__(kSelThreads) void select_hist_kernel(const uint32_t
   // 16-byte loads; `keys` is 16-byte aligned and the tail is handled by the last threads
   const int64_t n4 = total >> 2;
   const int64_t stride = (int64_t)gridDim.x * kSelThreads;
-  for (int64_t i = (int64_t)blockIdx.x * kSelThreads + threadIdx.x; i < n4; i += stride) {
-    const u32x4 w = ((const u32x4*)keys)[i];
+  // (four independent loads per round: a thread has some 17 of them to do, and one at a time each
+  // would cost a trip to memory)
+  for (int64_t i = (int64_t)blockIdx.x * kSelThreads + threadIdx.x; i < n4; i += 4 * stride) {
+    u32x4 w[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      uint32_t d;
-      if (digit_of<PASS>(w[q], prefix, &d)) atomicAdd(&s_hist[d], 1u);
+    for (int u = 0; u < 4; ++u) w[u] = ((const u32x4*)keys)[i + u * stride < n4 ? i + u * stride : i];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (i + u * stride >= n4) break;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        uint32_t d;
+        if (digit_of<PASS>(w[u][q], prefix, &d)) atomicAdd(&s_hist[d], 1u);
+      }
     }
   }
   if (blockIdx.x == 0) {
@@ -144,70 +152,86 @@ __global__ __launch_bounds__(kSelThreads) void select_hist_kernel(const uint32_t
   }
 }
 
-// item_cnt[h][i] = number of deviations above tau among the tokens of work item i of head h.  The
-// prologue takes the last digit of tau from the third histogram.  One wave per (item, head) at a
-// time, kCountItems items per workgroup.
-constexpr int kCountItems = 32;
+// item_cnt[h][i] = number of deviations above tau among the tokens of work item i of head h, and
+// wg_cnt[h][w] = their sum over the work items of workgroup w.  The prologue takes the last
+// digit of tau from the third histogram.  One wave per (item, head) at a time, kCountItems items per
+// workgroup.
+constexpr int kCountItems = kOutlierCountItems;
 __global__ __launch_bounds__(kSelThreads) void outlier_count_kernel(const float* __restrict__ eps, int64_t N,
                                                                     const WorkItem* __restrict__ items, int n_items,
                                                                     SelectState* __restrict__ st,
                                                                     const uint32_t* __restrict__ hist,
-                                                                    int32_t* __restrict__ item_cnt) {
+                                                                    int32_t* __restrict__ item_cnt,
+                                                                    int32_t* __restrict__ wg_cnt) {
+  __shared__ int s_sum[kSelThreads / 64];
   uint32_t digit, rank_in_bin;
   pick_digit(hist + 2 * kBins, st->rank2, &digit, &rank_in_bin);
   const float tau = __uint_as_float((st->prefix2 << 10) | digit);
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) st->tau = tau;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int wave_sum = 0;
   for (int i = wave; i < kCountItems; i += kSelThreads / 64) {
     const int item = blockIdx.x * kCountItems + i;
     if (item >= n_items) break;
     const WorkItem it = items[item];
     const float* e = eps + (int64_t)blockIdx.y * N + it.start;
     int c = 0;
-    for (int t = lane; t < it.n; t += 64) c += e[t] > tau ? 1 : 0;
+    for (int t = lane; t < it.n; t += 256) {   // four independent loads per round
+      float v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = e[t + 64 * u < it.n ? t + 64 * u : t];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) c += (t + 64 * u < it.n && v[u] > tau) ? 1 : 0;
+    }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d);
     if (lane == 0) item_cnt[(int64_t)blockIdx.y * n_items + item] = c;
+    wave_sum += c;
+  }
+  if (lane == 0) s_sum[wave] = wave_sum;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int tot = 0;
+    for (int w = 0; w < kSelThreads / 64; ++w) tot += s_sum[w];
+    wg_cnt[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = tot;
   }
 }
 
 // One workgroup per head h:
 //  - item_base[h][i] = exclusive prefix sum of item_cnt[h][.], so that every work item knows the first
 //    outlier row it owns (relative to its head);
-//  - the totals of ALL heads (every workgroup adds them up for itself, so no workgroup waits for
-//    another), from which workgroup 0 writes the first outlier row of every head and the (head,
-//    first row) list of the second attention's query tiles;
-//  - its share of the three histograms cleared for the next call.
+//  - its share of the three histograms cleared for the next call;
+//  - workgroup 0: the head totals from the sums of the count kernel's workgroups, the first outlier
+//    row of every head and the (head, first row) list of the second attention's query tiles.
 __global__ __launch_bounds__(kSelThreads) void outlier_offsets_kernel(const int32_t* __restrict__ item_cnt,
                                                                       int32_t* __restrict__ item_base, int n_items,
                                                                       int H, uint32_t* __restrict__ hist,
+                                                                      const int32_t* __restrict__ wg_cnt, int n_wg,
                                                                       int32_t* __restrict__ counts,
                                                                       int32_t* __restrict__ offsets,
                                                                       int32_t* __restrict__ tiles, int tile_rows,
                                                                       int max_tiles) {
-  __shared__ int s_part[kSelThreads];
+  __shared__ int s_part[kSelThreads / 64];
+  __shared__ int s_slice[kSelThreads];
   __shared__ int s_total[HTTM_MAX_HEADS];
   const int t = threadIdx.x, h = blockIdx.x;
-  for (int b = h * kSelThreads + t; b < 3 * kBins; b += H * kSelThreads) hist[b] = 0;
-  // totals of all heads: thread t adds a slice of head t % H
-  {
-    const int slices = kSelThreads / H, g = t % H, sl = t / H;   // H <= 64: at least 4 slices
+  if (h == 0) {
+    // thread t adds a slice of head t % H (H <= 64: at least four slices), thread g < H the slices of head g
+    const int slices = kSelThreads / H, g = t % H, sl = t / H;
     int sum = 0;
-    if (sl < slices) {
-      const int per = (n_items + slices - 1) / slices;
-      const int i0 = sl * per, i1 = i0 + per < n_items ? i0 + per : n_items;
-      const int32_t* c = item_cnt + (int64_t)g * n_items;
-      for (int i = i0; i < i1; ++i) sum += c[i];
-    }
-    s_part[t] = sum;
+    if (sl < slices)
+      for (int i = sl; i < n_wg; i += slices) sum += wg_cnt[(int64_t)g * n_wg + i];
+    s_slice[t] = sum;
     __syncthreads();
     if (t < H) {
       int tot = 0;
-      for (int u = 0; u < slices; ++u) tot += s_part[u * H + t];
+      for (int u = 0; u < slices; ++u) tot += s_slice[u * H + t];
       s_total[t] = tot;
+      counts[t] = tot;
     }
     __syncthreads();
   }
+  for (int b = h * kSelThreads + t; b < 3 * kBins; b += H * kSelThreads) hist[b] = 0;
   // prefix sum over this head's work items
   {
     const int32_t* c = item_cnt + (int64_t)h * n_items;
@@ -226,29 +250,37 @@ __global__ __launch_bounds__(kSelThreads) void outlier_offsets_kernel(const int3
       base += c[i];
     }
   }
-  if (h != 0 || t >= 64) return;
-  // one wave: lane g looks after head g
-  int32_t off = 0, first_tile = 0, mine = 0;
-  for (int g = 0; g < H; ++g) {
-    const int32_t c = s_total[g];
-    if (g < t) {
-      off += c;
-      first_tile += (c + tile_rows - 1) / tile_rows;
+  if (h != 0) return;
+  // first outlier row and first tile of every head (lane g of the first wave looks after head g),
+  // then the tile list with all threads
+  __shared__ int s_first[HTTM_MAX_HEADS + 1];
+  if (t < 64) {
+    int32_t off = 0, first_tile = 0, mine = 0;
+    for (int g = 0; g < H; ++g) {
+      const int32_t c = s_total[g];
+      if (g < t) {
+        off += c;
+        first_tile += (c + tile_rows - 1) / tile_rows;
+      }
+      if (g == t) mine = c;
     }
-    if (g == t) mine = c;
+    if (t < H) {
+      offsets[t] = off;
+      s_first[t] = first_tile;
+      if (t == H - 1) {
+        offsets[H] = off + mine;
+        const int nt = first_tile + (mine + tile_rows - 1) / tile_rows;
+        s_first[H] = nt < max_tiles ? nt : max_tiles;
+        tiles[0] = s_first[H];
+      }
+    }
   }
-  if (t < H) {
-    counts[t] = mine;
-    offsets[t] = off;
-    int nt = first_tile;
-    for (int32_t r = 0; r < mine && nt < max_tiles; r += tile_rows, ++nt) {
-      tiles[1 + 2 * nt] = t;
-      tiles[2 + 2 * nt] = r;
-    }
-    if (t == H - 1) {
-      offsets[H] = off + mine;
-      tiles[0] = nt < max_tiles ? nt : max_tiles;
-    }
+  __syncthreads();
+  for (int nt = t; nt < s_first[H]; nt += kSelThreads) {
+    int g = 0;
+    while (g + 1 < H && s_first[g + 1] <= nt) ++g;
+    tiles[1 + 2 * nt] = g;
+    tiles[2 + 2 * nt] = (nt - s_first[g]) * tile_rows;
   }
 }
 
@@ -269,9 +301,10 @@ hipError_t launch_outlier_select(const float* eps, int H, int64_t N, int64_t bud
   hipLaunchKernelGGL(select_hist_kernel<1>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist, bud);
   hipLaunchKernelGGL(select_hist_kernel<2>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist, bud);
   hipLaunchKernelGGL(outlier_count_kernel, dim3((unsigned)((n_items + kCountItems - 1) / kCountItems), (unsigned)H),
-                     dim3(kSelThreads), 0, stream, eps, N, items, n_items, b.state, b.hist, b.item_cnt);
+                     dim3(kSelThreads), 0, stream, eps, N, items, n_items, b.state, b.hist, b.item_cnt, b.wg_cnt);
   hipLaunchKernelGGL(outlier_offsets_kernel, dim3((unsigned)H), dim3(kSelThreads), 0, stream, b.item_cnt, b.item_base,
-                     n_items, H, b.hist, b.counts, b.offsets, b.tiles, tile_rows, b.max_tiles);
+                     n_items, H, b.hist, b.wg_cnt, (n_items + kCountItems - 1) / kCountItems, b.counts, b.offsets,
+                     b.tiles, tile_rows, b.max_tiles);
   return hipGetLastError();
 }
 
