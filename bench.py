@@ -93,6 +93,32 @@ def shader_clock_mhz():
         return None
 
 
+def mfma_sustained_tflops():
+    """What the chip sustains on the attention kernel's MFMA instruction alone: a register-only loop of
+    v_mfma_f32_32x32x16_bf16 with pseudo-random operands (paper_2511_21317_amd/csrc/mfma_probe.hip, its
+    own small library), two workgroups of four waves per compute unit, about 25 ms per launch so that
+    the clock has settled under the power limit.  Median of 5 launches; None if the probe is not built."""
+    import ctypes
+    import torch
+    path = os.path.join(ROOT, "paper_2511_21317_amd", "libhttm_probe.so")
+    if not os.path.exists(path):
+        return None
+    lib = ctypes.CDLL(path)
+    lib.httm_probe_mfma_bf16.restype = ctypes.c_double
+    lib.httm_probe_mfma_bf16.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    out = torch.zeros(1, dtype=torch.float32, device="cuda")
+    flop = [0.0]
+
+    def run():
+        flop[0] = lib.httm_probe_mfma_bf16(out.data_ptr(), 40000, 2, torch.cuda.current_stream().cuda_stream)
+    ts = event_times_ms(run, 5, warmup=2)
+    if flop[0] <= 0.0:
+        return None
+    ms = statistics.median(ts)
+    return {"TFLOP/s": flop[0] / (ms * 1e-3) / 1e12, "ms": ms, "flop": flop[0],
+            "what": "register-only loop of v_mfma_f32_32x32x16_bf16, pseudo-random operands, 512 workgroups of 4 waves"}
+
+
 def pmc_traffic_bytes(kernel: str, workload_index: int):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload
     (FETCH_SIZE + WRITE_SIZE, already scaled by the copy-kernel calibration), and the file, or None."""
@@ -272,6 +298,15 @@ def main():
                                 "run but read from the committed summary named in traffic_source)",
                 "traffic_source": None if special else traffic_file,
                 "flop_per_launch": a["algorithmic_flop"], "ms_per_launch": a["ms"], "ms_per_launch_min": a["ms_min"]}
+    # context for that fraction (the peak above stays the published one): the rate the same MFMA
+    # instruction reaches alone on this chip, under its power limit
+    if not args.no_extras:
+        sus = mfma_sustained_tflops()
+        if sus:
+            roofline["mfma_sustained_on_this_chip"] = sus
+            roofline["frac_of_sustained"] = a["TFLOP/s"] / sus["TFLOP/s"]
+            log(f"[bench] MFMA instruction alone: {sus['TFLOP/s']:.0f} TFLOP/s sustained ({sus['TFLOP/s'] / PEAK_BF16_TFLOPS:.3f} "
+                f"of the published peak); attention = {roofline['frac_of_sustained']:.3f} of that")
 
     # ---- extras: variants on the headline workload's inputs -------------------------------------
     extras = {}

@@ -28,6 +28,19 @@ def test_library_exports_every_declared_symbol():
     assert b"workspace" in L.httm_strerror(-3)
 
 
+def test_the_benchmark_probe_library_loads_and_rejects_bad_arguments():
+    """libhttm_probe.so is bench.py's measurement helper (a register-only MFMA loop), built next to the
+    library; without a GPU only its argument check can run (no launch happens before it)."""
+    path = os.path.join(ROOT, "paper_2511_21317_amd", "libhttm_probe.so")
+    assert os.path.exists(path), "build() did not produce the probe library"
+    L = C.CDLL(path)
+    L.httm_probe_mfma_bf16.restype = C.c_double
+    L.httm_probe_mfma_bf16.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+    assert L.httm_probe_mfma_bf16(None, 10, 1, None) == 0.0
+    assert L.httm_probe_mfma_bf16(C.c_void_p(256), 0, 1, None) == 0.0
+    assert L.httm_probe_mfma_bf16(C.c_void_p(256), 10, 9, None) == 0.0
+
+
 GEOMS = [
     (2, 16, 16, 4, 2, 0.5, 0.5),
     (8, 37, 37, 4, 2, 0.5, 0.5),
