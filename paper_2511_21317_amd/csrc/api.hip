@@ -147,7 +147,7 @@ int run_match_merge_filtered(const httm_plan_t* p, const void* q, const void* k,
                            st, eps_q);
   if (rc != HTTM_OK) return rc;
   HTTM_HIP(launch_outlier_select(eps_q, p->geom.H, p->sizes.N, p->outlier_cap, p->d_items_q,
-                                 p->n_items, p->ob, kAttnDevTileRows, st));
+                                 p->n_items, (int)p->sizes.max_block, p->ob, kAttnDevTileRows, st));
   RefineArgs r;
   std::memset(&r, 0, sizeof(r));
   r.x = q;
@@ -286,7 +286,7 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
     OutlierBuffers& b = p->ob;
     b.max_tiles = (int32_t)(p->outlier_cap / kAttnDevTileRows + g->H);
     const size_t words = sizeof(SelectState) / 4 + 3 * 2048 + (size_t)g->H * 2 + 1 +
-                         2 * (size_t)g->H * p->n_items + (size_t)g->H * (p->n_items / kOutlierCountItems + 1) + 1 +
+                         2 * (size_t)g->H * p->n_items + (size_t)g->H * (p->n_items / kOutlierCountItemsMin + 1) + 1 +
                          2 * (size_t)b.max_tiles;
     uint32_t* base = nullptr;
     e = hipMalloc((void**)&base, words * 4);
@@ -301,7 +301,7 @@ int httm_plan_create(const httm_geom_t* g, httm_plan_t** out) {
       b.item_cnt = b.offsets + g->H + 1;
       b.item_base = b.item_cnt + (size_t)g->H * p->n_items;
       b.wg_cnt = b.item_base + (size_t)g->H * p->n_items;
-      b.tiles = b.wg_cnt + (size_t)g->H * (p->n_items / kOutlierCountItems + 1);
+      b.tiles = b.wg_cnt + (size_t)g->H * (p->n_items / kOutlierCountItemsMin + 1);
     }
   }
   // "Synchronous": the copies and the memset above are complete before a kernel on any stream

@@ -82,14 +82,15 @@ struct SelectState {
   uint32_t rank2;
   uint32_t pad2[2];
 };
-constexpr int kOutlierCountItems = 16;   // work items per workgroup of the kernel that counts the outliers
+constexpr int kOutlierCountItems = 16;    // work items per workgroup of the kernel that counts the outliers,
+constexpr int kOutlierCountItemsMin = 4;  // and when the items are long (blocks of more than 1024 tokens)
 struct OutlierBuffers {      // all device memory, owned by the plan
   SelectState* state;
   uint32_t* hist;            // [3][2048] one histogram per pass of the select, zero between calls
   int32_t* counts;           // [H] outliers per head
   int32_t* offsets;          // [H + 1] first outlier row of every head in q_out / o_out
   int32_t* item_cnt;         // [H][n_items] outliers of a work item
-  int32_t* wg_cnt;           // [H][ceil(n_items / kOutlierCountItems)] the same summed per workgroup of the count kernel
+  int32_t* wg_cnt;           // [H][n_items / kOutlierCountItemsMin + 1] the same summed per workgroup of the count kernel
   int32_t* item_base;        // [H][n_items] first outlier row of a work item, relative to its head
   int32_t* tiles;            // [1 + 2 * max_tiles]: n, then (head, first row) per attention tile
   int32_t max_tiles;
@@ -98,7 +99,7 @@ struct OutlierBuffers {      // all device memory, owned by the plan
 // outlier counts per (work item, head), their prefix offsets and the tile list of the second
 // attention (`tile_rows` query rows per tile).
 hipError_t launch_outlier_select(const float* eps, int H, int64_t N, int64_t budget,
-                                 const WorkItem* items, int n_items, const OutlierBuffers& b,
+                                 const WorkItem* items, int n_items, int max_block, const OutlierBuffers& b,
                                  int tile_rows, hipStream_t stream);
 // Un-merge the outliers: recompute the merged queries that lose a constituent, give every
 // outlier token a row in q_out and rewrite its assign_q entry as -1 - row.

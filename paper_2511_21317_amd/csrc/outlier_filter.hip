@@ -154,15 +154,14 @@ __global__ __launch_bounds__(kSelThreads) void select_hist_kernel(const uint32_t
 
 // item_cnt[h][i] = number of deviations above tau among the tokens of work item i of head h, and
 // wg_cnt[h][w] = their sum over the work items of workgroup w.  The prologue takes the last
-// digit of tau from the third histogram.  One wave per (item, head) at a time, kCountItems items per
-// workgroup.
-constexpr int kCountItems = kOutlierCountItems;
+// digit of tau from the third histogram.  One wave per (item, head) at a time, `items_per_wg` items
+// per workgroup (fewer when the items are long, so that a wave does not walk several of them).
 __global__ __launch_bounds__(kSelThreads) void outlier_count_kernel(const float* __restrict__ eps, int64_t N,
                                                                     const WorkItem* __restrict__ items, int n_items,
                                                                     SelectState* __restrict__ st,
                                                                     const uint32_t* __restrict__ hist,
                                                                     int32_t* __restrict__ item_cnt,
-                                                                    int32_t* __restrict__ wg_cnt) {
+                                                                    int32_t* __restrict__ wg_cnt, int items_per_wg) {
   __shared__ int s_sum[kSelThreads / 64];
   uint32_t digit, rank_in_bin;
   pick_digit(hist + 2 * kBins, st->rank2, &digit, &rank_in_bin);
@@ -170,8 +169,8 @@ __global__ __launch_bounds__(kSelThreads) void outlier_count_kernel(const float*
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) st->tau = tau;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int wave_sum = 0;
-  for (int i = wave; i < kCountItems; i += kSelThreads / 64) {
-    const int item = blockIdx.x * kCountItems + i;
+  for (int i = wave; i < items_per_wg; i += kSelThreads / 64) {
+    const int item = blockIdx.x * items_per_wg + i;
     if (item >= n_items) break;
     const WorkItem it = items[item];
     const float* e = eps + (int64_t)blockIdx.y * N + it.start;
@@ -287,7 +286,7 @@ __global__ __launch_bounds__(kSelThreads) void outlier_offsets_kernel(const int3
 }  // namespace
 
 hipError_t launch_outlier_select(const float* eps, int H, int64_t N, int64_t budget,
-                                 const WorkItem* items, int n_items, const OutlierBuffers& b,
+                                 const WorkItem* items, int n_items, int max_block, const OutlierBuffers& b,
                                  int tile_rows, hipStream_t stream) {
   const int64_t total = (int64_t)H * N;
   if (total == 0) return hipSuccess;
@@ -300,11 +299,12 @@ hipError_t launch_outlier_select(const float* eps, int H, int64_t N, int64_t bud
   hipLaunchKernelGGL(select_hist_kernel<0>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist, bud);
   hipLaunchKernelGGL(select_hist_kernel<1>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist, bud);
   hipLaunchKernelGGL(select_hist_kernel<2>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist, bud);
-  hipLaunchKernelGGL(outlier_count_kernel, dim3((unsigned)((n_items + kCountItems - 1) / kCountItems), (unsigned)H),
-                     dim3(kSelThreads), 0, stream, eps, N, items, n_items, b.state, b.hist, b.item_cnt, b.wg_cnt);
+  const int per_wg = max_block > 1024 ? kOutlierCountItemsMin : kOutlierCountItems;
+  const int n_wg = (n_items + per_wg - 1) / per_wg;
+  hipLaunchKernelGGL(outlier_count_kernel, dim3((unsigned)n_wg, (unsigned)H), dim3(kSelThreads), 0, stream, eps, N, items,
+                     n_items, b.state, b.hist, b.item_cnt, b.wg_cnt, per_wg);
   hipLaunchKernelGGL(outlier_offsets_kernel, dim3((unsigned)H), dim3(kSelThreads), 0, stream, b.item_cnt, b.item_base,
-                     n_items, H, b.hist, b.wg_cnt, (n_items + kCountItems - 1) / kCountItems, b.counts, b.offsets,
-                     b.tiles, tile_rows, b.max_tiles);
+                     n_items, H, b.hist, b.wg_cnt, n_wg, b.counts, b.offsets, b.tiles, tile_rows, b.max_tiles);
   return hipGetLastError();
 }
 
