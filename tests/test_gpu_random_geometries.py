@@ -37,10 +37,36 @@ def _draw(seed):
     return w, rho_kv, variant, log2_keys
 
 
+def _draw_big(seed):
+    """The same with blocks of 513 .. 4096 tokens (runs of b patch tokens over T frames): the two-kernel
+    path of stage 2."""
+    rng = np.random.default_rng(424200 + seed)
+    Hp, Wp = int(rng.integers(8, 21)), int(rng.integers(8, 21))
+    P = Hp * Wp
+    T = int(rng.integers(2, 13))
+    S = int(rng.integers(T, max(T, min(3 * T, 6000 // (P + 5))) + 1))
+    b_lo, b_hi = max(8, -(-520 // T)), max(8, min(P, 4096 // T))
+    b = int(rng.integers(min(b_lo, b_hi), b_hi + 1))
+    w = Workload(f"big{seed}_S{S}_{Hp}x{Wp}_b{b}T{T}_chunked", 900 + seed, S, Hp, Wp, b, T,
+                 float(rng.choice(RHOS)), 1, H=int(rng.integers(1, 3)), n_special=int(rng.choice([0, 1, 5])),
+                 anchor=bool(rng.integers(0, 2)), chunked=True)
+    rho_kv = float(rng.choice(RHOS))
+    variant = "uniform" if rng.integers(0, 4) == 0 else "headwise"
+    return w, rho_kv, variant, bool(rng.integers(0, 2))
+
+
 @pytest.mark.parametrize("seed", range(40))
 def test_layer_on_a_random_geometry(seed):
+    _check_layer(*_draw(seed))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_layer_on_a_random_geometry_with_big_blocks(seed):
+    _check_layer(*_draw_big(seed))
+
+
+def _check_layer(w, rho_kv, variant, log2_keys):
     require_gpu()
-    w, rho_kv, variant, log2_keys = _draw(seed)
     g = oracle_geom(w)
     _, blocks = orc.temporal_reorder(g)
     max_block = max((n for _, n in blocks), default=0)
