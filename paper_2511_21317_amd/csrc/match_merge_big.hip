@@ -56,7 +56,11 @@ __device__ __forceinline__ float chunk_sumsq(const bf16x8 w, float ss) {
 
 constexpr int kBmWaves = 4;
 constexpr int kBmThreads = 64 * kBmWaves;
-constexpr int kBmTokens = 64 * kBmWaves;   // tokens per workgroup (two 32-token tiles per wave)
+// 32-token tiles per wave.  (Three or four would spread the per-dst-tile work over more scores, but the
+// operands they keep in registers cost a resident wave: 1.29 / 1.31 / 1.56 ms for stage 2 at 3840-token
+// blocks with 2 / 3 / 4.)
+constexpr int kBmQt = 2;
+constexpr int kBmTokens = 32 * kBmQt * kBmWaves;   // tokens per workgroup
 constexpr int kBmDstTile = 64;
 
 // WIDE: the work item may be a whole sequence (un-blocked matching): positions are computed with
@@ -102,19 +106,17 @@ void big_match_kernel(const MatchMergeArgs a) {
   float* __restrict__ score = s.score ? s.score + h * N + it.start : nullptr;
 
   if (k == n) {   // nothing to merge: every token is its own cluster
-    const int t = t0 + tid;
-    if (t < n) {
+    for (int t = t0 + tid; t < n && t < t0 + kBmTokens; t += kBmThreads) {
       assign[t] = it.moff + t;
       if (score) score[t] = 1.0f;
     }
     return;
   }
-  // tokens this workgroup matches: positions [t0, t0 + 256) (WIDE) or the src tokens of those ranks
+  // tokens this workgroup matches: positions [t0, t0 + kBmTokens) (WIDE) or the src tokens of those ranks
   const int n_tok = WIDE ? n : n - k;
   if constexpr (!WIDE) {
-    // the entries of the dst tokens themselves: chunk c writes those of the clusters [256 c, 256 c + 256)
-    const int m = t0 + tid;
-    if (m < k) {
+    // the entries of the dst tokens themselves: chunk c writes those of the clusters [c, c + 1) * kBmTokens
+    for (int m = t0 + tid; m < k && m < t0 + kBmTokens; m += kBmThreads) {
       const int p = bm.dst_position(m);
       assign[p] = it.moff + m;
       if (score) score[p] = 1.0f;
@@ -127,12 +129,12 @@ void big_match_kernel(const MatchMergeArgs a) {
   }
 
   // ---- this wave's 64 tokens as B operands: lane -> token column, 8 channels per k-step ---------
-  bf16x8 bx[2][4];
-  float invn[2], bias[2];
-  int tpos[2];
+  bf16x8 bx[kBmQt][4];
+  float invn[kBmQt], bias[kBmQt];
+  int tpos[kBmQt];
 #pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
-    const int tok = t0 + wave * 64 + qt * 32 + l32;
+  for (int qt = 0; qt < kBmQt; ++qt) {
+    const int tok = t0 + wave * (32 * kBmQt) + qt * 32 + l32;
     const int tokc = tok < n_tok ? tok : n_tok - 1;
     if constexpr (WIDE) tpos[qt] = tokc;
     else tpos[qt] = bm.src_position(tokc);
@@ -178,8 +180,13 @@ void big_match_kernel(const MatchMergeArgs a) {
   // non-negative floats, so a plain float maximum orders them by score and, among scores that agree
   // to 2^-19, by the lower dst index - two vector instructions per score (fma, and-or) plus the
   // maximum tree, instead of scale, compare and two selects.
-  float bestk[2] = {-1.0f, -1.0f};
-  int bd0[2] = {0, 0};
+  float bestk[kBmQt];
+  int bd0[kBmQt];
+#pragma unroll
+  for (int qt = 0; qt < kBmQt; ++qt) {
+    bestk[qt] = -1.0f;
+    bd0[qt] = 0;
+  }
   for (int j = 0; j < n_tiles; ++j) {
     const int buf = j & 1;
     // rows of tile j: registers -> LDS, and 1/||d|| from the 8 lanes that share a row
@@ -210,7 +217,7 @@ void big_match_kernel(const MatchMergeArgs a) {
       for (int ks = 0; ks < 4; ++ks)
         ad[ks] = *(const bf16x8*)(&s_d[buf][(step * 32 + l32) * kLdsRowBytes + ks * 32 + half * 16]);
 #pragma unroll
-      for (int qt = 0; qt < 2; ++qt) {
+      for (int qt = 0; qt < kBmQt; ++qt) {
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -241,7 +248,7 @@ void big_match_kernel(const MatchMergeArgs a) {
   }
 
 #pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
+  for (int qt = 0; qt < kBmQt; ++qt) {
     const int r = 15 - (int)(__float_as_uint(bestk[qt]) & 15u);
     int bmq = bd0[qt] + 8 * (r >> 2) + 4 * half + (r & 3);
     float bestq = __uint_as_float(__float_as_uint(bestk[qt]) & ~15u);
@@ -251,7 +258,7 @@ void big_match_kernel(const MatchMergeArgs a) {
       bestq = ob;
       bmq = om;
     }
-    const int tok = t0 + wave * 64 + qt * 32 + l32;
+    const int tok = t0 + wave * (32 * kBmQt) + qt * 32 + l32;
     if (half == 0 && tok < n_tok) {
       int c = -1;
       if constexpr (WIDE) c = cluster_at(tok, n, k, n0);   // (a src token by construction otherwise)
