@@ -22,6 +22,9 @@ namespace {
 
 constexpr int kBins = 2048;
 constexpr int kSelThreads = 256;
+// threads per workgroup of the histogram passes: few workgroups (see launch_outlier_select), so many
+// threads each - a thread then has one round of loads to wait for instead of four
+constexpr int kHistThreads = 1024;
 
 __device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t v) {
   const int lane = threadIdx.x & 63;
@@ -33,12 +36,13 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t v) {
   return v;
 }
 
-// All kSelThreads threads of a workgroup: the bin of `hist` (kBins counts, bin = digit) that holds the
+// All NTHR threads of a workgroup: the bin of `hist` (kBins counts, bin = digit) that holds the
 // value of descending rank `rank` (0 = the largest), and the rank inside that bin.
+template <int NTHR>
 __device__ __forceinline__ void pick_digit(const uint32_t* __restrict__ hist, uint32_t rank, uint32_t* digit,
                                            uint32_t* rank_in_bin) {
-  constexpr int PER = kBins / kSelThreads;
-  __shared__ uint32_t s_wave[kSelThreads / 64];
+  constexpr int PER = kBins / NTHR;
+  __shared__ uint32_t s_wave[NTHR / 64];
   __shared__ uint32_t s_res[2];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   uint32_t h[PER], mine = 0;
@@ -53,7 +57,7 @@ __device__ __forceinline__ void pick_digit(const uint32_t* __restrict__ hist, ui
   if (t == 0) s_res[0] = s_res[1] = 0;
   __syncthreads();
   uint32_t above = wave_total - incl;   // values in the bins of the threads above this one
-  for (int w = wave + 1; w < kSelThreads / 64; ++w) above += s_wave[w];
+  for (int w = wave + 1; w < NTHR / 64; ++w) above += s_wave[w];
 #pragma unroll
   for (int i = PER - 1; i >= 0; --i) {
     if (rank >= above && rank < above + h[i]) {
@@ -80,14 +84,14 @@ __device__ __forceinline__ void select_prologue(const uint32_t* __restrict__ his
   }
   uint32_t digit;
   if (PASS == 1) {
-    pick_digit(hist, budget, &digit, rank);
+    pick_digit<kHistThreads>(hist, budget, &digit, rank);
     *prefix = digit;
     if (writer && threadIdx.x == 0) {
       st->prefix1 = *prefix;
       st->rank1 = *rank;
     }
   } else {
-    pick_digit(hist + kBins, st->rank1, &digit, rank);
+    pick_digit<kHistThreads>(hist + kBins, st->rank1, &digit, rank);
     *prefix = (st->prefix1 << 11) | digit;
     if (writer && threadIdx.x == 0) {
       st->prefix2 = *prefix;
@@ -111,20 +115,20 @@ __device__ __forceinline__ bool digit_of(uint32_t key, uint32_t prefix, uint32_t
 }
 
 template <int PASS>
-__global__ __launch_bounds__(kSelThreads) void select_hist_kernel(const uint32_t* __restrict__ keys,
+__global__ __launch_bounds__(kHistThreads) void select_hist_kernel(const uint32_t* __restrict__ keys,
                                                                   int64_t total, SelectState* __restrict__ st,
                                                                   uint32_t* __restrict__ hist, uint32_t budget) {
   __shared__ uint32_t s_hist[kBins];
-  for (int b = threadIdx.x; b < kBins; b += kSelThreads) s_hist[b] = 0;
+  for (int b = threadIdx.x; b < kBins; b += kHistThreads) s_hist[b] = 0;
   uint32_t prefix, rank;
   select_prologue<PASS>(hist, st, budget, blockIdx.x == 0, &prefix, &rank);
   __syncthreads();
   // 16-byte loads; `keys` is 16-byte aligned and the tail is handled by the last threads
   const int64_t n4 = total >> 2;
-  const int64_t stride = (int64_t)gridDim.x * kSelThreads;
+  const int64_t stride = (int64_t)gridDim.x * kHistThreads;
   // (four independent loads per round: a thread has some 17 of them to do, and one at a time each
   // would cost a trip to memory)
-  for (int64_t i = (int64_t)blockIdx.x * kSelThreads + threadIdx.x; i < n4; i += 4 * stride) {
+  for (int64_t i = (int64_t)blockIdx.x * kHistThreads + threadIdx.x; i < n4; i += 4 * stride) {
     u32x4 w[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) w[u] = ((const u32x4*)keys)[i + u * stride < n4 ? i + u * stride : i];
@@ -139,14 +143,14 @@ __global__ __launch_bounds__(kSelThreads) void select_hist_kernel(const uint32_t
     }
   }
   if (blockIdx.x == 0) {
-    for (int64_t i = (n4 << 2) + threadIdx.x; i < total; i += kSelThreads) {
+    for (int64_t i = (n4 << 2) + threadIdx.x; i < total; i += kHistThreads) {
       uint32_t d;
       if (digit_of<PASS>(keys[i], prefix, &d)) atomicAdd(&s_hist[d], 1u);
     }
   }
   __syncthreads();
   uint32_t* __restrict__ out = hist + PASS * kBins;
-  for (int b = threadIdx.x; b < kBins; b += kSelThreads) {
+  for (int b = threadIdx.x; b < kBins; b += kHistThreads) {
     const uint32_t c = s_hist[b];
     if (c) atomicAdd(&out[b], c);
   }
@@ -164,7 +168,7 @@ __global__ __launch_bounds__(kSelThreads) void outlier_count_kernel(const float*
                                                                     int32_t* __restrict__ wg_cnt, int items_per_wg) {
   __shared__ int s_sum[kSelThreads / 64];
   uint32_t digit, rank_in_bin;
-  pick_digit(hist + 2 * kBins, st->rank2, &digit, &rank_in_bin);
+  pick_digit<kSelThreads>(hist + 2 * kBins, st->rank2, &digit, &rank_in_bin);
   const float tau = __uint_as_float((st->prefix2 << 10) | digit);
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) st->tau = tau;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -293,12 +297,12 @@ hipError_t launch_outlier_select(const float* eps, int H, int64_t N, int64_t bud
   const uint32_t* keys = (const uint32_t*)eps;
   // Few workgroups: each ends with one global atomic per non-empty bin, and the values crowd into
   // a handful of bins in the first pass, so the number of workgroups is what serialises there.
-  int64_t want = (total / 4 + kSelThreads - 1) / kSelThreads;
+  int64_t want = (total / 4 + kHistThreads - 1) / kHistThreads;
   const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 256 ? 256 : want));
   const uint32_t bud = (uint32_t)budget;
-  hipLaunchKernelGGL(select_hist_kernel<0>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist, bud);
-  hipLaunchKernelGGL(select_hist_kernel<1>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist, bud);
-  hipLaunchKernelGGL(select_hist_kernel<2>, dim3(grid), dim3(kSelThreads), 0, stream, keys, total, b.state, b.hist, bud);
+  hipLaunchKernelGGL(select_hist_kernel<0>, dim3(grid), dim3(kHistThreads), 0, stream, keys, total, b.state, b.hist, bud);
+  hipLaunchKernelGGL(select_hist_kernel<1>, dim3(grid), dim3(kHistThreads), 0, stream, keys, total, b.state, b.hist, bud);
+  hipLaunchKernelGGL(select_hist_kernel<2>, dim3(grid), dim3(kHistThreads), 0, stream, keys, total, b.state, b.hist, bud);
   const int per_wg = max_block > 1024 ? kOutlierCountItemsMin : kOutlierCountItems;
   const int n_wg = (n_items + per_wg - 1) / per_wg;
   hipLaunchKernelGGL(outlier_count_kernel, dim3((unsigned)n_wg, (unsigned)H), dim3(kSelThreads), 0, stream, eps, N, items,
